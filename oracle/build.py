@@ -1,0 +1,20 @@
+"""Builds the C oracle (test infrastructure) into oracle/libclasp_oracle.so with gcc."""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(HERE, "clasp_oracle.c")
+LIB = os.path.join(HERE, "libclasp_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+        return LIB
+    cmd = ["gcc", "-O2", "-fopenmp", "-fno-fast-math", "-std=c99", "-shared", "-fPIC", "-Wall", "-Wextra",
+           "-o", LIB, SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(force=True))

@@ -1,0 +1,248 @@
+"""ctypes front end of the C oracle plus the greedy decode loops -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import this module. It never imports the
+HIP package. Arithmetic lives in clasp_oracle.c; this file adds
+  * prefill / plain greedy decoding with the full model (the lossless reference of the paper's abstract and
+    "Performance Metrics": speculative decoding must not change the generated text),
+  * the Draft -> Verify -> Layer-Optimization loop of Sec. 3.1 with greedy acceptance,
+which are integer control flow around the C calls.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+from . import build as _build
+
+_LIB = None
+
+
+class _Model(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
+                ("wdtype", C.c_int32), ("rms_eps", C.c_double), ("rope_base", C.c_double),
+                ("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p),
+                ("attn_norm", C.POINTER(C.c_void_p)), ("mlp_norm", C.POINTER(C.c_void_p)),
+                ("wq", C.POINTER(C.c_void_p)), ("wk", C.POINTER(C.c_void_p)), ("wv", C.POINTER(C.c_void_p)),
+                ("wo", C.POINTER(C.c_void_p)), ("w_gate", C.POINTER(C.c_void_p)),
+                ("w_up", C.POINTER(C.c_void_p)), ("w_down", C.POINTER(C.c_void_p))]
+
+
+def _lib():
+    global _LIB
+    if _LIB is None:
+        path = _build.build()
+        lib = C.CDLL(path)
+        dp = C.POINTER(C.c_double)
+        lib.clasp_oracle_layer.argtypes = [C.POINTER(_Model), C.c_int, dp, C.c_int, C.c_int, dp, dp, dp, dp, dp]
+        lib.clasp_oracle_layer.restype = C.c_int
+        lib.clasp_oracle_token.argtypes = [C.POINTER(_Model), C.c_int, C.c_int, C.c_void_p, dp, dp, C.c_int, dp, dp]
+        lib.clasp_oracle_token.restype = C.c_int
+        lib.clasp_oracle_cosine.argtypes = [dp, dp, C.c_int]
+        lib.clasp_oracle_cosine.restype = C.c_double
+        lib.clasp_oracle_dp.argtypes = [C.POINTER(_Model), dp, C.c_int, dp, dp, C.c_int, C.c_int, C.c_void_p,
+                                        dp, dp, C.c_void_p, dp, C.c_void_p]
+        lib.clasp_oracle_dp.restype = C.c_int
+        lib.clasp_oracle_num_threads.restype = C.c_int
+        _LIB = lib
+    return _LIB
+
+
+def _dptr(a: Optional[np.ndarray]):
+    if a is None:
+        return None
+    assert a.dtype == np.float64 and a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(C.POINTER(C.c_double))
+
+
+def num_threads() -> int:
+    return int(_lib().clasp_oracle_num_threads())
+
+
+def cosine(a: np.ndarray, b: np.ndarray) -> float:
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    b = np.ascontiguousarray(b, dtype=np.float64)
+    return float(_lib().clasp_oracle_cosine(_dptr(a), _dptr(b), a.size))
+
+
+class KVCache:
+    """The full model's keys (rotated) and values: float64 [n_layers][t_max][n_kv_heads][head_dim]."""
+
+    def __init__(self, shape, t_max: int):
+        dims = (shape.n_layers, t_max, shape.n_kv_heads, shape.head_dim)
+        self.K = np.zeros(dims, dtype=np.float64)
+        self.V = np.zeros(dims, dtype=np.float64)
+        self.t_max = t_max
+
+    def load(self, K: np.ndarray, V: np.ndarray, layers: Optional[Sequence[int]] = None):
+        """Fill rows 0..T-1 from arrays [n][T][n_kv][hd] (synthetic contents or another cache)."""
+        layers = range(K.shape[0]) if layers is None else layers
+        for src, l in enumerate(layers):
+            self.K[l, :K.shape[1]] = K[src]
+            self.V[l, :V.shape[1]] = V[src]
+
+
+class OracleModel:
+    """Holds row-major numpy weights (float32, or uint16 bf16 bit patterns) and calls the C oracle."""
+
+    def __init__(self, shape, weights: Dict[str, object]):
+        self.shape = shape
+        self.w = weights  # keep the arrays alive
+        L = shape.n_layers
+        layers = weights["layers"]
+        assert len(layers) == L
+        wd = 0 if shape.dtype == "f32" else 1
+        want = np.float32 if wd == 0 else np.uint16
+
+        def p(a: np.ndarray, dt):
+            assert a.dtype == dt and a.flags["C_CONTIGUOUS"], (a.dtype, dt)
+            return a.ctypes.data
+
+        def arr(name: str, dt):
+            return (C.c_void_p * L)(*[p(layers[l][name], dt) for l in range(L)])
+
+        self._arrays = {n: arr(n, want) for n in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")}
+        self._arrays["attn_norm"] = arr("attn_norm", np.float32)
+        self._arrays["mlp_norm"] = arr("mlp_norm", np.float32)
+        m = _Model(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
+                   shape.vocab, wd, shape.rms_eps, shape.rope_base,
+                   p(weights["embed"], want), p(weights["lm_head"], want), p(weights["final_norm"], np.float32))
+        for n, a in self._arrays.items():
+            setattr(m, n, C.cast(a, C.POINTER(C.c_void_p)))
+        self._m = m
+
+    # ---- single calls -------------------------------------------------------------------------------------
+    def layer(self, l: int, h: np.ndarray, pos: int, n_prefix: int, Kl: np.ndarray, Vl: np.ndarray):
+        """f_l on one row: returns (out[d], k_new[kv_dim], v_new[kv_dim])."""
+        s = self.shape
+        h = np.ascontiguousarray(h, dtype=np.float64)
+        out = np.empty(s.d_model)
+        kn = np.empty(s.kv_dim)
+        vn = np.empty(s.kv_dim)
+        rc = _lib().clasp_oracle_layer(C.byref(self._m), l, _dptr(h), pos, n_prefix, _dptr(Kl), _dptr(Vl),
+                                       _dptr(out), _dptr(kn), _dptr(vn))
+        if rc:
+            raise ValueError("clasp_oracle_layer: bad argument")
+        return out, kn, vn
+
+    def token(self, token: int, pos: int, cache: KVCache, skip: Optional[np.ndarray] = None,
+              want_states: bool = False, want_logits: bool = True):
+        """One token through the (possibly layer-skipped) model; writes the cache row `pos`."""
+        s = self.shape
+        states = np.empty((s.n_layers + 1, s.d_model)) if want_states else None
+        logits = np.empty(s.vocab) if want_logits else None
+        sk = None
+        if skip is not None:
+            sk = np.ascontiguousarray(skip, dtype=np.uint8)
+            assert sk.size == s.n_layers
+        rc = _lib().clasp_oracle_token(C.byref(self._m), int(token), int(pos),
+                                       None if sk is None else sk.ctypes.data, _dptr(cache.K), _dptr(cache.V),
+                                       cache.t_max, _dptr(states), _dptr(logits))
+        if rc:
+            raise ValueError("clasp_oracle_token: bad argument")
+        return states, logits
+
+    def dp(self, X: np.ndarray, pos: int, cache: KVCache, M: int, override: Optional[np.ndarray] = None):
+        """Algorithm 1 for the token at `pos` with stored states X[(L+1)][d]."""
+        s = self.shape
+        L = s.n_layers
+        if not (0 <= M <= L):
+            raise ValueError("M out of range")
+        X = np.ascontiguousarray(X, dtype=np.float64)
+        assert X.shape == (L + 1, s.d_model)
+        sc = np.empty((L + 1, M + 1))
+        ss = np.empty((L + 1, M + 1))
+        ch = np.empty((L + 1, M + 1), dtype=np.uint8)
+        gf = np.empty(s.d_model)
+        mask = np.empty(L, dtype=np.uint8)
+        ov = None
+        if override is not None:
+            ov = np.ascontiguousarray(override, dtype=np.int8)
+            assert ov.shape == (L + 1, M + 1)
+        rc = _lib().clasp_oracle_dp(C.byref(self._m), _dptr(X), int(pos), _dptr(cache.K), _dptr(cache.V),
+                                    cache.t_max, int(M), None if ov is None else ov.ctypes.data, _dptr(sc),
+                                    _dptr(ss), ch.ctypes.data, _dptr(gf), mask.ctypes.data)
+        if rc:
+            raise ValueError("clasp_oracle_dp: bad argument")
+        return {"sigma_c": sc, "sigma_s": ss, "choice": ch, "g_final": gf, "mask": mask}
+
+    # ---- loops --------------------------------------------------------------------------------------------
+    def prefill(self, tokens: Sequence[int], cache: KVCache, pos0: int = 0):
+        """Full model over the prompt, one token at a time. Returns (states, logits) of the last token."""
+        states = logits = None
+        for t, tok in enumerate(tokens):
+            last = t == len(tokens) - 1
+            states, logits = self.token(tok, pos0 + t, cache, want_states=last, want_logits=last)
+        return states, logits
+
+    def greedy_decode(self, prompt: Sequence[int], n_gen: int, t_max: Optional[int] = None):
+        """Plain greedy decoding with the full model. Returns (tokens, margins): top-1 minus top-2 logit."""
+        t_max = t_max or len(prompt) + n_gen + 1
+        cache = KVCache(self.shape, t_max)
+        _, logits = self.prefill(prompt, cache)
+        out, margins = [], []
+        pos = len(prompt)
+        while len(out) < n_gen:
+            tok, mg = argmax_margin(logits)
+            out.append(tok)
+            margins.append(mg)
+            if len(out) == n_gen:
+                break
+            _, logits = self.token(tok, pos, cache)
+            pos += 1
+        return out, margins
+
+    def spec_decode(self, prompt: Sequence[int], n_gen: int, M: int, K: int, t_max: Optional[int] = None,
+                    dp_interval: int = 1):
+        """Greedy self-speculative decoding (Sec. 3.1): draft K tokens with the layer-skipped model, verify them
+        with the full model, accept the longest matching prefix plus the full model's next token, then re-run the
+        layer optimisation on the last accepted token's stored states. dp_interval > 1 re-optimises only every
+        that many verify steps (Sec. 3.7). Returns a dict with the tokens and a per-round trace."""
+        s = self.shape
+        t_max = t_max or len(prompt) + n_gen + K + 2
+        cache = KVCache(s, t_max)
+        states, logits = self.prefill(prompt, cache)
+        pending, _ = argmax_margin(logits)
+        out = [pending]
+        pos = len(prompt)  # position the pending token will occupy
+        dp = self.dp(states, pos - 1, cache, M)  # prefill counts as verification 0
+        mask = dp["mask"]
+        rounds = []
+        n_verify = 0
+        while len(out) < n_gen:
+            drafts, tok = [], pending
+            for k in range(K):
+                _, lg = self.token(tok, pos + k, cache, skip=mask)
+                tok, _ = argmax_margin(lg)
+                drafts.append(tok)
+            rows = [pending] + drafts
+            v, v_states, v_margin = [], [], []
+            for r, tk in enumerate(rows):  # the verify pass: full model, causal over the K+1 rows
+                st, lg = self.token(tk, pos + r, cache, want_states=True)
+                a_tok, a_mg = argmax_margin(lg)
+                v.append(a_tok)
+                v_margin.append(a_mg)
+                v_states.append(st)
+            a = 0
+            while a < K and drafts[a] == v[a]:
+                a += 1
+            out.extend(drafts[:a] + [v[a]])
+            n_verify += 1
+            rounds.append({"pos": pos, "mask": mask.copy(), "drafts": drafts, "verify": v, "accepted": a,
+                           "verify_margin": v_margin, "dp": dp})
+            if n_verify % dp_interval == 0:
+                dp = self.dp(v_states[a], pos + a, cache, M)
+                mask = dp["mask"]
+            pending = v[a]
+            pos += a + 1
+        return {"tokens": out[:n_gen], "rounds": rounds}
+
+
+def argmax_margin(logits: np.ndarray):
+    """(lowest index of the maximum, top-1 minus top-2 value)."""
+    i = int(np.argmax(logits))
+    rest = np.delete(logits, i)
+    return i, float(logits[i] - rest.max()) if rest.size else float("inf")
