@@ -1,0 +1,153 @@
+/*
+ * clasp.h -- C ABI of the MI355X (gfx950) CLaSp hot path: self-speculative decoding with an in-context
+ * layer-skip search (dynamic program over (layer, skip count)), the layer-skipped draft forward and the full
+ * verify forward that feeds it.
+ *
+ * General rules
+ *   - Plain C types only. "dev" pointers are device (HBM) addresses owned by the caller (e.g. PyTorch tensors);
+ *     "host" pointers are ordinary host memory. The library borrows every pointer for the duration of the call;
+ *     weights, workspace and KV caches are borrowed for the lifetime of the context.
+ *   - After clasp_create the library allocates no device memory: everything lives in the caller's workspace.
+ *   - Every call is asynchronous on the given HIP stream (a hipStream_t passed as void*, NULL = default
+ *     stream); the caller synchronises. Calls on one context must not overlap.
+ *   - Every function returns CLASP_OK (0) or a negative CLASP_E_* code; nothing aborts or throws.
+ *   - One GPU, the current HIP device at clasp_create time.
+ *
+ * Model: pre-norm LLaMA decoder (RMSNorm, q/k/v projections, rotary embedding with half-split pairing, grouped
+ * query attention over a KV cache, output projection, SwiGLU MLP, untied lm_head), the model family the paper
+ * evaluates (Experiments, "Model and Testbed"). h_{l+1} = f_l(h_l) as in Sec. 3.4.
+ *
+ * Data layouts
+ *   - dtype CLASP_BF16: matrices are bf16 in the packed tile order written by clasp_pack_matrix; activations,
+ *     residual stream, hidden states, scores and logits are fp32; MFMA inputs are rounded to bf16, accumulation
+ *     is fp32; the KV cache is bf16.
+ *   - dtype CLASP_F32: matrices are fp32 row-major [out_features][in_features] (clasp_pack_matrix is a copy);
+ *     everything is fp32.
+ *   - embed is always row-major [vocab][d_model] in the model dtype. RMSNorm gains are fp32 [d_model].
+ *   - KV cache, per K and per V: clasp_kv_cache_bytes() bytes. K is [layer][kv_head][max_seq][head_dim]
+ *     (keys stored after rotation), V is [layer][kv_head][head_dim][max_seq] (transposed), model dtype.
+ *     Validity is the caller's length counter: the library reads positions below the `pos` it is given and never
+ *     beyond. clasp_create zero-fills both caches.
+ */
+#ifndef CLASP_H
+#define CLASP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct clasp_ctx clasp_ctx;
+
+enum { CLASP_F32 = 0, CLASP_BF16 = 1 };
+
+enum {
+    CLASP_OK = 0,
+    CLASP_E_INVALID_ARG = -1, /* NULL required pointer, size or index out of range                     */
+    CLASP_E_UNSUPPORTED = -2, /* shape outside what the kernels are built for (see clasp_create)         */
+    CLASP_E_HIP = -3,         /* a HIP runtime call or kernel launch failed                              */
+    CLASP_E_WORKSPACE = -4    /* workspace smaller than clasp_workspace_bytes()                          */
+};
+
+typedef struct {
+    int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    int32_t max_seq;  /* KV cache capacity in tokens, multiple of 32                                      */
+    int32_t max_rows; /* most rows one launch carries (verify rows, or skip budget M), 1..32              */
+    int32_t dtype;    /* CLASP_F32 or CLASP_BF16                                                         */
+    float rms_eps, rope_base;
+} clasp_config;
+
+/* All pointers are dev pointers; the per-layer members are HOST arrays of n_layers dev pointers. */
+typedef struct {
+    const void *embed;      /* [vocab][d_model] row-major, model dtype                                    */
+    const void *lm_head;    /* [vocab][d_model], packed                                                   */
+    const float *final_norm;
+    const float *const *attn_norm; /* gains of the norm in front of attention                             */
+    const float *const *mlp_norm;  /* gains of the norm in front of the MLP                               */
+    const void *const *wq;     /* [n_heads*head_dim][d_model], packed                                     */
+    const void *const *wk;     /* [n_kv_heads*head_dim][d_model], packed                                  */
+    const void *const *wv;     /* [n_kv_heads*head_dim][d_model], packed                                  */
+    const void *const *wo;     /* [d_model][n_heads*head_dim], packed                                     */
+    const void *const *w_gate; /* [d_ffn][d_model], packed                                                */
+    const void *const *w_up;   /* [d_ffn][d_model], packed                                                */
+    const void *const *w_down; /* [d_model][d_ffn], packed                                                */
+} clasp_weights;
+
+/* Bytes of a packed [rows][cols] matrix (equals rows*cols*elem size; rows % 16 == 0 and, for bf16,
+ * cols % 32 == 0 are required, 0 is returned otherwise). */
+size_t clasp_packed_bytes(int rows, int cols, int dtype);
+
+/* Re-orders a row-major [rows][cols] dev matrix `src` into the library's streaming order in `dst` (dev, distinct
+ * from src, clasp_packed_bytes() bytes). bf16: tiles of 16 output features x 32 inputs, each tile stored so that
+ * one 64-lane wavefront reads it with a single coalesced 16-byte-per-lane load in MFMA operand order; tiles of
+ * one 16-feature group are contiguous along the input dimension. fp32: plain copy. */
+int clasp_pack_matrix(const void *src, void *dst, int rows, int cols, int dtype, void *stream);
+
+/* Device bytes clasp_create needs in `workspace` (256-byte aligned), and bytes of ONE of the two KV caches. */
+size_t clasp_workspace_bytes(const clasp_config *cfg);
+size_t clasp_kv_cache_bytes(const clasp_config *cfg);
+
+/* Builds a context. Requirements, else CLASP_E_UNSUPPORTED: n_heads % n_kv_heads == 0; d_model, d_ffn,
+ * n_heads*head_dim multiples of 32 (bf16) or 16 (fp32); vocab % 16 == 0; head_dim 64 or 128 (bf16), even (fp32);
+ * 1 <= max_rows <= 32; max_seq % 32 == 0. Zero-fills the KV caches and builds the rotary table (synchronous). */
+int clasp_create(const clasp_config *cfg, const clasp_weights *weights, void *workspace, size_t workspace_bytes,
+                 void *k_cache, void *v_cache, clasp_ctx **out);
+int clasp_destroy(clasp_ctx *ctx);
+
+/*
+ * Verification (Sec. 3.1 stage 2; Sec. 3.4: the verify pass's per-layer hidden states are the DP's objective):
+ * the full model over n_tokens rows at positions pos0..pos0+n_tokens-1, causal among themselves, attending cache
+ * positions 0..pos0-1. Writes the rows' keys/values into every layer's cache at their positions.
+ *   tokens      dev int32 [n_tokens]; ids outside [0, vocab) are clamped
+ *   n_tokens    1..max_rows;  pos0 >= 0, pos0 + n_tokens <= max_seq
+ *   hidden_out  dev fp32 [n_layers+1][n_tokens][d_model] or NULL: state l = input of layer l, state n_layers =
+ *               output of the last layer before the final norm
+ *   argmax_out  dev int32 [n_tokens] or NULL: greedy next token per row (lowest index on ties)
+ *   margin_out  dev fp32 [n_tokens] or NULL: top-1 minus top-2 logit
+ *   logits_out  dev fp32 [n_tokens][vocab] or NULL
+ * Plain greedy decoding of one token is this call with n_tokens = 1; prefill is this call in chunks.
+ */
+int clasp_verify_forward(clasp_ctx *ctx, const int32_t *tokens, int n_tokens, int pos0, float *hidden_out,
+                         int32_t *argmax_out, float *margin_out, float *logits_out, void *stream);
+
+/*
+ * Layer optimisation (Sec. 3.4, Eq. 2, Algorithm 1; batching of the candidates of one layer: Sec. 3.6).
+ * For the token at position `pos` with stored verify states x_0..x_L, runs the dynamic program
+ *   D(i,j) = max{ cos(x_i, g(i-1,j-1)), cos(x_i, f_{i-1}(g(i-1,j))) },  i = 1..L, j = 1..min(i, M)
+ * keeping the skip candidate on ties, and backtracks from (L, M) to the skip set. All candidates of one layer go
+ * through f_{i-1} in one batched pass that reads the layer's weights and the shared KV prefix once; each candidate
+ * attends cache positions 0..pos-1 plus its own key/value and no other candidate. Writes no KV.
+ *   states       dev fp32, state l at states + l*layer_stride (elements), l = 0..n_layers
+ *   M            skip budget, 0 <= M <= min(n_layers, max_rows)
+ *   mask_out     dev uint8 [n_layers]: 1 = layer skipped; exactly M ones
+ *   score_out    dev fp32 [(n_layers+1)][(M+1)][2] or NULL: (cosine of the computed candidate, cosine of the skip
+ *                candidate) per cell, NaN where a candidate does not exist
+ *   choice_out   dev uint8 [(n_layers+1)][(M+1)] or NULL: 0 computed kept, 1 skip kept, 255 no such cell
+ *   g_final_out  dev fp32 [d_model] or NULL: g(L, M)
+ */
+int clasp_dp_select(clasp_ctx *ctx, const float *states, size_t layer_stride, int pos, int M, uint8_t *mask_out,
+                    float *score_out, uint8_t *choice_out, float *g_final_out, void *stream);
+
+/*
+ * Drafting (Sec. 3.1 stage 1, Sec. 3.3): one token through the layers the skip set keeps, at position `pos`,
+ * attending cache positions 0..pos-1; writes the token's key/value at `pos` into the kept layers' caches only.
+ *   mask           host uint8 [n_layers], 1 = skip (NULL = keep all)
+ *   token          dev int32 [1]
+ *   next_token_out dev int32 [1]: greedy next token;  top1_prob_out dev fp32 [1] or NULL: its softmax probability
+ */
+int clasp_draft_step(clasp_ctx *ctx, const uint8_t *mask, const int32_t *token, int pos, int32_t *next_token_out,
+                     float *top1_prob_out, void *stream);
+
+/* Installs cache contents for one layer: K, V dev fp32 [n_tokens][n_kv_heads][head_dim] (keys already rotated) are
+ * converted to the cache dtype and layout at positions 0..n_tokens-1. For callers that hold a cache from elsewhere
+ * (and for tests that feed synthetic cache contents). */
+int clasp_kv_load(clasp_ctx *ctx, int layer, const float *K, const float *V, int n_tokens, void *stream);
+
+const char *clasp_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CLASP_H */

@@ -1,0 +1,234 @@
+"""ctypes binding of libclasp_hip.so (the C ABI of include/clasp.h). Argument marshalling only.
+
+PyTorch supplies device memory (tensors) and streams; every step of the hot path runs in the library's HIP kernels.
+There is no CPU or eager fallback: if the library is missing or no GPU is present the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libclasp_hip.so")
+
+CLASP_F32, CLASP_BF16 = 0, 1
+EXPORTS = ("clasp_strerror", "clasp_packed_bytes", "clasp_pack_matrix", "clasp_workspace_bytes",
+           "clasp_kv_cache_bytes", "clasp_create", "clasp_destroy", "clasp_verify_forward", "clasp_dp_select",
+           "clasp_draft_step", "clasp_kv_load")
+
+
+class ClaspError(RuntimeError):
+    pass
+
+
+class Config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32), ("max_seq", C.c_int32),
+                ("max_rows", C.c_int32), ("dtype", C.c_int32), ("rms_eps", C.c_float), ("rope_base", C.c_float)]
+
+
+class Weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p),
+                ("attn_norm", C.POINTER(C.c_void_p)), ("mlp_norm", C.POINTER(C.c_void_p)),
+                ("wq", C.POINTER(C.c_void_p)), ("wk", C.POINTER(C.c_void_p)), ("wv", C.POINTER(C.c_void_p)),
+                ("wo", C.POINTER(C.c_void_p)), ("w_gate", C.POINTER(C.c_void_p)), ("w_up", C.POINTER(C.c_void_p)),
+                ("w_down", C.POINTER(C.c_void_p))]
+
+
+_lib = None
+
+
+def lib():
+    """Loads the built library (build it first: python -m paper_2505_24196_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ClaspError(f"{LIB_PATH} is missing: build the HIP library first (python -m paper_2505_24196_amd.build)")
+        l = C.CDLL(LIB_PATH)
+        vp, i32, sz = C.c_void_p, C.c_int, C.c_size_t
+        l.clasp_strerror.restype = C.c_char_p
+        l.clasp_strerror.argtypes = [i32]
+        l.clasp_packed_bytes.restype = sz
+        l.clasp_packed_bytes.argtypes = [i32, i32, i32]
+        l.clasp_pack_matrix.argtypes = [vp, vp, i32, i32, i32, vp]
+        l.clasp_workspace_bytes.restype = sz
+        l.clasp_workspace_bytes.argtypes = [C.POINTER(Config)]
+        l.clasp_kv_cache_bytes.restype = sz
+        l.clasp_kv_cache_bytes.argtypes = [C.POINTER(Config)]
+        l.clasp_create.argtypes = [C.POINTER(Config), C.POINTER(Weights), vp, sz, vp, vp, C.POINTER(vp)]
+        l.clasp_destroy.argtypes = [vp]
+        l.clasp_verify_forward.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp]
+        l.clasp_dp_select.argtypes = [vp, vp, sz, i32, i32, vp, vp, vp, vp, vp]
+        l.clasp_draft_step.argtypes = [vp, vp, vp, i32, vp, vp, vp]
+        l.clasp_kv_load.argtypes = [vp, i32, vp, vp, i32, vp]
+        _lib = l
+    return _lib
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise ClaspError(f"{what}: {lib().clasp_strerror(rc).decode()} ({rc})")
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ClaspError("expected a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ClaspError(f"expected dtype {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dtype_code(dtype: str) -> int:
+    return CLASP_F32 if dtype == "f32" else CLASP_BF16
+
+
+def clasp_pack_matrix(src: torch.Tensor, dtype: str) -> torch.Tensor:
+    """Returns the packed copy of a row-major [rows][cols] device matrix (see clasp_pack_matrix in clasp.h)."""
+    rows, cols = src.shape
+    code = _dtype_code(dtype)
+    want = torch.float32 if code == CLASP_F32 else torch.bfloat16
+    if lib().clasp_packed_bytes(rows, cols, code) == 0:
+        raise ClaspError(f"matrix {rows}x{cols} cannot be packed for dtype {dtype}")
+    dst = torch.empty_like(src)
+    _check(lib().clasp_pack_matrix(_ptr(src, want), _ptr(dst), rows, cols, code, _stream()), "clasp_pack_matrix")
+    return dst
+
+
+_MATS = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+
+
+class Engine:
+    """Owns the device buffers of one model + KV cache and exposes the calls of clasp.h with the same names."""
+
+    def __init__(self, shape, max_seq: int, max_rows: int = 16, device: str = "cuda:0"):
+        if not torch.cuda.is_available():
+            raise ClaspError("no GPU: the CLaSp hot path has no CPU fallback")
+        self.shape = shape
+        self.device = torch.device(device)
+        self.cfg = Config(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
+                          shape.vocab, max_seq, max_rows, _dtype_code(shape.dtype), shape.rms_eps, shape.rope_base)
+        self.max_seq, self.max_rows = max_seq, max_rows
+        self._layers: List[Dict[str, torch.Tensor]] = [None] * shape.n_layers
+        self._head: Dict[str, torch.Tensor] = {}
+        self._ctx = None
+
+    # ---- weights ------------------------------------------------------------------------------------------------
+    def set_head(self, embed: torch.Tensor, lm_head: torch.Tensor, final_norm: torch.Tensor):
+        dev = self.device
+        self._head = {"embed": embed.to(dev).contiguous(), "lm_head": clasp_pack_matrix(lm_head.to(dev).contiguous(), self.shape.dtype),
+                      "final_norm": final_norm.to(dev, torch.float32).contiguous()}
+
+    def set_layer(self, l: int, w: Dict[str, torch.Tensor]):
+        """Packs one layer's row-major matrices (the row-major copies can be freed by the caller afterwards)."""
+        dev = self.device
+        out = {m: clasp_pack_matrix(w[m].to(dev).contiguous(), self.shape.dtype) for m in _MATS}
+        out["attn_norm"] = w["attn_norm"].to(dev, torch.float32).contiguous()
+        out["mlp_norm"] = w["mlp_norm"].to(dev, torch.float32).contiguous()
+        self._layers[l] = out
+
+    def load(self, model: Dict[str, object]):
+        self.set_head(model["embed"], model["lm_head"], model["final_norm"])
+        for l, w in enumerate(model["layers"]):
+            self.set_layer(l, w)
+        return self.create()
+
+    def create(self):
+        if self._ctx is not None:
+            return self
+        if not self._head or any(w is None for w in self._layers):
+            raise ClaspError("weights incomplete")
+        L = self.shape.n_layers
+        self._arrays = {}
+        wts = Weights(self._head["embed"].data_ptr(), self._head["lm_head"].data_ptr(), self._head["final_norm"].data_ptr())
+        for name in ("attn_norm", "mlp_norm") + _MATS:
+            arr = (C.c_void_p * L)(*[self._layers[l][name].data_ptr() for l in range(L)])
+            self._arrays[name] = arr
+            setattr(wts, name, C.cast(arr, C.POINTER(C.c_void_p)))
+        ws_bytes = lib().clasp_workspace_bytes(C.byref(self.cfg))
+        kv_bytes = lib().clasp_kv_cache_bytes(C.byref(self.cfg))
+        if ws_bytes == 0 or kv_bytes == 0:
+            raise ClaspError("configuration not supported by the kernels")
+        self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=self.device)
+        self.k_cache = torch.empty(kv_bytes, dtype=torch.uint8, device=self.device)
+        self.v_cache = torch.empty(kv_bytes, dtype=torch.uint8, device=self.device)
+        ctx = C.c_void_p()
+        torch.cuda.synchronize()
+        _check(lib().clasp_create(C.byref(self.cfg), C.byref(wts), self.workspace.data_ptr(), ws_bytes,
+                                  self.k_cache.data_ptr(), self.v_cache.data_ptr(), C.byref(ctx)), "clasp_create")
+        self._ctx = ctx
+        return self
+
+    def close(self):
+        if self._ctx is not None:
+            torch.cuda.synchronize()
+            lib().clasp_destroy(self._ctx)
+            self._ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- the calls of clasp.h -------------------------------------------------------------------------------------
+    def clasp_kv_load(self, layer: int, K: torch.Tensor, V: torch.Tensor):
+        """K, V: fp32 [T][n_kv_heads][head_dim] (keys already rotated) -> cache positions 0..T-1 of `layer`."""
+        K = K.to(self.device, torch.float32).contiguous()
+        V = V.to(self.device, torch.float32).contiguous()
+        _check(lib().clasp_kv_load(self._ctx, layer, _ptr(K), _ptr(V), K.shape[0], _stream()), "clasp_kv_load")
+
+    def clasp_verify_forward(self, tokens: torch.Tensor, pos0: int, want_hidden: bool = False, want_logits: bool = False,
+                             want_margin: bool = False):
+        """tokens: device int32 [n]. Returns dict(argmax, hidden?, logits?, margin?) of device tensors."""
+        n = tokens.numel()
+        s = self.shape
+        out = {"argmax": torch.empty(n, dtype=torch.int32, device=self.device)}
+        if want_hidden:
+            out["hidden"] = torch.empty(s.n_layers + 1, n, s.d_model, dtype=torch.float32, device=self.device)
+        if want_logits:
+            out["logits"] = torch.empty(n, s.vocab, dtype=torch.float32, device=self.device)
+        if want_margin:
+            out["margin"] = torch.empty(n, dtype=torch.float32, device=self.device)
+        _check(lib().clasp_verify_forward(self._ctx, _ptr(tokens, torch.int32), n, pos0, _ptr(out.get("hidden")),
+                                          _ptr(out["argmax"]), _ptr(out.get("margin")), _ptr(out.get("logits")),
+                                          _stream()), "clasp_verify_forward")
+        return out
+
+    def clasp_dp_select(self, states: torch.Tensor, pos: int, M: int, want_tables: bool = False,
+                        out: Optional[Dict[str, torch.Tensor]] = None):
+        """states: device fp32 [L+1][d] (may be a strided view along dim 0). Returns dict(mask, scores?, choice?,
+        g_final?) of device tensors; `out` lets the caller reuse the output tensors of an earlier call."""
+        s = self.shape
+        L = s.n_layers
+        if states.dtype != torch.float32 or not states.is_cuda or states.stride(1) != 1 or states.shape != (L + 1, s.d_model):
+            raise ClaspError("states must be device fp32 [L+1][d] with unit inner stride")
+        if out is None:
+            out = {"mask": torch.empty(L, dtype=torch.uint8, device=self.device)}
+            if want_tables:
+                out["scores"] = torch.empty(L + 1, M + 1, 2, dtype=torch.float32, device=self.device)
+                out["choice"] = torch.empty(L + 1, M + 1, dtype=torch.uint8, device=self.device)
+                out["g_final"] = torch.empty(s.d_model, dtype=torch.float32, device=self.device)
+        _check(lib().clasp_dp_select(self._ctx, states.data_ptr(), states.stride(0), pos, M, _ptr(out["mask"]),
+                                     _ptr(out.get("scores")), _ptr(out.get("choice")), _ptr(out.get("g_final")),
+                                     _stream()), "clasp_dp_select")
+        return out
+
+    def clasp_draft_step(self, mask: Optional[Sequence[int]], token: torch.Tensor, pos: int,
+                         next_token_out: torch.Tensor, top1_prob_out: Optional[torch.Tensor] = None):
+        """mask: host sequence of L 0/1 (1 = skip) or None; token / next_token_out: device int32 [1] (views ok)."""
+        mp = None
+        if mask is not None:
+            mb = (C.c_uint8 * self.shape.n_layers)(*[int(x) for x in mask])
+            mp = C.cast(mb, C.c_void_p)
+        _check(lib().clasp_draft_step(self._ctx, mp, token.data_ptr(), pos, next_token_out.data_ptr(),
+                                      None if top1_prob_out is None else top1_prob_out.data_ptr(), _stream()),
+               "clasp_draft_step")

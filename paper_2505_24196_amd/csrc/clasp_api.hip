@@ -1,0 +1,472 @@
+// Host side of the C ABI declared in include/clasp.h: argument checks, workspace carving and the kernel sequences
+// of the three calls of the hot path (verify forward, DP layer selection, draft step). Everything is enqueued on the
+// caller's stream; no call synchronises or allocates device memory.
+#include "../../include/clasp.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <new>
+#include <vector>
+
+#include "clasp_attn.h"
+#include "clasp_common.h"
+#include "clasp_gemm.h"
+#include "clasp_misc.h"
+
+using namespace clasp;
+
+namespace {
+
+constexpr int kGemmWaves = 8;   // wavefronts per GEMM workgroup (they split K)
+constexpr int kGemmDepth = 4;   // fragments per register stage (two stages in flight)
+constexpr int kAttnWaves = 4;
+constexpr int kMaxSplit = 64;   // most workgroups that share one KV head's prefix
+constexpr int kBlocksPerSplit = 16;  // 32-key blocks per workgroup before the prefix is split further
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Carver {
+    char* base;
+    size_t off = 0;
+    template <class T>
+    T* take(size_t bytes) {
+        T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+        off += align256(bytes);
+        return p;
+    }
+};
+
+}  // namespace
+
+struct clasp_ctx {
+    clasp_config cfg;
+    int qkv_dim, q_dim, kv_dim, group;
+    size_t esz;  // bytes of a weight / cache element
+    const void *embed, *lm_head;
+    const float* final_norm;
+    std::vector<const float*> attn_norm, mlp_norm;
+    std::vector<const void*> wq, wk, wv, wo, w_gate, w_up, w_down;
+    char *k_cache, *v_cache;
+    size_t kv_layer_bytes;
+    // workspace
+    float2* rope;
+    float* qkv;
+    void *op_h, *op_attn, *op_a, *op_act;
+    float *ss_h, *ss_a;
+    float *a_buf, *h[2], *g[2], *G;
+    float* logits;
+    float* attn_partial;
+    uint8_t* choice;
+    int32_t* tok_tmp;
+};
+
+namespace {
+
+size_t carve(const clasp_config& c, char* base, clasp_ctx* ctx) {
+    Carver w{base};
+    const size_t d = c.d_model, qd = (size_t)c.n_heads * c.head_dim, kvd = (size_t)c.n_kv_heads * c.head_dim;
+    const size_t qkvd = qd + 2 * kvd, rows = kMaxRows;
+    auto* rope = w.take<float2>((size_t)c.max_seq * (c.head_dim / 2) * sizeof(float2));
+    auto* qkv = w.take<float>(rows * qkvd * 4);
+    auto* op_h = w.take<void>(rows * d * 4);
+    auto* op_attn = w.take<void>(rows * qd * 4);
+    auto* op_a = w.take<void>(rows * d * 4);
+    auto* op_act = w.take<void>(rows * (size_t)c.d_ffn * 4);
+    auto* ss_h = w.take<float>((d / 16) * rows * 4);
+    auto* ss_a = w.take<float>((d / 16) * rows * 4);
+    auto* a_buf = w.take<float>(rows * d * 4);
+    auto* h0 = w.take<float>(rows * d * 4);
+    auto* h1 = w.take<float>(rows * d * 4);
+    auto* g0 = w.take<float>((rows + 1) * d * 4);
+    auto* g1 = w.take<float>((rows + 1) * d * 4);
+    auto* G = w.take<float>(rows * d * 4);
+    auto* logits = w.take<float>(rows * (size_t)c.vocab * 4);
+    const size_t nq_pad = rows * (c.n_heads / c.n_kv_heads);
+    auto* part = w.take<float>((size_t)c.n_kv_heads * kMaxSplit * nq_pad * (c.head_dim + 2) * 4);
+    auto* choice = w.take<uint8_t>((size_t)(c.n_layers + 1) * (rows + 1));
+    auto* tok = w.take<int32_t>(256);
+    if (ctx) {
+        ctx->rope = rope; ctx->qkv = qkv; ctx->op_h = op_h; ctx->op_attn = op_attn; ctx->op_a = op_a;
+        ctx->op_act = op_act; ctx->ss_h = ss_h; ctx->ss_a = ss_a; ctx->a_buf = a_buf; ctx->h[0] = h0; ctx->h[1] = h1;
+        ctx->g[0] = g0; ctx->g[1] = g1; ctx->G = G; ctx->logits = logits; ctx->attn_partial = part;
+        ctx->choice = choice; ctx->tok_tmp = tok;
+    }
+    return w.off;
+}
+
+int check_config(const clasp_config* c) {
+    if (!c) return CLASP_E_INVALID_ARG;
+    if (c->n_layers < 1 || c->d_model < 1 || c->n_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 2 || c->d_ffn < 1 ||
+        c->vocab < 1 || c->max_seq < 1 || c->max_rows < 1)
+        return CLASP_E_INVALID_ARG;
+    if (c->dtype != CLASP_F32 && c->dtype != CLASP_BF16) return CLASP_E_INVALID_ARG;
+    if (c->max_rows > kMaxRows || c->max_seq % 32 || c->n_heads % c->n_kv_heads || c->vocab % 16)
+        return CLASP_E_UNSUPPORTED;
+    const int qd = c->n_heads * c->head_dim, kvd = c->n_kv_heads * c->head_dim;
+    if (c->dtype == CLASP_BF16) {
+        if (c->d_model % 32 || c->d_ffn % 32 || qd % 32 || kvd % 16) return CLASP_E_UNSUPPORTED;
+        if (c->head_dim != 64 && c->head_dim != 128) return CLASP_E_UNSUPPORTED;
+        if (c->n_heads / c->n_kv_heads > 16) return CLASP_E_UNSUPPORTED;
+    } else {
+        if (c->d_model % 16 || c->d_ffn % 16 || qd % 16 || kvd % 16 || c->head_dim % 2) return CLASP_E_UNSUPPORTED;
+        if (c->max_seq > 8192 || c->head_dim > 256) return CLASP_E_UNSUPPORTED;  // attention keeps all scores in LDS
+    }
+    return CLASP_OK;
+}
+
+#define CLASP_LAUNCH_CHECK()                                 \
+    do {                                                     \
+        if (hipGetLastError() != hipSuccess) return CLASP_E_HIP; \
+    } while (0)
+
+// ---- GEMM dispatch ---------------------------------------------------------------------------------------------
+template <int EPI>
+int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st) {
+    const int tiles = g.N / 16;
+    if (ctx->cfg.dtype == CLASP_BF16) {
+        if (g.R == 1)
+            hipLaunchKernelGGL((gemm_bf16_kernel<1, kGemmWaves, EPI, kGemmDepth>), dim3(tiles), dim3(kGemmWaves * 64), 0, st, g);
+        else
+            hipLaunchKernelGGL((gemm_bf16_kernel<2, kGemmWaves, EPI, kGemmDepth>), dim3(tiles), dim3(kGemmWaves * 64), 0, st, g);
+    } else {
+        hipLaunchKernelGGL((gemm_f32_kernel<EPI>), dim3(tiles), dim3(256), 0, st, g);
+    }
+    CLASP_LAUNCH_CHECK();
+    return CLASP_OK;
+}
+
+template <int HD>
+int launch_attn_bf16(const AttnArgs& a, int nt, dim3 grid, hipStream_t st) {
+    switch (nt) {
+        case 1: hipLaunchKernelGGL((attn_bf16_kernel<HD, 1, kAttnWaves>), grid, dim3(kAttnWaves * 64), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((attn_bf16_kernel<HD, 2, kAttnWaves>), grid, dim3(kAttnWaves * 64), 0, st, a); break;
+        case 3: hipLaunchKernelGGL((attn_bf16_kernel<HD, 3, kAttnWaves>), grid, dim3(kAttnWaves * 64), 0, st, a); break;
+        default: hipLaunchKernelGGL((attn_bf16_kernel<HD, 4, kAttnWaves>), grid, dim3(kAttnWaves * 64), 0, st, a); break;
+    }
+    CLASP_LAUNCH_CHECK();
+    return CLASP_OK;
+}
+
+int launch_attention(const clasp_ctx* ctx, int layer, int n, int R, int mode, int pos0, hipStream_t st) {
+    const clasp_config& c = ctx->cfg;
+    AttnArgs a{};
+    a.qkv = ctx->qkv; a.ld_qkv = ctx->qkv_dim;
+    a.n_rows = n; a.n_heads = c.n_heads; a.n_kv_heads = c.n_kv_heads; a.head_dim = c.head_dim;
+    a.pos0 = pos0; a.mode = mode; a.rope = ctx->rope;
+    a.Kc = ctx->k_cache + (size_t)layer * ctx->kv_layer_bytes;
+    a.Vt = ctx->v_cache + (size_t)layer * ctx->kv_layer_bytes;
+    a.t_max = c.max_seq; a.out_op = ctx->op_attn; a.R = R;
+    a.partial = ctx->attn_partial; a.nq_pad = kMaxRows * ctx->group;
+    a.scale = 1.0f / sqrtf((float)c.head_dim);
+    a.n_split = 1;
+    if (c.dtype == CLASP_F32) {
+        const size_t lds = (size_t)(c.head_dim + pos0 + 32) * sizeof(float);
+        hipLaunchKernelGGL(attn_f32_kernel, dim3(c.n_heads, n), dim3(256), lds, st, a);
+        CLASP_LAUNCH_CHECK();
+        return CLASP_OK;
+    }
+    const int nQ = n * ctx->group, ntq = (nQ + 15) / 16;
+    const int nt = ntq < 4 ? ntq : 4, qgroups = (ntq + nt - 1) / nt;
+    const int nblk = (pos0 + 31) / 32;
+    int split = (nblk + kBlocksPerSplit - 1) / kBlocksPerSplit;
+    split = split < 1 ? 1 : (split > kMaxSplit ? kMaxSplit : split);
+    a.n_split = split;
+    const dim3 grid(c.n_kv_heads, qgroups, split);
+    const int rc = c.head_dim == 64 ? launch_attn_bf16<64>(a, nt, grid, st) : launch_attn_bf16<128>(a, nt, grid, st);
+    if (rc) return rc;
+    if (split > 1) {
+        hipLaunchKernelGGL((attn_combine_kernel<kDtBf16>), dim3(c.n_kv_heads, nQ), dim3(c.head_dim), 0, st, a);
+        CLASP_LAUNCH_CHECK();
+    }
+    return CLASP_OK;
+}
+
+// One decoder layer on n rows. The rows' fp32 values are at h_in ([n][d]); their GEMM operand (times the layer's
+// attention-norm gains) and sums of squares must already sit in op_h / ss_h. Writes h_out ([n][d]) and, if asked,
+// the operand / sums of squares of h_out for whatever consumes it next, and a copy for hidden-state capture.
+int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, const float* h_in, float* h_out,
+              void* next_op, const float* next_gain, float* next_ss, float* capture, hipStream_t st) {
+    const clasp_config& c = ctx->cfg;
+    const int d = c.d_model, F = c.d_ffn;
+    int rc;
+    {
+        GemmArgs g{};
+        g.W[0] = ctx->wq[l]; g.W[1] = ctx->wk[l]; g.W[2] = ctx->wv[l];
+        g.tile_end[0] = ctx->q_dim / 16; g.tile_end[1] = (ctx->q_dim + ctx->kv_dim) / 16; g.tile_end[2] = ctx->qkv_dim / 16;
+        g.A = ctx->op_h; g.n_rows = n; g.N = ctx->qkv_dim; g.K = d; g.R = R;
+        g.ss_parts = ctx->ss_h; g.n_parts = d / 16; g.inv_dim = 1.0f / d; g.eps = c.rms_eps;
+        g.out = ctx->qkv; g.ldo = ctx->qkv_dim;
+        if ((rc = launch_gemm<kEpiScale>(ctx, g, st))) return rc;
+    }
+    if ((rc = launch_attention(ctx, l, n, R, mode, pos0, st))) return rc;
+    {
+        GemmArgs g{};
+        g.W[0] = ctx->wo[l]; g.tile_end[0] = g.tile_end[1] = g.tile_end[2] = d / 16;
+        g.A = ctx->op_attn; g.n_rows = n; g.N = d; g.K = ctx->q_dim; g.R = R;
+        g.out = ctx->a_buf; g.ldo = d; g.resid = h_in; g.ldr = d;
+        g.next_op = ctx->op_a; g.next_gain = ctx->mlp_norm[l]; g.next_ss = ctx->ss_a;
+        if ((rc = launch_gemm<kEpiResid>(ctx, g, st))) return rc;
+    }
+    {
+        GemmArgs g{};
+        g.W[0] = ctx->w_gate[l]; g.W[1] = ctx->w_up[l]; g.tile_end[0] = g.tile_end[1] = g.tile_end[2] = F / 16;
+        g.A = ctx->op_a; g.n_rows = n; g.N = F; g.K = d; g.R = R;
+        g.ss_parts = ctx->ss_a; g.n_parts = d / 16; g.inv_dim = 1.0f / d; g.eps = c.rms_eps;
+        g.next_op = ctx->op_act;
+        if ((rc = launch_gemm<kEpiSwiglu>(ctx, g, st))) return rc;
+    }
+    {
+        GemmArgs g{};
+        g.W[0] = ctx->w_down[l]; g.tile_end[0] = g.tile_end[1] = g.tile_end[2] = d / 16;
+        g.A = ctx->op_act; g.n_rows = n; g.N = d; g.K = F; g.R = R;
+        g.out = h_out; g.ldo = d; g.resid = ctx->a_buf; g.ldr = d;
+        g.next_op = next_op; g.next_gain = next_gain; g.next_ss = next_ss;
+        g.capture = capture; g.ldc = d;
+        if ((rc = launch_gemm<kEpiResid>(ctx, g, st))) return rc;
+    }
+    return CLASP_OK;
+}
+
+int launch_embed(const clasp_ctx* ctx, const int32_t* tokens, int n, int R, float* h, const float* gain,
+                 float* capture, hipStream_t st) {
+    const clasp_config& c = ctx->cfg;
+    if (c.dtype == CLASP_BF16)
+        hipLaunchKernelGGL((embed_kernel<kDtBf16>), dim3(n), dim3(256), 0, st, tokens, ctx->embed, c.vocab, c.d_model, h,
+                           ctx->op_h, R, gain, ctx->ss_h, capture);
+    else
+        hipLaunchKernelGGL((embed_kernel<kDtF32>), dim3(n), dim3(256), 0, st, tokens, ctx->embed, c.vocab, c.d_model, h,
+                           ctx->op_h, R, gain, ctx->ss_h, capture);
+    CLASP_LAUNCH_CHECK();
+    return CLASP_OK;
+}
+
+// final norm (already folded into op_h / ss_h by the last layer's epilogue) -> lm_head -> greedy head
+int run_head(const clasp_ctx* ctx, int n, int R, float* logits, int32_t* argmax_out, float* margin_out,
+             float* prob_out, hipStream_t st) {
+    const clasp_config& c = ctx->cfg;
+    GemmArgs g{};
+    g.W[0] = ctx->lm_head; g.tile_end[0] = g.tile_end[1] = g.tile_end[2] = c.vocab / 16;
+    g.A = ctx->op_h; g.n_rows = n; g.N = c.vocab; g.K = c.d_model; g.R = R;
+    g.ss_parts = ctx->ss_h; g.n_parts = c.d_model / 16; g.inv_dim = 1.0f / c.d_model; g.eps = c.rms_eps;
+    g.out = logits; g.ldo = c.vocab;
+    int rc;
+    if ((rc = launch_gemm<kEpiScale>(ctx, g, st))) return rc;
+    if (argmax_out || margin_out || prob_out) {
+        hipLaunchKernelGGL(argmax_kernel, dim3(n), dim3(1024), 0, st, logits, c.vocab, argmax_out, margin_out, prob_out);
+        CLASP_LAUNCH_CHECK();
+    }
+    return CLASP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* clasp_strerror(int code) {
+    switch (code) {
+        case CLASP_OK: return "ok";
+        case CLASP_E_INVALID_ARG: return "invalid argument";
+        case CLASP_E_UNSUPPORTED: return "unsupported shape";
+        case CLASP_E_HIP: return "HIP runtime error";
+        case CLASP_E_WORKSPACE: return "workspace too small";
+        default: return "unknown error";
+    }
+}
+
+size_t clasp_packed_bytes(int rows, int cols, int dtype) {
+    if (rows <= 0 || cols <= 0 || rows % 16) return 0;
+    if (dtype == CLASP_BF16) return (cols % 32) ? 0 : (size_t)rows * cols * 2;
+    if (dtype == CLASP_F32) return (size_t)rows * cols * 4;
+    return 0;
+}
+
+int clasp_pack_matrix(const void* src, void* dst, int rows, int cols, int dtype, void* stream) {
+    if (!src || !dst || src == dst) return CLASP_E_INVALID_ARG;
+    const size_t bytes = clasp_packed_bytes(rows, cols, dtype);
+    if (!bytes) return CLASP_E_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dtype == CLASP_F32) {
+        if (hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, st) != hipSuccess) return CLASP_E_HIP;
+        return CLASP_OK;
+    }
+    hipLaunchKernelGGL(pack_bf16_kernel, dim3(2048), dim3(256), 0, st, reinterpret_cast<const u32x4*>(src),
+                       reinterpret_cast<u32x4*>(dst), rows, cols);
+    CLASP_LAUNCH_CHECK();
+    return CLASP_OK;
+}
+
+size_t clasp_workspace_bytes(const clasp_config* cfg) {
+    if (check_config(cfg) != CLASP_OK) return 0;
+    return carve(*cfg, nullptr, nullptr);
+}
+
+size_t clasp_kv_cache_bytes(const clasp_config* cfg) {
+    if (check_config(cfg) != CLASP_OK) return 0;
+    return (size_t)cfg->n_layers * cfg->n_kv_heads * cfg->max_seq * cfg->head_dim * (cfg->dtype == CLASP_BF16 ? 2 : 4);
+}
+
+int clasp_create(const clasp_config* cfg, const clasp_weights* w, void* workspace, size_t workspace_bytes,
+                 void* k_cache, void* v_cache, clasp_ctx** out) {
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (!w || !workspace || !k_cache || !v_cache || !out) return CLASP_E_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255) || (reinterpret_cast<uintptr_t>(k_cache) & 15) ||
+        (reinterpret_cast<uintptr_t>(v_cache) & 15))
+        return CLASP_E_INVALID_ARG;
+    if (workspace_bytes < carve(*cfg, nullptr, nullptr)) return CLASP_E_WORKSPACE;
+    if (!w->embed || !w->lm_head || !w->final_norm || !w->attn_norm || !w->mlp_norm || !w->wq || !w->wk || !w->wv ||
+        !w->wo || !w->w_gate || !w->w_up || !w->w_down)
+        return CLASP_E_INVALID_ARG;
+    for (int l = 0; l < cfg->n_layers; ++l)
+        if (!w->attn_norm[l] || !w->mlp_norm[l] || !w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->w_gate[l] ||
+            !w->w_up[l] || !w->w_down[l])
+            return CLASP_E_INVALID_ARG;
+    clasp_ctx* ctx = new (std::nothrow) clasp_ctx();
+    if (!ctx) return CLASP_E_INVALID_ARG;
+    ctx->cfg = *cfg;
+    ctx->q_dim = cfg->n_heads * cfg->head_dim;
+    ctx->kv_dim = cfg->n_kv_heads * cfg->head_dim;
+    ctx->qkv_dim = ctx->q_dim + 2 * ctx->kv_dim;
+    ctx->group = cfg->n_heads / cfg->n_kv_heads;
+    ctx->esz = cfg->dtype == CLASP_BF16 ? 2 : 4;
+    ctx->embed = w->embed; ctx->lm_head = w->lm_head; ctx->final_norm = w->final_norm;
+    const int L = cfg->n_layers;
+    ctx->attn_norm.assign(w->attn_norm, w->attn_norm + L);
+    ctx->mlp_norm.assign(w->mlp_norm, w->mlp_norm + L);
+    ctx->wq.assign(w->wq, w->wq + L); ctx->wk.assign(w->wk, w->wk + L); ctx->wv.assign(w->wv, w->wv + L);
+    ctx->wo.assign(w->wo, w->wo + L); ctx->w_gate.assign(w->w_gate, w->w_gate + L);
+    ctx->w_up.assign(w->w_up, w->w_up + L); ctx->w_down.assign(w->w_down, w->w_down + L);
+    ctx->k_cache = static_cast<char*>(k_cache);
+    ctx->v_cache = static_cast<char*>(v_cache);
+    ctx->kv_layer_bytes = (size_t)cfg->n_kv_heads * cfg->max_seq * cfg->head_dim * ctx->esz;
+    carve(*cfg, static_cast<char*>(workspace), ctx);
+
+    const size_t kvb = clasp_kv_cache_bytes(cfg);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(2048), dim3(256), 0, 0, reinterpret_cast<u32x4*>(k_cache), kvb / 16);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(2048), dim3(256), 0, 0, reinterpret_cast<u32x4*>(v_cache), kvb / 16);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(256), dim3(256), 0, 0, reinterpret_cast<u32x4*>(workspace),
+                       carve(*cfg, nullptr, nullptr) / 16);
+    hipLaunchKernelGGL(rope_table_kernel, dim3(1024), dim3(256), 0, 0, ctx->rope, cfg->max_seq, cfg->head_dim / 2,
+                       (double)cfg->rope_base);
+    if (hipGetLastError() != hipSuccess || hipStreamSynchronize(0) != hipSuccess) {
+        delete ctx;
+        return CLASP_E_HIP;
+    }
+    *out = ctx;
+    return CLASP_OK;
+}
+
+int clasp_destroy(clasp_ctx* ctx) {
+    if (!ctx) return CLASP_E_INVALID_ARG;
+    delete ctx;
+    return CLASP_OK;
+}
+
+int clasp_kv_load(clasp_ctx* ctx, int layer, const float* K, const float* V, int n_tokens, void* stream) {
+    if (!ctx || !K || !V) return CLASP_E_INVALID_ARG;
+    const clasp_config& c = ctx->cfg;
+    if (layer < 0 || layer >= c.n_layers || n_tokens < 0 || n_tokens > c.max_seq) return CLASP_E_INVALID_ARG;
+    if (n_tokens == 0) return CLASP_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    void* Kc = ctx->k_cache + (size_t)layer * ctx->kv_layer_bytes;
+    void* Vt = ctx->v_cache + (size_t)layer * ctx->kv_layer_bytes;
+    if (c.dtype == CLASP_BF16)
+        hipLaunchKernelGGL((kv_load_kernel<kDtBf16>), dim3(1024), dim3(256), 0, st, K, V, Kc, Vt, n_tokens, c.n_kv_heads,
+                           c.head_dim, c.max_seq);
+    else
+        hipLaunchKernelGGL((kv_load_kernel<kDtF32>), dim3(1024), dim3(256), 0, st, K, V, Kc, Vt, n_tokens, c.n_kv_heads,
+                           c.head_dim, c.max_seq);
+    CLASP_LAUNCH_CHECK();
+    return CLASP_OK;
+}
+
+int clasp_verify_forward(clasp_ctx* ctx, const int32_t* tokens, int n_tokens, int pos0, float* hidden_out,
+                         int32_t* argmax_out, float* margin_out, float* logits_out, void* stream) {
+    if (!ctx || !tokens) return CLASP_E_INVALID_ARG;
+    const clasp_config& c = ctx->cfg;
+    if (n_tokens < 1 || n_tokens > c.max_rows || pos0 < 0 || (long long)pos0 + n_tokens > c.max_seq)
+        return CLASP_E_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int n = n_tokens, R = (n + 15) / 16, L = c.n_layers, d = c.d_model;
+    const size_t cap_stride = (size_t)n * d;
+    int rc;
+    if ((rc = launch_embed(ctx, tokens, n, R, ctx->h[0], ctx->attn_norm[0], hidden_out, st))) return rc;
+    for (int l = 0; l < L; ++l) {
+        const float* gain = (l + 1 < L) ? ctx->attn_norm[l + 1] : ctx->final_norm;
+        float* cap = hidden_out ? hidden_out + (size_t)(l + 1) * cap_stride : nullptr;
+        if ((rc = run_layer(ctx, l, n, R, 1, pos0, ctx->h[l & 1], ctx->h[(l + 1) & 1], ctx->op_h, gain, ctx->ss_h, cap, st)))
+            return rc;
+    }
+    if (argmax_out || margin_out || logits_out)
+        return run_head(ctx, n, R, logits_out ? logits_out : ctx->logits, argmax_out, margin_out, nullptr, st);
+    return CLASP_OK;
+}
+
+int clasp_draft_step(clasp_ctx* ctx, const uint8_t* mask, const int32_t* token, int pos, int32_t* next_token_out,
+                     float* top1_prob_out, void* stream) {
+    if (!ctx || !token || !next_token_out) return CLASP_E_INVALID_ARG;
+    const clasp_config& c = ctx->cfg;
+    if (pos < 0 || pos >= c.max_seq) return CLASP_E_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int L = c.n_layers;
+    std::vector<int> kept;
+    for (int l = 0; l < L; ++l)
+        if (!mask || !mask[l]) kept.push_back(l);
+    int rc;
+    const float* gain0 = kept.empty() ? ctx->final_norm : ctx->attn_norm[kept[0]];
+    if ((rc = launch_embed(ctx, token, 1, 1, ctx->h[0], gain0, nullptr, st))) return rc;
+    for (size_t k = 0; k < kept.size(); ++k) {
+        const float* gain = (k + 1 < kept.size()) ? ctx->attn_norm[kept[k + 1]] : ctx->final_norm;
+        if ((rc = run_layer(ctx, kept[k], 1, 1, 1, pos, ctx->h[k & 1], ctx->h[(k + 1) & 1], ctx->op_h, gain, ctx->ss_h,
+                            nullptr, st)))
+            return rc;
+    }
+    return run_head(ctx, 1, 1, ctx->logits, next_token_out, nullptr, top1_prob_out, st);
+}
+
+int clasp_dp_select(clasp_ctx* ctx, const float* states, size_t layer_stride, int pos, int M, uint8_t* mask_out,
+                    float* score_out, uint8_t* choice_out, float* g_final_out, void* stream) {
+    if (!ctx || !states || !mask_out) return CLASP_E_INVALID_ARG;
+    const clasp_config& c = ctx->cfg;
+    const int L = c.n_layers, d = c.d_model;
+    if (M < 0 || M > L || M > c.max_rows || pos < 0 || pos > c.max_seq || layer_stride < (size_t)d)
+        return CLASP_E_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int R = M > 16 ? 2 : 1;
+    uint8_t* choice = choice_out ? choice_out : ctx->choice;
+    const int cells = (L + 1) * (M + 1);
+    hipLaunchKernelGGL(dp_table_init_kernel, dim3((cells + 255) / 256), dim3(256), 0, st, score_out, choice, cells);
+    CLASP_LAUNCH_CHECK();
+    int rc;
+    for (int i = 1; i <= L; ++i) {
+        const int ell = (i - 1 < M) ? i - 1 : M;
+        const float* g_prev = (i == 1) ? states : ctx->g[(i - 1) & 1];
+        float* g_cur = ctx->g[i & 1];
+        if (ell > 0) {  // candidates g(i-1, 1..ell) through layer i-1, all at position `pos`
+            if ((rc = run_layer(ctx, i - 1, ell, R, 0, pos, g_prev + d, ctx->G, nullptr, nullptr, nullptr, nullptr, st)))
+                return rc;
+        }
+        SelectArgs s{};
+        s.i = i; s.M = M; s.d = d; s.R = R;
+        s.x_i = states + (size_t)i * layer_stride;
+        s.g_prev = g_prev; s.G = ctx->G; s.g_cur = g_cur;
+        s.op = (i < L) ? ctx->op_h : nullptr;
+        s.gain = (i < L) ? ctx->attn_norm[i] : nullptr;
+        s.ss = ctx->ss_h;
+        s.scores = score_out; s.choice = choice;
+        const int cells_i = ((i < M) ? i : M) + 1;
+        if (c.dtype == CLASP_BF16)
+            hipLaunchKernelGGL((dp_select_kernel<kDtBf16>), dim3(cells_i), dim3(256), 0, st, s);
+        else
+            hipLaunchKernelGGL((dp_select_kernel<kDtF32>), dim3(cells_i), dim3(256), 0, st, s);
+        CLASP_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(dp_backtrack_kernel, dim3(2), dim3(256), 0, st, choice, L, M, mask_out, ctx->g[L & 1],
+                       g_final_out, d);
+    CLASP_LAUNCH_CHECK();
+    return CLASP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,367 @@
+// Grouped-query attention of the candidate / verify / draft rows over the layer's shared KV cache.
+//
+// All rows of a launch read the cached prefix (positions 0..pos0-1) ONCE: the rows times the query heads of one KV
+// group form the N dimension of S^T = K . Q^T, so a key fragment loaded from HBM serves every row (this is the
+// paper's Sec. 3.6 point: the DP's candidate states share one KV cache instead of duplicating it). The rows' own
+// keys/values form a small "self block" with a mode-dependent mask:
+//   mode 0 (DP candidates): every row sits at position pos0 and sees, besides the prefix, only its own key/value;
+//                           nothing is written to the cache.
+//   mode 1 (verify / draft): row r sits at pos0 + r, sees self rows 0..r (causal) and its key/value is written to
+//                           the cache at pos0 + r.
+// The rotary embedding is applied here (queries while staging them, keys before they are cached).
+//
+// bf16 kernel: flash-decoding on MFMA. Keys are the M dimension of S^T (a lane then holds 4 keys x 1 query, and the
+// two 16-key tiles of a 32-key block are interleaved so that the exponentiated scores of a lane are already the
+// 8-key B fragment of O^T = V^T . P^T); V is cached transposed so that its fragments are 16-byte loads too.
+// Wavefronts of a workgroup take 32-key blocks round-robin and are merged through LDS in a fixed order; several
+// workgroups may split a long prefix (grid.z) and are merged by attn_combine_kernel.
+#pragma once
+#include "clasp_common.h"
+
+namespace clasp {
+
+struct AttnArgs {
+    const float* qkv;  // [rows][ld_qkv]: q heads | k heads | v heads, un-rotated
+    int ld_qkv;
+    int n_rows, n_heads, n_kv_heads, head_dim;
+    int pos0, mode;
+    const float2* rope;  // [max_seq][head_dim/2] (cos, sin)
+    void* Kc;            // this layer: [n_kv_heads][t_max][head_dim]
+    void* Vt;            // this layer: [n_kv_heads][head_dim][t_max]
+    int t_max;
+    void* out_op;  // operand of the output projection (K = n_heads*head_dim)
+    int R;
+    int n_split;
+    float* partial;  // [n_kv_heads][n_split][nq_pad][head_dim+2] when n_split > 1
+    int nq_pad;
+    float scale;  // 1/sqrt(head_dim)
+};
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+template <int HD, int NT>
+struct AttnState {
+    float m[NT], l[NT];
+    f32x4 o[NT][HD / 16];
+};
+
+// One 32-key block: scores for NT query tiles, online softmax update, O^T accumulation.
+//   kf(u, kk) -> A fragment of key tile u (16 keys), k-step kk;  vf(c) -> A fragment of V^T rows c*16..c*16+15
+//   valid(u, r, t) -> whether key (lane/16)*8 + u*4 + r of the block is visible to query t*16 + lane%16
+template <int HD, int NT, class KF, class VF, class VALID>
+__device__ __forceinline__ void attn_block(AttnState<HD, NT>& st, const bf16x8 (&qf)[NT][HD / 32], KF kf, VF vf,
+                                           VALID valid) {
+    constexpr int KK = HD / 32, CT = HD / 16;
+    f32x4 s[2][NT];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) s[u][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            const bf16x8 k = kf(u, kk);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) s[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k, qf[t][kk], s[u][t], 0, 0, 0);
+        }
+    }
+    bf16x8 pf[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if (!valid(u, r, t)) s[u][t][r] = -INFINITY;
+                mx = fmaxf(mx, s[u][t][r]);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(st.m[t], mx);
+        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = exp2f(st.m[t] - m_safe);
+        float psum = 0.f;
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float p = exp2f(s[u][t][r] - m_safe);
+                psum += p;
+                pf[t][u * 4 + r] = to_bf16(p);
+            }
+        st.l[t] = st.l[t] * alpha + psum;
+        st.m[t] = m_new;
+#pragma unroll
+        for (int c = 0; c < CT; ++c) st.o[t][c] *= alpha;
+    }
+#pragma unroll
+    for (int c = 0; c < CT; ++c) {
+        const bf16x8 v = vf(c);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) st.o[t][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v, pf[t], st.o[t][c], 0, 0, 0);
+    }
+}
+
+template <int HD, int NT, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(AttnArgs a) {
+    constexpr int KK = HD / 32, CT = HD / 16, HALF = HD / 2;
+    // Staging tiles (queries, self keys, self values) and the merge buffer are live at different times and share
+    // one LDS region. Row strides are padded (+8 bf16, +1 float) so that rows land in different LDS banks.
+    constexpr int kStageBytes = (NT * 16 * (HD + 8) + 32 * (HD + 8) + HD * 40) * 2;
+    constexpr int kMergeBytes = NW * HD * 17 * 4;
+    __shared__ __attribute__((aligned(16))) unsigned char lds_raw[kStageBytes > kMergeBytes ? kStageBytes : kMergeBytes];
+    typedef bf16 (*QsT)[HD + 8];
+    typedef bf16 (*VtsT)[40];
+    typedef float (*MgT)[HD][17];
+    QsT Qs = reinterpret_cast<QsT>(lds_raw);
+    QsT Ks = reinterpret_cast<QsT>(lds_raw + NT * 16 * (HD + 8) * 2);
+    VtsT Vts = reinterpret_cast<VtsT>(lds_raw + (NT * 16 + 32) * (HD + 8) * 2);
+    MgT mg_o = reinterpret_cast<MgT>(lds_raw);
+    __shared__ float mg_m[NW][16], mg_l[NW][16];
+    const int kvh = blockIdx.x, qg = blockIdx.y, split = blockIdx.z;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int G = a.n_heads / a.n_kv_heads, nQ = a.n_rows * G;
+    const int q_base = qg * NT * 16;
+    const bool last = (split == a.n_split - 1);
+    const float qscale = a.scale * kLog2e;
+    bf16* Kc = reinterpret_cast<bf16*>(a.Kc);
+    bf16* Vt = reinterpret_cast<bf16*>(a.Vt);
+
+    for (int idx = tid; idx < NT * 16 * HALF; idx += NW * 64) {
+        const int ql = idx / HALF, e = idx % HALF, qi = q_base + ql;
+        float v0 = 0.f, v1 = 0.f;
+        if (qi < nQ) {
+            const int row = qi / G, h = kvh * G + qi % G;
+            const int pos = a.pos0 + (a.mode ? row : 0);
+            const float* qp = a.qkv + (size_t)row * a.ld_qkv + h * HD;
+            const float x0 = qp[e], x1 = qp[e + HALF];
+            const float2 cs = a.rope[(size_t)pos * HALF + e];
+            v0 = (x0 * cs.x - x1 * cs.y) * qscale;
+            v1 = (x1 * cs.x + x0 * cs.y) * qscale;
+        }
+        Qs[ql][e] = to_bf16(v0);
+        Qs[ql][e + HALF] = to_bf16(v1);
+    }
+    if (last) {
+        for (int idx = tid; idx < 32 * HALF; idx += NW * 64) {
+            const int r = idx / HALF, e = idx % HALF;
+            bf16 k0 = to_bf16(0.f), k1 = k0, v0 = k0, v1 = k0;
+            if (r < a.n_rows) {
+                const int pos = a.pos0 + (a.mode ? r : 0);
+                const float* kp = a.qkv + (size_t)r * a.ld_qkv + (a.n_heads + kvh) * HD;
+                const float* vp = kp + a.n_kv_heads * HD;
+                const float x0 = kp[e], x1 = kp[e + HALF];
+                const float2 cs = a.rope[(size_t)pos * HALF + e];
+                k0 = to_bf16(x0 * cs.x - x1 * cs.y);
+                k1 = to_bf16(x1 * cs.x + x0 * cs.y);
+                v0 = to_bf16(vp[e]);
+                v1 = to_bf16(vp[e + HALF]);
+                if (a.mode && qg == 0) {
+                    bf16* kc = Kc + ((size_t)kvh * a.t_max + pos) * HD;
+                    kc[e] = k0;
+                    kc[e + HALF] = k1;
+                    Vt[((size_t)kvh * HD + e) * a.t_max + pos] = v0;
+                    Vt[((size_t)kvh * HD + e + HALF) * a.t_max + pos] = v1;
+                }
+            }
+            Ks[r][e] = k0;
+            Ks[r][e + HALF] = k1;
+            Vts[e][r] = v0;
+            Vts[e + HALF][r] = v1;
+        }
+    }
+    __syncthreads();
+
+    bf16x8 qf[NT][KK];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+            qf[t][kk] = *reinterpret_cast<const bf16x8*>(&Qs[t * 16 + (lane & 15)][kk * 32 + (lane >> 4) * 8]);
+
+    AttnState<HD, NT> st;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        st.m[t] = -INFINITY;
+        st.l[t] = 0.f;
+#pragma unroll
+        for (int c = 0; c < CT; ++c) st.o[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    const int nblk = (a.pos0 + 31) >> 5;
+    const int b0 = (int)(((long long)nblk * split) / a.n_split), b1 = (int)(((long long)nblk * (split + 1)) / a.n_split);
+    const int m16 = lane & 15, q4 = lane >> 4;
+    for (int blk = b0 + wave; blk < b1; blk += NW) {
+        const int kb = blk << 5;
+        attn_block<HD, NT>(
+            st, qf,
+            [&](int u, int kk) {
+                const int key = min(kb + (m16 >> 2) * 8 + u * 4 + (m16 & 3), a.pos0 - 1);
+                const u32x4* kp = reinterpret_cast<const u32x4*>(Kc + ((size_t)kvh * a.t_max + key) * HD);
+                return as_bf16x8(load_stream(kp + kk * 4 + q4));
+            },
+            [&](int c) {
+                const u32x4* vp = reinterpret_cast<const u32x4*>(Vt + ((size_t)kvh * HD + c * 16 + m16) * a.t_max + kb);
+                return as_bf16x8(load_stream(vp + q4));
+            },
+            [&](int u, int r, int) { return kb + q4 * 8 + u * 4 + r < a.pos0; });
+    }
+    if (last && wave == (b1 - b0) % NW) {
+        attn_block<HD, NT>(
+            st, qf,
+            [&](int u, int kk) {
+                return *reinterpret_cast<const bf16x8*>(&Ks[(m16 >> 2) * 8 + u * 4 + (m16 & 3)][kk * 32 + q4 * 8]);
+            },
+            [&](int c) { return *reinterpret_cast<const bf16x8*>(&Vts[c * 16 + m16][q4 * 8]); },
+            [&](int u, int r, int t) {
+                const int kr = q4 * 8 + u * 4 + r, qi = q_base + t * 16 + m16, qrow = qi / G;
+                return kr < a.n_rows && qi < nQ && (a.mode ? kr <= qrow : kr == qrow);
+            });
+    }
+
+    __syncthreads();  // staging tiles are dead from here on; their LDS becomes the merge buffer
+    // merge the wavefronts' running (max, sum, O^T), one query tile at a time, fixed order
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        float l = st.l[t];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        if (lane < 16) {
+            mg_m[wave][lane] = st.m[t];
+            mg_l[wave][lane] = l;
+        }
+#pragma unroll
+        for (int c = 0; c < CT; ++c)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) mg_o[wave][c * 16 + q4 * 4 + r][m16] = st.o[t][c][r];
+        __syncthreads();
+        for (int idx = tid; idx < HD * 16; idx += NW * 64) {
+            const int e = idx >> 4, j = idx & 15, qi = q_base + t * 16 + j;
+            if (qi < nQ) {
+                float mstar = -INFINITY;
+                for (int w = 0; w < NW; ++w) mstar = fmaxf(mstar, mg_m[w][j]);
+                float L = 0.f, O = 0.f;
+                for (int w = 0; w < NW; ++w) {
+                    const float mw = mg_m[w][j];
+                    const float f = (mw == -INFINITY) ? 0.f : exp2f(mw - mstar);
+                    L += f * mg_l[w][j];
+                    O += f * mg_o[w][e][j];
+                }
+                if (a.n_split == 1) {
+                    const int row = qi / G, h = kvh * G + qi % G;
+                    store_operand<kDtBf16>(a.out_op, a.R, 0, row, h * HD + e, O / L);
+                } else {
+                    float* p = a.partial + (((size_t)kvh * a.n_split + split) * a.nq_pad + qi) * (HD + 2);
+                    p[e] = O;
+                    if (e == 0) {
+                        p[HD] = mstar;
+                        p[HD + 1] = L;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// Merges the n_split partial results of one query (fixed order) and writes the output-projection operand.
+template <int DT>
+__global__ void attn_combine_kernel(AttnArgs a) {
+    const int kvh = blockIdx.x, qi = blockIdx.y, HD = a.head_dim;
+    const int G = a.n_heads / a.n_kv_heads;
+    const float* base = a.partial + (((size_t)kvh * a.n_split) * a.nq_pad + qi) * (HD + 2);
+    const size_t stride = (size_t)a.nq_pad * (HD + 2);
+    float mstar = -INFINITY;
+    for (int s = 0; s < a.n_split; ++s) mstar = fmaxf(mstar, base[s * stride + HD]);
+    for (int e = threadIdx.x; e < HD; e += blockDim.x) {
+        float L = 0.f, O = 0.f;
+        for (int s = 0; s < a.n_split; ++s) {
+            const float ms = base[s * stride + HD];
+            const float f = (ms == -INFINITY) ? 0.f : exp2f(ms - mstar);
+            L += f * base[s * stride + HD + 1];
+            O += f * base[s * stride + e];
+        }
+        const int row = qi / G, h = kvh * G + qi % G;
+        store_operand<DT>(a.out_op, a.R, a.n_heads * HD, row, h * HD + e, O / L);
+    }
+}
+
+// fp32 path: one workgroup per (query head, row); plain loops, exact softmax over all visible keys.
+// Dynamic LDS: (head_dim + n_keys) floats with n_keys = pos0 + 32.
+__global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a) {
+    extern __shared__ float lds[];
+    __shared__ float red[8];
+    const int h = blockIdx.x, r = blockIdx.y, HD = a.head_dim, HALF = HD / 2;
+    const int G = a.n_heads / a.n_kv_heads, kvh = h / G;
+    const int pos = a.pos0 + (a.mode ? r : 0);
+    const int n_self = a.mode ? r + 1 : 1;  // visible self keys: rows 0..r, or only row r
+    const int self0 = a.mode ? 0 : r;
+    const int n_keys = a.pos0 + n_self;
+    float* q = lds;
+    float* sc = lds + HD;
+    const float* Kc = reinterpret_cast<const float*>(a.Kc) + (size_t)kvh * a.t_max * HD;
+    const float* Vt = reinterpret_cast<const float*>(a.Vt) + (size_t)kvh * HD * a.t_max;
+    for (int e = threadIdx.x; e < HALF; e += blockDim.x) {
+        const float* qp = a.qkv + (size_t)r * a.ld_qkv + h * HD;
+        const float2 cs = a.rope[(size_t)pos * HALF + e];
+        q[e] = qp[e] * cs.x - qp[e + HALF] * cs.y;
+        q[e + HALF] = qp[e + HALF] * cs.x + qp[e] * cs.y;
+    }
+    __syncthreads();
+    float mx = -INFINITY;
+    for (int t = threadIdx.x; t < n_keys; t += blockDim.x) {
+        float s = 0.f;
+        if (t < a.pos0) {
+            const float* kp = Kc + (size_t)t * HD;
+            for (int e = 0; e < HD; ++e) s = fmaf(q[e], kp[e], s);
+        } else {
+            const int sr = self0 + (t - a.pos0);
+            const int spos = a.pos0 + (a.mode ? sr : 0);
+            const float* kp = a.qkv + (size_t)sr * a.ld_qkv + (a.n_heads + kvh) * HD;
+            for (int e = 0; e < HALF; ++e) {
+                const float2 cs = a.rope[(size_t)spos * HALF + e];
+                s = fmaf(q[e], kp[e] * cs.x - kp[e + HALF] * cs.y, s);
+                s = fmaf(q[e + HALF], kp[e + HALF] * cs.x + kp[e] * cs.y, s);
+            }
+        }
+        s *= a.scale;
+        sc[t] = s;
+        mx = fmaxf(mx, s);
+    }
+    mx = wave_max(mx);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float den = 0.f;
+    for (int t = threadIdx.x; t < n_keys; t += blockDim.x) {
+        const float p = expf(sc[t] - mx);
+        sc[t] = p;
+        den += p;
+    }
+    den = block_sum(den, red + 4);
+    for (int e = threadIdx.x; e < HD; e += blockDim.x) {
+        float o = 0.f;
+        const float* vp = Vt + (size_t)e * a.t_max;
+        for (int t = 0; t < a.pos0; ++t) o = fmaf(sc[t], vp[t], o);
+        for (int t = a.pos0; t < n_keys; ++t) {
+            const int sr = self0 + (t - a.pos0);
+            o = fmaf(sc[t], a.qkv[(size_t)sr * a.ld_qkv + (a.n_heads + a.n_kv_heads + kvh) * HD + e], o);
+        }
+        store_operand<kDtF32>(a.out_op, a.R, a.n_heads * HD, r, h * HD + e, o / den);
+    }
+    if (a.mode && h % G == 0) {  // this row's key/value into the cache
+        float* Kw = reinterpret_cast<float*>(a.Kc) + ((size_t)kvh * a.t_max + pos) * HD;
+        float* Vw = reinterpret_cast<float*>(a.Vt) + (size_t)kvh * HD * a.t_max + pos;
+        const float* kp = a.qkv + (size_t)r * a.ld_qkv + (a.n_heads + kvh) * HD;
+        const float* vp = kp + a.n_kv_heads * HD;
+        for (int e = threadIdx.x; e < HALF; e += blockDim.x) {
+            const float2 cs = a.rope[(size_t)pos * HALF + e];
+            Kw[e] = kp[e] * cs.x - kp[e + HALF] * cs.y;
+            Kw[e + HALF] = kp[e + HALF] * cs.x + kp[e] * cs.y;
+            Vw[(size_t)e * a.t_max] = vp[e];
+            Vw[(size_t)(e + HALF) * a.t_max] = vp[e + HALF];
+        }
+    }
+}
+
+}  // namespace clasp

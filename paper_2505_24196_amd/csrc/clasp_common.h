@@ -1,0 +1,82 @@
+// Shared device-side definitions for the CLaSp gfx950 kernels: vector types, the bf16 MFMA operand ("fragment")
+// layout that every producer writes and every GEMM reads, and small wavefront helpers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace clasp {
+
+typedef __bf16 bf16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+constexpr int kMaxRows = 32;      // rows (tokens / DP candidates) one launch may carry
+constexpr int kWave = 64;         // CDNA wavefront
+constexpr int kDtF32 = 0, kDtBf16 = 1;
+
+// ---- bf16 activation operand layout -----------------------------------------------------------------------
+// An activation matrix X[rows <= 16*R][K] that a GEMM will contract over K is kept in HBM as MFMA operand
+// fragments: for k-step s (32 consecutive k) and row group rg (16 rows) one fragment of 64 lanes x 8 bf16, lane
+// (q*16 + r) holding X[rg*16 + r][s*32 + q*8 .. +8]. A wavefront fetches one fragment with one 16-byte-per-lane
+// load and feeds it to v_mfma_f32_16x16x32_bf16 unchanged. Weights use the same tile shape with the 16 output
+// features of a column tile in place of the 16 rows (see pack kernel).
+__device__ __forceinline__ size_t frag_elem_offset(int R, int row, int k) {
+    const int s = k >> 5, q = (k >> 3) & 3, e = k & 7, rg = row >> 4, r = row & 15;
+    return ((((size_t)s * R + rg) * 64) + q * 16 + r) * 8 + e;
+}
+
+__device__ __forceinline__ bf16 to_bf16(float x) { return static_cast<bf16>(x); }  // round-to-nearest-even
+__device__ __forceinline__ float from_bf16(bf16 x) { return static_cast<float>(x); }
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// Streaming (no-reuse) 16-byte load: weights and KV are read once per launch, keep them out of the way of the
+// small activation working set that every workgroup re-reads from L2.
+__device__ __forceinline__ u32x4 load_stream(const u32x4* p) { return __builtin_nontemporal_load(p); }
+
+// Sum over the 16 lanes that share lane/16 (xor butterflies stay inside the 16-lane row).
+__device__ __forceinline__ float sum16(float v) {
+    v += __shfl_xor(v, 1);
+    v += __shfl_xor(v, 2);
+    v += __shfl_xor(v, 4);
+    v += __shfl_xor(v, 8);
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+    v = sum16(v);
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    return v;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+
+// Deterministic block-wide sum (fixed tree): every thread gets the total. `scratch` holds >= blockDim/64 floats.
+__device__ __forceinline__ float block_sum(float v, float* scratch) {
+    v = wave_sum(v);
+    const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) scratch[wave] = v;
+    __syncthreads();
+    float t = 0.f;
+    for (int w = 0; w < nw; ++w) t += scratch[w];
+    return t;
+}
+
+// Store one activation element for a later GEMM: bf16 fragment order, or fp32 row-major [row][ld].
+template <int DT>
+__device__ __forceinline__ void store_operand(void* buf, int R, int ld, int row, int k, float v) {
+    if constexpr (DT == kDtBf16) {
+        reinterpret_cast<bf16*>(buf)[frag_elem_offset(R, row, k)] = to_bf16(v);
+    } else {
+        reinterpret_cast<float*>(buf)[(size_t)row * ld + k] = v;
+    }
+}
+
+}  // namespace clasp

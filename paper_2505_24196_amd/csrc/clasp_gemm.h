@@ -1,0 +1,267 @@
+// Skinny GEMMs of the decoder layer: Y[rows <= 32][N] = X[rows][K] . W[N][K]^T with the weights streamed from HBM
+// exactly once per launch for all rows (Sec. 3.6 of the paper batches the DP's candidate states of one layer into
+// one pass for this reason). The contraction is HBM-bound (arithmetic intensity = rows flop/byte), so the kernels
+// are organised around keeping 16-byte-per-lane weight loads in flight; MFMA does the arithmetic because the
+// vector ALUs could not keep up with 16..32 rows at 8 TB/s.
+//
+// bf16 kernel: one workgroup per tile of 16 output features; its NW wavefronts split K and each streams its slice
+// of the tile (contiguous in the packed weight order) with a register double buffer of P fragments; the activation
+// fragments come from L2 in the same order. Partial tiles are reduced through LDS in a fixed order (deterministic,
+// independent of the number of rows), then the first R wavefronts run the epilogue.
+//
+// Epilogues (they produce what the NEXT kernel consumes, so that no separate norm / activation kernels exist):
+//   kEpiScale   out = acc * rstd(row)                       (q/k/v projection, lm_head; RMSNorm's 1/rms factor
+//                                                            commutes with the contraction, its gains are already
+//                                                            folded into the activation fragments)
+//   kEpiResid   out = resid + acc; optionally a copy (hidden-state capture), the next GEMM's operand
+//               (out * gain, in operand layout) and per-tile partial sums of out^2 for the next 1/rms
+//   kEpiSwiglu  two weight streams (gate, up): operand of the down projection = silu(g*rstd) * (u*rstd)
+#pragma once
+#include "clasp_common.h"
+
+namespace clasp {
+
+constexpr int kEpiScale = 0, kEpiResid = 1, kEpiSwiglu = 2;
+
+struct GemmArgs {
+    const void* W[3];   // up to three matrices stacked along N (q|k|v); kEpiSwiglu: W[0] = gate, W[1] = up
+    int tile_end[3];    // exclusive end tile (16 features) of each stacked matrix
+    const void* A;      // activation operand: bf16 fragments, or fp32 row-major [rows][K]
+    int n_rows, N, K, R;
+    const float* ss_parts;  // [n_parts][32] partial sums of squares of the un-normalised input rows
+    int n_parts;
+    float inv_dim, eps;
+    float* out;  // fp32 [rows][ldo]
+    int ldo;
+    const float* resid;  // fp32 [rows][ldr]
+    int ldr;
+    void* next_op;           // operand for the next GEMM (its K = this N), may be null
+    const float* next_gain;  // [N] gains folded into next_op (null = 1)
+    float* next_ss;          // [N/16][32] partial sums of squares of `out`, may be null
+    float* capture;          // optional copy of out, [rows][ldc]
+    int ldc;
+};
+
+// rstd[row] = 1 / sqrt(sum_p parts[p][row] * inv_dim + eps), fixed summation order. Needs blockDim % 32 == 0.
+__device__ __forceinline__ void compute_rstd(const GemmArgs& g, float* rstd_s, float* tmp /* [blockDim] */) {
+    const int row = threadIdx.x & 31, sub = threadIdx.x >> 5, nsub = blockDim.x >> 5;
+    float s = 0.f;
+    for (int p = sub; p < g.n_parts; p += nsub) s += g.ss_parts[(size_t)p * kMaxRows + row];
+    tmp[threadIdx.x] = s;
+    __syncthreads();
+    if (threadIdx.x < 32) {
+        float t = 0.f;
+        for (int u = 0; u < nsub; ++u) t += tmp[u * 32 + threadIdx.x];
+        rstd_s[threadIdx.x] = 1.0f / sqrtf(t * g.inv_dim + g.eps);
+    }
+    __syncthreads();
+}
+
+template <int R, int NACC, int P>
+struct GemmStage {
+    u32x4 b[NACC][P];
+    u32x4 a[P][R];
+};
+
+template <int R, int NACC, int P>
+__device__ __forceinline__ void gemm_issue(GemmStage<R, NACC, P>& st, const u32x4* w0, const u32x4* w1,
+                                           const u32x4* af, int s, int ks1) {
+#pragma unroll
+    for (int u = 0; u < P; ++u) {
+        const int ss = min(s + u, ks1 - 1);
+        st.b[0][u] = load_stream(w0 + (size_t)ss * 64);
+        if constexpr (NACC == 2) st.b[1][u] = load_stream(w1 + (size_t)ss * 64);
+#pragma unroll
+        for (int rg = 0; rg < R; ++rg) st.a[u][rg] = af[((size_t)ss * R + rg) * 64];
+    }
+}
+
+template <int R, int NACC, int P>
+__device__ __forceinline__ void gemm_compute(const GemmStage<R, NACC, P>& st, f32x4 (&acc)[NACC][R], int s, int ks1) {
+#pragma unroll
+    for (int u = 0; u < P; ++u) {
+        if (s + u < ks1) {
+#pragma unroll
+            for (int rg = 0; rg < R; ++rg) {
+                acc[0][rg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(st.a[u][rg]), as_bf16x8(st.b[0][u]),
+                                                                     acc[0][rg], 0, 0, 0);
+                if constexpr (NACC == 2)
+                    acc[1][rg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(st.a[u][rg]),
+                                                                         as_bf16x8(st.b[1][u]), acc[1][rg], 0, 0, 0);
+            }
+        }
+    }
+}
+
+template <int R, int NW, int EPI, int P>
+__global__ __launch_bounds__(NW * 64) void gemm_bf16_kernel(GemmArgs g) {
+    constexpr int NACC = (EPI == kEpiSwiglu) ? 2 : 1;
+    __shared__ f32x4 red[NW][NACC][R][64];
+    __shared__ float rstd_s[kMaxRows];
+    __shared__ float tmp_s[NW * 64];
+    const int tile = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int KS = g.K >> 5;
+    const int ks0 = (KS * wave) / NW, ks1 = (KS * (wave + 1)) / NW;
+
+    int mi = 0, tl = tile;
+    if constexpr (EPI == kEpiScale) {
+        if (tile >= g.tile_end[0]) { mi = 1; tl = tile - g.tile_end[0]; }
+        if (tile >= g.tile_end[1]) { mi = 2; tl = tile - g.tile_end[1]; }
+    }
+    const u32x4* w0 = reinterpret_cast<const u32x4*>(g.W[mi]) + (size_t)tl * KS * 64 + lane;
+    const u32x4* w1 = (NACC == 2) ? reinterpret_cast<const u32x4*>(g.W[1]) + (size_t)tl * KS * 64 + lane : nullptr;
+    const u32x4* af = reinterpret_cast<const u32x4*>(g.A) + lane;
+
+    f32x4 acc[NACC][R];
+#pragma unroll
+    for (int a = 0; a < NACC; ++a)
+#pragma unroll
+        for (int rg = 0; rg < R; ++rg) acc[a][rg] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    GemmStage<R, NACC, P> st0, st1;
+    int s = ks0;
+    if (s < ks1) gemm_issue<R, NACC, P>(st0, w0, w1, af, s, ks1);  // weights first: they do not depend on rstd
+
+    if constexpr (EPI != kEpiResid) compute_rstd(g, rstd_s, tmp_s);
+
+    while (s < ks1) {
+        if (s + P < ks1) gemm_issue<R, NACC, P>(st1, w0, w1, af, s + P, ks1);
+        gemm_compute<R, NACC, P>(st0, acc, s, ks1);
+        s += P;
+        if (s >= ks1) break;
+        if (s + P < ks1) gemm_issue<R, NACC, P>(st0, w0, w1, af, s + P, ks1);
+        gemm_compute<R, NACC, P>(st1, acc, s, ks1);
+        s += P;
+    }
+
+#pragma unroll
+    for (int a = 0; a < NACC; ++a)
+#pragma unroll
+        for (int rg = 0; rg < R; ++rg) red[wave][a][rg][lane] = acc[a][rg];
+    __syncthreads();
+    if (wave >= R) return;
+
+    const int rg = wave;
+    f32x4 sum[NACC];
+#pragma unroll
+    for (int a = 0; a < NACC; ++a) {
+        sum[a] = red[0][a][rg][lane];
+        for (int w = 1; w < NW; ++w) sum[a] += red[w][a][rg][lane];
+    }
+    const int col = tile * 16 + (lane & 15);
+    const int row0 = rg * 16 + (lane >> 4) * 4;
+    if constexpr (EPI == kEpiScale) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = row0 + r;
+            if (row < g.n_rows) g.out[(size_t)row * g.ldo + col] = sum[0][r] * rstd_s[row];
+        }
+    } else if constexpr (EPI == kEpiResid) {
+        const float gain = g.next_gain ? g.next_gain[col] : 1.0f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = row0 + r;
+            float v = 0.f;
+            if (row < g.n_rows) {
+                v = g.resid[(size_t)row * g.ldr + col] + sum[0][r];
+                g.out[(size_t)row * g.ldo + col] = v;
+                if (g.capture) g.capture[(size_t)row * g.ldc + col] = v;
+            }
+            if (g.next_op) store_operand<kDtBf16>(g.next_op, g.R, 0, row, col, v * gain);
+            if (g.next_ss) {
+                const float sq = sum16(v * v);
+                if ((lane & 15) == 0) g.next_ss[(size_t)tile * kMaxRows + row] = sq;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = row0 + r;
+            float v = 0.f;
+            if (row < g.n_rows) {
+                const float gt = sum[0][r] * rstd_s[row], up = sum[1][r] * rstd_s[row];
+                v = gt / (1.0f + expf(-gt)) * up;
+            }
+            store_operand<kDtBf16>(g.next_op, g.R, 0, row, col, v);
+        }
+    }
+}
+
+// fp32 path (small models / exactness checks): row-major fp32 weights, plain FMA. One workgroup (4 wavefronts) per
+// tile of 16 output features, each wavefront takes 4 of them and splits K across its lanes.
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
+    constexpr int NACC = (EPI == kEpiSwiglu) ? 2 : 1;
+    __shared__ float rstd_s[kMaxRows];
+    __shared__ float tmp_s[256];
+    __shared__ float vals[NACC][16][kMaxRows];
+    const int tile = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if constexpr (EPI != kEpiResid) compute_rstd(g, rstd_s, tmp_s);
+
+    int mi = 0, tl = tile;
+    if constexpr (EPI == kEpiScale) {
+        if (tile >= g.tile_end[0]) { mi = 1; tl = tile - g.tile_end[0]; }
+        if (tile >= g.tile_end[1]) { mi = 2; tl = tile - g.tile_end[1]; }
+    }
+    const float* A = reinterpret_cast<const float*>(g.A);
+    for (int c = 0; c < 4; ++c) {
+        const int cl = wave * 4 + c;
+        const float* wrow[NACC];
+        wrow[0] = reinterpret_cast<const float*>(g.W[mi]) + ((size_t)tl * 16 + cl) * g.K;
+        if constexpr (NACC == 2) wrow[1] = reinterpret_cast<const float*>(g.W[1]) + ((size_t)tl * 16 + cl) * g.K;
+        float acc[NACC][kMaxRows];
+#pragma unroll
+        for (int a = 0; a < NACC; ++a)
+#pragma unroll
+            for (int r = 0; r < kMaxRows; ++r) acc[a][r] = 0.f;
+        for (int k = lane; k < g.K; k += 64) {
+            float wv[NACC];
+#pragma unroll
+            for (int a = 0; a < NACC; ++a) wv[a] = wrow[a][k];
+#pragma unroll
+            for (int r = 0; r < kMaxRows; ++r) {
+                if (r < g.n_rows) {
+                    const float x = A[(size_t)r * g.K + k];
+#pragma unroll
+                    for (int a = 0; a < NACC; ++a) acc[a][r] = fmaf(wv[a], x, acc[a][r]);
+                }
+            }
+        }
+#pragma unroll
+        for (int a = 0; a < NACC; ++a)
+#pragma unroll
+            for (int r = 0; r < kMaxRows; ++r) {
+                const float t = wave_sum(acc[a][r]);
+                if (lane == 0) vals[a][cl][r] = t;
+            }
+    }
+    __syncthreads();
+    // epilogue: thread (cl = tid/16 .. ) -> one (row, column) pair per thread per pass
+    for (int idx = threadIdx.x; idx < 16 * kMaxRows; idx += 256) {
+        const int row = idx >> 4, cl = idx & 15, col = tile * 16 + cl;
+        float v = 0.f;
+        if constexpr (EPI == kEpiScale) {
+            if (row < g.n_rows) g.out[(size_t)row * g.ldo + col] = vals[0][cl][row] * rstd_s[row];
+        } else if constexpr (EPI == kEpiResid) {
+            if (row < g.n_rows) {
+                v = g.resid[(size_t)row * g.ldr + col] + vals[0][cl][row];
+                g.out[(size_t)row * g.ldo + col] = v;
+                if (g.capture) g.capture[(size_t)row * g.ldc + col] = v;
+                if (g.next_op)
+                    store_operand<kDtF32>(g.next_op, g.R, g.N, row, col, v * (g.next_gain ? g.next_gain[col] : 1.0f));
+            }
+            if (g.next_ss) {  // idx>>4 == row is constant over 16 consecutive lanes
+                const float sq = sum16(v * v);
+                if (cl == 0) g.next_ss[(size_t)tile * kMaxRows + row] = sq;
+            }
+        } else {
+            if (row < g.n_rows) {
+                const float gt = vals[0][cl][row] * rstd_s[row], up = vals[1][cl][row] * rstd_s[row];
+                v = gt / (1.0f + expf(-gt)) * up;
+                store_operand<kDtF32>(g.next_op, g.R, g.N, row, col, v);
+            }
+        }
+    }
+}
+
+}  // namespace clasp

@@ -1,0 +1,237 @@
+// Small kernels around the GEMMs and attention: weight packing, rotary table, embedding gather, cache loading,
+// the DP's cosine/select step (Algorithm 1), backtracking, and greedy argmax over the logits.
+#pragma once
+#include "clasp_common.h"
+
+namespace clasp {
+
+// ---- weight packing: row-major bf16 [N][K] -> fragments (tile of 16 features x 32 inputs = 64 lanes x 8 bf16) ----
+// dst fragment index = (n/16)*(K/32) + k/32; lane q*16 + c holds W[(n/16)*16 + c][(k/32)*32 + q*8 .. +8].
+__global__ void pack_bf16_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int N, int K) {
+    const size_t total = (size_t)N * K / 8;  // 16-byte vectors
+    const int KS = K >> 5;
+    for (size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x; v < total; v += (size_t)gridDim.x * blockDim.x) {
+        const int lane = (int)(v & 63);
+        const size_t frag = v >> 6;
+        const int s = (int)(frag % KS);
+        const size_t tile = frag / KS;
+        const int c = lane & 15, q = lane >> 4;
+        const size_t row = tile * 16 + c;
+        dst[v] = src[(row * K + (size_t)s * 32 + q * 8) / 8];
+    }
+}
+
+// ---- rotary table: (cos, sin)(pos * base^(-2e/hd)) evaluated in double, stored as float2 ------------------------
+__global__ void rope_table_kernel(float2* table, int max_seq, int half, double base) {
+    const size_t total = (size_t)max_seq * half;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const int e = (int)(i % half);
+        const double pos = (double)(i / half);
+        const double theta = pos * pow(base, -(double)e / (double)half);
+        table[i] = make_float2((float)cos(theta), (float)sin(theta));
+    }
+}
+
+__global__ void fill_zero_kernel(u32x4* p, size_t n_vec) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = u32x4{0u, 0u, 0u, 0u};
+}
+
+// ---- emit one row for the next layer: fp32 copy, GEMM operand (row * gain), per-16-column sums of squares --------
+// Called by all threads of a workgroup; d % 16 == 0 and blockDim % 16 == 0 so a 16-column tile sits in 16 lanes.
+template <int DT, class F>
+__device__ __forceinline__ void emit_row(F value_at, int d, float* dst_f32, void* op, int R, int op_row,
+                                         const float* gain, float* ss /* [d/16][32] */) {
+    for (int c = threadIdx.x; c < d; c += blockDim.x) {
+        const float v = value_at(c);
+        if (dst_f32) dst_f32[c] = v;
+        if (op) {
+            store_operand<DT>(op, R, d, op_row, c, v * (gain ? gain[c] : 1.0f));
+            const float sq = sum16(v * v);
+            if ((c & 15) == 0) ss[(size_t)(c >> 4) * kMaxRows + op_row] = sq;
+        }
+    }
+}
+
+// ---- embedding gather: h_0 of each row, plus everything layer 0 consumes ------------------------------------------
+template <int DT>
+__global__ __launch_bounds__(256) void embed_kernel(const int32_t* tokens, const void* table, int vocab, int d,
+                                                    float* h, void* op, int R, const float* gain, float* ss,
+                                                    float* capture) {
+    const int row = blockIdx.x;
+    int tok = tokens[row];
+    tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
+    auto val = [&](int c) -> float {
+        if constexpr (DT == kDtBf16) return from_bf16(reinterpret_cast<const bf16*>(table)[(size_t)tok * d + c]);
+        else return reinterpret_cast<const float*>(table)[(size_t)tok * d + c];
+    };
+    emit_row<DT>(val, d, h + (size_t)row * d, op, R, row, gain, ss);
+    if (capture)
+        for (int c = threadIdx.x; c < d; c += blockDim.x) capture[(size_t)row * d + c] = val(c);
+}
+
+// ---- install cache contents given as fp32 [T][n_kv][hd] -----------------------------------------------------------
+template <int DT>
+__global__ void kv_load_kernel(const float* K, const float* V, void* Kc, void* Vt, int T, int nkv, int hd, int t_max) {
+    const size_t total = (size_t)T * nkv * hd;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const int e = (int)(i % hd);
+        const int kvh = (int)((i / hd) % nkv);
+        const size_t t = i / ((size_t)hd * nkv);
+        const size_t ko = ((size_t)kvh * t_max + t) * hd + e, vo = ((size_t)kvh * hd + e) * t_max + t;
+        if constexpr (DT == kDtBf16) {
+            reinterpret_cast<bf16*>(Kc)[ko] = to_bf16(K[i]);
+            reinterpret_cast<bf16*>(Vt)[vo] = to_bf16(V[i]);
+        } else {
+            reinterpret_cast<float*>(Kc)[ko] = K[i];
+            reinterpret_cast<float*>(Vt)[vo] = V[i];
+        }
+    }
+}
+
+// ---- the DP's score / select step for layer index i (Algorithm 1, Eq. 2) -------------------------------------------
+// Workgroup j = blockIdx.x handles cell (i, j), j = 0..min(i, M):
+//   j = 0          g(i,0) = x_i
+//   1 <= j <= ell  (ell = min(i-1, M)): keep the computed candidate G[j-1] = f_{i-1}(g(i-1,j)) if its cosine with x_i
+//                  is strictly larger than that of the skip candidate g(i-1,j-1), else the skip candidate
+//   j = i <= M     g(i,i) = g(i-1,i-1) (all layers so far skipped)
+// and emits g(i,j), j >= 1, as row j-1 of the next layer's input (fp32 + GEMM operand + sums of squares).
+struct SelectArgs {
+    int i, M, d, R;
+    const float* x_i;     // [d]
+    const float* g_prev;  // g(i-1, .) rows, [M+1][d]
+    const float* G;       // computed candidates, row j-1 for cell j, [ell][d]
+    float* g_cur;         // g(i, .) rows, [M+1][d]
+    void* op;             // next layer's operand (null when i == L)
+    const float* gain;    // next layer's attention-norm gains
+    float* ss;
+    float* scores;    // [(L+1)][(M+1)][2] or null
+    uint8_t* choice;  // [(L+1)][(M+1)]
+};
+
+template <int DT>
+__global__ __launch_bounds__(256) void dp_select_kernel(SelectArgs a) {
+    __shared__ float red[8];
+    const int j = blockIdx.x, d = a.d;
+    const int ell = min(a.i - 1, a.M);
+    float* dst = a.g_cur + (size_t)j * d;
+    if (j == 0) {
+        for (int c = threadIdx.x; c < d; c += blockDim.x) dst[c] = a.x_i[c];
+        return;
+    }
+    const float* skip = a.g_prev + (size_t)(j - 1) * d;
+    const bool has_comp = j <= ell;
+    const float* comp = a.G + (size_t)(j - 1) * d;
+    float xx = 0.f, sx = 0.f, ss = 0.f, cx = 0.f, cc = 0.f;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) {
+        const float x = a.x_i[c], s = skip[c];
+        xx = fmaf(x, x, xx);
+        sx = fmaf(s, x, sx);
+        ss = fmaf(s, s, ss);
+        if (has_comp) {
+            const float g = comp[c];
+            cx = fmaf(g, x, cx);
+            cc = fmaf(g, g, cc);
+        }
+    }
+    xx = block_sum(xx, red);
+    sx = block_sum(sx, red);
+    ss = block_sum(ss, red);
+    cx = block_sum(cx, red);
+    cc = block_sum(cc, red);
+    const float nx = fmaxf(sqrtf(xx), 1e-12f);
+    const float sig_s = sx / (fmaxf(sqrtf(ss), 1e-12f) * nx);
+    const float sig_c = has_comp ? cx / (fmaxf(sqrtf(cc), 1e-12f) * nx) : __builtin_nanf("");
+    const bool keep_comp = has_comp && (sig_c > sig_s);
+    if (threadIdx.x == 0) {
+        const size_t cell = (size_t)a.i * (a.M + 1) + j;
+        a.choice[cell] = keep_comp ? 0 : 1;
+        if (a.scores) {
+            a.scores[cell * 2] = sig_c;
+            a.scores[cell * 2 + 1] = sig_s;
+        }
+    }
+    const float* src = keep_comp ? comp : skip;
+    emit_row<DT>([&](int c) { return src[c]; }, d, dst, a.op, a.R, j - 1, a.gain, a.ss);
+}
+
+__global__ void dp_table_init_kernel(float* scores, uint8_t* choice, int cells) {
+    for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < cells; c += gridDim.x * blockDim.x) {
+        choice[c] = 255;
+        if (scores) {
+            scores[2 * c] = __builtin_nanf("");
+            scores[2 * c + 1] = __builtin_nanf("");
+        }
+    }
+}
+
+// Backtracking from (L, M): a kept skip candidate at (i, j) means layer i-1 is skipped.
+__global__ void dp_backtrack_kernel(const uint8_t* choice, int L, int M, uint8_t* mask, const float* g_last,
+                                    float* g_final, int d) {
+    if (blockIdx.x == 0) {
+        for (int l = threadIdx.x; l < L; l += blockDim.x) mask[l] = 0;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int i = L, j = M;
+            while (i > 0 && j > 0) {
+                if (choice[(size_t)i * (M + 1) + j] == 1) {
+                    mask[i - 1] = 1;
+                    --j;
+                }
+                --i;
+            }
+        }
+    } else if (g_final) {
+        for (int c = threadIdx.x; c < d; c += blockDim.x) g_final[c] = g_last[(size_t)M * d + c];
+    }
+}
+
+// ---- greedy head: argmax (lowest index on ties), top-1 minus top-2 logit, softmax probability of the top-1 -------
+__global__ __launch_bounds__(1024) void argmax_kernel(const float* logits, int vocab, int32_t* argmax_out,
+                                                      float* margin_out, float* prob_out) {
+    __shared__ float s_v1[16], s_v2[16], s_sum[16];
+    __shared__ int s_i1[16];
+    const float* lg = logits + (size_t)blockIdx.x * vocab;
+    float v1 = -INFINITY, v2 = -INFINITY;
+    int i1 = 0x7fffffff;
+    for (int c = threadIdx.x; c < vocab; c += blockDim.x) {
+        const float v = lg[c];
+        if (v > v1) { v2 = v1; v1 = v; i1 = c; }
+        else if (v > v2) v2 = v;
+    }
+    auto merge = [](float& a1, int& ai, float& a2, float b1, int bi, float b2) {
+        if (b1 > a1 || (b1 == a1 && bi < ai)) {
+            a2 = fmaxf(a1, b2);
+            a1 = b1;
+            ai = bi;
+        } else {
+            a2 = fmaxf(a2, b1);
+        }
+    };
+    for (int o = 1; o < 64; o <<= 1) {
+        const float b1 = __shfl_xor(v1, o), b2 = __shfl_xor(v2, o);
+        const int bi = __shfl_xor(i1, o);
+        merge(v1, i1, v2, b1, bi, b2);
+    }
+    const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    if ((threadIdx.x & 63) == 0) { s_v1[wave] = v1; s_v2[wave] = v2; s_i1[wave] = i1; }
+    __syncthreads();
+    v1 = s_v1[0]; v2 = s_v2[0]; i1 = s_i1[0];
+    for (int w = 1; w < nw; ++w) merge(v1, i1, v2, s_v1[w], s_i1[w], s_v2[w]);
+    float sum = 0.f;
+    if (prob_out) {
+        for (int c = threadIdx.x; c < vocab; c += blockDim.x) sum += expf(lg[c] - v1);
+        sum = wave_sum(sum);
+        if ((threadIdx.x & 63) == 0) s_sum[wave] = sum;
+        __syncthreads();
+        sum = 0.f;
+        for (int w = 0; w < nw; ++w) sum += s_sum[w];
+    }
+    if (threadIdx.x == 0) {
+        if (argmax_out) argmax_out[blockIdx.x] = i1;
+        if (margin_out) margin_out[blockIdx.x] = v1 - v2;
+        if (prob_out) prob_out[blockIdx.x] = 1.0f / sum;
+    }
+}
+
+}  // namespace clasp

@@ -1,0 +1,79 @@
+"""Host side of the Draft -> Verify -> Layer-Optimisation loop (Sec. 3.1 of the paper) on top of the C ABI.
+
+Only integer control flow lives here (greedy acceptance: the longest prefix of the draft that matches the full model's
+argmax, plus the full model's own next token); every forward, the DP and the argmax run in the HIP library.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+from .binding import Engine
+
+
+def prefill(engine: Engine, prompt: Sequence[int], pos0: int = 0):
+    """Full model over the prompt in chunks of max_rows. Returns (states [L+1][d] of the last token, its argmax)."""
+    toks = torch.as_tensor(list(prompt), dtype=torch.int32, device=engine.device)
+    n, step = toks.numel(), engine.max_rows
+    out = None
+    for s in range(0, n, step):
+        chunk = toks[s:s + step]
+        out = engine.clasp_verify_forward(chunk, pos0 + s, want_hidden=(s + step >= n), want_margin=True)
+    last = out["argmax"].numel() - 1
+    return out["hidden"][:, last, :], out["argmax"][last:last + 1], out["margin"][last:last + 1]
+
+
+def greedy_generate(engine: Engine, prompt: Sequence[int], n_gen: int):
+    """Plain greedy decoding with the full model (one row per step). Returns (tokens, top-1 minus top-2 margins)."""
+    _, nxt, mg = prefill(engine, prompt)
+    buf = torch.empty(n_gen, dtype=torch.int32, device=engine.device)
+    margins = torch.empty(n_gen, dtype=torch.float32, device=engine.device)
+    buf[0:1].copy_(nxt)
+    margins[0:1].copy_(mg)
+    pos = len(prompt)
+    for t in range(1, n_gen):
+        out = engine.clasp_verify_forward(buf[t - 1:t], pos, want_margin=True)
+        buf[t:t + 1].copy_(out["argmax"])
+        margins[t:t + 1].copy_(out["margin"])
+        pos += 1
+    return buf.cpu().tolist(), margins.cpu().tolist()
+
+
+def clasp_generate(engine: Engine, prompt: Sequence[int], n_gen: int, M: int, K: int, dp_interval: int = 1,
+                   trace: bool = False) -> Dict[str, object]:
+    """Greedy self-speculative decoding with the DP-selected skip set re-optimised every `dp_interval` verify steps
+    (1 = after every verification, the paper's default; larger values are its lower optimisation frequency)."""
+    dev = engine.device
+    states, nxt, _ = prefill(engine, prompt)
+    pos = len(prompt)
+    dp = engine.clasp_dp_select(states, pos - 1, M, want_tables=trace)  # prefill counts as verification 0
+    mask = dp["mask"].cpu().tolist()
+    out: List[int] = [int(nxt.item())]
+    tok = torch.empty(K + 1, dtype=torch.int32, device=dev)
+    tok[0:1].copy_(nxt)
+    rounds = []
+    n_verify = 0
+    while len(out) < n_gen:
+        for k in range(K):
+            engine.clasp_draft_step(mask, tok[k:k + 1], pos + k, tok[k + 1:k + 2])
+        ver = engine.clasp_verify_forward(tok, pos, want_hidden=True, want_margin=trace)
+        rows = tok.cpu().tolist()
+        v = ver["argmax"].cpu().tolist()
+        a = 0
+        while a < K and rows[a + 1] == v[a]:
+            a += 1
+        out.extend(rows[1:a + 1] + [v[a]])
+        n_verify += 1
+        if trace:
+            rounds.append({"pos": pos, "mask": list(mask), "drafts": rows[1:], "verify": v, "accepted": a,
+                           "verify_margin": ver["margin"].cpu().tolist(), "dp": {k: t.cpu() for k, t in dp.items()},
+                           "states": ver["hidden"][:, a, :].cpu()})
+        else:
+            rounds.append({"pos": pos, "accepted": a})
+        if n_verify % dp_interval == 0 and len(out) < n_gen:
+            dp = engine.clasp_dp_select(ver["hidden"][:, a, :], pos + a, M, want_tables=trace)
+            mask = dp["mask"].cpu().tolist()
+        tok[0:1].copy_(ver["argmax"][a:a + 1])
+        pos += a + 1
+    return {"tokens": out[:n_gen], "rounds": rounds}
