@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the CLaSp hot path on one MI355X.
+
+A "step" is one pass of the whole path over one batch of synthetic input: K draft steps with the current skip set,
+one verify forward over the K+1 rows, greedy acceptance on the host, and one DP layer selection on the last accepted
+token's stored states. Prints ONE JSON line:
+  metric/value : draft tokens/s of the layer-skipped draft model (1 / mean clasp_draft_step time), inputs resident
+  dp_select_ms : mean time of one clasp_dp_select call (one per verify step)
+  roofline     : the dominant kernel (gate/up SwiGLU GEMM) against the 8 TB/s HBM peak, its duration measured with
+                 HIP events around each of its launches in the timed region
+  cpu_baseline : the fp64 CPU oracle timed on the host cores on the same shapes
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+WORKLOADS = {
+    # BASELINE config 2: the configuration the metric is quoted on
+    "llama3-8b-shape/T512/M12/K4": dict(shape="llama3-8b-shape", T=512, M=12, K=4),
+    # BASELINE config 1: small case the oracle finishes in seconds
+    "tiny-f32/T64/M3/K4": dict(shape="tiny-f32", T=64, M=3, K=4),
+    "llama3-8b-shape/T4096/M12/K6": dict(shape="llama3-8b-shape", T=4096, M=12, K=6),
+}
+
+
+def build_engine(shape, seed, max_seq, max_rows, keep_host=False):
+    """Generates the random-init model layer by layer on the GPU and packs it; optionally keeps host copies."""
+    import torch
+    import synth_inputs as si
+    import paper_2505_24196_amd as clasp
+    eng = clasp.Engine(shape, max_seq=max_seq, max_rows=max_rows)
+    host = {"layers": []} if keep_host else None
+    head = si.gen_head(shape, seed, "cuda")
+    eng.set_head(head["embed"], head["lm_head"], head["final_norm"])
+    if keep_host:
+        host.update({k: si.to_numpy(v) for k, v in head.items()})
+    del head
+    for l in range(shape.n_layers):
+        w = si.gen_layer(shape, seed, l, "cuda")
+        eng.set_layer(l, w)
+        if keep_host:
+            host["layers"].append({k: si.to_numpy(v) for k, v in w.items()})
+        del w
+    torch.cuda.empty_cache()
+    eng.create()
+    return eng, host
+
+
+def algorithmic_bytes(shape, T, M):
+    """Bytes the method itself must move: weights of each evaluated layer once, the shared KV prefix once per layer."""
+    eb = shape.elem_bytes()
+    wl = shape.layer_weight_elems() * eb
+    kv = 2 * shape.kv_dim * eb * T
+    head = shape.vocab * shape.d_model * eb
+    L = shape.n_layers
+    return {"dp_select": (L - 1) * (wl + kv), "draft_step": (L - M) * (wl + kv) + head,
+            "verify_forward": L * (wl + kv) + head, "gate_up_kernel": 2 * shape.d_model * shape.d_ffn * eb}
+
+
+def cpu_baseline(shape, host_model, T, M, budget_s=30.0):
+    """Times the oracle (as it stands) on the host cores: one DP layer selection and one draft step on the same model,
+    with a seeded synthetic KV prefix of T tokens standing in for the prefill the oracle cannot afford."""
+    import numpy as np
+    import synth_inputs as si
+    from oracle import clasp_oracle as oc
+    om = oc.OracleModel(shape, host_model)
+    cache = oc.KVCache(shape, T + 8)
+    K, V = si.gen_kv(shape, 3, shape.n_layers, T)
+    cache.load(K.numpy().astype(np.float64), V.numpy().astype(np.float64))
+    del K, V
+    tok = int(si.gen_tokens(2, 1, shape.vocab, stream=7)[0])
+    t0 = time.time()
+    states, _ = om.token(tok, T, cache, want_states=True)
+    t_verify_row = time.time() - t0
+    # bound the sample: the DP costs about sum_i min(i-1, M) row-layers, one verify row costs L of them
+    L = shape.n_layers
+    row_layers = sum(min(i - 1, M) for i in range(1, L + 1))
+    est = t_verify_row / L * row_layers
+    M_s = M
+    while M_s > 1 and est > budget_s:
+        M_s -= 1
+        est = t_verify_row / L * sum(min(i - 1, M_s) for i in range(1, L + 1))
+    t0 = time.time()
+    res = om.dp(states, T, cache, M_s)
+    t_dp = time.time() - t0
+    scale = row_layers / max(1, sum(min(i - 1, M_s) for i in range(1, L + 1)))
+    t0 = time.time()
+    om.token(tok, T, cache, skip=res["mask"] if M_s == M else None)
+    t_draft = time.time() - t0
+    if M_s != M:
+        t_draft *= (L - M) / L
+    return {"value": round(1.0 / t_draft, 3), "unit": "draft tokens/s", "cores": oc.num_threads(), "kind": "oracle",
+            "dp_select_ms": round(t_dp * scale * 1e3, 1),
+            "sample": f"one oracle DP with M={M_s} (scaled x{scale:.2f} to M={M}) and one draft step at T={T} on "
+                      f"synthetic KV, {shape.name}"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama3-8b-shape/T512/M12/K4", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timer", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
+
+    import torch
+    import synth_inputs as si
+    import paper_2505_24196_amd as clasp
+    from paper_2505_24196_amd import decode
+
+    wl = WORKLOADS[args.workload]
+    shape = si.SHAPES[wl["shape"]]
+    T, M, K = wl["T"], wl["M"], wl["K"]
+    total_steps = args.steps + args.warmup
+    max_seq = ((T + (K + 1) * (total_steps + 2) + 31) // 32) * 32
+    want_cpu = not args.no_cpu_baseline
+    eng, host = build_engine(shape, 1, max_seq, 16, keep_host=want_cpu)
+    dev = eng.device
+
+    prompt = [int(t) for t in si.gen_tokens(2, T, shape.vocab)]
+    states, nxt, _ = decode.prefill(eng, prompt)
+    pos = T
+    dp_out = eng.clasp_dp_select(states, pos - 1, M)
+    mask = dp_out["mask"].cpu().tolist()
+    tok = torch.empty(K + 1, dtype=torch.int32, device=dev)
+    tok[0:1].copy_(nxt)
+    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+    t_draft = t_verify = t_dp = 0.0
+    accepted = 0
+    pairs = []
+    kt_ms, kt_n = 0.0, 0
+    for step in range(total_steps):
+        timed = step >= args.warmup
+        if step == args.warmup:
+            torch.cuda.synchronize()
+            if not args.no_kernel_timer:
+                eng.kernel_timer_begin("gate_up")
+            t_start = time.perf_counter()
+        e = [ev() for _ in range(4)]
+        e[0].record()
+        for k in range(K):
+            eng.clasp_draft_step(mask, tok[k:k + 1], pos + k, tok[k + 1:k + 2])
+        e[1].record()
+        ver = eng.clasp_verify_forward(tok, pos, want_hidden=True)
+        e[2].record()
+        rows = tok.cpu().tolist()
+        v = ver["argmax"].cpu().tolist()
+        a = 0
+        while a < K and rows[a + 1] == v[a]:
+            a += 1
+        e2 = ev()
+        e2.record()
+        eng.clasp_dp_select(ver["hidden"][:, a, :], pos + a, M, out=dp_out)
+        e[3].record()
+        mask = dp_out["mask"].cpu().tolist()
+        tok[0:1].copy_(ver["argmax"][a:a + 1])
+        pos += a + 1
+        if timed:
+            accepted += a
+            pairs.append((e[0], e[1], e[2], e2, e[3]))
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t_start
+    if not args.no_kernel_timer:
+        kt_ms, kt_n = eng.kernel_timer_end()
+    for p in pairs:
+        t_draft += p[0].elapsed_time(p[1])
+        t_verify += p[1].elapsed_time(p[2])
+        t_dp += p[3].elapsed_time(p[4])
+    n = args.steps
+    draft_ms = t_draft / (n * K)
+    dp_ms = t_dp / n
+    verify_ms = t_verify / n
+    ab = algorithmic_bytes(shape, T, M)
+    frac = lambda b, ms: round(b / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)  # noqa: E731
+    out = {
+        "metric": "DP-select ms/verify step + draft tokens/s (8B-shape, 1 GPU); % HBM roofline",
+        "value": round(1e3 / draft_ms, 2), "unit": "draft tokens/s", "n_gpus": 1, "steps": n, "warmup": args.warmup,
+        "ms_per_step": round(t_total * 1e3 / n, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": args.workload, "context_tokens": T, "skip_budget_M": M, "draft_len_K": K,
+                   "layers": shape.n_layers, "d_model": shape.d_model, "weights": "random-init N(0,0.02), seed 1"},
+        "dp_select_ms": round(dp_ms, 4), "draft_step_ms": round(draft_ms, 4), "verify_forward_ms": round(verify_ms, 4),
+        "mean_accepted": round(accepted / n, 3), "tokens_per_s_closed_loop": round((accepted + n) / t_total, 2),
+        "hbm_frac_of_8TBs": {"dp_select": frac(ab["dp_select"], dp_ms), "draft_step": frac(ab["draft_step"], draft_ms),
+                             "verify_forward": frac(ab["verify_forward"], verify_ms)},
+    }
+    if kt_n:
+        avg_ms = kt_ms / kt_n
+        ach = ab["gate_up_kernel"] / (avg_ms * 1e-3) / 1e9
+        out["roofline"] = {"bound": "hbm", "kernel": "gemm_bf16_kernel<SwiGLU> (gate/up projection)" if shape.dtype == "bf16"
+                           else "gemm_f32_kernel<SwiGLU> (gate/up projection)",
+                           "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None, "launches": kt_n,
+                           "avg_us": round(avg_ms * 1e3, 2), "bytes_per_launch": ab["gate_up_kernel"]}
+    eng.close()
+    del eng
+    torch.cuda.empty_cache()
+    if want_cpu:
+        out["cpu_baseline"] = cpu_baseline(shape, host, T, M)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

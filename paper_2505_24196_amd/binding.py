@@ -17,7 +17,9 @@ LIB_PATH = os.path.join(_HERE, "libclasp_hip.so")
 CLASP_F32, CLASP_BF16 = 0, 1
 EXPORTS = ("clasp_strerror", "clasp_packed_bytes", "clasp_pack_matrix", "clasp_workspace_bytes",
            "clasp_kv_cache_bytes", "clasp_create", "clasp_destroy", "clasp_verify_forward", "clasp_dp_select",
-           "clasp_draft_step", "clasp_kv_load")
+           "clasp_draft_step", "clasp_kv_load", "clasp_kernel_timer_begin", "clasp_kernel_timer_end")
+
+KERNEL_KINDS = {"qkv": 0, "attention": 1, "o_proj": 2, "gate_up": 3, "down": 4, "lm_head": 5}
 
 
 class ClaspError(RuntimeError):
@@ -64,6 +66,8 @@ def lib():
         l.clasp_dp_select.argtypes = [vp, vp, sz, i32, i32, vp, vp, vp, vp, vp]
         l.clasp_draft_step.argtypes = [vp, vp, vp, i32, vp, vp, vp]
         l.clasp_kv_load.argtypes = [vp, i32, vp, vp, i32, vp]
+        l.clasp_kernel_timer_begin.argtypes = [vp, i32, i32]
+        l.clasp_kernel_timer_end.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int)]
         _lib = l
     return _lib
 
@@ -117,6 +121,8 @@ class Engine:
         self.cfg = Config(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
                           shape.vocab, max_seq, max_rows, _dtype_code(shape.dtype), shape.rms_eps, shape.rope_base)
         self.max_seq, self.max_rows = max_seq, max_rows
+        if lib().clasp_workspace_bytes(C.byref(self.cfg)) == 0:
+            raise ClaspError("configuration not supported by the kernels (see clasp_create in clasp.h)")
         self._layers: List[Dict[str, torch.Tensor]] = [None] * shape.n_layers
         self._head: Dict[str, torch.Tensor] = {}
         self._ctx = None
@@ -232,3 +238,13 @@ class Engine:
         _check(lib().clasp_draft_step(self._ctx, mp, token.data_ptr(), pos, next_token_out.data_ptr(),
                                       None if top1_prob_out is None else top1_prob_out.data_ptr(), _stream()),
                "clasp_draft_step")
+
+    # ---- measurement aid ------------------------------------------------------------------------------------------
+    def kernel_timer_begin(self, kind: str, capacity: int = 1 << 16):
+        _check(lib().clasp_kernel_timer_begin(self._ctx, KERNEL_KINDS[kind], capacity), "clasp_kernel_timer_begin")
+
+    def kernel_timer_end(self):
+        """Returns (summed elapsed ms, launches timed) of the kernel kind chosen at begin."""
+        ms, n = C.c_float(), C.c_int()
+        _check(lib().clasp_kernel_timer_end(self._ctx, C.byref(ms), C.byref(n)), "clasp_kernel_timer_end")
+        return float(ms.value), int(n.value)

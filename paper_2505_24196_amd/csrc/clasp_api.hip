@@ -60,6 +60,10 @@ struct clasp_ctx {
     float* attn_partial;
     uint8_t* choice;
     int32_t* tok_tmp;
+    // optional per-kernel timing (host-side event objects only; no device memory)
+    int timer_kind = -1;
+    size_t timer_used = 0;
+    std::vector<hipEvent_t> timer_start, timer_stop;
 };
 
 namespace {
@@ -121,10 +125,25 @@ int check_config(const clasp_config* c) {
         if (hipGetLastError() != hipSuccess) return CLASP_E_HIP; \
     } while (0)
 
+// ---- per-kernel timer: brackets the launches of one kernel kind with event pairs ------------------------------
+struct TimerScope {
+    clasp_ctx* ctx;
+    hipStream_t st;
+    bool on;
+    TimerScope(const clasp_ctx* c, int kind, hipStream_t s) : ctx(const_cast<clasp_ctx*>(c)), st(s) {
+        on = ctx->timer_kind == kind && ctx->timer_used < ctx->timer_start.size();
+        if (on) (void)hipEventRecord(ctx->timer_start[ctx->timer_used], st);
+    }
+    ~TimerScope() {
+        if (on) (void)hipEventRecord(ctx->timer_stop[ctx->timer_used++], st);
+    }
+};
+
 // ---- GEMM dispatch ---------------------------------------------------------------------------------------------
 template <int EPI>
-int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st) {
+int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kind) {
     const int tiles = g.N / 16;
+    TimerScope timer(ctx, kind, st);
     if (ctx->cfg.dtype == CLASP_BF16) {
         if (g.R == 1)
             hipLaunchKernelGGL((gemm_bf16_kernel<1, kGemmWaves, EPI, kGemmDepth>), dim3(tiles), dim3(kGemmWaves * 64), 0, st, g);
@@ -174,6 +193,7 @@ int launch_attention(const clasp_ctx* ctx, int layer, int n, int R, int mode, in
     split = split < 1 ? 1 : (split > kMaxSplit ? kMaxSplit : split);
     a.n_split = split;
     const dim3 grid(c.n_kv_heads, qgroups, split);
+    TimerScope timer(ctx, CLASP_KERNEL_ATTENTION, st);
     const int rc = c.head_dim == 64 ? launch_attn_bf16<64>(a, nt, grid, st) : launch_attn_bf16<128>(a, nt, grid, st);
     if (rc) return rc;
     if (split > 1) {
@@ -198,7 +218,7 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
         g.A = ctx->op_h; g.n_rows = n; g.N = ctx->qkv_dim; g.K = d; g.R = R;
         g.ss_parts = ctx->ss_h; g.n_parts = d / 16; g.inv_dim = 1.0f / d; g.eps = c.rms_eps;
         g.out = ctx->qkv; g.ldo = ctx->qkv_dim;
-        if ((rc = launch_gemm<kEpiScale>(ctx, g, st))) return rc;
+        if ((rc = launch_gemm<kEpiScale>(ctx, g, st, CLASP_KERNEL_QKV))) return rc;
     }
     if ((rc = launch_attention(ctx, l, n, R, mode, pos0, st))) return rc;
     {
@@ -207,7 +227,7 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
         g.A = ctx->op_attn; g.n_rows = n; g.N = d; g.K = ctx->q_dim; g.R = R;
         g.out = ctx->a_buf; g.ldo = d; g.resid = h_in; g.ldr = d;
         g.next_op = ctx->op_a; g.next_gain = ctx->mlp_norm[l]; g.next_ss = ctx->ss_a;
-        if ((rc = launch_gemm<kEpiResid>(ctx, g, st))) return rc;
+        if ((rc = launch_gemm<kEpiResid>(ctx, g, st, CLASP_KERNEL_O_PROJ))) return rc;
     }
     {
         GemmArgs g{};
@@ -215,7 +235,7 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
         g.A = ctx->op_a; g.n_rows = n; g.N = F; g.K = d; g.R = R;
         g.ss_parts = ctx->ss_a; g.n_parts = d / 16; g.inv_dim = 1.0f / d; g.eps = c.rms_eps;
         g.next_op = ctx->op_act;
-        if ((rc = launch_gemm<kEpiSwiglu>(ctx, g, st))) return rc;
+        if ((rc = launch_gemm<kEpiSwiglu>(ctx, g, st, CLASP_KERNEL_GATE_UP))) return rc;
     }
     {
         GemmArgs g{};
@@ -224,7 +244,7 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
         g.out = h_out; g.ldo = d; g.resid = ctx->a_buf; g.ldr = d;
         g.next_op = next_op; g.next_gain = next_gain; g.next_ss = next_ss;
         g.capture = capture; g.ldc = d;
-        if ((rc = launch_gemm<kEpiResid>(ctx, g, st))) return rc;
+        if ((rc = launch_gemm<kEpiResid>(ctx, g, st, CLASP_KERNEL_DOWN))) return rc;
     }
     return CLASP_OK;
 }
@@ -252,7 +272,7 @@ int run_head(const clasp_ctx* ctx, int n, int R, float* logits, int32_t* argmax_
     g.ss_parts = ctx->ss_h; g.n_parts = c.d_model / 16; g.inv_dim = 1.0f / c.d_model; g.eps = c.rms_eps;
     g.out = logits; g.ldo = c.vocab;
     int rc;
-    if ((rc = launch_gemm<kEpiScale>(ctx, g, st))) return rc;
+    if ((rc = launch_gemm<kEpiScale>(ctx, g, st, CLASP_KERNEL_LM_HEAD))) return rc;
     if (argmax_out || margin_out || prob_out) {
         hipLaunchKernelGGL(argmax_kernel, dim3(n), dim3(1024), 0, st, logits, c.vocab, argmax_out, margin_out, prob_out);
         CLASP_LAUNCH_CHECK();
@@ -362,6 +382,43 @@ int clasp_destroy(clasp_ctx* ctx) {
     if (!ctx) return CLASP_E_INVALID_ARG;
     delete ctx;
     return CLASP_OK;
+}
+
+int clasp_kernel_timer_begin(clasp_ctx* ctx, int kind, int capacity) {
+    if (!ctx || kind < 0 || kind >= CLASP_KERNEL_KINDS || capacity < 1 || capacity > (1 << 20)) return CLASP_E_INVALID_ARG;
+    if (ctx->timer_kind >= 0) return CLASP_E_INVALID_ARG;
+    ctx->timer_start.resize(capacity);
+    ctx->timer_stop.resize(capacity);
+    for (int i = 0; i < capacity; ++i)
+        if (hipEventCreate(&ctx->timer_start[i]) != hipSuccess || hipEventCreate(&ctx->timer_stop[i]) != hipSuccess)
+            return CLASP_E_HIP;
+    ctx->timer_used = 0;
+    ctx->timer_kind = kind;
+    return CLASP_OK;
+}
+
+int clasp_kernel_timer_end(clasp_ctx* ctx, float* total_ms, int* launches) {
+    if (!ctx || !total_ms || !launches || ctx->timer_kind < 0) return CLASP_E_INVALID_ARG;
+    float sum = 0.f;
+    int rc = CLASP_OK;
+    for (size_t i = 0; i < ctx->timer_used; ++i) {
+        float ms = 0.f;
+        if (hipEventSynchronize(ctx->timer_stop[i]) != hipSuccess ||
+            hipEventElapsedTime(&ms, ctx->timer_start[i], ctx->timer_stop[i]) != hipSuccess)
+            rc = CLASP_E_HIP;
+        sum += ms;
+    }
+    for (size_t i = 0; i < ctx->timer_start.size(); ++i) {
+        (void)hipEventDestroy(ctx->timer_start[i]);
+        (void)hipEventDestroy(ctx->timer_stop[i]);
+    }
+    *total_ms = sum;
+    *launches = (int)ctx->timer_used;
+    ctx->timer_start.clear();
+    ctx->timer_stop.clear();
+    ctx->timer_kind = -1;
+    ctx->timer_used = 0;
+    return rc;
 }
 
 int clasp_kv_load(clasp_ctx* ctx, int layer, const float* K, const float* V, int n_tokens, void* stream) {

@@ -1,0 +1,63 @@
+"""CPU-side checks of the boundary: the built library loads and exports every function include/clasp.h declares,
+and the size / validation entry points that need no GPU behave."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "clasp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(clasp_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_the_three_hot_path_calls():
+    names = declared_functions()
+    for n in ("clasp_verify_forward", "clasp_dp_select", "clasp_draft_step"):
+        assert n in names
+
+
+def test_library_exports_every_declared_function():
+    from paper_2505_24196_amd import binding
+    lib = binding.lib()
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+    assert set(binding.EXPORTS) == set(declared_functions())
+
+
+def test_sizes_and_validation_without_a_gpu():
+    from paper_2505_24196_amd import binding
+    import synth_inputs as si
+    lib = binding.lib()
+    assert lib.clasp_strerror(0) == b"ok" and lib.clasp_strerror(-2) == b"unsupported shape"
+    assert lib.clasp_packed_bytes(4096, 14336, binding.CLASP_BF16) == 4096 * 14336 * 2
+    assert lib.clasp_packed_bytes(100, 128, binding.CLASP_BF16) == 0  # rows not a multiple of 16
+    assert lib.clasp_packed_bytes(128, 100, binding.CLASP_BF16) == 0  # cols not a multiple of 32
+    assert lib.clasp_packed_bytes(688, 256, binding.CLASP_F32) == 688 * 256 * 4
+    s = si.LLAMA3_8B
+    cfg = binding.Config(s.n_layers, s.d_model, s.n_heads, s.n_kv_heads, s.head_dim, s.d_ffn, s.vocab, 1024, 16, 1,
+                         s.rms_eps, s.rope_base)
+    assert lib.clasp_kv_cache_bytes(C.byref(cfg)) == 32 * 8 * 1024 * 128 * 2
+    assert lib.clasp_workspace_bytes(C.byref(cfg)) > 0
+    cfg.max_rows = 33
+    assert lib.clasp_workspace_bytes(C.byref(cfg)) == 0
+    cfg.max_rows, cfg.max_seq = 16, 1000  # not a multiple of 32
+    assert lib.clasp_workspace_bytes(C.byref(cfg)) == 0
+    out = C.c_void_p()
+    cfg.max_seq = 1024
+    assert lib.clasp_create(C.byref(cfg), None, None, 0, None, None, C.byref(out)) == -1
+    assert lib.clasp_destroy(None) == -1
+
+
+def test_engine_refuses_to_run_without_a_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    import paper_2505_24196_amd as clasp
+    import synth_inputs as si
+    with pytest.raises(clasp.ClaspError):
+        clasp.Engine(si.TINY_F32, max_seq=64)

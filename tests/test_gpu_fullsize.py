@@ -1,0 +1,60 @@
+"""Parity at BASELINE's full size (LLaMA-3-8B shape, bf16, T = 512, M = 12), in the launch configuration bench.py
+times. The oracle cannot afford a 512-token prefill at this size, so a seeded synthetic KV prefix (shared input)
+stands in for it on both sides; the verify rows, the DP and a draft step are then compared call by call."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import clasp_oracle as oc
+from tests.test_gpu_parity import HID_TOL, check_dp, dev, relerr
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def setup_8b():
+    import bench
+    shape = si.LLAMA3_8B
+    T = 512
+    eng, host = bench.build_engine(shape, 1, 1024, 16, keep_host=True)
+    om = oc.OracleModel(shape, host)
+    K, V = si.gen_kv(shape, 3, shape.n_layers, T)
+    cache = oc.KVCache(shape, T + 8)
+    cache.load(K.numpy().astype(np.float64), V.numpy().astype(np.float64))
+    for l in range(shape.n_layers):
+        eng.clasp_kv_load(l, K[l], V[l])
+    yield shape, T, eng, om, cache
+    eng.close()
+
+
+def test_8b_verify_dp_and_draft(setup_8b):
+    shape, T, eng, om, cache = setup_8b
+    toks = [int(t) for t in si.gen_tokens(2, 3, shape.vocab, stream=9)]
+    st, lg = [], []
+    for r, tk in enumerate(toks):
+        print(f"oracle verify row {r}", flush=True)
+        s, l_ = om.token(tk, T + r, cache, want_states=True)
+        st.append(s)
+        lg.append(l_)
+    ost, olg = np.stack(st, 1), np.stack(lg)
+    out = eng.clasp_verify_forward(dev(toks, torch.int32), T, want_hidden=True, want_logits=True)
+    for l in range(shape.n_layers + 1):
+        assert relerr(out["hidden"][l].cpu().numpy(), ost[l]) <= HID_TOL["bf16"], f"layer {l}"
+    assert relerr(out["logits"].cpu().numpy(), olg) <= HID_TOL["bf16"]
+    # DP on row 1 (position T+1): cache rows 0..T of the oracle are the synthetic prefix plus row 0's own k/v
+    print("oracle dp", flush=True)
+    c = oc.KVCache(shape, T + 8)
+    c.K[:, :T + 1] = cache.K[:, :T + 1]
+    c.V[:, :T + 1] = cache.V[:, :T + 1]
+    gpu, ref = check_dp(om, eng, ost[:, 1], T + 1, c, 12)
+    # one draft step with the selected skip set, from row 2's token at position T+2
+    print("oracle draft", flush=True)
+    nxt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    eng.clasp_draft_step(ref["mask"].tolist(), dev(toks[2:3], torch.int32), T + 2, nxt)
+    c.K[:, T + 1] = cache.K[:, T + 1]
+    c.V[:, T + 1] = cache.V[:, T + 1]
+    _, dl = om.token(toks[2], T + 2, c, skip=ref["mask"])
+    ref_tok, ref_margin = oc.argmax_margin(dl)
+    if ref_margin > HID_TOL["bf16"] * np.abs(dl).max() * 2:
+        assert int(nxt) == ref_tok
