@@ -82,8 +82,10 @@ size_t clasp_packed_bytes(int rows, int cols, int dtype);
 /* Re-orders a row-major [rows][cols] dev matrix `src` into the library's streaming order in `dst` (dev, distinct
  * from src, clasp_packed_bytes() bytes). bf16: tiles of 16 output features x 32 inputs, each tile stored so that
  * one 64-lane wavefront reads it with a single coalesced 16-byte-per-lane load in MFMA operand order; tiles of
- * one 16-feature group are contiguous along the input dimension. fp32: plain copy. */
-int clasp_pack_matrix(const void *src, void *dst, int rows, int cols, int dtype, void *stream);
+ * one 16-feature group are contiguous along the input dimension. fp32: plain copy.
+ * rope_head_dim: 0 for every matrix except wq and wk, which take the model's head_dim: their output features are
+ * regrouped per head so that a rotary pair (e, e + head_dim/2) falls into one tile (ignored for fp32). */
+int clasp_pack_matrix(const void *src, void *dst, int rows, int cols, int dtype, int rope_head_dim, void *stream);
 
 /* Device bytes clasp_create needs in `workspace` (256-byte aligned), and bytes of ONE of the two KV caches. */
 size_t clasp_workspace_bytes(const clasp_config *cfg);
@@ -119,7 +121,8 @@ int clasp_verify_forward(clasp_ctx *ctx, const int32_t *tokens, int n_tokens, in
  * keeping the skip candidate on ties, and backtracks from (L, M) to the skip set. All candidates of one layer go
  * through f_{i-1} in one batched pass that reads the layer's weights and the shared KV prefix once; each candidate
  * attends cache positions 0..pos-1 plus its own key/value and no other candidate. Writes no KV.
- *   states       dev fp32, state l at states + l*layer_stride (elements), l = 0..n_layers
+ *   states       dev fp32, 16-byte aligned, state l at states + l*layer_stride (elements, multiple of 4),
+ *                l = 0..n_layers;  0 <= pos < max_seq
  *   M            skip budget, 0 <= M <= min(n_layers, max_rows)
  *   mask_out     dev uint8 [n_layers]: 1 = layer skipped; exactly M ones
  *   score_out    dev fp32 [(n_layers+1)][(M+1)][2] or NULL: (cosine of the computed candidate, cosine of the skip

@@ -55,7 +55,7 @@ def lib():
         l.clasp_strerror.argtypes = [i32]
         l.clasp_packed_bytes.restype = sz
         l.clasp_packed_bytes.argtypes = [i32, i32, i32]
-        l.clasp_pack_matrix.argtypes = [vp, vp, i32, i32, i32, vp]
+        l.clasp_pack_matrix.argtypes = [vp, vp, i32, i32, i32, i32, vp]
         l.clasp_workspace_bytes.restype = sz
         l.clasp_workspace_bytes.argtypes = [C.POINTER(Config)]
         l.clasp_kv_cache_bytes.restype = sz
@@ -95,15 +95,17 @@ def _dtype_code(dtype: str) -> int:
     return CLASP_F32 if dtype == "f32" else CLASP_BF16
 
 
-def clasp_pack_matrix(src: torch.Tensor, dtype: str) -> torch.Tensor:
-    """Returns the packed copy of a row-major [rows][cols] device matrix (see clasp_pack_matrix in clasp.h)."""
+def clasp_pack_matrix(src: torch.Tensor, dtype: str, rope_head_dim: int = 0) -> torch.Tensor:
+    """Returns the packed copy of a row-major [rows][cols] device matrix (see clasp_pack_matrix in clasp.h);
+    rope_head_dim = head_dim for wq and wk, 0 otherwise."""
     rows, cols = src.shape
     code = _dtype_code(dtype)
     want = torch.float32 if code == CLASP_F32 else torch.bfloat16
     if lib().clasp_packed_bytes(rows, cols, code) == 0:
         raise ClaspError(f"matrix {rows}x{cols} cannot be packed for dtype {dtype}")
     dst = torch.empty_like(src)
-    _check(lib().clasp_pack_matrix(_ptr(src, want), _ptr(dst), rows, cols, code, _stream()), "clasp_pack_matrix")
+    _check(lib().clasp_pack_matrix(_ptr(src, want), _ptr(dst), rows, cols, code, rope_head_dim, _stream()),
+           "clasp_pack_matrix")
     return dst
 
 
@@ -136,7 +138,8 @@ class Engine:
     def set_layer(self, l: int, w: Dict[str, torch.Tensor]):
         """Packs one layer's row-major matrices (the row-major copies can be freed by the caller afterwards)."""
         dev = self.device
-        out = {m: clasp_pack_matrix(w[m].to(dev).contiguous(), self.shape.dtype) for m in _MATS}
+        out = {m: clasp_pack_matrix(w[m].to(dev).contiguous(), self.shape.dtype,
+                                    self.shape.head_dim if m in ("wq", "wk") else 0) for m in _MATS}
         out["attn_norm"] = w["attn_norm"].to(dev, torch.float32).contiguous()
         out["mlp_norm"] = w["mlp_norm"].to(dev, torch.float32).contiguous()
         self._layers[l] = out

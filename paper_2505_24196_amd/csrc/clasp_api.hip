@@ -19,11 +19,24 @@ using namespace clasp;
 
 namespace {
 
-constexpr int kGemmWaves = 8;   // wavefronts per GEMM workgroup (they split K)
-constexpr int kGemmDepth = 4;   // fragments per register stage (two stages in flight)
+// Launch shapes of the bf16 GEMMs: wavefronts per workgroup (they split K of one 16-feature tile) and fragments per
+// register stage (two stages are in flight). Chosen per projection from sweeps on the 8B shape.
+#ifndef CLASP_NW_QKV
+#define CLASP_NW_QKV 8
+#define CLASP_NW_OPROJ 8
+#define CLASP_NW_GATEUP 8
+#define CLASP_NW_DOWN 8
+#define CLASP_NW_HEAD 8
+#define CLASP_GEMM_DEPTH 4
+#endif
+#ifndef CLASP_ACT_SPLIT
+#define CLASP_ACT_SPLIT 2  // 2: activations enter the MFMAs as bf16 hi + lo; 1: hi only
+#endif
 constexpr int kAttnWaves = 4;
 constexpr int kMaxSplit = 64;   // most workgroups that share one KV head's prefix
-constexpr int kBlocksPerSplit = 16;  // 32-key blocks per workgroup before the prefix is split further
+#ifndef CLASP_ATTN_BLOCKS_PER_SPLIT
+#define CLASP_ATTN_BLOCKS_PER_SPLIT 8  // 32-key blocks per workgroup before the prefix is split further
+#endif
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -58,6 +71,8 @@ struct clasp_ctx {
     float *a_buf, *h[2], *g[2], *G;
     float* logits;
     float* attn_partial;
+    unsigned* attn_counters;
+    void *q_frag, *k_self, *v_self;
     uint8_t* choice;
     int32_t* tok_tmp;
     // optional per-kernel timing (host-side event objects only; no device memory)
@@ -87,15 +102,20 @@ size_t carve(const clasp_config& c, char* base, clasp_ctx* ctx) {
     auto* g1 = w.take<float>((rows + 1) * d * 4);
     auto* G = w.take<float>(rows * d * 4);
     auto* logits = w.take<float>(rows * (size_t)c.vocab * 4);
-    const size_t nq_pad = rows * (c.n_heads / c.n_kv_heads);
-    auto* part = w.take<float>((size_t)c.n_kv_heads * kMaxSplit * nq_pad * (c.head_dim + 2) * 4);
+    const size_t grp = c.n_heads / c.n_kv_heads;
+    auto* part = w.take<float>((size_t)c.n_kv_heads * (2 * grp + 4) * 16 * kMaxSplit * (c.head_dim + 2) * 4);
+    auto* counters = w.take<unsigned>((size_t)c.n_kv_heads * (2 * grp + 4) * 4);
+    auto* q_frag = w.take<void>(qd * 64 + 4 * (size_t)c.head_dim * 32);  // + 4 query tiles of slack for padded groups
+    auto* k_self = w.take<void>(kvd * 64);
+    auto* v_self = w.take<void>(kvd * 64);
     auto* choice = w.take<uint8_t>((size_t)(c.n_layers + 1) * (rows + 1));
     auto* tok = w.take<int32_t>(256);
     if (ctx) {
         ctx->rope = rope; ctx->qkv = qkv; ctx->op_h = op_h; ctx->op_attn = op_attn; ctx->op_a = op_a;
         ctx->op_act = op_act; ctx->ss_h = ss_h; ctx->ss_a = ss_a; ctx->a_buf = a_buf; ctx->h[0] = h0; ctx->h[1] = h1;
         ctx->g[0] = g0; ctx->g[1] = g1; ctx->G = G; ctx->logits = logits; ctx->attn_partial = part;
-        ctx->choice = choice; ctx->tok_tmp = tok;
+        ctx->choice = choice; ctx->tok_tmp = tok; ctx->attn_counters = counters;
+        ctx->q_frag = q_frag; ctx->k_self = k_self; ctx->v_self = v_self;
     }
     return w.off;
 }
@@ -140,17 +160,18 @@ struct TimerScope {
 };
 
 // ---- GEMM dispatch ---------------------------------------------------------------------------------------------
-template <int EPI>
+template <int EPI, int NW>
 int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kind) {
     const int tiles = g.N / 16;
     TimerScope timer(ctx, kind, st);
     if (ctx->cfg.dtype == CLASP_BF16) {
         if (g.R == 1)
-            hipLaunchKernelGGL((gemm_bf16_kernel<1, kGemmWaves, EPI, kGemmDepth>), dim3(tiles), dim3(kGemmWaves * 64), 0, st, g);
+            hipLaunchKernelGGL((gemm_bf16_kernel<1, NW, EPI, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>), dim3(tiles), dim3(NW * 64), 0, st, g);
         else
-            hipLaunchKernelGGL((gemm_bf16_kernel<2, kGemmWaves, EPI, kGemmDepth>), dim3(tiles), dim3(kGemmWaves * 64), 0, st, g);
+            hipLaunchKernelGGL((gemm_bf16_kernel<2, NW, EPI, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>), dim3(tiles), dim3(NW * 64), 0, st, g);
     } else {
-        hipLaunchKernelGGL((gemm_f32_kernel<EPI>), dim3(tiles), dim3(256), 0, st, g);
+        if constexpr (EPI == kEpiQkv) return CLASP_E_UNSUPPORTED;
+        else hipLaunchKernelGGL((gemm_f32_kernel<EPI>), dim3(tiles), dim3(256), 0, st, g);
     }
     CLASP_LAUNCH_CHECK();
     return CLASP_OK;
@@ -177,9 +198,11 @@ int launch_attention(const clasp_ctx* ctx, int layer, int n, int R, int mode, in
     a.Kc = ctx->k_cache + (size_t)layer * ctx->kv_layer_bytes;
     a.Vt = ctx->v_cache + (size_t)layer * ctx->kv_layer_bytes;
     a.t_max = c.max_seq; a.out_op = ctx->op_attn; a.R = R;
-    a.partial = ctx->attn_partial; a.nq_pad = kMaxRows * ctx->group;
+    a.partial = ctx->attn_partial; a.counters = ctx->attn_counters;
     a.scale = 1.0f / sqrtf((float)c.head_dim);
+    a.q_frag = ctx->q_frag; a.k_self = ctx->k_self; a.v_self = ctx->v_self;
     a.n_split = 1;
+    TimerScope timer(ctx, CLASP_KERNEL_ATTENTION, st);
     if (c.dtype == CLASP_F32) {
         const size_t lds = (size_t)(c.head_dim + pos0 + 32) * sizeof(float);
         hipLaunchKernelGGL(attn_f32_kernel, dim3(c.n_heads, n), dim3(256), lds, st, a);
@@ -188,19 +211,12 @@ int launch_attention(const clasp_ctx* ctx, int layer, int n, int R, int mode, in
     }
     const int nQ = n * ctx->group, ntq = (nQ + 15) / 16;
     const int nt = ntq < 4 ? ntq : 4, qgroups = (ntq + nt - 1) / nt;
-    const int nblk = (pos0 + 31) / 32;
-    int split = (nblk + kBlocksPerSplit - 1) / kBlocksPerSplit;
+    const int nblk = (pos0 + (mode ? n : 0) + 31) / 32;
+    int split = (nblk + CLASP_ATTN_BLOCKS_PER_SPLIT - 1) / CLASP_ATTN_BLOCKS_PER_SPLIT;
     split = split < 1 ? 1 : (split > kMaxSplit ? kMaxSplit : split);
     a.n_split = split;
     const dim3 grid(c.n_kv_heads, qgroups, split);
-    TimerScope timer(ctx, CLASP_KERNEL_ATTENTION, st);
-    const int rc = c.head_dim == 64 ? launch_attn_bf16<64>(a, nt, grid, st) : launch_attn_bf16<128>(a, nt, grid, st);
-    if (rc) return rc;
-    if (split > 1) {
-        hipLaunchKernelGGL((attn_combine_kernel<kDtBf16>), dim3(c.n_kv_heads, nQ), dim3(c.head_dim), 0, st, a);
-        CLASP_LAUNCH_CHECK();
-    }
-    return CLASP_OK;
+    return c.head_dim == 64 ? launch_attn_bf16<64>(a, nt, grid, st) : launch_attn_bf16<128>(a, nt, grid, st);
 }
 
 // One decoder layer on n rows. The rows' fp32 values are at h_in ([n][d]); their GEMM operand (times the layer's
@@ -218,7 +234,19 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
         g.A = ctx->op_h; g.n_rows = n; g.N = ctx->qkv_dim; g.K = d; g.R = R;
         g.ss_parts = ctx->ss_h; g.n_parts = d / 16; g.inv_dim = 1.0f / d; g.eps = c.rms_eps;
         g.out = ctx->qkv; g.ldo = ctx->qkv_dim;
-        if ((rc = launch_gemm<kEpiScale>(ctx, g, st, CLASP_KERNEL_QKV))) return rc;
+        if (c.dtype == CLASP_BF16) {
+            QkvOut& o = g.qkv;
+            o.n_heads = c.n_heads; o.n_kv_heads = c.n_kv_heads; o.head_dim = c.head_dim;
+            o.pos0 = pos0; o.mode = mode; o.t_max = c.max_seq; o.rope = ctx->rope;
+            o.q_scale = 1.4426950408889634f / sqrtf((float)c.head_dim);
+            o.q_frag = ctx->q_frag;
+            o.k_cache = ctx->k_cache + (size_t)l * ctx->kv_layer_bytes;
+            o.v_cache = ctx->v_cache + (size_t)l * ctx->kv_layer_bytes;
+            o.k_self = ctx->k_self; o.v_self = ctx->v_self;
+            if ((rc = launch_gemm<kEpiQkv, CLASP_NW_QKV>(ctx, g, st, CLASP_KERNEL_QKV))) return rc;
+        } else {
+            if ((rc = launch_gemm<kEpiScale, 8>(ctx, g, st, CLASP_KERNEL_QKV))) return rc;
+        }
     }
     if ((rc = launch_attention(ctx, l, n, R, mode, pos0, st))) return rc;
     {
@@ -227,7 +255,7 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
         g.A = ctx->op_attn; g.n_rows = n; g.N = d; g.K = ctx->q_dim; g.R = R;
         g.out = ctx->a_buf; g.ldo = d; g.resid = h_in; g.ldr = d;
         g.next_op = ctx->op_a; g.next_gain = ctx->mlp_norm[l]; g.next_ss = ctx->ss_a;
-        if ((rc = launch_gemm<kEpiResid>(ctx, g, st, CLASP_KERNEL_O_PROJ))) return rc;
+        if ((rc = launch_gemm<kEpiResid, CLASP_NW_OPROJ>(ctx, g, st, CLASP_KERNEL_O_PROJ))) return rc;
     }
     {
         GemmArgs g{};
@@ -235,7 +263,7 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
         g.A = ctx->op_a; g.n_rows = n; g.N = F; g.K = d; g.R = R;
         g.ss_parts = ctx->ss_a; g.n_parts = d / 16; g.inv_dim = 1.0f / d; g.eps = c.rms_eps;
         g.next_op = ctx->op_act;
-        if ((rc = launch_gemm<kEpiSwiglu>(ctx, g, st, CLASP_KERNEL_GATE_UP))) return rc;
+        if ((rc = launch_gemm<kEpiSwiglu, CLASP_NW_GATEUP>(ctx, g, st, CLASP_KERNEL_GATE_UP))) return rc;
     }
     {
         GemmArgs g{};
@@ -244,7 +272,7 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
         g.out = h_out; g.ldo = d; g.resid = ctx->a_buf; g.ldr = d;
         g.next_op = next_op; g.next_gain = next_gain; g.next_ss = next_ss;
         g.capture = capture; g.ldc = d;
-        if ((rc = launch_gemm<kEpiResid>(ctx, g, st, CLASP_KERNEL_DOWN))) return rc;
+        if ((rc = launch_gemm<kEpiResid, CLASP_NW_DOWN>(ctx, g, st, CLASP_KERNEL_DOWN))) return rc;
     }
     return CLASP_OK;
 }
@@ -272,7 +300,7 @@ int run_head(const clasp_ctx* ctx, int n, int R, float* logits, int32_t* argmax_
     g.ss_parts = ctx->ss_h; g.n_parts = c.d_model / 16; g.inv_dim = 1.0f / c.d_model; g.eps = c.rms_eps;
     g.out = logits; g.ldo = c.vocab;
     int rc;
-    if ((rc = launch_gemm<kEpiScale>(ctx, g, st, CLASP_KERNEL_LM_HEAD))) return rc;
+    if ((rc = launch_gemm<kEpiScale, CLASP_NW_HEAD>(ctx, g, st, CLASP_KERNEL_LM_HEAD))) return rc;
     if (argmax_out || margin_out || prob_out) {
         hipLaunchKernelGGL(argmax_kernel, dim3(n), dim3(1024), 0, st, logits, c.vocab, argmax_out, margin_out, prob_out);
         CLASP_LAUNCH_CHECK();
@@ -302,8 +330,9 @@ size_t clasp_packed_bytes(int rows, int cols, int dtype) {
     return 0;
 }
 
-int clasp_pack_matrix(const void* src, void* dst, int rows, int cols, int dtype, void* stream) {
-    if (!src || !dst || src == dst) return CLASP_E_INVALID_ARG;
+int clasp_pack_matrix(const void* src, void* dst, int rows, int cols, int dtype, int rope_head_dim, void* stream) {
+    if (!src || !dst || src == dst || rope_head_dim < 0) return CLASP_E_INVALID_ARG;
+    if (rope_head_dim && (rope_head_dim % 16 || rows % rope_head_dim)) return CLASP_E_UNSUPPORTED;
     const size_t bytes = clasp_packed_bytes(rows, cols, dtype);
     if (!bytes) return CLASP_E_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -312,7 +341,7 @@ int clasp_pack_matrix(const void* src, void* dst, int rows, int cols, int dtype,
         return CLASP_OK;
     }
     hipLaunchKernelGGL(pack_bf16_kernel, dim3(2048), dim3(256), 0, st, reinterpret_cast<const u32x4*>(src),
-                       reinterpret_cast<u32x4*>(dst), rows, cols);
+                       reinterpret_cast<u32x4*>(dst), rows, cols, rope_head_dim);
     CLASP_LAUNCH_CHECK();
     return CLASP_OK;
 }
@@ -488,8 +517,9 @@ int clasp_dp_select(clasp_ctx* ctx, const float* states, size_t layer_stride, in
     if (!ctx || !states || !mask_out) return CLASP_E_INVALID_ARG;
     const clasp_config& c = ctx->cfg;
     const int L = c.n_layers, d = c.d_model;
-    if (M < 0 || M > L || M > c.max_rows || pos < 0 || pos > c.max_seq || layer_stride < (size_t)d)
+    if (M < 0 || M > L || M > c.max_rows || pos < 0 || pos >= c.max_seq || layer_stride < (size_t)d)
         return CLASP_E_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(states) & 15) || (layer_stride & 3)) return CLASP_E_INVALID_ARG;  // float4 loads
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int R = M > 16 ? 2 : 1;
     uint8_t* choice = choice_out ? choice_out : ctx->choice;
@@ -515,9 +545,9 @@ int clasp_dp_select(clasp_ctx* ctx, const float* states, size_t layer_stride, in
         s.scores = score_out; s.choice = choice;
         const int cells_i = ((i < M) ? i : M) + 1;
         if (c.dtype == CLASP_BF16)
-            hipLaunchKernelGGL((dp_select_kernel<kDtBf16>), dim3(cells_i), dim3(256), 0, st, s);
+            hipLaunchKernelGGL((dp_select_kernel<kDtBf16>), dim3(cells_i), dim3(1024), 0, st, s);
         else
-            hipLaunchKernelGGL((dp_select_kernel<kDtF32>), dim3(cells_i), dim3(256), 0, st, s);
+            hipLaunchKernelGGL((dp_select_kernel<kDtF32>), dim3(cells_i), dim3(1024), 0, st, s);
         CLASP_LAUNCH_CHECK();
     }
     hipLaunchKernelGGL(dp_backtrack_kernel, dim3(2), dim3(256), 0, st, choice, L, M, mask_out, ctx->g[L & 1],

@@ -1,27 +1,27 @@
 // Grouped-query attention of the candidate / verify / draft rows over the layer's shared KV cache.
 //
-// All rows of a launch read the cached prefix (positions 0..pos0-1) ONCE: the rows times the query heads of one KV
-// group form the N dimension of S^T = K . Q^T, so a key fragment loaded from HBM serves every row (this is the
-// paper's Sec. 3.6 point: the DP's candidate states share one KV cache instead of duplicating it). The rows' own
-// keys/values form a small "self block" with a mode-dependent mask:
-//   mode 0 (DP candidates): every row sits at position pos0 and sees, besides the prefix, only its own key/value;
-//                           nothing is written to the cache.
-//   mode 1 (verify / draft): row r sits at pos0 + r, sees self rows 0..r (causal) and its key/value is written to
-//                           the cache at pos0 + r.
-// The rotary embedding is applied here (queries while staging them, keys before they are cached).
+// All rows of a launch read the cached prefix ONCE: the rows times the query heads of one KV group form the N
+// dimension of S^T = K . Q^T, so a key fragment loaded from HBM serves every row (this is the paper's Sec. 3.6
+// point: the DP's candidate states share one KV cache instead of duplicating it).
+//   mode 0 (DP candidates): every row sits at position pos0 and sees cache positions 0..pos0-1 plus its own
+//                           key/value, which live in a small per-launch self block; the cache is not touched.
+//   mode 1 (verify / draft): row r sits at pos0 + r; its key/value is in the cache at that position already (the
+//                           projection kernel wrote it) and it sees cache positions 0..pos0+r.
 //
-// bf16 kernel: flash-decoding on MFMA. Keys are the M dimension of S^T (a lane then holds 4 keys x 1 query, and the
-// two 16-key tiles of a 32-key block are interleaved so that the exponentiated scores of a lane are already the
-// 8-key B fragment of O^T = V^T . P^T); V is cached transposed so that its fragments are 16-byte loads too.
-// Wavefronts of a workgroup take 32-key blocks round-robin and are merged through LDS in a fixed order; several
-// workgroups may split a long prefix (grid.z) and are merged by attn_combine_kernel.
+// bf16 kernel: flash-decoding on MFMA. Queries arrive rotated, scaled and in MFMA operand order from the q/k/v
+// projection's epilogue. Keys are the M dimension of S^T (a lane then holds 4 keys x 1 query, and the two 16-key
+// tiles of a 32-key block are interleaved so that the exponentiated scores of a lane are already the 8-key B
+// fragment of O^T = V^T . P^T); V is cached transposed so that its fragments are 16-byte loads too. Wavefronts of a
+// workgroup take 32-key blocks round-robin and are merged through LDS in a fixed order; several workgroups may split
+// a long prefix (grid.z), the last one to finish merges their partial results in split order.
+// fp32 kernel: plain loops, rotary embedding applied in the kernel, exact softmax over all visible keys.
 #pragma once
 #include "clasp_common.h"
 
 namespace clasp {
 
 struct AttnArgs {
-    const float* qkv;  // [rows][ld_qkv]: q heads | k heads | v heads, un-rotated
+    const float* qkv;  // fp32 path: [rows][ld_qkv]: q heads | k heads | v heads, un-rotated
     int ld_qkv;
     int n_rows, n_heads, n_kv_heads, head_dim;
     int pos0, mode;
@@ -32,9 +32,13 @@ struct AttnArgs {
     void* out_op;  // operand of the output projection (K = n_heads*head_dim)
     int R;
     int n_split;
-    float* partial;  // [n_kv_heads][n_split][nq_pad][head_dim+2] when n_split > 1
-    int nq_pad;
-    float scale;  // 1/sqrt(head_dim)
+    float* partial;      // [n_kv_heads][query groups][n_split][NT*16][head_dim+2] when n_split > 1
+    unsigned* counters;  // [n_kv_heads * query groups], zero between launches
+    float scale;         // 1/sqrt(head_dim)
+    // bf16 path: written by the q/k/v projection's epilogue
+    const void* q_frag;
+    const void* k_self;  // [n_kv_heads][32][head_dim]   (DP candidates' own keys)
+    const void* v_self;  // [n_kv_heads][head_dim][32]
 };
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -102,82 +106,41 @@ __device__ __forceinline__ void attn_block(AttnState<HD, NT>& st, const bf16x8 (
     }
 }
 
+// q_frag: queries of one KV head (query index qi = row*group + head%group) as MFMA B fragments,
+// [kv_head][qi/16][x/32][lane = ((x%32)/8)*16 + qi%16][x%8], written by the q/k/v projection's epilogue.
 template <int HD, int NT, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(AttnArgs a) {
-    constexpr int KK = HD / 32, CT = HD / 16, HALF = HD / 2;
-    // Staging tiles (queries, self keys, self values) and the merge buffer are live at different times and share
-    // one LDS region. Row strides are padded (+8 bf16, +1 float) so that rows land in different LDS banks.
-    constexpr int kStageBytes = (NT * 16 * (HD + 8) + 32 * (HD + 8) + HD * 40) * 2;
-    constexpr int kMergeBytes = NW * HD * 17 * 4;
-    __shared__ __attribute__((aligned(16))) unsigned char lds_raw[kStageBytes > kMergeBytes ? kStageBytes : kMergeBytes];
-    typedef bf16 (*QsT)[HD + 8];
-    typedef bf16 (*VtsT)[40];
-    typedef float (*MgT)[HD][17];
-    QsT Qs = reinterpret_cast<QsT>(lds_raw);
-    QsT Ks = reinterpret_cast<QsT>(lds_raw + NT * 16 * (HD + 8) * 2);
-    VtsT Vts = reinterpret_cast<VtsT>(lds_raw + (NT * 16 + 32) * (HD + 8) * 2);
-    MgT mg_o = reinterpret_cast<MgT>(lds_raw);
-    __shared__ float mg_m[NW][16], mg_l[NW][16];
+    constexpr int KK = HD / 32, CT = HD / 16;
+    __shared__ float mg_o[NW][HD][17];  // +1: rows land in different LDS banks
+    __shared__ float mg_m[NW][16], mg_l[NW][16], mg_f[NW][16];
+    __shared__ int s_last;
     const int kvh = blockIdx.x, qg = blockIdx.y, split = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int G = a.n_heads / a.n_kv_heads, nQ = a.n_rows * G;
     const int q_base = qg * NT * 16;
-    const bool last = (split == a.n_split - 1);
-    const float qscale = a.scale * kLog2e;
-    bf16* Kc = reinterpret_cast<bf16*>(a.Kc);
-    bf16* Vt = reinterpret_cast<bf16*>(a.Vt);
+    const int m16 = lane & 15, q4 = lane >> 4;
+    const bf16* Kc = reinterpret_cast<const bf16*>(a.Kc);
+    const bf16* Vt = reinterpret_cast<const bf16*>(a.Vt);
 
-    for (int idx = tid; idx < NT * 16 * HALF; idx += NW * 64) {
-        const int ql = idx / HALF, e = idx % HALF, qi = q_base + ql;
-        float v0 = 0.f, v1 = 0.f;
-        if (qi < nQ) {
-            const int row = qi / G, h = kvh * G + qi % G;
-            const int pos = a.pos0 + (a.mode ? row : 0);
-            const float* qp = a.qkv + (size_t)row * a.ld_qkv + h * HD;
-            const float x0 = qp[e], x1 = qp[e + HALF];
-            const float2 cs = a.rope[(size_t)pos * HALF + e];
-            v0 = (x0 * cs.x - x1 * cs.y) * qscale;
-            v1 = (x1 * cs.x + x0 * cs.y) * qscale;
-        }
-        Qs[ql][e] = to_bf16(v0);
-        Qs[ql][e + HALF] = to_bf16(v1);
-    }
-    if (last) {
-        for (int idx = tid; idx < 32 * HALF; idx += NW * 64) {
-            const int r = idx / HALF, e = idx % HALF;
-            bf16 k0 = to_bf16(0.f), k1 = k0, v0 = k0, v1 = k0;
-            if (r < a.n_rows) {
-                const int pos = a.pos0 + (a.mode ? r : 0);
-                const float* kp = a.qkv + (size_t)r * a.ld_qkv + (a.n_heads + kvh) * HD;
-                const float* vp = kp + a.n_kv_heads * HD;
-                const float x0 = kp[e], x1 = kp[e + HALF];
-                const float2 cs = a.rope[(size_t)pos * HALF + e];
-                k0 = to_bf16(x0 * cs.x - x1 * cs.y);
-                k1 = to_bf16(x1 * cs.x + x0 * cs.y);
-                v0 = to_bf16(vp[e]);
-                v1 = to_bf16(vp[e + HALF]);
-                if (a.mode && qg == 0) {
-                    bf16* kc = Kc + ((size_t)kvh * a.t_max + pos) * HD;
-                    kc[e] = k0;
-                    kc[e + HALF] = k1;
-                    Vt[((size_t)kvh * HD + e) * a.t_max + pos] = v0;
-                    Vt[((size_t)kvh * HD + e + HALF) * a.t_max + pos] = v1;
-                }
-            }
-            Ks[r][e] = k0;
-            Ks[r][e + HALF] = k1;
-            Vts[e][r] = v0;
-            Vts[e + HALF][r] = v1;
-        }
-    }
-    __syncthreads();
-
+    // query fragments straight from HBM/L2 (already rotated, scaled and in B-operand order)
     bf16x8 qf[NT][KK];
+    {
+        const u32x4* qp = reinterpret_cast<const u32x4*>(a.q_frag) + ((size_t)kvh * (2 * G) + qg * NT) * KK * 64 + lane;
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk)
-            qf[t][kk] = *reinterpret_cast<const bf16x8*>(&Qs[t * 16 + (lane & 15)][kk * 32 + (lane >> 4) * 8]);
+            for (int kk = 0; kk < KK; ++kk) qf[t][kk] = as_bf16x8(qp[(t * KK + kk) * 64]);
+    }
+    // visibility: query qi of row r sees cache keys <= limit (verify/draft: pos0 + r, its own position, whose
+    // key/value the projection kernel has just written; DP candidates: pos0 - 1) and, for DP candidates, its own
+    // entry of the self block
+    int limit[NT], qrow[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int qi = q_base + t * 16 + m16;
+        qrow[t] = qi < nQ ? qi / G : -1;
+        limit[t] = qi < nQ ? (a.mode ? a.pos0 + qrow[t] : a.pos0 - 1) : -1;
+    }
 
     AttnState<HD, NT> st;
 #pragma unroll
@@ -188,15 +151,15 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(AttnArgs a) {
         for (int c = 0; c < CT; ++c) st.o[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    const int nblk = (a.pos0 + 31) >> 5;
+    const int n_cache = a.pos0 + (a.mode ? a.n_rows : 0);  // cache positions any row may see
+    const int nblk = (n_cache + 31) >> 5;
     const int b0 = (int)(((long long)nblk * split) / a.n_split), b1 = (int)(((long long)nblk * (split + 1)) / a.n_split);
-    const int m16 = lane & 15, q4 = lane >> 4;
     for (int blk = b0 + wave; blk < b1; blk += NW) {
         const int kb = blk << 5;
         attn_block<HD, NT>(
             st, qf,
             [&](int u, int kk) {
-                const int key = min(kb + (m16 >> 2) * 8 + u * 4 + (m16 & 3), a.pos0 - 1);
+                const int key = min(kb + (m16 >> 2) * 8 + u * 4 + (m16 & 3), n_cache - 1);
                 const u32x4* kp = reinterpret_cast<const u32x4*>(Kc + ((size_t)kvh * a.t_max + key) * HD);
                 return as_bf16x8(load_stream(kp + kk * 4 + q4));
             },
@@ -204,23 +167,23 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(AttnArgs a) {
                 const u32x4* vp = reinterpret_cast<const u32x4*>(Vt + ((size_t)kvh * HD + c * 16 + m16) * a.t_max + kb);
                 return as_bf16x8(load_stream(vp + q4));
             },
-            [&](int u, int r, int) { return kb + q4 * 8 + u * 4 + r < a.pos0; });
+            [&](int u, int r, int t) { return kb + q4 * 8 + u * 4 + r <= limit[t]; });
     }
-    if (last && wave == (b1 - b0) % NW) {
+    if (!a.mode && split == a.n_split - 1 && wave == (b1 - b0) % NW) {  // DP candidates: own key/value only
+        const bf16* Ks = reinterpret_cast<const bf16*>(a.k_self) + (size_t)kvh * 32 * HD;
+        const bf16* Vs = reinterpret_cast<const bf16*>(a.v_self) + (size_t)kvh * HD * 32;
         attn_block<HD, NT>(
             st, qf,
             [&](int u, int kk) {
-                return *reinterpret_cast<const bf16x8*>(&Ks[(m16 >> 2) * 8 + u * 4 + (m16 & 3)][kk * 32 + q4 * 8]);
+                const int kr = (m16 >> 2) * 8 + u * 4 + (m16 & 3);
+                return as_bf16x8(*reinterpret_cast<const u32x4*>(Ks + (size_t)kr * HD + kk * 32 + q4 * 8));
             },
-            [&](int c) { return *reinterpret_cast<const bf16x8*>(&Vts[c * 16 + m16][q4 * 8]); },
-            [&](int u, int r, int t) {
-                const int kr = q4 * 8 + u * 4 + r, qi = q_base + t * 16 + m16, qrow = qi / G;
-                return kr < a.n_rows && qi < nQ && (a.mode ? kr <= qrow : kr == qrow);
-            });
+            [&](int c) { return as_bf16x8(*reinterpret_cast<const u32x4*>(Vs + (size_t)(c * 16 + m16) * 32 + q4 * 8)); },
+            [&](int u, int r, int t) { return q4 * 8 + u * 4 + r == qrow[t]; });
     }
 
-    __syncthreads();  // staging tiles are dead from here on; their LDS becomes the merge buffer
     // merge the wavefronts' running (max, sum, O^T), one query tile at a time, fixed order
+    float* part = a.partial + ((((size_t)kvh * gridDim.y + qg) * a.n_split + split) * NT * 16) * (HD + 2);
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         float l = st.l[t];
@@ -235,55 +198,72 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) mg_o[wave][c * 16 + q4 * 4 + r][m16] = st.o[t][c][r];
         __syncthreads();
+        if (tid < 16) {  // per query: global max, rescale factors, total sum
+            float mstar = -INFINITY;
+            for (int w = 0; w < NW; ++w) mstar = fmaxf(mstar, mg_m[w][tid]);
+            float L = 0.f;
+            for (int w = 0; w < NW; ++w) {
+                const float mw = mg_m[w][tid];
+                const float f = (mw == -INFINITY) ? 0.f : exp2f(mw - mstar);
+                mg_f[w][tid] = f;
+                L += f * mg_l[w][tid];
+            }
+            mg_m[0][tid] = mstar;
+            mg_l[0][tid] = L;
+        }
+        __syncthreads();
         for (int idx = tid; idx < HD * 16; idx += NW * 64) {
             const int e = idx >> 4, j = idx & 15, qi = q_base + t * 16 + j;
             if (qi < nQ) {
-                float mstar = -INFINITY;
-                for (int w = 0; w < NW; ++w) mstar = fmaxf(mstar, mg_m[w][j]);
-                float L = 0.f, O = 0.f;
-                for (int w = 0; w < NW; ++w) {
-                    const float mw = mg_m[w][j];
-                    const float f = (mw == -INFINITY) ? 0.f : exp2f(mw - mstar);
-                    L += f * mg_l[w][j];
-                    O += f * mg_o[w][e][j];
-                }
+                float O = 0.f;
+                for (int w = 0; w < NW; ++w) O += mg_f[w][j] * mg_o[w][e][j];
                 if (a.n_split == 1) {
                     const int row = qi / G, h = kvh * G + qi % G;
-                    store_operand<kDtBf16>(a.out_op, a.R, 0, row, h * HD + e, O / L);
+                    store_operand<kDtBf16>(a.out_op, a.R, 0, row, h * HD + e, O / mg_l[0][j]);
                 } else {
-                    float* p = a.partial + (((size_t)kvh * a.n_split + split) * a.nq_pad + qi) * (HD + 2);
+                    float* p = part + (size_t)(t * 16 + j) * (HD + 2);
                     p[e] = O;
                     if (e == 0) {
-                        p[HD] = mstar;
-                        p[HD + 1] = L;
+                        p[HD] = mg_m[0][j];
+                        p[HD + 1] = mg_l[0][j];
                     }
                 }
             }
         }
         __syncthreads();
     }
-}
+    if (a.n_split == 1) return;
 
-// Merges the n_split partial results of one query (fixed order) and writes the output-projection operand.
-template <int DT>
-__global__ void attn_combine_kernel(AttnArgs a) {
-    const int kvh = blockIdx.x, qi = blockIdx.y, HD = a.head_dim;
-    const int G = a.n_heads / a.n_kv_heads;
-    const float* base = a.partial + (((size_t)kvh * a.n_split) * a.nq_pad + qi) * (HD + 2);
-    const size_t stride = (size_t)a.nq_pad * (HD + 2);
-    float mstar = -INFINITY;
-    for (int s = 0; s < a.n_split; ++s) mstar = fmaxf(mstar, base[s * stride + HD]);
-    for (int e = threadIdx.x; e < HD; e += blockDim.x) {
+    // several workgroups shared this (kv head, query group): the last one to arrive merges their partial results
+    // in split order (the result does not depend on which workgroup happens to be last)
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        const unsigned old = atomicAdd(a.counters + kvh * gridDim.y + qg, 1u);
+        s_last = (old == (unsigned)a.n_split - 1);
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    const float* base = a.partial + (((size_t)kvh * gridDim.y + qg) * a.n_split * NT * 16) * (HD + 2);
+    const size_t sstride = (size_t)NT * 16 * (HD + 2);
+    for (int idx = tid; idx < NT * 16 * HD; idx += NW * 64) {
+        const int ql = idx / HD, e = idx % HD, qi = q_base + ql;
+        if (qi >= nQ) continue;
+        const float* pq = base + (size_t)ql * (HD + 2);
+        float mstar = -INFINITY;
+        for (int s = 0; s < a.n_split; ++s) mstar = fmaxf(mstar, pq[s * sstride + HD]);
         float L = 0.f, O = 0.f;
         for (int s = 0; s < a.n_split; ++s) {
-            const float ms = base[s * stride + HD];
+            const float ms = pq[s * sstride + HD];
             const float f = (ms == -INFINITY) ? 0.f : exp2f(ms - mstar);
-            L += f * base[s * stride + HD + 1];
-            O += f * base[s * stride + e];
+            L += f * pq[s * sstride + HD + 1];
+            O += f * pq[s * sstride + e];
         }
         const int row = qi / G, h = kvh * G + qi % G;
-        store_operand<DT>(a.out_op, a.R, a.n_heads * HD, row, h * HD + e, O / L);
+        store_operand<kDtBf16>(a.out_op, a.R, 0, row, h * HD + e, O / L);
     }
+    if (tid == 0) a.counters[kvh * gridDim.y + qg] = 0u;  // ready for the next launch (stream-ordered)
 }
 
 // fp32 path: one workgroup per (query head, row); plain loops, exact softmax over all visible keys.

@@ -17,13 +17,15 @@ constexpr int kDtF32 = 0, kDtBf16 = 1;
 
 // ---- bf16 activation operand layout -----------------------------------------------------------------------
 // An activation matrix X[rows <= 16*R][K] that a GEMM will contract over K is kept in HBM as MFMA operand
-// fragments: for k-step s (32 consecutive k) and row group rg (16 rows) one fragment of 64 lanes x 8 bf16, lane
-// (q*16 + r) holding X[rg*16 + r][s*32 + q*8 .. +8]. A wavefront fetches one fragment with one 16-byte-per-lane
-// load and feeds it to v_mfma_f32_16x16x32_bf16 unchanged. Weights use the same tile shape with the 16 output
+// fragments: for k-step s (32 consecutive k) and row group rg (16 rows) one fragment of 64 lanes, lane (q*16 + r)
+// holding X[rg*16 + r][s*32 + q*8 .. +8] twice: 8 bf16 "hi" = round(x) followed by 8 bf16 "lo" = round(x - hi).
+// A wavefront fetches a fragment with two 16-byte-per-lane loads (32 contiguous bytes per lane) and feeds hi and
+// lo to v_mfma_f32_16x16x32_bf16 unchanged; hi + lo carries 16 mantissa bits, so the activations lose next to
+// nothing against fp32 while the weights stay bf16. Weights use the same tile shape (one plane) with the 16 output
 // features of a column tile in place of the 16 rows (see pack kernel).
 __device__ __forceinline__ size_t frag_elem_offset(int R, int row, int k) {
     const int s = k >> 5, q = (k >> 3) & 3, e = k & 7, rg = row >> 4, r = row & 15;
-    return ((((size_t)s * R + rg) * 64) + q * 16 + r) * 8 + e;
+    return ((((size_t)s * R + rg) * 64) + q * 16 + r) * 16 + e;  // hi element; lo sits 8 elements further
 }
 
 __device__ __forceinline__ bf16 to_bf16(float x) { return static_cast<bf16>(x); }  // round-to-nearest-even
@@ -69,13 +71,35 @@ __device__ __forceinline__ float block_sum(float v, float* scratch) {
     return t;
 }
 
-// Store one activation element for a later GEMM: bf16 fragment order, or fp32 row-major [row][ld].
+// Store one activation element for a later GEMM: bf16 hi/lo fragment order, or fp32 row-major [row][ld].
 template <int DT>
 __device__ __forceinline__ void store_operand(void* buf, int R, int ld, int row, int k, float v) {
     if constexpr (DT == kDtBf16) {
-        reinterpret_cast<bf16*>(buf)[frag_elem_offset(R, row, k)] = to_bf16(v);
+        bf16* p = reinterpret_cast<bf16*>(buf) + frag_elem_offset(R, row, k);
+        const bf16 hi = to_bf16(v);
+        p[0] = hi;
+        p[8] = to_bf16(v - from_bf16(hi));
     } else {
         reinterpret_cast<float*>(buf)[(size_t)row * ld + k] = v;
+    }
+}
+
+// Four consecutive elements k..k+3 (k % 4 == 0) of one row.
+template <int DT>
+__device__ __forceinline__ void store_operand4(void* buf, int R, int ld, int row, int k, f32x4 v) {
+    if constexpr (DT == kDtBf16) {
+        typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+        bf16* p = reinterpret_cast<bf16*>(buf) + frag_elem_offset(R, row, k);
+        bf16x4 hi, lo;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            hi[i] = to_bf16(v[i]);
+            lo[i] = to_bf16(v[i] - from_bf16(hi[i]));
+        }
+        *reinterpret_cast<bf16x4*>(p) = hi;
+        *reinterpret_cast<bf16x4*>(p + 8) = lo;
+    } else {
+        *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(buf) + (size_t)row * ld + k) = v;
     }
 }
 

@@ -6,27 +6,43 @@
 //
 // bf16 kernel: one workgroup per tile of 16 output features; its NW wavefronts split K and each streams its slice
 // of the tile (contiguous in the packed weight order) with a register double buffer of P fragments; the activation
-// fragments come from L2 in the same order. Partial tiles are reduced through LDS in a fixed order (deterministic,
-// independent of the number of rows), then the first R wavefronts run the epilogue.
+// fragments (hi and lo planes) come from L2 in the same order. Partial tiles are reduced through LDS in a fixed
+// order (deterministic, independent of the number of rows), then the first R wavefronts run the epilogue.
 //
-// Epilogues (they produce what the NEXT kernel consumes, so that no separate norm / activation kernels exist):
-//   kEpiScale   out = acc * rstd(row)                       (q/k/v projection, lm_head; RMSNorm's 1/rms factor
+// Epilogues (they produce what the NEXT kernel consumes, so that no separate norm / rotary / activation kernels
+// exist):
+//   kEpiScale   out = acc * rstd(row)                       (lm_head; fp32 path q/k/v; RMSNorm's 1/rms factor
 //                                                            commutes with the contraction, its gains are already
 //                                                            folded into the activation fragments)
 //   kEpiResid   out = resid + acc; optionally a copy (hidden-state capture), the next GEMM's operand
 //               (out * gain, in operand layout) and per-tile partial sums of out^2 for the next 1/rms
 //   kEpiSwiglu  two weight streams (gate, up): operand of the down projection = silu(g*rstd) * (u*rstd)
+//   kEpiQkv     q/k/v projection for the MFMA attention kernel: scales by rstd, applies the rotary embedding to q
+//               and k (the packed wq/wk put the two halves of a rotary pair into one 16-feature tile), and writes
+//               q as ready-made MFMA fragments, k and v into the KV cache (verify/draft rows) or into the small
+//               per-launch self block (DP candidates, which must not touch the cache)
 #pragma once
 #include "clasp_common.h"
 
 namespace clasp {
 
-constexpr int kEpiScale = 0, kEpiResid = 1, kEpiSwiglu = 2;
+constexpr int kEpiScale = 0, kEpiResid = 1, kEpiSwiglu = 2, kEpiQkv = 3;
+
+struct QkvOut {
+    int n_heads, n_kv_heads, head_dim, pos0, mode, t_max;
+    const float2* rope;  // [max_seq][head_dim/2] (cos, sin)
+    float q_scale;       // softmax scale * log2(e), folded into q
+    void* q_frag;        // [n_kv_heads][2*group][head_dim/32][64][8] bf16 (see attention kernel)
+    void* k_cache;       // this layer, [n_kv_heads][t_max][head_dim]
+    void* v_cache;       // this layer, [n_kv_heads][head_dim][t_max]
+    void* k_self;        // [n_kv_heads][32][head_dim]
+    void* v_self;        // [n_kv_heads][head_dim][32]
+};
 
 struct GemmArgs {
     const void* W[3];   // up to three matrices stacked along N (q|k|v); kEpiSwiglu: W[0] = gate, W[1] = up
     int tile_end[3];    // exclusive end tile (16 features) of each stacked matrix
-    const void* A;      // activation operand: bf16 fragments, or fp32 row-major [rows][K]
+    const void* A;      // activation operand: bf16 hi/lo fragments, or fp32 row-major [rows][K]
     int n_rows, N, K, R;
     const float* ss_parts;  // [n_parts][32] partial sums of squares of the un-normalised input rows
     int n_parts;
@@ -40,14 +56,23 @@ struct GemmArgs {
     float* next_ss;          // [N/16][32] partial sums of squares of `out`, may be null
     float* capture;          // optional copy of out, [rows][ldc]
     int ldc;
+    QkvOut qkv;  // kEpiQkv only
 };
 
 // rstd[row] = 1 / sqrt(sum_p parts[p][row] * inv_dim + eps), fixed summation order. Needs blockDim % 32 == 0.
 __device__ __forceinline__ void compute_rstd(const GemmArgs& g, float* rstd_s, float* tmp /* [blockDim] */) {
     const int row = threadIdx.x & 31, sub = threadIdx.x >> 5, nsub = blockDim.x >> 5;
-    float s = 0.f;
-    for (int p = sub; p < g.n_parts; p += nsub) s += g.ss_parts[(size_t)p * kMaxRows + row];
-    tmp[threadIdx.x] = s;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    int p = sub;
+    for (; p + 3 * nsub < g.n_parts; p += 4 * nsub) {  // four independent loads in flight
+        const float a = g.ss_parts[(size_t)p * kMaxRows + row];
+        const float b = g.ss_parts[(size_t)(p + nsub) * kMaxRows + row];
+        const float c = g.ss_parts[(size_t)(p + 2 * nsub) * kMaxRows + row];
+        const float d = g.ss_parts[(size_t)(p + 3 * nsub) * kMaxRows + row];
+        s0 += a; s1 += b; s2 += c; s3 += d;
+    }
+    for (; p < g.n_parts; p += nsub) s0 += g.ss_parts[(size_t)p * kMaxRows + row];
+    tmp[threadIdx.x] = (s0 + s1) + (s2 + s3);
     __syncthreads();
     if (threadIdx.x < 32) {
         float t = 0.f;
@@ -57,14 +82,14 @@ __device__ __forceinline__ void compute_rstd(const GemmArgs& g, float* rstd_s, f
     __syncthreads();
 }
 
-template <int R, int NACC, int P>
+template <int R, int NACC, int P, int SPLIT>
 struct GemmStage {
     u32x4 b[NACC][P];
-    u32x4 a[P][R];
+    u32x4 a[P][R][SPLIT];
 };
 
-template <int R, int NACC, int P>
-__device__ __forceinline__ void gemm_issue(GemmStage<R, NACC, P>& st, const u32x4* w0, const u32x4* w1,
+template <int R, int NACC, int P, int SPLIT>
+__device__ __forceinline__ void gemm_issue(GemmStage<R, NACC, P, SPLIT>& st, const u32x4* w0, const u32x4* w1,
                                            const u32x4* af, int s, int ks1) {
 #pragma unroll
     for (int u = 0; u < P; ++u) {
@@ -72,28 +97,77 @@ __device__ __forceinline__ void gemm_issue(GemmStage<R, NACC, P>& st, const u32x
         st.b[0][u] = load_stream(w0 + (size_t)ss * 64);
         if constexpr (NACC == 2) st.b[1][u] = load_stream(w1 + (size_t)ss * 64);
 #pragma unroll
-        for (int rg = 0; rg < R; ++rg) st.a[u][rg] = af[((size_t)ss * R + rg) * 64];
+        for (int rg = 0; rg < R; ++rg)
+#pragma unroll
+            for (int h = 0; h < SPLIT; ++h) st.a[u][rg][h] = af[((size_t)ss * R + rg) * 128 + h];
     }
 }
 
-template <int R, int NACC, int P>
-__device__ __forceinline__ void gemm_compute(const GemmStage<R, NACC, P>& st, f32x4 (&acc)[NACC][R], int s, int ks1) {
+template <int R, int NACC, int P, int SPLIT>
+__device__ __forceinline__ void gemm_compute(const GemmStage<R, NACC, P, SPLIT>& st, f32x4 (&acc)[NACC][R], int s,
+                                             int ks1) {
 #pragma unroll
     for (int u = 0; u < P; ++u) {
         if (s + u < ks1) {
 #pragma unroll
-            for (int rg = 0; rg < R; ++rg) {
-                acc[0][rg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(st.a[u][rg]), as_bf16x8(st.b[0][u]),
-                                                                     acc[0][rg], 0, 0, 0);
-                if constexpr (NACC == 2)
-                    acc[1][rg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(st.a[u][rg]),
-                                                                         as_bf16x8(st.b[1][u]), acc[1][rg], 0, 0, 0);
+            for (int rg = 0; rg < R; ++rg)
+#pragma unroll
+                for (int h = 0; h < SPLIT; ++h)
+#pragma unroll
+                    for (int a = 0; a < NACC; ++a)
+                        acc[a][rg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(st.a[u][rg][h]),
+                                                                             as_bf16x8(st.b[a][u]), acc[a][rg], 0, 0, 0);
+        }
+    }
+}
+
+// q/k/v epilogue of one lane: 4 rows x 1 feature of tile `tile` (see kEpiQkv above).
+__device__ __forceinline__ void qkv_epilogue(const GemmArgs& g, int tile, int lane, int rg, const f32x4& sum,
+                                             const float* rstd_s) {
+    const QkvOut& o = g.qkv;
+    const int HD = o.head_dim, HALF = HD >> 1, tph = HD >> 4;  // tiles per head
+    const int c = lane & 15, row0 = rg * 16 + (lane >> 4) * 4;
+    const int G = o.n_heads / o.n_kv_heads;
+    const int which = tile < g.tile_end[0] ? 0 : (tile < g.tile_end[1] ? 1 : 2);
+    const int tl = tile - (which == 0 ? 0 : g.tile_end[which - 1]);
+    const int head = tl / tph, u = tl % tph;
+    bf16* kc = reinterpret_cast<bf16*>(o.k_cache);
+    bf16* vc = reinterpret_cast<bf16*>(o.v_cache);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int row = row0 + r;
+        const float own = sum[r] * rstd_s[row & 31];
+        const float partner = __shfl_xor(own, 8);
+        if (which == 2) {  // v: plain feature order
+            const int x = u * 16 + c;
+            if (row < g.n_rows) {
+                const bf16 v = to_bf16(own);
+                if (o.mode) vc[((size_t)head * HD + x) * o.t_max + o.pos0 + row] = v;
+                else reinterpret_cast<bf16*>(o.v_self)[((size_t)head * HD + x) * 32 + row] = v;
+            }
+            continue;
+        }
+        // q / k: lanes 0..7 hold feature e = 8u + c, lanes 8..15 its rotary partner e + HALF
+        const int e = u * 8 + (c & 7), x = e + ((c & 8) ? HALF : 0);
+        if (row < g.n_rows) {
+            const int pos = o.pos0 + (o.mode ? row : 0);
+            const float2 cs = o.rope[(size_t)pos * HALF + e];
+            const float rot = own * cs.x + ((c & 8) ? partner : -partner) * cs.y;
+            if (which == 0) {
+                const int kvh = head / G, qi = row * G + head % G;
+                const size_t off = (((((size_t)kvh * (2 * G) + (qi >> 4)) * (HD >> 5) + (x >> 5)) * 64) +
+                                    ((x >> 3) & 3) * 16 + (qi & 15)) * 8 + (x & 7);
+                reinterpret_cast<bf16*>(o.q_frag)[off] = to_bf16(rot * o.q_scale);
+            } else if (o.mode) {
+                kc[((size_t)head * o.t_max + pos) * HD + x] = to_bf16(rot);
+            } else {
+                reinterpret_cast<bf16*>(o.k_self)[((size_t)head * 32 + row) * HD + x] = to_bf16(rot);
             }
         }
     }
 }
 
-template <int R, int NW, int EPI, int P>
+template <int R, int NW, int EPI, int P, int SPLIT>
 __global__ __launch_bounds__(NW * 64) void gemm_bf16_kernel(GemmArgs g) {
     constexpr int NACC = (EPI == kEpiSwiglu) ? 2 : 1;
     __shared__ f32x4 red[NW][NACC][R][64];
@@ -104,13 +178,13 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_kernel(GemmArgs g) {
     const int ks0 = (KS * wave) / NW, ks1 = (KS * (wave + 1)) / NW;
 
     int mi = 0, tl = tile;
-    if constexpr (EPI == kEpiScale) {
+    if constexpr (EPI == kEpiScale || EPI == kEpiQkv) {
         if (tile >= g.tile_end[0]) { mi = 1; tl = tile - g.tile_end[0]; }
         if (tile >= g.tile_end[1]) { mi = 2; tl = tile - g.tile_end[1]; }
     }
     const u32x4* w0 = reinterpret_cast<const u32x4*>(g.W[mi]) + (size_t)tl * KS * 64 + lane;
     const u32x4* w1 = (NACC == 2) ? reinterpret_cast<const u32x4*>(g.W[1]) + (size_t)tl * KS * 64 + lane : nullptr;
-    const u32x4* af = reinterpret_cast<const u32x4*>(g.A) + lane;
+    const u32x4* af = reinterpret_cast<const u32x4*>(g.A) + lane * 2;
 
     f32x4 acc[NACC][R];
 #pragma unroll
@@ -118,19 +192,19 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
         for (int rg = 0; rg < R; ++rg) acc[a][rg] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    GemmStage<R, NACC, P> st0, st1;
+    GemmStage<R, NACC, P, SPLIT> st0, st1;
     int s = ks0;
-    if (s < ks1) gemm_issue<R, NACC, P>(st0, w0, w1, af, s, ks1);  // weights first: they do not depend on rstd
+    if (s < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w0, w1, af, s, ks1);  // weights first: independent of rstd
 
     if constexpr (EPI != kEpiResid) compute_rstd(g, rstd_s, tmp_s);
 
     while (s < ks1) {
-        if (s + P < ks1) gemm_issue<R, NACC, P>(st1, w0, w1, af, s + P, ks1);
-        gemm_compute<R, NACC, P>(st0, acc, s, ks1);
+        if (s + P < ks1) gemm_issue<R, NACC, P, SPLIT>(st1, w0, w1, af, s + P, ks1);
+        gemm_compute<R, NACC, P, SPLIT>(st0, acc, s, ks1);
         s += P;
         if (s >= ks1) break;
-        if (s + P < ks1) gemm_issue<R, NACC, P>(st0, w0, w1, af, s + P, ks1);
-        gemm_compute<R, NACC, P>(st1, acc, s, ks1);
+        if (s + P < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w0, w1, af, s + P, ks1);
+        gemm_compute<R, NACC, P, SPLIT>(st1, acc, s, ks1);
         s += P;
     }
 
@@ -156,6 +230,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_kernel(GemmArgs g) {
             const int row = row0 + r;
             if (row < g.n_rows) g.out[(size_t)row * g.ldo + col] = sum[0][r] * rstd_s[row];
         }
+    } else if constexpr (EPI == kEpiQkv) {
+        qkv_epilogue(g, tile, lane, rg, sum[0], rstd_s);
     } else if constexpr (EPI == kEpiResid) {
         const float gain = g.next_gain ? g.next_gain[col] : 1.0f;
 #pragma unroll
@@ -236,7 +312,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
             }
     }
     __syncthreads();
-    // epilogue: thread (cl = tid/16 .. ) -> one (row, column) pair per thread per pass
+    // epilogue: one (row, column) pair per thread per pass; 16 consecutive lanes share a row
     for (int idx = threadIdx.x; idx < 16 * kMaxRows; idx += 256) {
         const int row = idx >> 4, cl = idx & 15, col = tile * 16 + cl;
         float v = 0.f;
@@ -250,7 +326,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
                 if (g.next_op)
                     store_operand<kDtF32>(g.next_op, g.R, g.N, row, col, v * (g.next_gain ? g.next_gain[col] : 1.0f));
             }
-            if (g.next_ss) {  // idx>>4 == row is constant over 16 consecutive lanes
+            if (g.next_ss) {
                 const float sq = sum16(v * v);
                 if (cl == 0) g.next_ss[(size_t)tile * kMaxRows + row] = sq;
             }

@@ -6,8 +6,11 @@
 namespace clasp {
 
 // ---- weight packing: row-major bf16 [N][K] -> fragments (tile of 16 features x 32 inputs = 64 lanes x 8 bf16) ----
-// dst fragment index = (n/16)*(K/32) + k/32; lane q*16 + c holds W[(n/16)*16 + c][(k/32)*32 + q*8 .. +8].
-__global__ void pack_bf16_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int N, int K) {
+// dst fragment index = tile*(K/32) + k/32; lane q*16 + c holds W[feature(tile, c)][(k/32)*32 + q*8 .. +8].
+// feature(tile, c) = tile*16 + c, except for rotary matrices (rope_hd > 0: wq, wk), where the features of each head
+// are regrouped so that tile u of a head holds features 8u..8u+7 (c < 8) and their rotary partners
+// rope_hd/2 + 8u.. (c >= 8): the projection's epilogue can then rotate a pair inside one tile.
+__global__ void pack_bf16_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int N, int K, int rope_hd) {
     const size_t total = (size_t)N * K / 8;  // 16-byte vectors
     const int KS = K >> 5;
     for (size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x; v < total; v += (size_t)gridDim.x * blockDim.x) {
@@ -16,7 +19,13 @@ __global__ void pack_bf16_kernel(const u32x4* __restrict__ src, u32x4* __restric
         const int s = (int)(frag % KS);
         const size_t tile = frag / KS;
         const int c = lane & 15, q = lane >> 4;
-        const size_t row = tile * 16 + c;
+        size_t row = tile * 16 + c;
+        if (rope_hd > 0) {
+            const int tph = rope_hd >> 4;
+            const size_t head = tile / tph;
+            const int u = (int)(tile % tph);
+            row = head * rope_hd + (c < 8 ? u * 8 + c : (rope_hd >> 1) + u * 8 + (c - 8));
+        }
         dst[v] = src[(row * K + (size_t)s * 32 + q * 8) / 8];
     }
 }
@@ -109,39 +118,51 @@ struct SelectArgs {
     uint8_t* choice;  // [(L+1)][(M+1)]
 };
 
+// One workgroup of 1024 threads per cell; every thread owns 4 consecutive columns per pass, all loads of a pass are
+// issued together and the five dot products share one block reduction.
 template <int DT>
-__global__ __launch_bounds__(256) void dp_select_kernel(SelectArgs a) {
-    __shared__ float red[8];
+__global__ __launch_bounds__(1024) void dp_select_kernel(SelectArgs a) {
+    __shared__ float red[16][5];
     const int j = blockIdx.x, d = a.d;
     const int ell = min(a.i - 1, a.M);
     float* dst = a.g_cur + (size_t)j * d;
+    const f32x4* x4 = reinterpret_cast<const f32x4*>(a.x_i);
     if (j == 0) {
-        for (int c = threadIdx.x; c < d; c += blockDim.x) dst[c] = a.x_i[c];
+        for (int c = threadIdx.x; c < d / 4; c += blockDim.x) reinterpret_cast<f32x4*>(dst)[c] = x4[c];
         return;
     }
-    const float* skip = a.g_prev + (size_t)(j - 1) * d;
+    const f32x4* skip4 = reinterpret_cast<const f32x4*>(a.g_prev + (size_t)(j - 1) * d);
     const bool has_comp = j <= ell;
-    const float* comp = a.G + (size_t)(j - 1) * d;
-    float xx = 0.f, sx = 0.f, ss = 0.f, cx = 0.f, cc = 0.f;
-    for (int c = threadIdx.x; c < d; c += blockDim.x) {
-        const float x = a.x_i[c], s = skip[c];
-        xx = fmaf(x, x, xx);
-        sx = fmaf(s, x, sx);
-        ss = fmaf(s, s, ss);
-        if (has_comp) {
-            const float g = comp[c];
-            cx = fmaf(g, x, cx);
-            cc = fmaf(g, g, cc);
+    const f32x4* comp4 = reinterpret_cast<const f32x4*>(a.G + (size_t)(j - 1) * d);
+    float acc[5] = {0.f, 0.f, 0.f, 0.f, 0.f};  // x.x, s.x, s.s, c.x, c.c
+    for (int c = threadIdx.x; c < d / 4; c += blockDim.x) {
+        const f32x4 x = x4[c], s = skip4[c];
+        const f32x4 g = has_comp ? comp4[c] : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            acc[0] = fmaf(x[e], x[e], acc[0]);
+            acc[1] = fmaf(s[e], x[e], acc[1]);
+            acc[2] = fmaf(s[e], s[e], acc[2]);
+            acc[3] = fmaf(g[e], x[e], acc[3]);
+            acc[4] = fmaf(g[e], g[e], acc[4]);
         }
     }
-    xx = block_sum(xx, red);
-    sx = block_sum(sx, red);
-    ss = block_sum(ss, red);
-    cx = block_sum(cx, red);
-    cc = block_sum(cc, red);
-    const float nx = fmaxf(sqrtf(xx), 1e-12f);
-    const float sig_s = sx / (fmaxf(sqrtf(ss), 1e-12f) * nx);
-    const float sig_c = has_comp ? cx / (fmaxf(sqrtf(cc), 1e-12f) * nx) : __builtin_nanf("");
+    const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+#pragma unroll
+    for (int k = 0; k < 5; ++k) {
+        acc[k] = wave_sum(acc[k]);
+        if ((threadIdx.x & 63) == 0) red[wave][k] = acc[k];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 5; ++k) {
+        float t = 0.f;
+        for (int w = 0; w < nw; ++w) t += red[w][k];
+        acc[k] = t;
+    }
+    const float nx = fmaxf(sqrtf(acc[0]), 1e-12f);
+    const float sig_s = acc[1] / (fmaxf(sqrtf(acc[2]), 1e-12f) * nx);
+    const float sig_c = has_comp ? acc[3] / (fmaxf(sqrtf(acc[4]), 1e-12f) * nx) : __builtin_nanf("");
     const bool keep_comp = has_comp && (sig_c > sig_s);
     if (threadIdx.x == 0) {
         const size_t cell = (size_t)a.i * (a.M + 1) + j;
@@ -151,8 +172,20 @@ __global__ __launch_bounds__(256) void dp_select_kernel(SelectArgs a) {
             a.scores[cell * 2 + 1] = sig_s;
         }
     }
-    const float* src = keep_comp ? comp : skip;
-    emit_row<DT>([&](int c) { return src[c]; }, d, dst, a.op, a.R, j - 1, a.gain, a.ss);
+    const f32x4* src4 = keep_comp ? comp4 : skip4;
+    const f32x4* gain4 = reinterpret_cast<const f32x4*>(a.gain);
+    for (int c = threadIdx.x; c < d / 4; c += blockDim.x) {
+        const f32x4 v = src4[c];
+        reinterpret_cast<f32x4*>(dst)[c] = v;
+        if (a.op) {
+            const f32x4 gn = gain4 ? gain4[c] : f32x4{1.f, 1.f, 1.f, 1.f};
+            store_operand4<DT>(a.op, a.R, d, j - 1, c * 4, v * gn);
+            float sq = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];  // 4 lanes cover one 16-column tile
+            sq += __shfl_xor(sq, 1);
+            sq += __shfl_xor(sq, 2);
+            if ((c & 3) == 0) a.ss[(size_t)(c >> 2) * kMaxRows + (j - 1)] = sq;
+        }
+    }
 }
 
 __global__ void dp_table_init_kernel(float* scores, uint8_t* choice, int cells) {
