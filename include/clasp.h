@@ -24,10 +24,11 @@
  *   - dtype CLASP_F32: matrices are fp32 row-major [out_features][in_features] (clasp_pack_matrix is a copy);
  *     everything is fp32.
  *   - embed is always row-major [vocab][d_model] in the model dtype. RMSNorm gains are fp32 [d_model].
- *   - KV cache, per K and per V: clasp_kv_cache_bytes() bytes. K is [layer][kv_head][max_seq][head_dim]
- *     (keys stored after rotation), V is [layer][kv_head][head_dim][max_seq] (transposed), model dtype.
- *     Validity is the caller's length counter: the library reads positions below the `pos` it is given and never
- *     beyond. clasp_create zero-fills both caches.
+ *   - KV cache, per K and per V: clasp_kv_cache_bytes() bytes in the model dtype, [layer][kv_head] major; inside a
+ *     head the order is the library's own (fp32: K [max_seq][head_dim], V [head_dim][max_seq]; bf16: blocks of 32
+ *     positions in MFMA operand order), so contents from elsewhere go in through clasp_kv_load. Keys are stored
+ *     after rotation. Validity is the caller's length counter: the library reads positions below the `pos` it is
+ *     given and never beyond. clasp_create zero-fills both caches.
  */
 #ifndef CLASP_H
 #define CLASP_H
@@ -70,8 +71,7 @@ typedef struct {
     const void *const *wk;     /* [n_kv_heads*head_dim][d_model], packed                                  */
     const void *const *wv;     /* [n_kv_heads*head_dim][d_model], packed                                  */
     const void *const *wo;     /* [d_model][n_heads*head_dim], packed                                     */
-    const void *const *w_gate; /* [d_ffn][d_model], packed                                                */
-    const void *const *w_up;   /* [d_ffn][d_model], packed                                                */
+    const void *const *w_gate_up; /* gate and up projections, [2*d_ffn][d_model], from clasp_pack_gate_up          */
     const void *const *w_down; /* [d_model][d_ffn], packed                                                */
 } clasp_weights;
 
@@ -86,6 +86,11 @@ size_t clasp_packed_bytes(int rows, int cols, int dtype);
  * rope_head_dim: 0 for every matrix except wq and wk, which take the model's head_dim: their output features are
  * regrouped per head so that a rotary pair (e, e + head_dim/2) falls into one tile (ignored for fp32). */
 int clasp_pack_matrix(const void *src, void *dst, int rows, int cols, int dtype, int rope_head_dim, void *stream);
+
+/* Packs the row-major dev matrices gate and up ([d_ffn][d_model] each) into ONE matrix dst of 2 * clasp_packed_bytes(
+ * d_ffn, d_model, dtype) bytes. bf16: the two projections are interleaved, 8 gate features and the 8 matching up
+ * features per 16-feature tile, so that one weight stream feeds the fused SwiGLU; fp32: gate rows, then up rows. */
+int clasp_pack_gate_up(const void *gate, const void *up, void *dst, int d_ffn, int d_model, int dtype, void *stream);
 
 /* Device bytes clasp_create needs in `workspace` (256-byte aligned), and bytes of ONE of the two KV caches. */
 size_t clasp_workspace_bytes(const clasp_config *cfg);

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libclasp_hip.so")
 
 CLASP_F32, CLASP_BF16 = 0, 1
-EXPORTS = ("clasp_strerror", "clasp_packed_bytes", "clasp_pack_matrix", "clasp_workspace_bytes",
+EXPORTS = ("clasp_strerror", "clasp_packed_bytes", "clasp_pack_matrix", "clasp_pack_gate_up", "clasp_workspace_bytes",
            "clasp_kv_cache_bytes", "clasp_create", "clasp_destroy", "clasp_verify_forward", "clasp_dp_select",
            "clasp_draft_step", "clasp_kv_load", "clasp_kernel_timer_begin", "clasp_kernel_timer_end")
 
@@ -36,8 +36,7 @@ class Weights(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p),
                 ("attn_norm", C.POINTER(C.c_void_p)), ("mlp_norm", C.POINTER(C.c_void_p)),
                 ("wq", C.POINTER(C.c_void_p)), ("wk", C.POINTER(C.c_void_p)), ("wv", C.POINTER(C.c_void_p)),
-                ("wo", C.POINTER(C.c_void_p)), ("w_gate", C.POINTER(C.c_void_p)), ("w_up", C.POINTER(C.c_void_p)),
-                ("w_down", C.POINTER(C.c_void_p))]
+                ("wo", C.POINTER(C.c_void_p)), ("w_gate_up", C.POINTER(C.c_void_p)), ("w_down", C.POINTER(C.c_void_p))]
 
 
 _lib = None
@@ -56,6 +55,7 @@ def lib():
         l.clasp_packed_bytes.restype = sz
         l.clasp_packed_bytes.argtypes = [i32, i32, i32]
         l.clasp_pack_matrix.argtypes = [vp, vp, i32, i32, i32, i32, vp]
+        l.clasp_pack_gate_up.argtypes = [vp, vp, vp, i32, i32, i32, vp]
         l.clasp_workspace_bytes.restype = sz
         l.clasp_workspace_bytes.argtypes = [C.POINTER(Config)]
         l.clasp_kv_cache_bytes.restype = sz
@@ -109,7 +109,21 @@ def clasp_pack_matrix(src: torch.Tensor, dtype: str, rope_head_dim: int = 0) -> 
     return dst
 
 
-_MATS = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+def clasp_pack_gate_up(gate: torch.Tensor, up: torch.Tensor, dtype: str) -> torch.Tensor:
+    """Returns the single packed [2*d_ffn][d_model] matrix of the two MLP input projections (clasp_pack_gate_up)."""
+    f, d = gate.shape
+    code = _dtype_code(dtype)
+    want = torch.float32 if code == CLASP_F32 else torch.bfloat16
+    if up.shape != gate.shape or lib().clasp_packed_bytes(f, d, code) == 0:
+        raise ClaspError(f"gate/up {tuple(gate.shape)} cannot be packed for dtype {dtype}")
+    dst = torch.empty(2 * f, d, dtype=gate.dtype, device=gate.device)
+    _check(lib().clasp_pack_gate_up(_ptr(gate, want), _ptr(up, want), _ptr(dst), f, d, code, _stream()),
+           "clasp_pack_gate_up")
+    return dst
+
+
+_MATS = ("wq", "wk", "wv", "wo", "w_down")  # packed one by one; gate and up are packed together
+_PACKED = ("wq", "wk", "wv", "wo", "w_gate_up", "w_down")
 
 
 class Engine:
@@ -140,6 +154,8 @@ class Engine:
         dev = self.device
         out = {m: clasp_pack_matrix(w[m].to(dev).contiguous(), self.shape.dtype,
                                     self.shape.head_dim if m in ("wq", "wk") else 0) for m in _MATS}
+        out["w_gate_up"] = clasp_pack_gate_up(w["w_gate"].to(dev).contiguous(), w["w_up"].to(dev).contiguous(),
+                                              self.shape.dtype)
         out["attn_norm"] = w["attn_norm"].to(dev, torch.float32).contiguous()
         out["mlp_norm"] = w["mlp_norm"].to(dev, torch.float32).contiguous()
         self._layers[l] = out
@@ -158,7 +174,7 @@ class Engine:
         L = self.shape.n_layers
         self._arrays = {}
         wts = Weights(self._head["embed"].data_ptr(), self._head["lm_head"].data_ptr(), self._head["final_norm"].data_ptr())
-        for name in ("attn_norm", "mlp_norm") + _MATS:
+        for name in ("attn_norm", "mlp_norm") + _PACKED:
             arr = (C.c_void_p * L)(*[self._layers[l][name].data_ptr() for l in range(L)])
             self._arrays[name] = arr
             setattr(wts, name, C.cast(arr, C.POINTER(C.c_void_p)))

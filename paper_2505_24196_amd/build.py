@@ -17,12 +17,13 @@ def is_stale() -> bool:
     return any(os.path.getmtime(p) > t for p in SOURCES + HEADERS)
 
 
-def build(force: bool = True, verbose: bool = False) -> str:
+def build(force: bool = True, verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
+    """extra_flags / out: for tuning sweeps (e.g. -DCLASP_NW_DOWN=16 into another file); the product uses neither."""
     if not force and not is_stale():
         return LIB
     cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",  # no packed-fp32 code generation
-           "-Wno-unused-command-line-argument", "-o", LIB] + SOURCES
+           "-Wno-unused-command-line-argument", "-o", out] + list(extra_flags) + SOURCES
     if verbose:
         print(" ".join(cmd))
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -32,7 +33,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

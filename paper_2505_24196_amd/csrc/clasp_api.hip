@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <new>
@@ -19,23 +20,51 @@ using namespace clasp;
 
 namespace {
 
-// Launch shapes of the bf16 GEMMs: wavefronts per workgroup (they split K of one 16-feature tile) and fragments per
-// register stage (two stages are in flight). Chosen per projection from sweeps on the 8B shape.
-#ifndef CLASP_NW_QKV
-#define CLASP_NW_QKV 8
-#define CLASP_NW_OPROJ 8
-#define CLASP_NW_GATEUP 8
-#define CLASP_NW_DOWN 8
-#define CLASP_NW_HEAD 8
+// Launch shapes of the bf16 GEMMs, per projection: a workgroup has CW x KW wavefronts (CW column tiles that share
+// their activation fragments, KW slices of K reduced through LDS). P = fragments per register stage (two stages in
+// flight).
+#ifndef CLASP_QKV_CW
+#define CLASP_QKV_CW 2
+#endif
+#ifndef CLASP_QKV_KW
+#define CLASP_QKV_KW 4
+#endif
+#ifndef CLASP_OPROJ_CW
+#define CLASP_OPROJ_CW 1
+#endif
+#ifndef CLASP_OPROJ_KW
+#define CLASP_OPROJ_KW 8
+#endif
+#ifndef CLASP_GATEUP_CW
+#define CLASP_GATEUP_CW 4
+#endif
+#ifndef CLASP_GATEUP_KW
+#define CLASP_GATEUP_KW 2
+#endif
+#ifndef CLASP_DOWN_CW
+#define CLASP_DOWN_CW 1
+#endif
+#ifndef CLASP_DOWN_KW
+#define CLASP_DOWN_KW 8
+#endif
+#ifndef CLASP_HEAD_CW
+#define CLASP_HEAD_CW 4
+#endif
+#ifndef CLASP_HEAD_KW
+#define CLASP_HEAD_KW 2
+#endif
+#ifndef CLASP_GEMM_DEPTH
 #define CLASP_GEMM_DEPTH 4
 #endif
 #ifndef CLASP_ACT_SPLIT
 #define CLASP_ACT_SPLIT 2  // 2: activations enter the MFMAs as bf16 hi + lo; 1: hi only
 #endif
-constexpr int kAttnWaves = 4;
+#ifndef CLASP_ATTN_SHORT_BLOCKS
+#define CLASP_ATTN_SHORT_BLOCKS 40  // prefixes of up to this many 32-key blocks take the latency-oriented launch
+#endif
 constexpr int kMaxSplit = 64;   // most workgroups that share one KV head's prefix
 #ifndef CLASP_ATTN_BLOCKS_PER_SPLIT
-#define CLASP_ATTN_BLOCKS_PER_SPLIT 8  // 32-key blocks per workgroup before the prefix is split further
+#define CLASP_ATTN_BLOCKS_PER_SPLIT 32  // 32-key blocks per workgroup before the prefix is split further
 #endif
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -60,7 +89,7 @@ struct clasp_ctx {
     const void *embed, *lm_head;
     const float* final_norm;
     std::vector<const float*> attn_norm, mlp_norm;
-    std::vector<const void*> wq, wk, wv, wo, w_gate, w_up, w_down;
+    std::vector<const void*> wq, wk, wv, wo, w_gate_up, w_down;
     char *k_cache, *v_cache;
     size_t kv_layer_bytes;
     // workspace
@@ -71,11 +100,11 @@ struct clasp_ctx {
     float *a_buf, *h[2], *g[2], *G;
     float* logits;
     float* attn_partial;
-    unsigned* attn_counters;
     void *q_frag, *k_self, *v_self;
     uint8_t* choice;
     int32_t* tok_tmp;
     // optional per-kernel timing (host-side event objects only; no device memory)
+    int n_cu = 256;  // compute units of the device (grid size of the persistent kernels)
     int timer_kind = -1;
     size_t timer_used = 0;
     std::vector<hipEvent_t> timer_start, timer_stop;
@@ -104,7 +133,6 @@ size_t carve(const clasp_config& c, char* base, clasp_ctx* ctx) {
     auto* logits = w.take<float>(rows * (size_t)c.vocab * 4);
     const size_t grp = c.n_heads / c.n_kv_heads;
     auto* part = w.take<float>((size_t)c.n_kv_heads * (2 * grp + 4) * 16 * kMaxSplit * (c.head_dim + 2) * 4);
-    auto* counters = w.take<unsigned>((size_t)c.n_kv_heads * (2 * grp + 4) * 4);
     auto* q_frag = w.take<void>(qd * 64 + 4 * (size_t)c.head_dim * 32);  // + 4 query tiles of slack for padded groups
     auto* k_self = w.take<void>(kvd * 64);
     auto* v_self = w.take<void>(kvd * 64);
@@ -114,7 +142,7 @@ size_t carve(const clasp_config& c, char* base, clasp_ctx* ctx) {
         ctx->rope = rope; ctx->qkv = qkv; ctx->op_h = op_h; ctx->op_attn = op_attn; ctx->op_a = op_a;
         ctx->op_act = op_act; ctx->ss_h = ss_h; ctx->ss_a = ss_a; ctx->a_buf = a_buf; ctx->h[0] = h0; ctx->h[1] = h1;
         ctx->g[0] = g0; ctx->g[1] = g1; ctx->G = G; ctx->logits = logits; ctx->attn_partial = part;
-        ctx->choice = choice; ctx->tok_tmp = tok; ctx->attn_counters = counters;
+        ctx->choice = choice; ctx->tok_tmp = tok; 
         ctx->q_frag = q_frag; ctx->k_self = k_self; ctx->v_self = v_self;
     }
     return w.off;
@@ -160,15 +188,30 @@ struct TimerScope {
 };
 
 // ---- GEMM dispatch ---------------------------------------------------------------------------------------------
-template <int EPI, int NW>
+// Which projections may use the resident-activation kernel (bit = CLASP_KERNEL_* kind) when it applies (one row group
+// and K <= 32 * kResidentKW * kResidentKSW).
+#ifndef CLASP_RESIDENT_MASK
+#define CLASP_RESIDENT_MASK ((1 << CLASP_KERNEL_GATE_UP) | (1 << CLASP_KERNEL_LM_HEAD))
+#endif
+constexpr int kResidentKW = 8, kResidentKSW = 16;
+
+template <int EPI, int CW, int KW>
 int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kind) {
     const int tiles = g.N / 16;
     TimerScope timer(ctx, kind, st);
     if (ctx->cfg.dtype == CLASP_BF16) {
-        if (g.R == 1)
-            hipLaunchKernelGGL((gemm_bf16_kernel<1, NW, EPI, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>), dim3(tiles), dim3(NW * 64), 0, st, g);
-        else
-            hipLaunchKernelGGL((gemm_bf16_kernel<2, NW, EPI, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>), dim3(tiles), dim3(NW * 64), 0, st, g);
+        const bool resident = g.R == 1 && ((CLASP_RESIDENT_MASK >> kind) & 1) &&
+                              (g.K / 32 + kResidentKW - 1) / kResidentKW <= kResidentKSW && tiles > ctx->n_cu;
+        if (resident) {
+            hipLaunchKernelGGL((gemm_bf16_resident_kernel<kResidentKSW, kResidentKW, EPI, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>),
+                               dim3(ctx->n_cu), dim3(kResidentKW * 64), 0, st, g);
+        } else {
+            const dim3 grid((tiles + CW - 1) / CW);
+            if (g.R == 1)
+                hipLaunchKernelGGL((gemm_bf16_kernel<1, CW, KW, EPI, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>), grid, dim3(CW * KW * 64), 0, st, g);
+            else
+                hipLaunchKernelGGL((gemm_bf16_kernel<2, CW, KW, EPI, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>), grid, dim3(CW * KW * 64), 0, st, g);
+        }
     } else {
         if constexpr (EPI == kEpiQkv) return CLASP_E_UNSUPPORTED;
         else hipLaunchKernelGGL((gemm_f32_kernel<EPI>), dim3(tiles), dim3(256), 0, st, g);
@@ -177,16 +220,31 @@ int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kin
     return CLASP_OK;
 }
 
-template <int HD>
-int launch_attn_bf16(const AttnArgs& a, int nt, dim3 grid, hipStream_t st) {
-    switch (nt) {
-        case 1: hipLaunchKernelGGL((attn_bf16_kernel<HD, 1, kAttnWaves>), grid, dim3(kAttnWaves * 64), 0, st, a); break;
-        case 2: hipLaunchKernelGGL((attn_bf16_kernel<HD, 2, kAttnWaves>), grid, dim3(kAttnWaves * 64), 0, st, a); break;
-        case 3: hipLaunchKernelGGL((attn_bf16_kernel<HD, 3, kAttnWaves>), grid, dim3(kAttnWaves * 64), 0, st, a); break;
-        default: hipLaunchKernelGGL((attn_bf16_kernel<HD, 4, kAttnWaves>), grid, dim3(kAttnWaves * 64), 0, st, a); break;
+template <int HD, int NT, int NW>
+int launch_attn_one(const AttnArgs& a, dim3 grid, hipStream_t st) {
+    constexpr size_t lds = (size_t)NW * HD * 17 * sizeof(float);
+    static bool opted_in = false;  // more than 64 KiB of LDS per workgroup has to be requested once per kernel
+    if (!opted_in) {
+        if (hipFuncSetAttribute((const void*)attn_bf16_kernel<HD, NT, NW>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess)
+            return CLASP_E_HIP;
+        opted_in = true;
     }
+    hipLaunchKernelGGL((attn_bf16_kernel<HD, NT, NW>), grid, dim3(NW * 64), lds, st, a);
     CLASP_LAUNCH_CHECK();
     return CLASP_OK;
+}
+
+// short = latency-oriented launch: one query tile per workgroup, 16 wavefronts
+template <int HD>
+int launch_attn_bf16(const AttnArgs& a, bool short_prefix, int nt, dim3 grid, hipStream_t st) {
+    if (short_prefix) return launch_attn_one<HD, 1, 16>(a, grid, st);
+    switch (nt) {
+        case 1: return launch_attn_one<HD, 1, 8>(a, grid, st);
+        case 2: return launch_attn_one<HD, 2, 8>(a, grid, st);
+        case 3: return launch_attn_one<HD, 3, 8>(a, grid, st);
+        default: return launch_attn_one<HD, 4, 8>(a, grid, st);
+    }
 }
 
 int launch_attention(const clasp_ctx* ctx, int layer, int n, int R, int mode, int pos0, hipStream_t st) {
@@ -198,7 +256,7 @@ int launch_attention(const clasp_ctx* ctx, int layer, int n, int R, int mode, in
     a.Kc = ctx->k_cache + (size_t)layer * ctx->kv_layer_bytes;
     a.Vt = ctx->v_cache + (size_t)layer * ctx->kv_layer_bytes;
     a.t_max = c.max_seq; a.out_op = ctx->op_attn; a.R = R;
-    a.partial = ctx->attn_partial; a.counters = ctx->attn_counters;
+    a.partial = ctx->attn_partial;
     a.scale = 1.0f / sqrtf((float)c.head_dim);
     a.q_frag = ctx->q_frag; a.k_self = ctx->k_self; a.v_self = ctx->v_self;
     a.n_split = 1;
@@ -209,14 +267,26 @@ int launch_attention(const clasp_ctx* ctx, int layer, int n, int R, int mode, in
         CLASP_LAUNCH_CHECK();
         return CLASP_OK;
     }
+    // Short prefixes are latency-bound: one query tile per workgroup (more workgroups, each key block re-read from
+    // L2 by the few workgroups of a KV head) and 16 wavefronts, so that a wavefront sees one or two key blocks.
+    // Long prefixes are bandwidth-bound: up to 4 query tiles per workgroup (keys read once) and the prefix split
+    // across workgroups.
     const int nQ = n * ctx->group, ntq = (nQ + 15) / 16;
-    const int nt = ntq < 4 ? ntq : 4, qgroups = (ntq + nt - 1) / nt;
     const int nblk = (pos0 + (mode ? n : 0) + 31) / 32;
-    int split = (nblk + CLASP_ATTN_BLOCKS_PER_SPLIT - 1) / CLASP_ATTN_BLOCKS_PER_SPLIT;
+    const bool short_prefix = nblk <= CLASP_ATTN_SHORT_BLOCKS;
+    const int nt = short_prefix ? 1 : (ntq < 4 ? ntq : 4), qgroups = (ntq + nt - 1) / nt;
+    int split = short_prefix ? 1 : (nblk + CLASP_ATTN_BLOCKS_PER_SPLIT - 1) / CLASP_ATTN_BLOCKS_PER_SPLIT;
     split = split < 1 ? 1 : (split > kMaxSplit ? kMaxSplit : split);
     a.n_split = split;
     const dim3 grid(c.n_kv_heads, qgroups, split);
-    return c.head_dim == 64 ? launch_attn_bf16<64>(a, nt, grid, st) : launch_attn_bf16<128>(a, nt, grid, st);
+    const int rc = c.head_dim == 64 ? launch_attn_bf16<64>(a, short_prefix, nt, grid, st)
+                                    : launch_attn_bf16<128>(a, short_prefix, nt, grid, st);
+    if (rc) return rc;
+    if (split > 1) {
+        hipLaunchKernelGGL(attn_combine_kernel, dim3(c.n_kv_heads, nQ), dim3(c.head_dim), 0, st, a, nt, qgroups);
+        CLASP_LAUNCH_CHECK();
+    }
+    return CLASP_OK;
 }
 
 // One decoder layer on n rows. The rows' fp32 values are at h_in ([n][d]); their GEMM operand (times the layer's
@@ -243,9 +313,9 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
             o.k_cache = ctx->k_cache + (size_t)l * ctx->kv_layer_bytes;
             o.v_cache = ctx->v_cache + (size_t)l * ctx->kv_layer_bytes;
             o.k_self = ctx->k_self; o.v_self = ctx->v_self;
-            if ((rc = launch_gemm<kEpiQkv, CLASP_NW_QKV>(ctx, g, st, CLASP_KERNEL_QKV))) return rc;
+            if ((rc = launch_gemm<kEpiQkv, CLASP_QKV_CW, CLASP_QKV_KW>(ctx, g, st, CLASP_KERNEL_QKV))) return rc;
         } else {
-            if ((rc = launch_gemm<kEpiScale, 8>(ctx, g, st, CLASP_KERNEL_QKV))) return rc;
+            if ((rc = launch_gemm<kEpiScale, 1, 1>(ctx, g, st, CLASP_KERNEL_QKV))) return rc;
         }
     }
     if ((rc = launch_attention(ctx, l, n, R, mode, pos0, st))) return rc;
@@ -255,15 +325,20 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
         g.A = ctx->op_attn; g.n_rows = n; g.N = d; g.K = ctx->q_dim; g.R = R;
         g.out = ctx->a_buf; g.ldo = d; g.resid = h_in; g.ldr = d;
         g.next_op = ctx->op_a; g.next_gain = ctx->mlp_norm[l]; g.next_ss = ctx->ss_a;
-        if ((rc = launch_gemm<kEpiResid, CLASP_NW_OPROJ>(ctx, g, st, CLASP_KERNEL_O_PROJ))) return rc;
+        if ((rc = launch_gemm<kEpiResid, CLASP_OPROJ_CW, CLASP_OPROJ_KW>(ctx, g, st, CLASP_KERNEL_O_PROJ))) return rc;
     }
     {
         GemmArgs g{};
-        g.W[0] = ctx->w_gate[l]; g.W[1] = ctx->w_up[l]; g.tile_end[0] = g.tile_end[1] = g.tile_end[2] = F / 16;
-        g.A = ctx->op_a; g.n_rows = n; g.N = F; g.K = d; g.R = R;
+        if (c.dtype == CLASP_BF16) {  // interleaved gate|up: 2F/16 tiles of one stream
+            g.W[0] = ctx->w_gate_up[l]; g.N = 2 * F;
+        } else {  // fp32: gate rows followed by up rows
+            g.W[0] = ctx->w_gate_up[l]; g.W[1] = static_cast<const float*>(ctx->w_gate_up[l]) + (size_t)F * d; g.N = F;
+        }
+        g.tile_end[0] = g.tile_end[1] = g.tile_end[2] = g.N / 16;
+        g.A = ctx->op_a; g.n_rows = n; g.K = d; g.R = R;
         g.ss_parts = ctx->ss_a; g.n_parts = d / 16; g.inv_dim = 1.0f / d; g.eps = c.rms_eps;
         g.next_op = ctx->op_act;
-        if ((rc = launch_gemm<kEpiSwiglu, CLASP_NW_GATEUP>(ctx, g, st, CLASP_KERNEL_GATE_UP))) return rc;
+        if ((rc = launch_gemm<kEpiSwiglu, CLASP_GATEUP_CW, CLASP_GATEUP_KW>(ctx, g, st, CLASP_KERNEL_GATE_UP))) return rc;
     }
     {
         GemmArgs g{};
@@ -272,7 +347,7 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
         g.out = h_out; g.ldo = d; g.resid = ctx->a_buf; g.ldr = d;
         g.next_op = next_op; g.next_gain = next_gain; g.next_ss = next_ss;
         g.capture = capture; g.ldc = d;
-        if ((rc = launch_gemm<kEpiResid, CLASP_NW_DOWN>(ctx, g, st, CLASP_KERNEL_DOWN))) return rc;
+        if ((rc = launch_gemm<kEpiResid, CLASP_DOWN_CW, CLASP_DOWN_KW>(ctx, g, st, CLASP_KERNEL_DOWN))) return rc;
     }
     return CLASP_OK;
 }
@@ -300,7 +375,7 @@ int run_head(const clasp_ctx* ctx, int n, int R, float* logits, int32_t* argmax_
     g.ss_parts = ctx->ss_h; g.n_parts = c.d_model / 16; g.inv_dim = 1.0f / c.d_model; g.eps = c.rms_eps;
     g.out = logits; g.ldo = c.vocab;
     int rc;
-    if ((rc = launch_gemm<kEpiScale, CLASP_NW_HEAD>(ctx, g, st, CLASP_KERNEL_LM_HEAD))) return rc;
+    if ((rc = launch_gemm<kEpiScale, CLASP_HEAD_CW, CLASP_HEAD_KW>(ctx, g, st, CLASP_KERNEL_LM_HEAD))) return rc;
     if (argmax_out || margin_out || prob_out) {
         hipLaunchKernelGGL(argmax_kernel, dim3(n), dim3(1024), 0, st, logits, c.vocab, argmax_out, margin_out, prob_out);
         CLASP_LAUNCH_CHECK();
@@ -346,6 +421,23 @@ int clasp_pack_matrix(const void* src, void* dst, int rows, int cols, int dtype,
     return CLASP_OK;
 }
 
+int clasp_pack_gate_up(const void* gate, const void* up, void* dst, int d_ffn, int d_model, int dtype, void* stream) {
+    if (!gate || !up || !dst || gate == dst || up == dst) return CLASP_E_INVALID_ARG;
+    const size_t bytes = clasp_packed_bytes(d_ffn, d_model, dtype);
+    if (!bytes) return CLASP_E_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dtype == CLASP_F32) {
+        if (hipMemcpyAsync(dst, gate, bytes, hipMemcpyDeviceToDevice, st) != hipSuccess ||
+            hipMemcpyAsync(static_cast<char*>(dst) + bytes, up, bytes, hipMemcpyDeviceToDevice, st) != hipSuccess)
+            return CLASP_E_HIP;
+        return CLASP_OK;
+    }
+    hipLaunchKernelGGL(pack_gate_up_bf16_kernel, dim3(2048), dim3(256), 0, st, reinterpret_cast<const u32x4*>(gate),
+                       reinterpret_cast<const u32x4*>(up), reinterpret_cast<u32x4*>(dst), d_ffn, d_model);
+    CLASP_LAUNCH_CHECK();
+    return CLASP_OK;
+}
+
 size_t clasp_workspace_bytes(const clasp_config* cfg) {
     if (check_config(cfg) != CLASP_OK) return 0;
     return carve(*cfg, nullptr, nullptr);
@@ -366,11 +458,11 @@ int clasp_create(const clasp_config* cfg, const clasp_weights* w, void* workspac
         return CLASP_E_INVALID_ARG;
     if (workspace_bytes < carve(*cfg, nullptr, nullptr)) return CLASP_E_WORKSPACE;
     if (!w->embed || !w->lm_head || !w->final_norm || !w->attn_norm || !w->mlp_norm || !w->wq || !w->wk || !w->wv ||
-        !w->wo || !w->w_gate || !w->w_up || !w->w_down)
+        !w->wo || !w->w_gate_up || !w->w_down)
         return CLASP_E_INVALID_ARG;
     for (int l = 0; l < cfg->n_layers; ++l)
-        if (!w->attn_norm[l] || !w->mlp_norm[l] || !w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->w_gate[l] ||
-            !w->w_up[l] || !w->w_down[l])
+        if (!w->attn_norm[l] || !w->mlp_norm[l] || !w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] ||
+            !w->w_gate_up[l] || !w->w_down[l])
             return CLASP_E_INVALID_ARG;
     clasp_ctx* ctx = new (std::nothrow) clasp_ctx();
     if (!ctx) return CLASP_E_INVALID_ARG;
@@ -385,12 +477,18 @@ int clasp_create(const clasp_config* cfg, const clasp_weights* w, void* workspac
     ctx->attn_norm.assign(w->attn_norm, w->attn_norm + L);
     ctx->mlp_norm.assign(w->mlp_norm, w->mlp_norm + L);
     ctx->wq.assign(w->wq, w->wq + L); ctx->wk.assign(w->wk, w->wk + L); ctx->wv.assign(w->wv, w->wv + L);
-    ctx->wo.assign(w->wo, w->wo + L); ctx->w_gate.assign(w->w_gate, w->w_gate + L);
-    ctx->w_up.assign(w->w_up, w->w_up + L); ctx->w_down.assign(w->w_down, w->w_down + L);
+    ctx->wo.assign(w->wo, w->wo + L); ctx->w_gate_up.assign(w->w_gate_up, w->w_gate_up + L);
+    ctx->w_down.assign(w->w_down, w->w_down + L);
     ctx->k_cache = static_cast<char*>(k_cache);
     ctx->v_cache = static_cast<char*>(v_cache);
     ctx->kv_layer_bytes = (size_t)cfg->n_kv_heads * cfg->max_seq * cfg->head_dim * ctx->esz;
     carve(*cfg, static_cast<char*>(workspace), ctx);
+    {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+            ctx->n_cu = cus;
+    }
 
     const size_t kvb = clasp_kv_cache_bytes(cfg);
     hipLaunchKernelGGL(fill_zero_kernel, dim3(2048), dim3(256), 0, 0, reinterpret_cast<u32x4*>(k_cache), kvb / 16);

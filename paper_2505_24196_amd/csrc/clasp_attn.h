@@ -13,7 +13,7 @@
 // tiles of a 32-key block are interleaved so that the exponentiated scores of a lane are already the 8-key B
 // fragment of O^T = V^T . P^T); V is cached transposed so that its fragments are 16-byte loads too. Wavefronts of a
 // workgroup take 32-key blocks round-robin and are merged through LDS in a fixed order; several workgroups may split
-// a long prefix (grid.z), the last one to finish merges their partial results in split order.
+// a long prefix (grid.z); attn_combine_kernel then merges their partial results in split order.
 // fp32 kernel: plain loops, rotary embedding applied in the kernel, exact softmax over all visible keys.
 #pragma once
 #include "clasp_common.h"
@@ -26,19 +26,18 @@ struct AttnArgs {
     int n_rows, n_heads, n_kv_heads, head_dim;
     int pos0, mode;
     const float2* rope;  // [max_seq][head_dim/2] (cos, sin)
-    void* Kc;            // this layer: [n_kv_heads][t_max][head_dim]
-    void* Vt;            // this layer: [n_kv_heads][head_dim][t_max]
+    void* Kc;            // this layer: fp32 [n_kv_heads][t_max][head_dim]; bf16: fragment order (kfrag_offset)
+    void* Vt;            // this layer: fp32 [n_kv_heads][head_dim][t_max]; bf16: fragment order (vfrag_offset)
     int t_max;
     void* out_op;  // operand of the output projection (K = n_heads*head_dim)
     int R;
     int n_split;
     float* partial;      // [n_kv_heads][query groups][n_split][NT*16][head_dim+2] when n_split > 1
-    unsigned* counters;  // [n_kv_heads * query groups], zero between launches
     float scale;         // 1/sqrt(head_dim)
     // bf16 path: written by the q/k/v projection's epilogue
     const void* q_frag;
-    const void* k_self;  // [n_kv_heads][32][head_dim]   (DP candidates' own keys)
-    const void* v_self;  // [n_kv_heads][head_dim][32]
+    const void* k_self;  // [n_kv_heads] one 32-position block each: the DP candidates' own keys / values
+    const void* v_self;
 };
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -56,6 +55,15 @@ template <int HD, int NT, class KF, class VF, class VALID>
 __device__ __forceinline__ void attn_block(AttnState<HD, NT>& st, const bf16x8 (&qf)[NT][HD / 32], KF kf, VF vf,
                                            VALID valid) {
     constexpr int KK = HD / 32, CT = HD / 16;
+    // all of the block's key and value fragments are requested before the first MFMA, so that the value loads do not
+    // wait behind the softmax
+    bf16x8 kfr[2][KK], vfr[CT];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) kfr[u][kk] = kf(u, kk);
+#pragma unroll
+    for (int c = 0; c < CT; ++c) vfr[c] = vf(c);
     f32x4 s[2][NT];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
@@ -63,9 +71,9 @@ __device__ __forceinline__ void attn_block(AttnState<HD, NT>& st, const bf16x8 (
         for (int t = 0; t < NT; ++t) s[u][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-            const bf16x8 k = kf(u, kk);
 #pragma unroll
-            for (int t = 0; t < NT; ++t) s[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k, qf[t][kk], s[u][t], 0, 0, 0);
+            for (int t = 0; t < NT; ++t)
+                s[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr[u][kk], qf[t][kk], s[u][t], 0, 0, 0);
         }
     }
     bf16x8 pf[NT];
@@ -100,9 +108,9 @@ __device__ __forceinline__ void attn_block(AttnState<HD, NT>& st, const bf16x8 (
     }
 #pragma unroll
     for (int c = 0; c < CT; ++c) {
-        const bf16x8 v = vf(c);
 #pragma unroll
-        for (int t = 0; t < NT; ++t) st.o[t][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v, pf[t], st.o[t][c], 0, 0, 0);
+        for (int t = 0; t < NT; ++t)
+            st.o[t][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vfr[c], pf[t], st.o[t][c], 0, 0, 0);
     }
 }
 
@@ -111,9 +119,10 @@ __device__ __forceinline__ void attn_block(AttnState<HD, NT>& st, const bf16x8 (
 template <int HD, int NT, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(AttnArgs a) {
     constexpr int KK = HD / 32, CT = HD / 16;
-    __shared__ float mg_o[NW][HD][17];  // +1: rows land in different LDS banks
+    extern __shared__ float lds_dyn[];  // NW*HD*17 floats: per-wavefront O^T tiles (+1 column against bank conflicts)
+    typedef float (*MgT)[HD][17];
+    MgT mg_o = reinterpret_cast<MgT>(lds_dyn);
     __shared__ float mg_m[NW][16], mg_l[NW][16], mg_f[NW][16];
-    __shared__ int s_last;
     const int kvh = blockIdx.x, qg = blockIdx.y, split = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int G = a.n_heads / a.n_kv_heads, nQ = a.n_rows * G;
@@ -154,31 +163,23 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(AttnArgs a) {
     const int n_cache = a.pos0 + (a.mode ? a.n_rows : 0);  // cache positions any row may see
     const int nblk = (n_cache + 31) >> 5;
     const int b0 = (int)(((long long)nblk * split) / a.n_split), b1 = (int)(((long long)nblk * (split + 1)) / a.n_split);
+    const u32x4* Kh = reinterpret_cast<const u32x4*>(Kc + (size_t)kvh * a.t_max * HD) + lane;
+    const u32x4* Vh = reinterpret_cast<const u32x4*>(Vt + (size_t)kvh * a.t_max * HD) + lane;
     for (int blk = b0 + wave; blk < b1; blk += NW) {
         const int kb = blk << 5;
+        const u32x4* kp = Kh + (size_t)blk * (2 * KK * 64);
+        const u32x4* vp = Vh + (size_t)blk * (CT * 64);
         attn_block<HD, NT>(
-            st, qf,
-            [&](int u, int kk) {
-                const int key = min(kb + (m16 >> 2) * 8 + u * 4 + (m16 & 3), n_cache - 1);
-                const u32x4* kp = reinterpret_cast<const u32x4*>(Kc + ((size_t)kvh * a.t_max + key) * HD);
-                return as_bf16x8(load_stream(kp + kk * 4 + q4));
-            },
-            [&](int c) {
-                const u32x4* vp = reinterpret_cast<const u32x4*>(Vt + ((size_t)kvh * HD + c * 16 + m16) * a.t_max + kb);
-                return as_bf16x8(load_stream(vp + q4));
-            },
+            st, qf, [&](int u, int kk) { return as_bf16x8(load_stream(kp + (u * KK + kk) * 64)); },
+            [&](int c) { return as_bf16x8(load_stream(vp + c * 64)); },
             [&](int u, int r, int t) { return kb + q4 * 8 + u * 4 + r <= limit[t]; });
     }
     if (!a.mode && split == a.n_split - 1 && wave == (b1 - b0) % NW) {  // DP candidates: own key/value only
-        const bf16* Ks = reinterpret_cast<const bf16*>(a.k_self) + (size_t)kvh * 32 * HD;
-        const bf16* Vs = reinterpret_cast<const bf16*>(a.v_self) + (size_t)kvh * HD * 32;
+        const u32x4* kp = reinterpret_cast<const u32x4*>(a.k_self) + (size_t)kvh * (2 * KK * 64) + lane;
+        const u32x4* vp = reinterpret_cast<const u32x4*>(a.v_self) + (size_t)kvh * (CT * 64) + lane;
         attn_block<HD, NT>(
-            st, qf,
-            [&](int u, int kk) {
-                const int kr = (m16 >> 2) * 8 + u * 4 + (m16 & 3);
-                return as_bf16x8(*reinterpret_cast<const u32x4*>(Ks + (size_t)kr * HD + kk * 32 + q4 * 8));
-            },
-            [&](int c) { return as_bf16x8(*reinterpret_cast<const u32x4*>(Vs + (size_t)(c * 16 + m16) * 32 + q4 * 8)); },
+            st, qf, [&](int u, int kk) { return as_bf16x8(kp[(u * KK + kk) * 64]); },
+            [&](int c) { return as_bf16x8(vp[c * 64]); },
             [&](int u, int r, int t) { return q4 * 8 + u * 4 + r == qrow[t]; });
     }
 
@@ -232,28 +233,21 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(AttnArgs a) {
         }
         __syncthreads();
     }
-    if (a.n_split == 1) return;
+}
 
-    // several workgroups shared this (kv head, query group): the last one to arrive merges their partial results
-    // in split order (the result does not depend on which workgroup happens to be last)
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const unsigned old = atomicAdd(a.counters + kvh * gridDim.y + qg, 1u);
-        s_last = (old == (unsigned)a.n_split - 1);
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    const float* base = a.partial + (((size_t)kvh * gridDim.y + qg) * a.n_split * NT * 16) * (HD + 2);
-    const size_t sstride = (size_t)NT * 16 * (HD + 2);
-    for (int idx = tid; idx < NT * 16 * HD; idx += NW * 64) {
-        const int ql = idx / HD, e = idx % HD, qi = q_base + ql;
-        if (qi >= nQ) continue;
-        const float* pq = base + (size_t)ql * (HD + 2);
-        float mstar = -INFINITY;
-        for (int s = 0; s < a.n_split; ++s) mstar = fmaxf(mstar, pq[s * sstride + HD]);
+// Merges the n_split partial results of one query in split order and writes the output-projection operand.
+// Grid (kv heads, queries), one thread per head-dim element.
+__global__ void attn_combine_kernel(AttnArgs a, int nt, int qgroups) {
+    const int kvh = blockIdx.x, qi = blockIdx.y, HD = a.head_dim;
+    const int G = a.n_heads / a.n_kv_heads;
+    const int qg = qi / (nt * 16), ql = qi % (nt * 16);
+    const size_t sstride = (size_t)nt * 16 * (HD + 2);
+    const float* pq = a.partial + (((size_t)kvh * qgroups + qg) * a.n_split) * sstride + (size_t)ql * (HD + 2);
+    float mstar = -INFINITY;
+    for (int s = 0; s < a.n_split; ++s) mstar = fmaxf(mstar, pq[s * sstride + HD]);
+    for (int e = threadIdx.x; e < HD; e += blockDim.x) {
         float L = 0.f, O = 0.f;
+#pragma unroll 4
         for (int s = 0; s < a.n_split; ++s) {
             const float ms = pq[s * sstride + HD];
             const float f = (ms == -INFINITY) ? 0.f : exp2f(ms - mstar);
@@ -263,7 +257,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(AttnArgs a) {
         const int row = qi / G, h = kvh * G + qi % G;
         store_operand<kDtBf16>(a.out_op, a.R, 0, row, h * HD + e, O / L);
     }
-    if (tid == 0) a.counters[kvh * gridDim.y + qg] = 0u;  // ready for the next launch (stream-ordered)
 }
 
 // fp32 path: one workgroup per (query head, row); plain loops, exact softmax over all visible keys.

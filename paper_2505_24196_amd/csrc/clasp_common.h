@@ -16,16 +16,33 @@ constexpr int kWave = 64;         // CDNA wavefront
 constexpr int kDtF32 = 0, kDtBf16 = 1;
 
 // ---- bf16 activation operand layout -----------------------------------------------------------------------
-// An activation matrix X[rows <= 16*R][K] that a GEMM will contract over K is kept in HBM as MFMA operand
-// fragments: for k-step s (32 consecutive k) and row group rg (16 rows) one fragment of 64 lanes, lane (q*16 + r)
-// holding X[rg*16 + r][s*32 + q*8 .. +8] twice: 8 bf16 "hi" = round(x) followed by 8 bf16 "lo" = round(x - hi).
-// A wavefront fetches a fragment with two 16-byte-per-lane loads (32 contiguous bytes per lane) and feeds hi and
-// lo to v_mfma_f32_16x16x32_bf16 unchanged; hi + lo carries 16 mantissa bits, so the activations lose next to
-// nothing against fp32 while the weights stay bf16. Weights use the same tile shape (one plane) with the 16 output
-// features of a column tile in place of the 16 rows (see pack kernel).
+// An activation matrix X[rows <= 16*R][K] that a GEMM will contract over K is kept in HBM per k-step s (32
+// consecutive k) and row group rg (16 rows) as two planes of 16 rows x 32 bf16, row-major: "hi" = round(x) and
+// "lo" = round(x - hi). MFMA lane (q*16 + r) fetches X[rg*16 + r][s*32 + q*8 .. +8] of each plane with one 16-byte
+// load and feeds it to v_mfma_f32_16x16x32_bf16 unchanged; lanes whose row does not exist fetch nothing, so the
+// traffic follows the number of live rows. hi + lo carries 16 mantissa bits: the activations lose next to nothing
+// against fp32 while the weights stay bf16.
 __device__ __forceinline__ size_t frag_elem_offset(int R, int row, int k) {
-    const int s = k >> 5, q = (k >> 3) & 3, e = k & 7, rg = row >> 4, r = row & 15;
-    return ((((size_t)s * R + rg) * 64) + q * 16 + r) * 16 + e;  // hi element; lo sits 8 elements further
+    const int s = k >> 5, rg = row >> 4, r = row & 15;
+    return ((((size_t)s * R + rg) * 2) * 16 + r) * 32 + (k & 31);  // hi plane; the lo plane sits 512 elements on
+}
+constexpr int kLoPlane = 512;
+
+// ---- bf16 KV cache layout -------------------------------------------------------------------------------------
+// Per KV head the cache is a sequence of 32-position blocks, each stored as the MFMA operand fragments the
+// attention kernel consumes, so that every wavefront-wide load is one contiguous KiB (gathers of 64-byte row pieces
+// cost this part several times more issue time than they move data):
+//   K block: [u = 2 key tiles][kk = head_dim/32 k-steps][64 lanes][8]; lane q*16 + m of tile u holds
+//            K[position 8*(m/4) + 4*u + m%4][kk*32 + q*8 .. +8]   (the two 16-key tiles interleave in groups of 4 so
+//            that a lane's exponentiated scores are directly the 8-key fragment of the P.V product)
+//   V block: [c = head_dim/16 feature tiles][64 lanes][8]; lane q*16 + m holds V[position q*8 .. +8][c*16 + m]
+// Offsets are in elements from the head's base (head stride = t_max * head_dim).
+__device__ __forceinline__ size_t kfrag_offset(int HD, int t, int x) {
+    const int o = t & 31, u = (o >> 2) & 1, m = ((o >> 3) << 2) | (o & 3);
+    return ((((size_t)(t >> 5) * 2 + u) * (HD >> 5) + (x >> 5)) * 64 + ((x >> 3) & 3) * 16 + m) * 8 + (x & 7);
+}
+__device__ __forceinline__ size_t vfrag_offset(int HD, int t, int x) {
+    return ((((size_t)(t >> 5) * (HD >> 4) + (x >> 4)) * 64) + ((t >> 3) & 3) * 16 + (x & 15)) * 8 + (t & 7);
 }
 
 __device__ __forceinline__ bf16 to_bf16(float x) { return static_cast<bf16>(x); }  // round-to-nearest-even
@@ -78,7 +95,7 @@ __device__ __forceinline__ void store_operand(void* buf, int R, int ld, int row,
         bf16* p = reinterpret_cast<bf16*>(buf) + frag_elem_offset(R, row, k);
         const bf16 hi = to_bf16(v);
         p[0] = hi;
-        p[8] = to_bf16(v - from_bf16(hi));
+        p[kLoPlane] = to_bf16(v - from_bf16(hi));
     } else {
         reinterpret_cast<float*>(buf)[(size_t)row * ld + k] = v;
     }
@@ -97,7 +114,7 @@ __device__ __forceinline__ void store_operand4(void* buf, int R, int ld, int row
             lo[i] = to_bf16(v[i] - from_bf16(hi[i]));
         }
         *reinterpret_cast<bf16x4*>(p) = hi;
-        *reinterpret_cast<bf16x4*>(p + 8) = lo;
+        *reinterpret_cast<bf16x4*>(p + kLoPlane) = lo;
     } else {
         *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(buf) + (size_t)row * ld + k) = v;
     }

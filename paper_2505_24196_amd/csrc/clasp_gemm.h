@@ -4,10 +4,10 @@
 // are organised around keeping 16-byte-per-lane weight loads in flight; MFMA does the arithmetic because the
 // vector ALUs could not keep up with 16..32 rows at 8 TB/s.
 //
-// bf16 kernel: one workgroup per tile of 16 output features; its NW wavefronts split K and each streams its slice
-// of the tile (contiguous in the packed weight order) with a register double buffer of P fragments; the activation
-// fragments (hi and lo planes) come from L2 in the same order. Partial tiles are reduced through LDS in a fixed
-// order (deterministic, independent of the number of rows), then the first R wavefronts run the epilogue.
+// bf16 kernel: a wavefront streams a k-slice of one tile of 16 output features (contiguous in the packed weight
+// order) with a register double buffer of P fragments; the activation fragments (hi and lo planes) come from L2/L1
+// in the same order. Partial tiles are reduced in a fixed order (deterministic, independent of the number of rows)
+// through LDS and, when K is also split across workgroups, through a scratch buffer; then the epilogue runs.
 //
 // Epilogues (they produce what the NEXT kernel consumes, so that no separate norm / rotary / activation kernels
 // exist):
@@ -16,7 +16,8 @@
 //                                                            folded into the activation fragments)
 //   kEpiResid   out = resid + acc; optionally a copy (hidden-state capture), the next GEMM's operand
 //               (out * gain, in operand layout) and per-tile partial sums of out^2 for the next 1/rms
-//   kEpiSwiglu  two weight streams (gate, up): operand of the down projection = silu(g*rstd) * (u*rstd)
+//   kEpiSwiglu  gate and up projections interleaved in one packed matrix (8 gate + 8 up features per tile):
+//               operand of the down projection = silu(g*rstd) * (u*rstd)
 //   kEpiQkv     q/k/v projection for the MFMA attention kernel: scales by rstd, applies the rotary embedding to q
 //               and k (the packed wq/wk put the two halves of a rotary pair into one 16-feature tile), and writes
 //               q as ready-made MFMA fragments, k and v into the KV cache (verify/draft rows) or into the small
@@ -33,14 +34,14 @@ struct QkvOut {
     const float2* rope;  // [max_seq][head_dim/2] (cos, sin)
     float q_scale;       // softmax scale * log2(e), folded into q
     void* q_frag;        // [n_kv_heads][2*group][head_dim/32][64][8] bf16 (see attention kernel)
-    void* k_cache;       // this layer, [n_kv_heads][t_max][head_dim]
-    void* v_cache;       // this layer, [n_kv_heads][head_dim][t_max]
-    void* k_self;        // [n_kv_heads][32][head_dim]
-    void* v_self;        // [n_kv_heads][head_dim][32]
+    void* k_cache;       // this layer, per KV head t_max/32 blocks in fragment order (kfrag_offset)
+    void* v_cache;       // this layer, same (vfrag_offset)
+    void* k_self;        // [n_kv_heads] one block each: the DP candidates' own keys
+    void* v_self;        // [n_kv_heads] one block each
 };
 
 struct GemmArgs {
-    const void* W[3];   // up to three matrices stacked along N (q|k|v); kEpiSwiglu: W[0] = gate, W[1] = up
+    const void* W[3];   // up to three matrices stacked along N (q|k|v); fp32 kEpiSwiglu: W[0] = gate, W[1] = up
     int tile_end[3];    // exclusive end tile (16 features) of each stacked matrix
     const void* A;      // activation operand: bf16 hi/lo fragments, or fp32 row-major [rows][K]
     int n_rows, N, K, R;
@@ -88,9 +89,11 @@ struct GemmStage {
     u32x4 a[P][R][SPLIT];
 };
 
+// af already points at this lane's 16 bytes inside a plane; row_live[rg] tells whether the lane's row exists (rows
+// beyond n_rows are not fetched at all: the operand is row-major inside a k-step, so they cost no traffic).
 template <int R, int NACC, int P, int SPLIT>
 __device__ __forceinline__ void gemm_issue(GemmStage<R, NACC, P, SPLIT>& st, const u32x4* w0, const u32x4* w1,
-                                           const u32x4* af, int s, int ks1) {
+                                           const u32x4* af, const bool (&row_live)[R], int s, int ks1) {
 #pragma unroll
     for (int u = 0; u < P; ++u) {
         const int ss = min(s + u, ks1 - 1);
@@ -99,7 +102,8 @@ __device__ __forceinline__ void gemm_issue(GemmStage<R, NACC, P, SPLIT>& st, con
 #pragma unroll
         for (int rg = 0; rg < R; ++rg)
 #pragma unroll
-            for (int h = 0; h < SPLIT; ++h) st.a[u][rg][h] = af[((size_t)ss * R + rg) * 128 + h];
+            for (int h = 0; h < SPLIT; ++h)
+                st.a[u][rg][h] = row_live[rg] ? af[(((size_t)ss * R + rg) * 2 + h) * 64] : u32x4{0u, 0u, 0u, 0u};
     }
 }
 
@@ -142,8 +146,8 @@ __device__ __forceinline__ void qkv_epilogue(const GemmArgs& g, int tile, int la
             const int x = u * 16 + c;
             if (row < g.n_rows) {
                 const bf16 v = to_bf16(own);
-                if (o.mode) vc[((size_t)head * HD + x) * o.t_max + o.pos0 + row] = v;
-                else reinterpret_cast<bf16*>(o.v_self)[((size_t)head * HD + x) * 32 + row] = v;
+                if (o.mode) vc[(size_t)head * o.t_max * HD + vfrag_offset(HD, o.pos0 + row, x)] = v;
+                else reinterpret_cast<bf16*>(o.v_self)[(size_t)head * 32 * HD + vfrag_offset(HD, row, x)] = v;
             }
             continue;
         }
@@ -159,69 +163,18 @@ __device__ __forceinline__ void qkv_epilogue(const GemmArgs& g, int tile, int la
                                     ((x >> 3) & 3) * 16 + (qi & 15)) * 8 + (x & 7);
                 reinterpret_cast<bf16*>(o.q_frag)[off] = to_bf16(rot * o.q_scale);
             } else if (o.mode) {
-                kc[((size_t)head * o.t_max + pos) * HD + x] = to_bf16(rot);
+                kc[(size_t)head * o.t_max * HD + kfrag_offset(HD, pos, x)] = to_bf16(rot);
             } else {
-                reinterpret_cast<bf16*>(o.k_self)[((size_t)head * 32 + row) * HD + x] = to_bf16(rot);
+                reinterpret_cast<bf16*>(o.k_self)[(size_t)head * 32 * HD + kfrag_offset(HD, row, x)] = to_bf16(rot);
             }
         }
     }
 }
 
-template <int R, int NW, int EPI, int P, int SPLIT>
-__global__ __launch_bounds__(NW * 64) void gemm_bf16_kernel(GemmArgs g) {
-    constexpr int NACC = (EPI == kEpiSwiglu) ? 2 : 1;
-    __shared__ f32x4 red[NW][NACC][R][64];
-    __shared__ float rstd_s[kMaxRows];
-    __shared__ float tmp_s[NW * 64];
-    const int tile = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int KS = g.K >> 5;
-    const int ks0 = (KS * wave) / NW, ks1 = (KS * (wave + 1)) / NW;
-
-    int mi = 0, tl = tile;
-    if constexpr (EPI == kEpiScale || EPI == kEpiQkv) {
-        if (tile >= g.tile_end[0]) { mi = 1; tl = tile - g.tile_end[0]; }
-        if (tile >= g.tile_end[1]) { mi = 2; tl = tile - g.tile_end[1]; }
-    }
-    const u32x4* w0 = reinterpret_cast<const u32x4*>(g.W[mi]) + (size_t)tl * KS * 64 + lane;
-    const u32x4* w1 = (NACC == 2) ? reinterpret_cast<const u32x4*>(g.W[1]) + (size_t)tl * KS * 64 + lane : nullptr;
-    const u32x4* af = reinterpret_cast<const u32x4*>(g.A) + lane * 2;
-
-    f32x4 acc[NACC][R];
-#pragma unroll
-    for (int a = 0; a < NACC; ++a)
-#pragma unroll
-        for (int rg = 0; rg < R; ++rg) acc[a][rg] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    GemmStage<R, NACC, P, SPLIT> st0, st1;
-    int s = ks0;
-    if (s < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w0, w1, af, s, ks1);  // weights first: independent of rstd
-
-    if constexpr (EPI != kEpiResid) compute_rstd(g, rstd_s, tmp_s);
-
-    while (s < ks1) {
-        if (s + P < ks1) gemm_issue<R, NACC, P, SPLIT>(st1, w0, w1, af, s + P, ks1);
-        gemm_compute<R, NACC, P, SPLIT>(st0, acc, s, ks1);
-        s += P;
-        if (s >= ks1) break;
-        if (s + P < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w0, w1, af, s + P, ks1);
-        gemm_compute<R, NACC, P, SPLIT>(st1, acc, s, ks1);
-        s += P;
-    }
-
-#pragma unroll
-    for (int a = 0; a < NACC; ++a)
-#pragma unroll
-        for (int rg = 0; rg < R; ++rg) red[wave][a][rg][lane] = acc[a][rg];
-    __syncthreads();
-    if (wave >= R) return;
-
-    const int rg = wave;
-    f32x4 sum[NACC];
-#pragma unroll
-    for (int a = 0; a < NACC; ++a) {
-        sum[a] = red[0][a][rg][lane];
-        for (int w = 1; w < NW; ++w) sum[a] += red[w][a][rg][lane];
-    }
+// Epilogue of one (tile, row group) for one lane: 4 rows x 1 feature; sum[a] = finished accumulators.
+template <int EPI, int NACC>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, int tile, int lane, int rg, const f32x4 (&sum)[NACC],
+                                              const float* rstd_s) {
     const int col = tile * 16 + (lane & 15);
     const int row0 = rg * 16 + (lane >> 4) * 4;
     if constexpr (EPI == kEpiScale) {
@@ -250,15 +203,197 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_kernel(GemmArgs g) {
             }
         }
     } else {
+        // the packed gate|up matrix interleaves the two projections: lanes 0..7 of a tile hold gate features
+        // 8*tile .. 8*tile+7, lanes 8..15 the matching up features
+        const int c = lane & 15;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int row = row0 + r;
-            float v = 0.f;
-            if (row < g.n_rows) {
-                const float gt = sum[0][r] * rstd_s[row], up = sum[1][r] * rstd_s[row];
-                v = gt / (1.0f + expf(-gt)) * up;
+            const float own = sum[0][r] * rstd_s[row & 31];
+            const float up = __shfl_xor(own, 8);
+            const float v = (row < g.n_rows) ? own / (1.0f + expf(-own)) * up : 0.f;
+            if (c < 8) store_operand<kDtBf16>(g.next_op, g.R, 0, row, tile * 8 + c, v);
+        }
+    }
+}
+
+// Workgroup = CW x KW wavefronts: wavefront (cw, kw) streams column tile blockIdx.x*CW + cw over k-slice kw of KW
+// equal slices. The CW wavefronts that share a k-slice read the same activation fragments at about the same time
+// (one L2 fetch, the rest hit in L1); the KW partial tiles of a column tile are summed through LDS in slice order.
+// (Cross-workgroup split-K inside one kernel is not used: agent-scope release fences cost far more than they save
+// on this part, every one of them writes the whole L2 back.)
+template <int R, int CW, int KW, int EPI, int P, int SPLIT>
+__global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
+    constexpr int NW = CW * KW;
+    constexpr int NACC = 1;
+    __shared__ f32x4 red[KW][CW][NACC][R][64];
+    __shared__ float rstd_s[kMaxRows];
+    __shared__ float tmp_s[NW * 64];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int cw = wave % CW, kw = wave / CW;
+    const int n_tiles = g.N >> 4;
+    const int tile_raw = blockIdx.x * CW + cw;
+    const bool live = tile_raw < n_tiles;
+    const int tile = live ? tile_raw : n_tiles - 1;  // idle wavefronts shadow the last tile, their result is dropped
+    const int KS = g.K >> 5;
+    const int ks0 = (KS * kw) / KW, ks1 = (KS * (kw + 1)) / KW;
+
+    int mi = 0, tl = tile;
+    if constexpr (EPI == kEpiScale || EPI == kEpiQkv) {
+        if (tile >= g.tile_end[0]) { mi = 1; tl = tile - g.tile_end[0]; }
+        if (tile >= g.tile_end[1]) { mi = 2; tl = tile - g.tile_end[1]; }
+    }
+    const u32x4* w0 = reinterpret_cast<const u32x4*>(g.W[mi]) + (size_t)tl * KS * 64 + lane;
+    const u32x4* w1 = (NACC == 2) ? reinterpret_cast<const u32x4*>(g.W[1]) + (size_t)tl * KS * 64 + lane : nullptr;
+    const u32x4* af = reinterpret_cast<const u32x4*>(g.A) + (lane & 15) * 4 + (lane >> 4);
+    bool row_live[R];
+#pragma unroll
+    for (int rg = 0; rg < R; ++rg) row_live[rg] = rg * 16 + (lane & 15) < g.n_rows;
+
+    f32x4 acc[NACC][R];
+#pragma unroll
+    for (int a = 0; a < NACC; ++a)
+#pragma unroll
+        for (int rg = 0; rg < R; ++rg) acc[a][rg] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    GemmStage<R, NACC, P, SPLIT> st0, st1;
+    int s = ks0;
+    if (s < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w0, w1, af, row_live, s, ks1);  // weights first: independent of rstd
+
+    if constexpr (EPI != kEpiResid) compute_rstd(g, rstd_s, tmp_s);
+
+    while (s < ks1) {
+        if (s + P < ks1) gemm_issue<R, NACC, P, SPLIT>(st1, w0, w1, af, row_live, s + P, ks1);
+        gemm_compute<R, NACC, P, SPLIT>(st0, acc, s, ks1);
+        s += P;
+        if (s >= ks1) break;
+        if (s + P < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w0, w1, af, row_live, s + P, ks1);
+        gemm_compute<R, NACC, P, SPLIT>(st1, acc, s, ks1);
+        s += P;
+    }
+
+    f32x4 sum[NACC][R];
+    if constexpr (KW > 1) {
+#pragma unroll
+        for (int a = 0; a < NACC; ++a)
+#pragma unroll
+            for (int rg = 0; rg < R; ++rg) red[kw][cw][a][rg][lane] = acc[a][rg];
+        __syncthreads();
+        if (kw == 0) {
+#pragma unroll
+            for (int a = 0; a < NACC; ++a)
+#pragma unroll
+                for (int rg = 0; rg < R; ++rg) {
+                    sum[a][rg] = red[0][cw][a][rg][lane];
+                    for (int k = 1; k < KW; ++k) sum[a][rg] += red[k][cw][a][rg][lane];
+                }
+        }
+    } else {
+#pragma unroll
+        for (int a = 0; a < NACC; ++a)
+#pragma unroll
+            for (int rg = 0; rg < R; ++rg) sum[a][rg] = acc[a][rg];
+    }
+
+    if (kw != 0 || !live) return;
+
+#pragma unroll
+    for (int rg = 0; rg < R; ++rg) {
+        f32x4 fin[NACC];
+#pragma unroll
+        for (int x = 0; x < NACC; ++x) fin[x] = sum[x][rg];
+        gemm_epilogue<EPI, NACC>(g, tile, lane, rg, fin, rstd_s);
+    }
+}
+
+// Resident-activation variant for one row group (rows <= 16) and K/32 <= KW*KSW: wavefront kw keeps ITS k-slice of the
+// activation fragments (hi and lo) in registers for the whole kernel, and the workgroup walks over column tiles
+// blockIdx.x, blockIdx.x + gridDim.x, ... streaming nothing but weights: one 16-byte load per lane per MFMA pair.
+// The register double buffer runs across tile boundaries (the next tile's first fragments are requested before the
+// current tile's last ones are consumed), the per-tile reduction over the KW slices goes through a double-buffered
+// LDS tile with one barrier per tile, and the epilogue duty rotates over the wavefronts.
+template <int KSW, int KW, int EPI, int P, int SPLIT>
+__global__ __launch_bounds__(KW * 64) void gemm_bf16_resident_kernel(GemmArgs g) {
+    static_assert(KSW % P == 0 && (KSW / P) % 2 == 0, "a tile must take an even number of register stages");
+    constexpr int NACC = 1;
+    constexpr int NST = KSW / P;
+    __shared__ f32x4 red[2][KW][NACC][64];
+    __shared__ float rstd_s[kMaxRows];
+    __shared__ float tmp_s[KW * 64];
+    const int kw = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int n_tiles = g.N >> 4, KS = g.K >> 5;
+    const int ks0 = (KS * kw) / KW, nks = (KS * (kw + 1)) / KW - ks0;  // nks <= KSW (checked on the host)
+
+    // this wavefront's slice of the activations, resident for the whole kernel
+    u32x4 areg[KSW][SPLIT];
+    {
+        const u32x4* af = reinterpret_cast<const u32x4*>(g.A) + (lane & 15) * 4 + (lane >> 4);
+        const bool row_live = (lane & 15) < g.n_rows;
+#pragma unroll
+        for (int i = 0; i < KSW; ++i)
+#pragma unroll
+            for (int h = 0; h < SPLIT; ++h)
+                areg[i][h] = (row_live && i < nks) ? af[((size_t)(ks0 + i) * 2 + h) * 64] : u32x4{0u, 0u, 0u, 0u};
+    }
+
+    auto wptr = [&](int tile, int which) -> const u32x4* {
+        int mi = which, tl = tile;
+        if constexpr (EPI == kEpiScale || EPI == kEpiQkv) {
+            if (tile >= g.tile_end[0]) { mi = 1; tl = tile - g.tile_end[0]; }
+            if (tile >= g.tile_end[1]) { mi = 2; tl = tile - g.tile_end[1]; }
+        }
+        return reinterpret_cast<const u32x4*>(g.W[mi]) + ((size_t)tl * KS + ks0) * 64 + lane;
+    };
+    u32x4 wb[2][NACC][P];
+    auto issue = [&](u32x4 (&buf)[NACC][P], int tile, int j) {  // stage j of `tile`: k-steps j*P .. j*P+P-1 of the slice
+#pragma unroll
+        for (int a = 0; a < NACC; ++a) {
+            const u32x4* w = wptr(tile, a);
+#pragma unroll
+            for (int u = 0; u < P; ++u) buf[a][u] = load_stream(w + (size_t)min(j * P + u, nks - 1) * 64);
+        }
+    };
+
+    int tile = blockIdx.x;
+    if (tile < n_tiles && nks > 0) issue(wb[0], tile, 0);
+    if constexpr (EPI != kEpiResid) compute_rstd(g, rstd_s, tmp_s);
+
+    for (int it = 0; tile < n_tiles; tile += gridDim.x, ++it) {
+        f32x4 acc[NACC];
+#pragma unroll
+        for (int a = 0; a < NACC; ++a) acc[a] = f32x4{0.f, 0.f, 0.f, 0.f};
+        const int next_tile = tile + gridDim.x;
+#pragma unroll
+        for (int j = 0; j < NST; ++j) {
+            // request the next stage (of this tile, or the first one of the next tile) before consuming this one
+            if (nks > 0) {
+                if (j + 1 < NST) issue(wb[(j + 1) & 1], tile, j + 1);
+                else if (next_tile < n_tiles) issue(wb[0], next_tile, 0);
             }
-            store_operand<kDtBf16>(g.next_op, g.R, 0, row, col, v);
+#pragma unroll
+            for (int u = 0; u < P; ++u) {
+                if (j * P + u < nks) {
+#pragma unroll
+                    for (int h = 0; h < SPLIT; ++h)
+#pragma unroll
+                        for (int a = 0; a < NACC; ++a)
+                            acc[a] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(areg[j * P + u][h]),
+                                                                             as_bf16x8(wb[j & 1][a][u]), acc[a], 0, 0, 0);
+                }
+            }
+        }
+        f32x4(&rb)[KW][NACC][64] = red[it & 1];
+#pragma unroll
+        for (int a = 0; a < NACC; ++a) rb[kw][a][lane] = acc[a];
+        __syncthreads();
+        if (kw == it % KW) {
+            f32x4 fin[NACC];
+#pragma unroll
+            for (int a = 0; a < NACC; ++a) {
+                fin[a] = rb[0][a][lane];
+                for (int k = 1; k < KW; ++k) fin[a] += rb[k][a][lane];
+            }
+            gemm_epilogue<EPI, NACC>(g, tile, lane, 0, fin, rstd_s);
         }
     }
 }

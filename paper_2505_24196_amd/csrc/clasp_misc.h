@@ -30,6 +30,24 @@ __global__ void pack_bf16_kernel(const u32x4* __restrict__ src, u32x4* __restric
     }
 }
 
+// gate|up interleave: packed tile t holds gate features 8t..8t+7 (lanes c < 8) and up features 8t..8t+7 (c >= 8), so
+// that one weight stream feeds the SwiGLU epilogue and the tile count is 2*F/16 (finer, better balanced work).
+__global__ void pack_gate_up_bf16_kernel(const u32x4* __restrict__ gate, const u32x4* __restrict__ up,
+                                         u32x4* __restrict__ dst, int F, int K) {
+    const size_t total = (size_t)2 * F * K / 8;
+    const int KS = K >> 5;
+    for (size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x; v < total; v += (size_t)gridDim.x * blockDim.x) {
+        const int lane = (int)(v & 63);
+        const size_t frag = v >> 6;
+        const int s = (int)(frag % KS);
+        const size_t tile = frag / KS;
+        const int c = lane & 15, q = lane >> 4;
+        const size_t row = tile * 8 + (c & 7);
+        const u32x4* src = (c < 8) ? gate : up;
+        dst[v] = src[(row * K + (size_t)s * 32 + q * 8) / 8];
+    }
+}
+
 // ---- rotary table: (cos, sin)(pos * base^(-2e/hd)) evaluated in double, stored as float2 ------------------------
 __global__ void rope_table_kernel(float2* table, int max_seq, int half, double base) {
     const size_t total = (size_t)max_seq * half;
@@ -89,8 +107,9 @@ __global__ void kv_load_kernel(const float* K, const float* V, void* Kc, void* V
         const size_t t = i / ((size_t)hd * nkv);
         const size_t ko = ((size_t)kvh * t_max + t) * hd + e, vo = ((size_t)kvh * hd + e) * t_max + t;
         if constexpr (DT == kDtBf16) {
-            reinterpret_cast<bf16*>(Kc)[ko] = to_bf16(K[i]);
-            reinterpret_cast<bf16*>(Vt)[vo] = to_bf16(V[i]);
+            const size_t head = (size_t)kvh * t_max * hd;
+            reinterpret_cast<bf16*>(Kc)[head + kfrag_offset(hd, (int)t, e)] = to_bf16(K[i]);
+            reinterpret_cast<bf16*>(Vt)[head + vfrag_offset(hd, (int)t, e)] = to_bf16(V[i]);
         } else {
             reinterpret_cast<float*>(Kc)[ko] = K[i];
             reinterpret_cast<float*>(Vt)[vo] = V[i];
