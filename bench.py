@@ -20,6 +20,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the dominant kernel from rocprofv3 PMC runs (FETCH_SIZE + WRITE_SIZE, each scaled by what the
+# counter reads for a 1 GiB copy); see profiles/gate_up_gemm_llama3-8b-shape_hbm_traffic.md
+MEASURED_TRAFFIC = {"llama3-8b-shape": 236.8e6 + 1.84e6}
 
 WORKLOADS = {
     # BASELINE config 2: the configuration the metric is quoted on
@@ -110,6 +113,9 @@ def main():
     ap.add_argument("--workload", default="llama3-8b-shape/T512/M12/K4", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timer", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="only run plain device copies of a known size (1 GiB read + 1 GiB written per copy), to scale "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
@@ -118,6 +124,15 @@ def main():
     import synth_inputs as si
     import paper_2505_24196_amd as clasp
     from paper_2505_24196_amd import decode
+
+    if args.pmc_calibration:
+        src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda")  # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "5 device copies, each reads 1 GiB and writes 1 GiB (1048576 KiB)"}))
+        return
 
     wl = WORKLOADS[args.workload]
     shape = si.SHAPES[wl["shape"]]
@@ -198,10 +213,11 @@ def main():
     if kt_n:
         avg_ms = kt_ms / kt_n
         ach = ab["gate_up_kernel"] / (avg_ms * 1e-3) / 1e9
-        out["roofline"] = {"bound": "hbm", "kernel": "gemm_bf16_kernel<SwiGLU> (gate/up projection)" if shape.dtype == "bf16"
+        out["roofline"] = {"bound": "hbm", "kernel": "gemm_bf16_resident_kernel<SwiGLU> (gate|up projection)" if shape.dtype == "bf16"
                            else "gemm_f32_kernel<SwiGLU> (gate/up projection)",
                            "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                           "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None, "launches": kt_n,
+                           "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get(shape.name),
+                           "launches": kt_n,
                            "avg_us": round(avg_ms * 1e3, 2), "bytes_per_launch": ab["gate_up_kernel"]}
     eng.close()
     del eng

@@ -56,6 +56,16 @@ namespace {
 #ifndef CLASP_GEMM_DEPTH
 #define CLASP_GEMM_DEPTH 4
 #endif
+// the DP's down projection: K split over CLASP_DOWNP_KS workgroups per group of CLASP_DOWNP_CW column tiles
+#ifndef CLASP_DOWNP_CW
+#define CLASP_DOWNP_CW 4
+#endif
+#ifndef CLASP_DOWNP_KW
+#define CLASP_DOWNP_KW 2
+#endif
+#ifndef CLASP_DOWNP_KS
+#define CLASP_DOWNP_KS 4
+#endif
 #ifndef CLASP_ACT_SPLIT
 #define CLASP_ACT_SPLIT 2  // 2: activations enter the MFMAs as bf16 hi + lo; 1: hi only
 #endif
@@ -100,6 +110,7 @@ struct clasp_ctx {
     float *a_buf, *h[2], *g[2], *G;
     float* logits;
     float* attn_partial;
+    float* down_parts;  // [CLASP_DOWNP_KS][32][d] K-slices of the DP's down projection
     void *q_frag, *k_self, *v_self;
     uint8_t* choice;
     int32_t* tok_tmp;
@@ -133,6 +144,7 @@ size_t carve(const clasp_config& c, char* base, clasp_ctx* ctx) {
     auto* logits = w.take<float>(rows * (size_t)c.vocab * 4);
     const size_t grp = c.n_heads / c.n_kv_heads;
     auto* part = w.take<float>((size_t)c.n_kv_heads * (2 * grp + 4) * 16 * kMaxSplit * (c.head_dim + 2) * 4);
+    auto* down_parts = w.take<float>((size_t)CLASP_DOWNP_KS * rows * d * 4);
     auto* q_frag = w.take<void>(qd * 64 + 4 * (size_t)c.head_dim * 32);  // + 4 query tiles of slack for padded groups
     auto* k_self = w.take<void>(kvd * 64);
     auto* v_self = w.take<void>(kvd * 64);
@@ -143,7 +155,7 @@ size_t carve(const clasp_config& c, char* base, clasp_ctx* ctx) {
         ctx->op_act = op_act; ctx->ss_h = ss_h; ctx->ss_a = ss_a; ctx->a_buf = a_buf; ctx->h[0] = h0; ctx->h[1] = h1;
         ctx->g[0] = g0; ctx->g[1] = g1; ctx->G = G; ctx->logits = logits; ctx->attn_partial = part;
         ctx->choice = choice; ctx->tok_tmp = tok; 
-        ctx->q_frag = q_frag; ctx->k_self = k_self; ctx->v_self = v_self;
+        ctx->down_parts = down_parts; ctx->q_frag = q_frag; ctx->k_self = k_self; ctx->v_self = v_self;
     }
     return w.off;
 }
@@ -203,8 +215,10 @@ int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kin
         const bool resident = g.R == 1 && ((CLASP_RESIDENT_MASK >> kind) & 1) &&
                               (g.K / 32 + kResidentKW - 1) / kResidentKW <= kResidentKSW && tiles > ctx->n_cu;
         if (resident) {
+            // every workgroup takes the same number of tiles (+-1): rounds = ceil(tiles / CUs), grid = ceil(tiles / rounds)
+            const int rounds = (tiles + ctx->n_cu - 1) / ctx->n_cu, grid = (tiles + rounds - 1) / rounds;
             hipLaunchKernelGGL((gemm_bf16_resident_kernel<kResidentKSW, kResidentKW, EPI, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>),
-                               dim3(ctx->n_cu), dim3(kResidentKW * 64), 0, st, g);
+                               dim3(grid), dim3(kResidentKW * 64), 0, st, g);
         } else {
             const dim3 grid((tiles + CW - 1) / CW);
             if (g.R == 1)
@@ -292,8 +306,11 @@ int launch_attention(const clasp_ctx* ctx, int layer, int n, int R, int mode, in
 // One decoder layer on n rows. The rows' fp32 values are at h_in ([n][d]); their GEMM operand (times the layer's
 // attention-norm gains) and sums of squares must already sit in op_h / ss_h. Writes h_out ([n][d]) and, if asked,
 // the operand / sums of squares of h_out for whatever consumes it next, and a copy for hidden-state capture.
+// down_split > 1: the down projection only leaves its K-slices in ctx->down_parts (rows of a_buf are the residual);
+// the caller's next kernel adds them up (the DP's select kernel does).
 int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, const float* h_in, float* h_out,
-              void* next_op, const float* next_gain, float* next_ss, float* capture, hipStream_t st) {
+              void* next_op, const float* next_gain, float* next_ss, float* capture, hipStream_t st,
+              int down_split = 1) {
     const clasp_config& c = ctx->cfg;
     const int d = c.d_model, F = c.d_ffn;
     int rc;
@@ -340,7 +357,21 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
         g.next_op = ctx->op_act;
         if ((rc = launch_gemm<kEpiSwiglu, CLASP_GATEUP_CW, CLASP_GATEUP_KW>(ctx, g, st, CLASP_KERNEL_GATE_UP))) return rc;
     }
-    {
+    if (down_split > 1 && c.dtype == CLASP_BF16) {
+        GemmArgs g{};
+        g.W[0] = ctx->w_down[l]; g.tile_end[0] = g.tile_end[1] = g.tile_end[2] = d / 16;
+        g.A = ctx->op_act; g.n_rows = n; g.N = d; g.K = F; g.R = R;
+        g.out = ctx->down_parts; g.ldo = d; g.ldr = kMaxRows * d;
+        TimerScope timer(ctx, CLASP_KERNEL_DOWN, st);
+        const dim3 grid((d / 16 + CLASP_DOWNP_CW - 1) / CLASP_DOWNP_CW, down_split);
+        if (R == 1)
+            hipLaunchKernelGGL((gemm_bf16_kernel<1, CLASP_DOWNP_CW, CLASP_DOWNP_KW, kEpiPartial, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>),
+                               grid, dim3(CLASP_DOWNP_CW * CLASP_DOWNP_KW * 64), 0, st, g);
+        else
+            hipLaunchKernelGGL((gemm_bf16_kernel<2, CLASP_DOWNP_CW, CLASP_DOWNP_KW, kEpiPartial, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>),
+                               grid, dim3(CLASP_DOWNP_CW * CLASP_DOWNP_KW * 64), 0, st, g);
+        CLASP_LAUNCH_CHECK();
+    } else {
         GemmArgs g{};
         g.W[0] = ctx->w_down[l]; g.tile_end[0] = g.tile_end[1] = g.tile_end[2] = d / 16;
         g.A = ctx->op_act; g.n_rows = n; g.N = d; g.K = F; g.R = R;
@@ -620,6 +651,7 @@ int clasp_dp_select(clasp_ctx* ctx, const float* states, size_t layer_stride, in
     if ((reinterpret_cast<uintptr_t>(states) & 15) || (layer_stride & 3)) return CLASP_E_INVALID_ARG;  // float4 loads
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int R = M > 16 ? 2 : 1;
+    const int down_split = (c.dtype == CLASP_BF16 && c.d_ffn / 32 >= CLASP_DOWNP_KS * CLASP_DOWNP_KW * 8) ? CLASP_DOWNP_KS : 1;
     uint8_t* choice = choice_out ? choice_out : ctx->choice;
     const int cells = (L + 1) * (M + 1);
     hipLaunchKernelGGL(dp_table_init_kernel, dim3((cells + 255) / 256), dim3(256), 0, st, score_out, choice, cells);
@@ -630,13 +662,19 @@ int clasp_dp_select(clasp_ctx* ctx, const float* states, size_t layer_stride, in
         const float* g_prev = (i == 1) ? states : ctx->g[(i - 1) & 1];
         float* g_cur = ctx->g[i & 1];
         if (ell > 0) {  // candidates g(i-1, 1..ell) through layer i-1, all at position `pos`
-            if ((rc = run_layer(ctx, i - 1, ell, R, 0, pos, g_prev + d, ctx->G, nullptr, nullptr, nullptr, nullptr, st)))
+            if ((rc = run_layer(ctx, i - 1, ell, R, 0, pos, g_prev + d, ctx->G, nullptr, nullptr, nullptr, nullptr, st,
+                                down_split)))
                 return rc;
         }
         SelectArgs s{};
         s.i = i; s.M = M; s.d = d; s.R = R;
         s.x_i = states + (size_t)i * layer_stride;
-        s.g_prev = g_prev; s.G = ctx->G; s.g_cur = g_cur;
+        s.g_prev = g_prev; s.g_cur = g_cur;
+        if (down_split > 1) {  // candidates = residual rows (a_buf) + the K-slices the down projection left behind
+            s.G = ctx->a_buf; s.parts = ctx->down_parts; s.n_parts = down_split; s.part_stride = (size_t)kMaxRows * d;
+        } else {
+            s.G = ctx->G;
+        }
         s.op = (i < L) ? ctx->op_h : nullptr;
         s.gain = (i < L) ? ctx->attn_norm[i] : nullptr;
         s.ss = ctx->ss_h;

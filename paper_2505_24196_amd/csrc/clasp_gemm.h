@@ -18,6 +18,9 @@
 //               (out * gain, in operand layout) and per-tile partial sums of out^2 for the next 1/rms
 //   kEpiSwiglu  gate and up projections interleaved in one packed matrix (8 gate + 8 up features per tile):
 //               operand of the down projection = silu(g*rstd) * (u*rstd)
+//   kEpiPartial raw partial sums of this workgroup's K slice, out[blockIdx.y][row][col]: K is split over gridDim.y
+//               workgroups and the consumer (the DP's select kernel, which reads whole rows anyway) adds the slices
+//               in a fixed order together with the residual; there is no cross-workgroup traffic inside the kernel
 //   kEpiQkv     q/k/v projection for the MFMA attention kernel: scales by rstd, applies the rotary embedding to q
 //               and k (the packed wq/wk put the two halves of a rotary pair into one 16-feature tile), and writes
 //               q as ready-made MFMA fragments, k and v into the KV cache (verify/draft rows) or into the small
@@ -27,7 +30,7 @@
 
 namespace clasp {
 
-constexpr int kEpiScale = 0, kEpiResid = 1, kEpiSwiglu = 2, kEpiQkv = 3;
+constexpr int kEpiScale = 0, kEpiResid = 1, kEpiSwiglu = 2, kEpiQkv = 3, kEpiPartial = 4;
 
 struct QkvOut {
     int n_heads, n_kv_heads, head_dim, pos0, mode, t_max;
@@ -185,6 +188,13 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, int tile, int l
         }
     } else if constexpr (EPI == kEpiQkv) {
         qkv_epilogue(g, tile, lane, rg, sum[0], rstd_s);
+    } else if constexpr (EPI == kEpiPartial) {
+        float* slab = g.out + (size_t)blockIdx.y * g.ldr;  // ldr = elements per slab
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = row0 + r;
+            if (row < g.n_rows) slab[(size_t)row * g.ldo + col] = sum[0][r];
+        }
     } else if constexpr (EPI == kEpiResid) {
         const float gain = g.next_gain ? g.next_gain[col] : 1.0f;
 #pragma unroll
@@ -236,7 +246,8 @@ __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
     const bool live = tile_raw < n_tiles;
     const int tile = live ? tile_raw : n_tiles - 1;  // idle wavefronts shadow the last tile, their result is dropped
     const int KS = g.K >> 5;
-    const int ks0 = (KS * kw) / KW, ks1 = (KS * (kw + 1)) / KW;
+    const int nslice = gridDim.y * KW, slice = blockIdx.y * KW + kw;  // gridDim.y > 1 only with kEpiPartial
+    const int ks0 = (int)(((long long)KS * slice) / nslice), ks1 = (int)(((long long)KS * (slice + 1)) / nslice);
 
     int mi = 0, tl = tile;
     if constexpr (EPI == kEpiScale || EPI == kEpiQkv) {
@@ -260,7 +271,7 @@ __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
     int s = ks0;
     if (s < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w0, w1, af, row_live, s, ks1);  // weights first: independent of rstd
 
-    if constexpr (EPI != kEpiResid) compute_rstd(g, rstd_s, tmp_s);
+    if constexpr (EPI != kEpiResid && EPI != kEpiPartial) compute_rstd(g, rstd_s, tmp_s);
 
     while (s < ks1) {
         if (s + P < ks1) gemm_issue<R, NACC, P, SPLIT>(st1, w0, w1, af, row_live, s + P, ks1);

@@ -128,7 +128,11 @@ struct SelectArgs {
     int i, M, d, R;
     const float* x_i;     // [d]
     const float* g_prev;  // g(i-1, .) rows, [M+1][d]
-    const float* G;       // computed candidates, row j-1 for cell j, [ell][d]
+    const float* G;       // computed candidates, row j-1 for cell j, [ell][d]; or, when n_parts > 0, the residual
+                          // rows to which the n_parts K-slices of the down projection still have to be added
+    const float* parts;   // [n_parts][part_stride] partial sums of the down projection, rows of length d
+    int n_parts;
+    size_t part_stride;
     float* g_cur;         // g(i, .) rows, [M+1][d]
     void* op;             // next layer's operand (null when i == L)
     const float* gain;    // next layer's attention-norm gains
@@ -153,10 +157,17 @@ __global__ __launch_bounds__(1024) void dp_select_kernel(SelectArgs a) {
     const f32x4* skip4 = reinterpret_cast<const f32x4*>(a.g_prev + (size_t)(j - 1) * d);
     const bool has_comp = j <= ell;
     const f32x4* comp4 = reinterpret_cast<const f32x4*>(a.G + (size_t)(j - 1) * d);
+    // the computed candidate: a finished row, or residual + K-slices of the down projection added in slice order
+    const f32x4* part4 = reinterpret_cast<const f32x4*>(a.parts + (size_t)(j - 1) * d);
+    auto load_comp = [&](int c) -> f32x4 {
+        f32x4 v = comp4[c];
+        for (int p = 0; p < a.n_parts; ++p) v += part4[p * (a.part_stride / 4) + c];
+        return v;
+    };
     float acc[5] = {0.f, 0.f, 0.f, 0.f, 0.f};  // x.x, s.x, s.s, c.x, c.c
     for (int c = threadIdx.x; c < d / 4; c += blockDim.x) {
         const f32x4 x = x4[c], s = skip4[c];
-        const f32x4 g = has_comp ? comp4[c] : f32x4{0.f, 0.f, 0.f, 0.f};
+        const f32x4 g = has_comp ? load_comp(c) : f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             acc[0] = fmaf(x[e], x[e], acc[0]);
@@ -191,10 +202,9 @@ __global__ __launch_bounds__(1024) void dp_select_kernel(SelectArgs a) {
             a.scores[cell * 2 + 1] = sig_s;
         }
     }
-    const f32x4* src4 = keep_comp ? comp4 : skip4;
     const f32x4* gain4 = reinterpret_cast<const f32x4*>(a.gain);
     for (int c = threadIdx.x; c < d / 4; c += blockDim.x) {
-        const f32x4 v = src4[c];
+        const f32x4 v = keep_comp ? load_comp(c) : skip4[c];
         reinterpret_cast<f32x4*>(dst)[c] = v;
         if (a.op) {
             const f32x4 gn = gain4 ? gain4[c] : f32x4{1.f, 1.f, 1.f, 1.f};
