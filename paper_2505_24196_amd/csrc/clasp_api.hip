@@ -111,6 +111,7 @@ struct clasp_ctx {
     float* logits;
     float* attn_partial;
     float* down_parts;  // [CLASP_DOWNP_KS][32][d] K-slices of the DP's down projection
+    void* head_parts;   // [vocab/16][32] x 16 bytes: per-tile pieces of the greedy head
     void *q_frag, *k_self, *v_self;
     uint8_t* choice;
     int32_t* tok_tmp;
@@ -144,6 +145,7 @@ size_t carve(const clasp_config& c, char* base, clasp_ctx* ctx) {
     auto* logits = w.take<float>(rows * (size_t)c.vocab * 4);
     const size_t grp = c.n_heads / c.n_kv_heads;
     auto* part = w.take<float>((size_t)c.n_kv_heads * (2 * grp + 4) * 16 * kMaxSplit * (c.head_dim + 2) * 4);
+    auto* head_parts = w.take<void>((size_t)(c.vocab / 16) * rows * 16);
     auto* down_parts = w.take<float>((size_t)CLASP_DOWNP_KS * rows * d * 4);
     auto* q_frag = w.take<void>(qd * 64 + 4 * (size_t)c.head_dim * 32);  // + 4 query tiles of slack for padded groups
     auto* k_self = w.take<void>(kvd * 64);
@@ -155,7 +157,7 @@ size_t carve(const clasp_config& c, char* base, clasp_ctx* ctx) {
         ctx->op_act = op_act; ctx->ss_h = ss_h; ctx->ss_a = ss_a; ctx->a_buf = a_buf; ctx->h[0] = h0; ctx->h[1] = h1;
         ctx->g[0] = g0; ctx->g[1] = g1; ctx->G = G; ctx->logits = logits; ctx->attn_partial = part;
         ctx->choice = choice; ctx->tok_tmp = tok; 
-        ctx->down_parts = down_parts; ctx->q_frag = q_frag; ctx->k_self = k_self; ctx->v_self = v_self;
+        ctx->down_parts = down_parts; ctx->head_parts = head_parts; ctx->q_frag = q_frag; ctx->k_self = k_self; ctx->v_self = v_self;
     }
     return w.off;
 }
@@ -227,7 +229,7 @@ int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kin
                 hipLaunchKernelGGL((gemm_bf16_kernel<2, CW, KW, EPI, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>), grid, dim3(CW * KW * 64), 0, st, g);
         }
     } else {
-        if constexpr (EPI == kEpiQkv) return CLASP_E_UNSUPPORTED;
+        if constexpr (EPI == kEpiQkv || EPI == kEpiHead || EPI == kEpiPartial) return CLASP_E_UNSUPPORTED;
         else hipLaunchKernelGGL((gemm_f32_kernel<EPI>), dim3(tiles), dim3(256), 0, st, g);
     }
     CLASP_LAUNCH_CHECK();
@@ -397,17 +399,31 @@ int launch_embed(const clasp_ctx* ctx, const int32_t* tokens, int n, int R, floa
 }
 
 // final norm (already folded into op_h / ss_h by the last layer's epilogue) -> lm_head -> greedy head
-int run_head(const clasp_ctx* ctx, int n, int R, float* logits, int32_t* argmax_out, float* margin_out,
+int run_head(const clasp_ctx* ctx, int n, int R, float* logits_out, int32_t* argmax_out, float* margin_out,
              float* prob_out, hipStream_t st) {
     const clasp_config& c = ctx->cfg;
     GemmArgs g{};
     g.W[0] = ctx->lm_head; g.tile_end[0] = g.tile_end[1] = g.tile_end[2] = c.vocab / 16;
     g.A = ctx->op_h; g.n_rows = n; g.N = c.vocab; g.K = c.d_model; g.R = R;
     g.ss_parts = ctx->ss_h; g.n_parts = c.d_model / 16; g.inv_dim = 1.0f / c.d_model; g.eps = c.rms_eps;
-    g.out = logits; g.ldo = c.vocab;
     int rc;
-    if ((rc = launch_gemm<kEpiScale, CLASP_HEAD_CW, CLASP_HEAD_KW>(ctx, g, st, CLASP_KERNEL_LM_HEAD))) return rc;
-    if (argmax_out || margin_out || prob_out) {
+    const bool want_head = argmax_out || margin_out || prob_out;
+    if (c.dtype == CLASP_BF16) {
+        // logits are only written when the caller asked for them; the greedy head comes from per-tile pieces
+        g.out = logits_out; g.ldo = c.vocab;
+        g.head_parts = static_cast<f32x4*>(ctx->head_parts);
+        if ((rc = launch_gemm<kEpiHead, CLASP_HEAD_CW, CLASP_HEAD_KW>(ctx, g, st, CLASP_KERNEL_LM_HEAD))) return rc;
+        if (want_head) {
+            hipLaunchKernelGGL(head_reduce_kernel, dim3(n), dim3(1024), 0, st, static_cast<const f32x4*>(ctx->head_parts),
+                               c.vocab / 16, argmax_out, margin_out, prob_out);
+            CLASP_LAUNCH_CHECK();
+        }
+        return CLASP_OK;
+    }
+    float* logits = logits_out ? logits_out : ctx->logits;
+    g.out = logits; g.ldo = c.vocab;
+    if ((rc = launch_gemm<kEpiScale, 1, 1>(ctx, g, st, CLASP_KERNEL_LM_HEAD))) return rc;
+    if (want_head) {
         hipLaunchKernelGGL(argmax_kernel, dim3(n), dim3(1024), 0, st, logits, c.vocab, argmax_out, margin_out, prob_out);
         CLASP_LAUNCH_CHECK();
     }
@@ -615,7 +631,7 @@ int clasp_verify_forward(clasp_ctx* ctx, const int32_t* tokens, int n_tokens, in
             return rc;
     }
     if (argmax_out || margin_out || logits_out)
-        return run_head(ctx, n, R, logits_out ? logits_out : ctx->logits, argmax_out, margin_out, nullptr, st);
+        return run_head(ctx, n, R, logits_out, argmax_out, margin_out, nullptr, st);
     return CLASP_OK;
 }
 
@@ -638,7 +654,7 @@ int clasp_draft_step(clasp_ctx* ctx, const uint8_t* mask, const int32_t* token, 
                             nullptr, st)))
             return rc;
     }
-    return run_head(ctx, 1, 1, ctx->logits, next_token_out, nullptr, top1_prob_out, st);
+    return run_head(ctx, 1, 1, nullptr, next_token_out, nullptr, top1_prob_out, st);
 }
 
 int clasp_dp_select(clasp_ctx* ctx, const float* states, size_t layer_stride, int pos, int M, uint8_t* mask_out,

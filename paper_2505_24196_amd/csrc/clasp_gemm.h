@@ -21,6 +21,9 @@
 //   kEpiPartial raw partial sums of this workgroup's K slice, out[blockIdx.y][row][col]: K is split over gridDim.y
 //               workgroups and the consumer (the DP's select kernel, which reads whole rows anyway) adds the slices
 //               in a fixed order together with the residual; there is no cross-workgroup traffic inside the kernel
+//   kEpiHead    lm_head: logits = acc * rstd (stored only if asked for) and, per tile and row, the running pieces of
+//               the greedy head: largest logit, its index, second largest, sum of exp(logit - largest); a small
+//               kernel merges the tiles' pieces
 //   kEpiQkv     q/k/v projection for the MFMA attention kernel: scales by rstd, applies the rotary embedding to q
 //               and k (the packed wq/wk put the two halves of a rotary pair into one 16-feature tile), and writes
 //               q as ready-made MFMA fragments, k and v into the KV cache (verify/draft rows) or into the small
@@ -30,7 +33,7 @@
 
 namespace clasp {
 
-constexpr int kEpiScale = 0, kEpiResid = 1, kEpiSwiglu = 2, kEpiQkv = 3, kEpiPartial = 4;
+constexpr int kEpiScale = 0, kEpiResid = 1, kEpiSwiglu = 2, kEpiQkv = 3, kEpiPartial = 4, kEpiHead = 5;
 
 struct QkvOut {
     int n_heads, n_kv_heads, head_dim, pos0, mode, t_max;
@@ -61,22 +64,37 @@ struct GemmArgs {
     float* capture;          // optional copy of out, [rows][ldc]
     int ldc;
     QkvOut qkv;  // kEpiQkv only
+    f32x4* head_parts;  // kEpiHead: [N/16][32] (max, index bits, second max, sum exp)
 };
 
-// rstd[row] = 1 / sqrt(sum_p parts[p][row] * inv_dim + eps), fixed summation order. Needs blockDim % 32 == 0.
+// (largest, index, second largest) of two disjoint sets; equal maxima keep the lower index.
+__device__ __forceinline__ void top2_merge(float& a1, int& ai, float& a2, float b1, int bi, float b2) {
+    if (b1 > a1 || (b1 == a1 && bi < ai)) {
+        a2 = fmaxf(a1, b2);
+        a1 = b1;
+        ai = bi;
+    } else {
+        a2 = fmaxf(a2, b1);
+    }
+}
+
+// rstd[row] = 1 / sqrt(sum_p parts[p][row] * inv_dim + eps), fixed summation order. Needs blockDim % 32 == 0. Every
+// thread issues 16 loads before it adds anything, so up to 16 * blockDim / 32 partials (256 for a 512-thread
+// workgroup) cost one memory round trip; rows that do not exist are not read.
 __device__ __forceinline__ void compute_rstd(const GemmArgs& g, float* rstd_s, float* tmp /* [blockDim] */) {
     const int row = threadIdx.x & 31, sub = threadIdx.x >> 5, nsub = blockDim.x >> 5;
-    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-    int p = sub;
-    for (; p + 3 * nsub < g.n_parts; p += 4 * nsub) {  // four independent loads in flight
-        const float a = g.ss_parts[(size_t)p * kMaxRows + row];
-        const float b = g.ss_parts[(size_t)(p + nsub) * kMaxRows + row];
-        const float c = g.ss_parts[(size_t)(p + 2 * nsub) * kMaxRows + row];
-        const float d = g.ss_parts[(size_t)(p + 3 * nsub) * kMaxRows + row];
-        s0 += a; s1 += b; s2 += c; s3 += d;
+    float s = 0.f;
+    for (int base = 0; base < g.n_parts; base += 16 * nsub) {
+        float v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int p = base + sub + u * nsub;
+            v[u] = (p < g.n_parts && row < g.n_rows) ? g.ss_parts[(size_t)p * kMaxRows + row] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) s += v[u];
     }
-    for (; p < g.n_parts; p += nsub) s0 += g.ss_parts[(size_t)p * kMaxRows + row];
-    tmp[threadIdx.x] = (s0 + s1) + (s2 + s3);
+    tmp[threadIdx.x] = s;
     __syncthreads();
     if (threadIdx.x < 32) {
         float t = 0.f;
@@ -188,6 +206,24 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, int tile, int l
         }
     } else if constexpr (EPI == kEpiQkv) {
         qkv_epilogue(g, tile, lane, rg, sum[0], rstd_s);
+    } else if constexpr (EPI == kEpiHead) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = row0 + r;
+            if (row >= g.n_rows) continue;  // uniform over the 16 lanes that share a row; the shuffles stay inside them
+            const float x = sum[0][r] * rstd_s[row];
+            if (g.out) g.out[(size_t)row * g.ldo + col] = x;
+            float v1 = x, v2 = -INFINITY;
+            int i1 = col;
+#pragma unroll
+            for (int o = 1; o < 16; o <<= 1) {
+                const float b1 = __shfl_xor(v1, o), b2 = __shfl_xor(v2, o);
+                const int bi = __shfl_xor(i1, o);
+                top2_merge(v1, i1, v2, b1, bi, b2);
+            }
+            const float se = sum16(expf(x - v1));
+            if ((lane & 15) == 0) g.head_parts[(size_t)tile * kMaxRows + row] = f32x4{v1, __int_as_float(i1), v2, se};
+        }
     } else if constexpr (EPI == kEpiPartial) {
         float* slab = g.out + (size_t)blockIdx.y * g.ldr;  // ldr = elements per slab
 #pragma unroll

@@ -248,7 +248,50 @@ __global__ void dp_backtrack_kernel(const uint8_t* choice, int L, int M, uint8_t
     }
 }
 
-// ---- greedy head: argmax (lowest index on ties), top-1 minus top-2 logit, softmax probability of the top-1 -------
+// ---- greedy head ----------------------------------------------------------------------------------------------
+// bf16 path: merges the per-tile pieces the lm_head epilogue left behind ([tiles][32] x (max, index, second max, sum of
+// exp(logit - max))) into argmax (lowest index on ties), top-1 minus top-2 logit and the softmax probability of the
+// top-1. One workgroup per row.
+__global__ __launch_bounds__(1024) void head_reduce_kernel(const f32x4* parts, int n_tiles, int32_t* argmax_out,
+                                                           float* margin_out, float* prob_out) {
+    __shared__ float s_v1[16], s_v2[16], s_se[16];
+    __shared__ int s_i1[16];
+    const int row = blockIdx.x;
+    float v1 = -INFINITY, v2 = -INFINITY, se = 0.f;
+    int i1 = 0x7fffffff;
+    auto merge = [](float& a1, int& ai, float& a2, float& ase, float b1, int bi, float b2, float bse) {
+        const float m = fmaxf(a1, b1);
+        const float fa = (a1 == -INFINITY) ? 0.f : expf(a1 - m), fb = (b1 == -INFINITY) ? 0.f : expf(b1 - m);
+        ase = ase * fa + bse * fb;
+        if (b1 > a1 || (b1 == a1 && bi < ai)) {
+            a2 = fmaxf(a1, b2);
+            a1 = b1;
+            ai = bi;
+        } else {
+            a2 = fmaxf(a2, b1);
+        }
+    };
+    for (int t = threadIdx.x; t < n_tiles; t += blockDim.x) {
+        const f32x4 p = parts[(size_t)t * kMaxRows + row];
+        merge(v1, i1, v2, se, p[0], __float_as_int(p[1]), p[2], p[3]);
+    }
+    for (int o = 1; o < 64; o <<= 1) {
+        const float b1 = __shfl_xor(v1, o), b2 = __shfl_xor(v2, o), bs = __shfl_xor(se, o);
+        const int bi = __shfl_xor(i1, o);
+        merge(v1, i1, v2, se, b1, bi, b2, bs);
+    }
+    const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    if ((threadIdx.x & 63) == 0) { s_v1[wave] = v1; s_v2[wave] = v2; s_i1[wave] = i1; s_se[wave] = se; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < nw; ++w) merge(v1, i1, v2, se, s_v1[w], s_i1[w], s_v2[w], s_se[w]);
+        if (argmax_out) argmax_out[row] = i1;
+        if (margin_out) margin_out[row] = v1 - v2;
+        if (prob_out) prob_out[row] = 1.0f / se;
+    }
+}
+
+// fp32 path: the same three results straight from the logits.
 __global__ __launch_bounds__(1024) void argmax_kernel(const float* logits, int vocab, int32_t* argmax_out,
                                                       float* margin_out, float* prob_out) {
     __shared__ float s_v1[16], s_v2[16], s_sum[16];
