@@ -69,6 +69,9 @@ namespace {
 #ifndef CLASP_ACT_SPLIT
 #define CLASP_ACT_SPLIT 2  // 2: activations enter the MFMAs as bf16 hi + lo; 1: hi only
 #endif
+#ifndef CLASP_ATTN_SHORT_WAVES
+#define CLASP_ATTN_SHORT_WAVES 8
+#endif
 #ifndef CLASP_ATTN_SHORT_BLOCKS
 #define CLASP_ATTN_SHORT_BLOCKS 40  // prefixes of up to this many 32-key blocks take the latency-oriented launch
 #endif
@@ -254,7 +257,7 @@ int launch_attn_one(const AttnArgs& a, dim3 grid, hipStream_t st) {
 // short = latency-oriented launch: one query tile per workgroup, 16 wavefronts
 template <int HD>
 int launch_attn_bf16(const AttnArgs& a, bool short_prefix, int nt, dim3 grid, hipStream_t st) {
-    if (short_prefix) return launch_attn_one<HD, 1, 16>(a, grid, st);
+    if (short_prefix) return launch_attn_one<HD, 1, CLASP_ATTN_SHORT_WAVES>(a, grid, st);
     switch (nt) {
         case 1: return launch_attn_one<HD, 1, 8>(a, grid, st);
         case 2: return launch_attn_one<HD, 2, 8>(a, grid, st);

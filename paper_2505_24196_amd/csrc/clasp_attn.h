@@ -48,22 +48,33 @@ struct AttnState {
     f32x4 o[NT][HD / 16];
 };
 
-// One 32-key block: scores for NT query tiles, online softmax update, O^T accumulation.
-//   kf(u, kk) -> A fragment of key tile u (16 keys), k-step kk;  vf(c) -> A fragment of V^T rows c*16..c*16+15
-//   valid(u, r, t) -> whether key (lane/16)*8 + u*4 + r of the block is visible to query t*16 + lane%16
-template <int HD, int NT, class KF, class VF, class VALID>
-__device__ __forceinline__ void attn_block(AttnState<HD, NT>& st, const bf16x8 (&qf)[NT][HD / 32], KF kf, VF vf,
-                                           VALID valid) {
-    constexpr int KK = HD / 32, CT = HD / 16;
-    // all of the block's key and value fragments are requested before the first MFMA, so that the value loads do not
-    // wait behind the softmax
-    bf16x8 kfr[2][KK], vfr[CT];
+// Fragments of one 32-key block: k[u][kk] = A fragment of key tile u (16 keys), k-step kk; v[c] = A fragment of V^T
+// rows c*16..c*16+15.
+template <int HD>
+struct AttnFrags {
+    bf16x8 k[2][HD / 32], v[HD / 16];
+};
+
+// All of a block's key and value fragments are requested together (and, in the pipelined loop, one block ahead), so
+// that neither the value loads nor the next block wait behind the softmax.
+template <int HD, class KF, class VF>
+__device__ __forceinline__ void attn_load(AttnFrags<HD>& f, KF kf, VF vf) {
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) kfr[u][kk] = kf(u, kk);
+        for (int kk = 0; kk < HD / 32; ++kk) f.k[u][kk] = kf(u, kk);
 #pragma unroll
-    for (int c = 0; c < CT; ++c) vfr[c] = vf(c);
+    for (int c = 0; c < HD / 16; ++c) f.v[c] = vf(c);
+}
+
+// One 32-key block: scores for NT query tiles, online softmax update, O^T accumulation.
+//   valid(u, r, t) -> whether key (lane/16)*8 + u*4 + r of the block is visible to query t*16 + lane%16
+template <int HD, int NT, class VALID>
+__device__ __forceinline__ void attn_compute(AttnState<HD, NT>& st, const bf16x8 (&qf)[NT][HD / 32],
+                                             const AttnFrags<HD>& f, VALID valid) {
+    constexpr int KK = HD / 32, CT = HD / 16;
+    const bf16x8 (&kfr)[2][KK] = f.k;
+    const bf16x8 (&vfr)[CT] = f.v;
     f32x4 s[2][NT];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
@@ -165,22 +176,43 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(AttnArgs a) {
     const int b0 = (int)(((long long)nblk * split) / a.n_split), b1 = (int)(((long long)nblk * (split + 1)) / a.n_split);
     const u32x4* Kh = reinterpret_cast<const u32x4*>(Kc + (size_t)kvh * a.t_max * HD) + lane;
     const u32x4* Vh = reinterpret_cast<const u32x4*>(Vt + (size_t)kvh * a.t_max * HD) + lane;
-    for (int blk = b0 + wave; blk < b1; blk += NW) {
-        const int kb = blk << 5;
+    auto load_blk = [&](AttnFrags<HD>& f, int blk) {
         const u32x4* kp = Kh + (size_t)blk * (2 * KK * 64);
         const u32x4* vp = Vh + (size_t)blk * (CT * 64);
-        attn_block<HD, NT>(
-            st, qf, [&](int u, int kk) { return as_bf16x8(load_stream(kp + (u * KK + kk) * 64)); },
-            [&](int c) { return as_bf16x8(load_stream(vp + c * 64)); },
-            [&](int u, int r, int t) { return kb + q4 * 8 + u * 4 + r <= limit[t]; });
+        attn_load<HD>(f, [&](int u, int kk) { return as_bf16x8(load_stream(kp + (u * KK + kk) * 64)); },
+                      [&](int c) { return as_bf16x8(load_stream(vp + c * 64)); });
+    };
+    auto compute_blk = [&](const AttnFrags<HD>& f, int blk) {
+        const int kb = blk << 5;
+        attn_compute<HD, NT>(st, qf, f, [&](int u, int r, int t) { return kb + q4 * 8 + u * 4 + r <= limit[t]; });
+    };
+    int blk = b0 + wave;
+    if constexpr (NT <= 2) {  // registers allow a second fragment set: the next block is in flight during the MFMAs
+        AttnFrags<HD> f0, f1;
+        if (blk < b1) load_blk(f0, blk);
+        while (blk < b1) {
+            if (blk + NW < b1) load_blk(f1, blk + NW);
+            compute_blk(f0, blk);
+            blk += NW;
+            if (blk >= b1) break;
+            if (blk + NW < b1) load_blk(f0, blk + NW);
+            compute_blk(f1, blk);
+            blk += NW;
+        }
+    } else {
+        AttnFrags<HD> f;
+        for (; blk < b1; blk += NW) {
+            load_blk(f, blk);
+            compute_blk(f, blk);
+        }
     }
     if (!a.mode && split == a.n_split - 1 && wave == (b1 - b0) % NW) {  // DP candidates: own key/value only
         const u32x4* kp = reinterpret_cast<const u32x4*>(a.k_self) + (size_t)kvh * (2 * KK * 64) + lane;
         const u32x4* vp = reinterpret_cast<const u32x4*>(a.v_self) + (size_t)kvh * (CT * 64) + lane;
-        attn_block<HD, NT>(
-            st, qf, [&](int u, int kk) { return as_bf16x8(kp[(u * KK + kk) * 64]); },
-            [&](int c) { return as_bf16x8(vp[c * 64]); },
-            [&](int u, int r, int t) { return q4 * 8 + u * 4 + r == qrow[t]; });
+        AttnFrags<HD> f;
+        attn_load<HD>(f, [&](int u, int kk) { return as_bf16x8(kp[(u * KK + kk) * 64]); },
+                      [&](int c) { return as_bf16x8(vp[c * 64]); });
+        attn_compute<HD, NT>(st, qf, f, [&](int u, int r, int t) { return q4 * 8 + u * 4 + r == qrow[t]; });
     }
 
     // merge the wavefronts' running (max, sum, O^T), one query tile at a time, fixed order
