@@ -24,10 +24,10 @@ namespace {
 // their activation fragments, KW slices of K reduced through LDS). P = fragments per register stage (two stages in
 // flight).
 #ifndef CLASP_QKV_CW
-#define CLASP_QKV_CW 2
+#define CLASP_QKV_CW 1
 #endif
 #ifndef CLASP_QKV_KW
-#define CLASP_QKV_KW 4
+#define CLASP_QKV_KW 8
 #endif
 #ifndef CLASP_OPROJ_CW
 #define CLASP_OPROJ_CW 1

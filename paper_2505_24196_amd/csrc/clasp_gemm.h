@@ -146,9 +146,38 @@ __device__ __forceinline__ void gemm_compute(const GemmStage<R, NACC, P, SPLIT>&
     }
 }
 
+// Inputs of the epilogue that do not depend on the contraction (residual values, gain, rotary factors). The
+// epilogue wavefront requests them before the main loop so that the tail of the kernel has no dependent global load.
+struct EpiPre {
+    float resid[4];
+    float2 cs[4];
+    float gain;
+};
+
+template <int EPI>
+__device__ __forceinline__ void epi_prefetch(const GemmArgs& g, int tile, int lane, int rg, EpiPre& pre) {
+    const int c = lane & 15, col = tile * 16 + c, row0 = rg * 16 + (lane >> 4) * 4;
+    if constexpr (EPI == kEpiResid) {
+        pre.gain = g.next_gain ? g.next_gain[col] : 1.0f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) pre.resid[r] = (row0 + r < g.n_rows) ? g.resid[(size_t)(row0 + r) * g.ldr + col] : 0.f;
+    } else if constexpr (EPI == kEpiQkv) {
+        const QkvOut& o = g.qkv;
+        const int HALF = o.head_dim >> 1, tph = o.head_dim >> 4;
+        const int tl = tile - (tile < g.tile_end[0] ? 0 : g.tile_end[0]);  // q or k tile inside its matrix
+        const int e = (tl % tph) * 8 + (c & 7);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = row0 + r;
+            pre.cs[r] = (tile < g.tile_end[1] && row < g.n_rows) ? o.rope[(size_t)(o.pos0 + (o.mode ? row : 0)) * HALF + e]
+                                                                  : make_float2(1.f, 0.f);
+        }
+    }
+}
+
 // q/k/v epilogue of one lane: 4 rows x 1 feature of tile `tile` (see kEpiQkv above).
 __device__ __forceinline__ void qkv_epilogue(const GemmArgs& g, int tile, int lane, int rg, const f32x4& sum,
-                                             const float* rstd_s) {
+                                             const float* rstd_s, const EpiPre& pre) {
     const QkvOut& o = g.qkv;
     const int HD = o.head_dim, HALF = HD >> 1, tph = HD >> 4;  // tiles per head
     const int c = lane & 15, row0 = rg * 16 + (lane >> 4) * 4;
@@ -176,7 +205,7 @@ __device__ __forceinline__ void qkv_epilogue(const GemmArgs& g, int tile, int la
         const int e = u * 8 + (c & 7), x = e + ((c & 8) ? HALF : 0);
         if (row < g.n_rows) {
             const int pos = o.pos0 + (o.mode ? row : 0);
-            const float2 cs = o.rope[(size_t)pos * HALF + e];
+            const float2 cs = pre.cs[r];
             const float rot = own * cs.x + ((c & 8) ? partner : -partner) * cs.y;
             if (which == 0) {
                 const int kvh = head / G, qi = row * G + head % G;
@@ -195,7 +224,7 @@ __device__ __forceinline__ void qkv_epilogue(const GemmArgs& g, int tile, int la
 // Epilogue of one (tile, row group) for one lane: 4 rows x 1 feature; sum[a] = finished accumulators.
 template <int EPI, int NACC>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, int tile, int lane, int rg, const f32x4 (&sum)[NACC],
-                                              const float* rstd_s) {
+                                              const float* rstd_s, const EpiPre& pre) {
     const int col = tile * 16 + (lane & 15);
     const int row0 = rg * 16 + (lane >> 4) * 4;
     if constexpr (EPI == kEpiScale) {
@@ -205,7 +234,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, int tile, int l
             if (row < g.n_rows) g.out[(size_t)row * g.ldo + col] = sum[0][r] * rstd_s[row];
         }
     } else if constexpr (EPI == kEpiQkv) {
-        qkv_epilogue(g, tile, lane, rg, sum[0], rstd_s);
+        qkv_epilogue(g, tile, lane, rg, sum[0], rstd_s, pre);
     } else if constexpr (EPI == kEpiHead) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -232,13 +261,13 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, int tile, int l
             if (row < g.n_rows) slab[(size_t)row * g.ldo + col] = sum[0][r];
         }
     } else if constexpr (EPI == kEpiResid) {
-        const float gain = g.next_gain ? g.next_gain[col] : 1.0f;
+        const float gain = pre.gain;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int row = row0 + r;
             float v = 0.f;
             if (row < g.n_rows) {
-                v = g.resid[(size_t)row * g.ldr + col] + sum[0][r];
+                v = pre.resid[r] + sum[0][r];
                 g.out[(size_t)row * g.ldo + col] = v;
                 if (g.capture) g.capture[(size_t)row * g.ldc + col] = v;
             }
@@ -307,6 +336,11 @@ __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
     int s = ks0;
     if (s < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w0, w1, af, row_live, s, ks1);  // weights first: independent of rstd
 
+    EpiPre pre[R];
+    if (kw == 0) {
+#pragma unroll
+        for (int rg = 0; rg < R; ++rg) epi_prefetch<EPI>(g, tile, lane, rg, pre[rg]);
+    }
     if constexpr (EPI != kEpiResid && EPI != kEpiPartial) compute_rstd(g, rstd_s, tmp_s);
 
     while (s < ks1) {
@@ -349,7 +383,7 @@ __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
         f32x4 fin[NACC];
 #pragma unroll
         for (int x = 0; x < NACC; ++x) fin[x] = sum[x][rg];
-        gemm_epilogue<EPI, NACC>(g, tile, lane, rg, fin, rstd_s);
+        gemm_epilogue<EPI, NACC>(g, tile, lane, rg, fin, rstd_s, pre[rg]);
     }
 }
 
@@ -410,6 +444,8 @@ __global__ __launch_bounds__(KW * 64) void gemm_bf16_resident_kernel(GemmArgs g)
 #pragma unroll
         for (int a = 0; a < NACC; ++a) acc[a] = f32x4{0.f, 0.f, 0.f, 0.f};
         const int next_tile = tile + gridDim.x;
+        EpiPre pre;
+        if (kw == it % KW) epi_prefetch<EPI>(g, tile, lane, 0, pre);
 #pragma unroll
         for (int j = 0; j < NST; ++j) {
             // request the next stage (of this tile, or the first one of the next tile) before consuming this one
@@ -440,7 +476,7 @@ __global__ __launch_bounds__(KW * 64) void gemm_bf16_resident_kernel(GemmArgs g)
                 fin[a] = rb[0][a][lane];
                 for (int k = 1; k < KW; ++k) fin[a] += rb[k][a][lane];
             }
-            gemm_epilogue<EPI, NACC>(g, tile, lane, 0, fin, rstd_s);
+            gemm_epilogue<EPI, NACC>(g, tile, lane, 0, fin, rstd_s, pre);
         }
     }
 }
