@@ -29,7 +29,14 @@ WORKLOADS = {
     "llama3-8b-shape/T512/M12/K4": dict(shape="llama3-8b-shape", T=512, M=12, K=4),
     # BASELINE config 1: small case the oracle finishes in seconds
     "tiny-f32/T64/M3/K4": dict(shape="tiny-f32", T=64, M=3, K=4),
+    # BASELINE config 5 (closed loop shape) and config 3 (context sweep), config 4 (70B shape)
     "llama3-8b-shape/T4096/M12/K6": dict(shape="llama3-8b-shape", T=4096, M=12, K=6),
+    "llama3-8b-shape/T2048/M12/K4": dict(shape="llama3-8b-shape", T=2048, M=12, K=4),
+    "llama3-8b-shape/T8192/M12/K4": dict(shape="llama3-8b-shape", T=8192, M=12, K=4),
+    "llama3-8b-shape/T32768/M12/K4": dict(shape="llama3-8b-shape", T=32768, M=12, K=4),
+    "llama3-8b-shape/T32768/M8/K4": dict(shape="llama3-8b-shape", T=32768, M=8, K=4),
+    "llama3-8b-shape/T32768/M16/K4": dict(shape="llama3-8b-shape", T=32768, M=16, K=4),
+    "llama3-70b-shape/T1024/M32/K4": dict(shape="llama3-70b-shape", T=1024, M=32, K=4),
 }
 
 
@@ -140,7 +147,7 @@ def main():
     total_steps = args.steps + args.warmup
     max_seq = ((T + (K + 1) * (total_steps + 2) + 31) // 32) * 32
     want_cpu = not args.no_cpu_baseline
-    eng, host = build_engine(shape, 1, max_seq, 16, keep_host=want_cpu)
+    eng, host = build_engine(shape, 1, max_seq, 32 if M > 16 else 16, keep_host=want_cpu)
     dev = eng.device
 
     prompt = [int(t) for t in si.gen_tokens(2, T, shape.vocab)]

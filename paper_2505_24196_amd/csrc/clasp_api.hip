@@ -27,7 +27,7 @@ namespace {
 #define CLASP_QKV_CW 1
 #endif
 #ifndef CLASP_QKV_KW
-#define CLASP_QKV_KW 8
+#define CLASP_QKV_KW 4
 #endif
 #ifndef CLASP_OPROJ_CW
 #define CLASP_OPROJ_CW 1
@@ -52,6 +52,9 @@ namespace {
 #endif
 #ifndef CLASP_HEAD_KW
 #define CLASP_HEAD_KW 2
+#endif
+#ifndef CLASP_STREAM_DEPTH
+#define CLASP_STREAM_DEPTH 8  // streaming kernel with one row group
 #endif
 #ifndef CLASP_GEMM_DEPTH
 #define CLASP_GEMM_DEPTH 4
@@ -227,7 +230,7 @@ int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kin
         } else {
             const dim3 grid((tiles + CW - 1) / CW);
             if (g.R == 1)
-                hipLaunchKernelGGL((gemm_bf16_kernel<1, CW, KW, EPI, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>), grid, dim3(CW * KW * 64), 0, st, g);
+                hipLaunchKernelGGL((gemm_bf16_kernel<1, CW, KW, EPI, CLASP_STREAM_DEPTH, CLASP_ACT_SPLIT>), grid, dim3(CW * KW * 64), 0, st, g);
             else
                 hipLaunchKernelGGL((gemm_bf16_kernel<2, CW, KW, EPI, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>), grid, dim3(CW * KW * 64), 0, st, g);
         }
@@ -370,7 +373,7 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
         TimerScope timer(ctx, CLASP_KERNEL_DOWN, st);
         const dim3 grid((d / 16 + CLASP_DOWNP_CW - 1) / CLASP_DOWNP_CW, down_split);
         if (R == 1)
-            hipLaunchKernelGGL((gemm_bf16_kernel<1, CLASP_DOWNP_CW, CLASP_DOWNP_KW, kEpiPartial, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>),
+            hipLaunchKernelGGL((gemm_bf16_kernel<1, CLASP_DOWNP_CW, CLASP_DOWNP_KW, kEpiPartial, CLASP_STREAM_DEPTH, CLASP_ACT_SPLIT>),
                                grid, dim3(CLASP_DOWNP_CW * CLASP_DOWNP_KW * 64), 0, st, g);
         else
             hipLaunchKernelGGL((gemm_bf16_kernel<2, CLASP_DOWNP_CW, CLASP_DOWNP_KW, kEpiPartial, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>),
