@@ -153,9 +153,10 @@ int clasp_draft_step(clasp_ctx *ctx, const uint8_t *mask, const int32_t *token, 
  * (and for tests that feed synthetic cache contents). */
 int clasp_kv_load(clasp_ctx *ctx, int layer, const float *K, const float *V, int n_tokens, void *stream);
 
-/* Measurement aid: between begin and end, every launch of the chosen kernel kind inside the three calls above is
- * bracketed by a pair of HIP events on the call's stream (up to `capacity` launches; host-side event objects only).
- * clasp_kernel_timer_end waits for them and returns the summed elapsed time and the number of launches timed. */
+/* Measurement aid: between begin and end, every `every`-th launch of the chosen kernel kind inside the three calls
+ * above is bracketed by a pair of HIP events on the call's stream (up to `capacity` launches; host-side event objects
+ * only; each pair costs the stream a few microseconds, hence the sampling). clasp_kernel_timer_end waits for them and
+ * returns the summed elapsed time and the number of launches timed. */
 enum {
     CLASP_KERNEL_QKV = 0,      /* RMSNorm-scaled q/k/v projection                      */
     CLASP_KERNEL_ATTENTION = 1,
@@ -165,7 +166,7 @@ enum {
     CLASP_KERNEL_LM_HEAD = 5,
     CLASP_KERNEL_KINDS = 6
 };
-int clasp_kernel_timer_begin(clasp_ctx *ctx, int kind, int capacity);
+int clasp_kernel_timer_begin(clasp_ctx *ctx, int kind, int capacity, int every);
 int clasp_kernel_timer_end(clasp_ctx *ctx, float *total_ms, int *launches);
 
 const char *clasp_strerror(int code);

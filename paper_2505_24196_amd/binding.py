@@ -66,7 +66,7 @@ def lib():
         l.clasp_dp_select.argtypes = [vp, vp, sz, i32, i32, vp, vp, vp, vp, vp]
         l.clasp_draft_step.argtypes = [vp, vp, vp, i32, vp, vp, vp]
         l.clasp_kv_load.argtypes = [vp, i32, vp, vp, i32, vp]
-        l.clasp_kernel_timer_begin.argtypes = [vp, i32, i32]
+        l.clasp_kernel_timer_begin.argtypes = [vp, i32, i32, i32]
         l.clasp_kernel_timer_end.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int)]
         _lib = l
     return _lib
@@ -259,8 +259,9 @@ class Engine:
                "clasp_draft_step")
 
     # ---- measurement aid ------------------------------------------------------------------------------------------
-    def kernel_timer_begin(self, kind: str, capacity: int = 1 << 16):
-        _check(lib().clasp_kernel_timer_begin(self._ctx, KERNEL_KINDS[kind], capacity), "clasp_kernel_timer_begin")
+    def kernel_timer_begin(self, kind: str, capacity: int = 1 << 16, every: int = 1):
+        _check(lib().clasp_kernel_timer_begin(self._ctx, KERNEL_KINDS[kind], capacity, every),
+               "clasp_kernel_timer_begin")
 
     def kernel_timer_end(self):
         """Returns (summed elapsed ms, launches timed) of the kernel kind chosen at begin."""

@@ -123,8 +123,8 @@ struct clasp_ctx {
     int32_t* tok_tmp;
     // optional per-kernel timing (host-side event objects only; no device memory)
     int n_cu = 256;  // compute units of the device (grid size of the persistent kernels)
-    int timer_kind = -1;
-    size_t timer_used = 0;
+    int timer_kind = -1, timer_every = 1;
+    size_t timer_used = 0, timer_seen = 0;
     std::vector<hipEvent_t> timer_start, timer_stop;
 };
 
@@ -199,7 +199,8 @@ struct TimerScope {
     hipStream_t st;
     bool on;
     TimerScope(const clasp_ctx* c, int kind, hipStream_t s) : ctx(const_cast<clasp_ctx*>(c)), st(s) {
-        on = ctx->timer_kind == kind && ctx->timer_used < ctx->timer_start.size();
+        on = ctx->timer_kind == kind && ctx->timer_used < ctx->timer_start.size() &&
+             (ctx->timer_seen++ % ctx->timer_every) == 0;
         if (on) (void)hipEventRecord(ctx->timer_start[ctx->timer_used], st);
     }
     ~TimerScope() {
@@ -564,15 +565,17 @@ int clasp_destroy(clasp_ctx* ctx) {
     return CLASP_OK;
 }
 
-int clasp_kernel_timer_begin(clasp_ctx* ctx, int kind, int capacity) {
-    if (!ctx || kind < 0 || kind >= CLASP_KERNEL_KINDS || capacity < 1 || capacity > (1 << 20)) return CLASP_E_INVALID_ARG;
+int clasp_kernel_timer_begin(clasp_ctx* ctx, int kind, int capacity, int every) {
+    if (!ctx || kind < 0 || kind >= CLASP_KERNEL_KINDS || capacity < 1 || capacity > (1 << 20) || every < 1)
+        return CLASP_E_INVALID_ARG;
     if (ctx->timer_kind >= 0) return CLASP_E_INVALID_ARG;
     ctx->timer_start.resize(capacity);
     ctx->timer_stop.resize(capacity);
     for (int i = 0; i < capacity; ++i)
         if (hipEventCreate(&ctx->timer_start[i]) != hipSuccess || hipEventCreate(&ctx->timer_stop[i]) != hipSuccess)
             return CLASP_E_HIP;
-    ctx->timer_used = 0;
+    ctx->timer_used = ctx->timer_seen = 0;
+    ctx->timer_every = every;
     ctx->timer_kind = kind;
     return CLASP_OK;
 }

@@ -178,12 +178,13 @@ def test_draft_step_chain(name):
     assert int(a) == int(b) == int(v["argmax"][0])
 
 
-def test_long_prefix_split_and_ragged_blocks():
-    """Synthetic cache of 700 tokens: the prefix spans several workgroups per KV head and ends inside a 32-key block."""
+@pytest.mark.parametrize("T", [700, 1500, 2601])
+def test_long_prefix_split_and_ragged_blocks(T):
+    """Synthetic cache: the prefix ends inside a 32-key block; 700 tokens take the latency-oriented single-workgroup
+    launch, 1500 and 2601 the split launch (2 and 3 workgroups per KV head and query group) plus the merge kernel."""
     name = "small-bf16"
     shape = si.SHAPES[name]
-    T = 700
-    om, eng = oracle_model(name), engine(name, max_seq=1024)
+    om, eng = oracle_model(name), engine(name, max_seq=2688)
     K, V = si.gen_kv(shape, 3, shape.n_layers, T)
     cache = oc.KVCache(shape, T + 8)
     cache.load(K.numpy().astype(np.float64), V.numpy().astype(np.float64))
