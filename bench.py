@@ -40,7 +40,7 @@ WORKLOADS = {
 }
 
 
-def build_engine(shape, seed, max_seq, max_rows, keep_host=False):
+def build_engine(shape, seed, max_seq, max_rows, keep_host=False, resid_scale=1.0):
     """Generates the random-init model layer by layer on the GPU and packs it; optionally keeps host copies."""
     import torch
     import synth_inputs as si
@@ -53,7 +53,7 @@ def build_engine(shape, seed, max_seq, max_rows, keep_host=False):
         host.update({k: si.to_numpy(v) for k, v in head.items()})
     del head
     for l in range(shape.n_layers):
-        w = si.gen_layer(shape, seed, l, "cuda")
+        w = si.gen_layer(shape, seed, l, "cuda", resid_scale)
         eng.set_layer(l, w)
         if keep_host:
             host["layers"].append({k: si.to_numpy(v) for k, v in w.items()})
@@ -120,6 +120,12 @@ def main():
     ap.add_argument("--workload", default="llama3-8b-shape/T512/M12/K4", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timer", action="store_true")
+    ap.add_argument("--closed-loop", type=int, default=0, metavar="N_TOKENS",
+                    help="instead of the step benchmark: generate N_TOKENS with the full draft/verify/optimise loop and "
+                         "with plain greedy decoding on the chosen workload, compare the tokens, report tokens/s of both")
+    ap.add_argument("--resid-scale", type=float, default=1.0,
+                    help="closed loop only: std multiplier of wo / w_down (0.05 = slow-drift variant whose drafts get "
+                         "accepted; 1.0 = the plain N(0, 0.02) init of the benchmark configurations)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="only run plain device copies of a known size (1 GiB read + 1 GiB written per copy), to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -144,6 +150,29 @@ def main():
     wl = WORKLOADS[args.workload]
     shape = si.SHAPES[wl["shape"]]
     T, M, K = wl["T"], wl["M"], wl["K"]
+    if args.closed_loop:
+        n_gen = args.closed_loop
+        max_seq = ((T + n_gen + K + 2 + 31) // 32) * 32
+        eng, _ = build_engine(shape, 1, max_seq, 32 if M > 16 else 16, resid_scale=args.resid_scale)
+        prompt = [int(t) for t in si.gen_tokens(2, T, shape.vocab)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        plain, margins = decode.greedy_generate(eng, prompt, n_gen)
+        torch.cuda.synchronize()
+        t_plain = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        spec = decode.clasp_generate(eng, prompt, n_gen, M, K)
+        torch.cuda.synchronize()
+        t_spec = time.perf_counter() - t0
+        first_diff = next((i for i, (a, b) in enumerate(zip(plain, spec["tokens"])) if a != b), None)
+        acc = [r["accepted"] for r in spec["rounds"]]
+        print(json.dumps({"closed_loop": args.workload, "resid_scale": args.resid_scale, "generated": n_gen, "includes_prefill": True,
+                          "plain_greedy_tokens_per_s": round(n_gen / t_plain, 2),
+                          "clasp_tokens_per_s": round(n_gen / t_spec, 2), "speedup": round(t_plain / t_spec, 3),
+                          "rounds": len(acc), "mean_tokens_per_round": round(n_gen / max(1, len(acc)), 3),
+                          "tokens_equal": first_diff is None, "first_difference_at": first_diff,
+                          "plain_margin_at_difference": None if first_diff is None else margins[first_diff]}))
+        return
     total_steps = args.steps + args.warmup
     max_seq = ((T + (K + 1) * (total_steps + 2) + 31) // 32) * 32
     want_cpu = not args.no_cpu_baseline

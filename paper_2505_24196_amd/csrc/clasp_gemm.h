@@ -110,11 +110,13 @@ struct GemmStage {
     u32x4 a[P][R][SPLIT];
 };
 
-// af already points at this lane's 16 bytes inside a plane; row_live[rg] tells whether the lane's row exists (rows
-// beyond n_rows are not fetched at all: the operand is row-major inside a k-step, so they cost no traffic).
+// af[rg] points at this lane's 16 bytes inside a plane of row group rg. Lanes whose row does not exist read the last
+// live row instead (same cache line as a live lane, so no extra traffic): their products land in output rows that are
+// never stored, and unconditional loads keep the load stream free of exec-mask merges, which would make every stage
+// wait for the previous one.
 template <int R, int NACC, int P, int SPLIT>
 __device__ __forceinline__ void gemm_issue(GemmStage<R, NACC, P, SPLIT>& st, const u32x4* w0, const u32x4* w1,
-                                           const u32x4* af, const bool (&row_live)[R], int s, int ks1) {
+                                           const u32x4* const (&af)[R], int s, int ks1) {
 #pragma unroll
     for (int u = 0; u < P; ++u) {
         const int ss = min(s + u, ks1 - 1);
@@ -123,8 +125,7 @@ __device__ __forceinline__ void gemm_issue(GemmStage<R, NACC, P, SPLIT>& st, con
 #pragma unroll
         for (int rg = 0; rg < R; ++rg)
 #pragma unroll
-            for (int h = 0; h < SPLIT; ++h)
-                st.a[u][rg][h] = row_live[rg] ? af[(((size_t)ss * R + rg) * 2 + h) * 64] : u32x4{0u, 0u, 0u, 0u};
+            for (int h = 0; h < SPLIT; ++h) st.a[u][rg][h] = af[rg][((size_t)ss * R * 2 + h) * 64];
     }
 }
 
@@ -321,10 +322,12 @@ __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
     }
     const u32x4* w0 = reinterpret_cast<const u32x4*>(g.W[mi]) + (size_t)tl * KS * 64 + lane;
     const u32x4* w1 = (NACC == 2) ? reinterpret_cast<const u32x4*>(g.W[1]) + (size_t)tl * KS * 64 + lane : nullptr;
-    const u32x4* af = reinterpret_cast<const u32x4*>(g.A) + (lane & 15) * 4 + (lane >> 4);
-    bool row_live[R];
+    const u32x4* af[R];
 #pragma unroll
-    for (int rg = 0; rg < R; ++rg) row_live[rg] = rg * 16 + (lane & 15) < g.n_rows;
+    for (int rg = 0; rg < R; ++rg) {  // row of this lane, clamped to the last live row; may sit in an earlier group
+        const int row = min(rg * 16 + (lane & 15), g.n_rows - 1);
+        af[rg] = reinterpret_cast<const u32x4*>(g.A) + (size_t)(row >> 4) * 128 + (row & 15) * 4 + (lane >> 4);
+    }
 
     f32x4 acc[NACC][R];
 #pragma unroll
@@ -334,7 +337,7 @@ __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
 
     GemmStage<R, NACC, P, SPLIT> st0, st1;
     int s = ks0;
-    if (s < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w0, w1, af, row_live, s, ks1);  // weights first: independent of rstd
+    if (s < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w0, w1, af, s, ks1);  // weights first: independent of rstd
 
     EpiPre pre[R];
     if (kw == 0) {
@@ -344,11 +347,11 @@ __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
     if constexpr (EPI != kEpiResid && EPI != kEpiPartial) compute_rstd(g, rstd_s, tmp_s);
 
     while (s < ks1) {
-        if (s + P < ks1) gemm_issue<R, NACC, P, SPLIT>(st1, w0, w1, af, row_live, s + P, ks1);
+        if (s + P < ks1) gemm_issue<R, NACC, P, SPLIT>(st1, w0, w1, af, s + P, ks1);
         gemm_compute<R, NACC, P, SPLIT>(st0, acc, s, ks1);
         s += P;
         if (s >= ks1) break;
-        if (s + P < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w0, w1, af, row_live, s + P, ks1);
+        if (s + P < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w0, w1, af, s + P, ks1);
         gemm_compute<R, NACC, P, SPLIT>(st1, acc, s, ks1);
         s += P;
     }
@@ -408,13 +411,11 @@ __global__ __launch_bounds__(KW * 64) void gemm_bf16_resident_kernel(GemmArgs g)
     // this wavefront's slice of the activations, resident for the whole kernel
     u32x4 areg[KSW][SPLIT];
     {
-        const u32x4* af = reinterpret_cast<const u32x4*>(g.A) + (lane & 15) * 4 + (lane >> 4);
-        const bool row_live = (lane & 15) < g.n_rows;
+        const u32x4* af = reinterpret_cast<const u32x4*>(g.A) + min(lane & 15, g.n_rows - 1) * 4 + (lane >> 4);
 #pragma unroll
-        for (int i = 0; i < KSW; ++i)
+        for (int i = 0; i < KSW; ++i)  // rows that do not exist mirror the last live row, steps beyond the slice its last step
 #pragma unroll
-            for (int h = 0; h < SPLIT; ++h)
-                areg[i][h] = (row_live && i < nks) ? af[((size_t)(ks0 + i) * 2 + h) * 64] : u32x4{0u, 0u, 0u, 0u};
+            for (int h = 0; h < SPLIT; ++h) areg[i][h] = af[((size_t)(ks0 + min(i, max(nks - 1, 0))) * 2 + h) * 64];
     }
 
     auto wptr = [&](int tile, int which) -> const u32x4* {
