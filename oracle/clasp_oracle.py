@@ -196,11 +196,13 @@ class OracleModel:
         return out, margins
 
     def spec_decode(self, prompt: Sequence[int], n_gen: int, M: int, K: int, t_max: Optional[int] = None,
-                    dp_interval: int = 1):
+                    dp_interval: int = 1, det_threshold: Optional[float] = None):
         """Greedy self-speculative decoding (Sec. 3.1): draft K tokens with the layer-skipped model, verify them
         with the full model, accept the longest matching prefix plus the full model's next token, then re-run the
         layer optimisation on the last accepted token's stored states. dp_interval > 1 re-optimises only every
-        that many verify steps (Sec. 3.7). Returns a dict with the tokens and a per-round trace."""
+        that many verify steps (Sec. 3.7). det_threshold (Sec. 5.3.3): drafting stops after the first draft token
+        whose softmax probability under the draft model is below the threshold (that token is still proposed), so a
+        round holds 1..K drafts. Returns a dict with the tokens and a per-round trace."""
         s = self.shape
         t_max = t_max or len(prompt) + n_gen + K + 2
         cache = KVCache(s, t_max)
@@ -213,11 +215,15 @@ class OracleModel:
         rounds = []
         n_verify = 0
         while len(out) < n_gen:
-            drafts, tok = [], pending
+            drafts, conf, tok = [], [], pending
             for k in range(K):
                 _, lg = self.token(tok, pos + k, cache, skip=mask)
                 tok, _ = argmax_margin(lg)
                 drafts.append(tok)
+                conf.append(top1_prob(lg))
+                if det_threshold is not None and conf[-1] < det_threshold:
+                    break
+            n_draft = len(drafts)
             rows = [pending] + drafts
             v, v_states, v_margin = [], [], []
             for r, tk in enumerate(rows):  # the verify pass: full model, causal over the K+1 rows
@@ -227,18 +233,24 @@ class OracleModel:
                 v_margin.append(a_mg)
                 v_states.append(st)
             a = 0
-            while a < K and drafts[a] == v[a]:
+            while a < n_draft and drafts[a] == v[a]:
                 a += 1
             out.extend(drafts[:a] + [v[a]])
             n_verify += 1
             rounds.append({"pos": pos, "mask": mask.copy(), "drafts": drafts, "verify": v, "accepted": a,
-                           "verify_margin": v_margin, "dp": dp})
+                           "verify_margin": v_margin, "dp": dp, "draft_conf": conf})
             if n_verify % dp_interval == 0:
                 dp = self.dp(v_states[a], pos + a, cache, M)
                 mask = dp["mask"]
             pending = v[a]
             pos += a + 1
         return {"tokens": out[:n_gen], "rounds": rounds}
+
+
+def top1_prob(logits: np.ndarray) -> float:
+    """Largest softmax probability: 1 / sum_v exp(logit_v - max logit), in fp64."""
+    lg = np.asarray(logits, dtype=np.float64)
+    return float(1.0 / np.exp(lg - lg.max()).sum())
 
 
 def argmax_margin(logits: np.ndarray):

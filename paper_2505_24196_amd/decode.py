@@ -41,9 +41,12 @@ def greedy_generate(engine: Engine, prompt: Sequence[int], n_gen: int):
 
 
 def clasp_generate(engine: Engine, prompt: Sequence[int], n_gen: int, M: int, K: int, dp_interval: int = 1,
-                   trace: bool = False) -> Dict[str, object]:
+                   trace: bool = False, det_threshold: Optional[float] = None) -> Dict[str, object]:
     """Greedy self-speculative decoding with the DP-selected skip set re-optimised every `dp_interval` verify steps
-    (1 = after every verification, the paper's default; larger values are its lower optimisation frequency)."""
+    (1 = after every verification, the paper's default; larger values are its lower optimisation frequency).
+    det_threshold (Sec. 5.3.3, draft-exiting threshold): drafting stops after the first draft token whose top-1
+    probability under the draft model is below the threshold; that token is still proposed, so a round verifies
+    2..K+1 rows. Reading the probability costs one 4-byte device-to-host copy per draft step."""
     dev = engine.device
     states, nxt, _ = prefill(engine, prompt)
     pos = len(prompt)
@@ -52,22 +55,29 @@ def clasp_generate(engine: Engine, prompt: Sequence[int], n_gen: int, M: int, K:
     out: List[int] = [int(nxt.item())]
     tok = torch.empty(K + 1, dtype=torch.int32, device=dev)
     tok[0:1].copy_(nxt)
+    conf = torch.zeros(K, dtype=torch.float32, device=dev) if (det_threshold is not None or trace) else None
     rounds = []
     n_verify = 0
     while len(out) < n_gen:
+        n_draft = 0
         for k in range(K):
-            engine.clasp_draft_step(mask, tok[k:k + 1], pos + k, tok[k + 1:k + 2])
-        ver = engine.clasp_verify_forward(tok, pos, want_hidden=True, want_margin=trace)
-        rows = tok.cpu().tolist()
+            engine.clasp_draft_step(mask, tok[k:k + 1], pos + k, tok[k + 1:k + 2],
+                                    None if conf is None else conf[k:k + 1])
+            n_draft += 1
+            if det_threshold is not None and float(conf[k].item()) < det_threshold:
+                break
+        ver = engine.clasp_verify_forward(tok[:n_draft + 1], pos, want_hidden=True, want_margin=trace)
+        rows = tok[:n_draft + 1].cpu().tolist()
         v = ver["argmax"].cpu().tolist()
         a = 0
-        while a < K and rows[a + 1] == v[a]:
+        while a < n_draft and rows[a + 1] == v[a]:
             a += 1
         out.extend(rows[1:a + 1] + [v[a]])
         n_verify += 1
         if trace:
             rounds.append({"pos": pos, "mask": list(mask), "drafts": rows[1:], "verify": v, "accepted": a,
                            "verify_margin": ver["margin"].cpu().tolist(), "dp": {k: t.cpu() for k, t in dp.items()},
+                           "draft_conf": conf[:n_draft].cpu().tolist(),
                            "states": ver["hidden"][:, a, :].cpu()})
         else:
             rounds.append({"pos": pos, "accepted": a})

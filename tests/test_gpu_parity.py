@@ -305,3 +305,35 @@ def test_closed_loop_tiny_matches_oracle_and_is_lossless(resid_scale, M):
         assert all(r["accepted"] == 4 for r in spec_gpu["rounds"])
     if resid_scale == 0.05 and M:
         assert sum(r["accepted"] for r in spec_gpu["rounds"]) > 0
+
+
+@pytest.mark.parametrize("thr", [0.0026, 1.5])
+def test_closed_loop_with_draft_exiting_threshold(thr):
+    """Sec. 5.3.3 on the device: rounds end at the first draft whose top-1 probability is below the threshold, the
+    output stays the device's own plain greedy decoding, and round lengths follow the oracle's wherever no
+    confidence sits within 5 % of the threshold (0.0026 is about the median confidence of this vocab-1024 model)."""
+    import paper_2505_24196_amd as clasp
+    name, M, K, n_gen = "tiny-f32", 3, 4, 24
+    shape = si.SHAPES[name]
+    om, eng = oracle_model(name, 1, 0.05), engine(name, 1, 0.05)
+    pr = [int(t) for t in si.gen_tokens(2, 64, shape.vocab)]
+    plain_gpu, _ = clasp.greedy_generate(eng, pr, n_gen)
+    spec_gpu = clasp.clasp_generate(eng, pr, n_gen, M, K, trace=True, det_threshold=thr)
+    assert spec_gpu["tokens"] == plain_gpu
+    for r in spec_gpu["rounds"]:
+        n = len(r["drafts"])
+        assert 1 <= n <= K and len(r["verify"]) == n + 1 and r["accepted"] <= n
+        assert all(c >= thr for c in r["draft_conf"][:-1]) and (n == K or r["draft_conf"][-1] < thr)
+        if thr > 1.0:
+            assert n == 1
+    plain_ref, plain_margin = om.greedy_decode(pr, n_gen)
+    spec_ref = om.spec_decode(pr, n_gen, M, K, det_threshold=thr)
+    assert spec_ref["tokens"] == plain_ref
+    if plain_gpu == plain_ref:
+        for rg, ro in zip(spec_gpu["rounds"], spec_ref["rounds"]):
+            if np.nanmin(np.abs(ro["dp"]["sigma_c"] - ro["dp"]["sigma_s"])) <= COS_MARGIN:
+                break
+            if any(abs(c - thr) <= 0.05 * thr for c in ro["draft_conf"]) or min(ro["verify_margin"]) < 1e-3:
+                break
+            assert rg["mask"] == ro["mask"].tolist() and len(rg["drafts"]) == len(ro["drafts"])
+            np.testing.assert_allclose(rg["draft_conf"], ro["draft_conf"], rtol=5e-3)

@@ -207,3 +207,38 @@ def test_dp_interval_keeps_the_mask_between_updates():
     masks = [r["mask"].tolist() for r in spec["rounds"]]
     for a, b, c in zip(masks[0::3], masks[1::3], masks[2::3]):
         assert a == b == c
+
+
+def test_top1_prob_closed_forms():
+    """Equal logits give 1/V; one logit far above the rest gives 1; shifting all logits changes nothing."""
+    assert oc.top1_prob(np.zeros(50)) == pytest.approx(1.0 / 50, rel=1e-12)
+    lg = np.array([0.0, np.log(3.0)])
+    assert oc.top1_prob(lg) == pytest.approx(0.75, rel=1e-12)
+    assert oc.top1_prob(lg + 1000.0) == pytest.approx(0.75, rel=1e-12)
+    assert oc.top1_prob(np.array([100.0, 0.0, 0.0])) == pytest.approx(1.0, abs=1e-40)
+
+
+@pytest.mark.parametrize("thr", [0.0, 0.0026, 0.3, 1.5])
+def test_draft_exiting_threshold_shortens_rounds_and_stays_lossless(thr):
+    """Sec. 5.3.3: a round stops drafting after the first token whose draft confidence is below the threshold.
+    The output must still be plain greedy decoding; threshold 0 never exits early; a threshold above 1 drafts one
+    token per round; in between, every round ends exactly at its first low-confidence draft."""
+    om = oracle_model("tiny-f32", 1, 0.05)
+    pr = prompt(om.shape, 24)
+    K = 4
+    plain, _ = om.greedy_decode(pr, 24)
+    spec = om.spec_decode(pr, 24, 3, K, det_threshold=thr)
+    assert spec["tokens"] == plain
+    base = om.spec_decode(pr, 24, 3, K)
+    if thr == 0.0:
+        assert [r["drafts"] for r in spec["rounds"]] == [r["drafts"] for r in base["rounds"]]
+    for r in spec["rounds"]:
+        n = len(r["drafts"])
+        assert 1 <= n <= K and len(r["verify"]) == n + 1 and r["accepted"] <= n
+        assert all(c >= thr for c in r["draft_conf"][:-1])
+        assert n == K or r["draft_conf"][-1] < thr
+        if thr > 1.0:
+            assert n == 1
+    if thr == 0.0026:  # about the median confidence of this random-init model (vocab 1024): rounds of mixed length
+        lens = [len(r["drafts"]) for r in spec["rounds"]]
+        assert min(lens) < K and max(lens) > 1
