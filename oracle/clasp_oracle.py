@@ -5,7 +5,9 @@ HIP package. Arithmetic lives in clasp_oracle.c; this file adds
   * prefill / plain greedy decoding with the full model (the lossless reference of the paper's abstract and
     "Performance Metrics": speculative decoding must not change the generated text),
   * the Draft -> Verify -> Layer-Optimization loop of Sec. 3.1 with greedy acceptance,
-which are integer control flow around the C calls.
+  * its stochastic form (Temperature = 1 setting of Sec. 4): inverse-CDF draws and the speculative-sampling
+    acceptance rule, in fp64 numpy, with every uniform number passed in,
+which are control flow around the C calls.
 """
 from __future__ import annotations
 
@@ -245,6 +247,104 @@ class OracleModel:
             pending = v[a]
             pos += a + 1
         return {"tokens": out[:n_gen], "rounds": rounds}
+
+    def spec_sample_decode(self, prompt: Sequence[int], n_gen: int, M: int, K: int, uniforms: Dict[str, np.ndarray],
+                           temperature: float = 1.0, t_max: Optional[int] = None):
+        """Stochastic self-speculative decoding: as spec_decode, but draft tokens are drawn from the layer-skipped
+        model's softmax, verified with the speculative-sampling acceptance rule (spec_accept), and the layer
+        optimisation runs on the last accepted row. uniforms: "first" [1], "draft" [rounds*K], "accept"
+        [rounds*K], "final" [rounds] numbers in [0, 1), consumed by round r at indices r*K + k (draft, accept) and r
+        (final), so that a device run with the same arrays makes the same draws."""
+        s = self.shape
+        t_max = t_max or len(prompt) + n_gen + K + 2
+        cache = KVCache(s, t_max)
+        states, logits = self.prefill(prompt, cache)
+        pending, first_margin = sample_cdf(softmax_t(logits, temperature), uniforms["first"][0])
+        out = [pending]
+        pos = len(prompt)
+        dp = self.dp(states, pos - 1, cache, M)
+        mask = dp["mask"]
+        rounds = []
+        r = 0
+        while len(out) < n_gen:
+            drafts, q_logits, draft_margin, tok = [], [], [], pending
+            for k in range(K):
+                _, lg = self.token(tok, pos + k, cache, skip=mask)
+                tok, mg = sample_cdf(softmax_t(lg, temperature), uniforms["draft"][r * K + k])
+                drafts.append(tok)
+                q_logits.append(lg)
+                draft_margin.append(mg)
+            rows = [pending] + drafts
+            p_logits, v_states = [], []
+            for i, tk in enumerate(rows):
+                st, lg = self.token(tk, pos + i, cache, want_states=True)
+                p_logits.append(lg)
+                v_states.append(st)
+            a, nxt, info = spec_accept(np.stack(p_logits), np.stack(q_logits), drafts,
+                                       uniforms["accept"][r * K:(r + 1) * K], uniforms["final"][r], temperature)
+            out.extend(drafts[:a] + [nxt])
+            rounds.append({"pos": pos, "mask": mask.copy(), "drafts": drafts, "accepted": a, "next": nxt, "dp": dp,
+                           "draft_margin": draft_margin, "ratio_margin": info["ratio_margin"],
+                           "cdf_margin": info["cdf_margin"]})
+            dp = self.dp(v_states[a], pos + a, cache, M)
+            mask = dp["mask"]
+            pending = nxt
+            pos += a + 1
+            r += 1
+        return {"tokens": out[:n_gen], "rounds": rounds, "first_margin": first_margin}
+
+
+def softmax_t(logits: np.ndarray, temperature: float = 1.0) -> np.ndarray:
+    """softmax(logits / temperature) in fp64."""
+    lg = np.asarray(logits, dtype=np.float64) / float(temperature)
+    e = np.exp(lg - lg.max())
+    return e / e.sum()
+
+
+def sample_cdf(weights: np.ndarray, u: float):
+    """Inverse-CDF draw from non-negative (not necessarily normalised) weights with one uniform u in [0, 1): the
+    smallest index v whose running sum c_v = w_0 + .. + w_v exceeds u * c_last (the last index of positive weight if
+    rounding leaves none). Also returns how far u * c_last is from the two ends of the chosen interval, as a
+    fraction of c_last: a device result in lower precision may only differ when that distance is tiny."""
+    w = np.asarray(weights, dtype=np.float64)
+    c = np.cumsum(w)
+    target = float(u) * c[-1]
+    v = int(np.searchsorted(c, target, side="right"))
+    if v >= w.size:
+        v = int(np.nonzero(w > 0)[0][-1])
+    lo = c[v - 1] if v > 0 else 0.0
+    margin = min(target - lo, c[v] - target) / c[-1] if c[-1] > 0 else 0.0
+    return v, float(margin)
+
+
+def spec_accept(p_logits: np.ndarray, q_logits: np.ndarray, drafts: Sequence[int], u_accept: Sequence[float],
+                u_final: float, temperature: float = 1.0):
+    """Acceptance rule of speculative sampling (the lossless scheme the paper relies on in its Sec. 4.1 and its
+    Temperature = 1 results, from the work it cites there): with p_i = softmax of the full model's logits for the
+    token after row i and q_i the draft model's, draft x_i is kept when u_i * q_i(x_i) < p_i(x_i); at the first
+    rejection the replacement token is drawn from max(0, p_i - q_i) renormalised; when every draft is kept the
+    bonus token is drawn from p_n. p_logits [n+1][V], q_logits [n][V].
+    Returns (accepted count a, next token, dict of decision margins)."""
+    n = len(drafts)
+    info = {"ratio_margin": [], "cdf_margin": None}
+    a = n
+    for i in range(n):
+        p, q = softmax_t(p_logits[i], temperature), softmax_t(q_logits[i], temperature)
+        x = int(drafts[i])
+        lhs, rhs = float(u_accept[i]) * q[x], p[x]
+        info["ratio_margin"].append(abs(lhs - rhs) / max(rhs, lhs, 1e-300))
+        if not lhs < rhs:
+            a = i
+            break
+    if a < n:
+        p, q = softmax_t(p_logits[a], temperature), softmax_t(q_logits[a], temperature)
+        w = np.maximum(p - q, 0.0)
+        if w.sum() <= 0.0:
+            w = p
+    else:
+        w = softmax_t(p_logits[n], temperature)
+    tok, info["cdf_margin"] = sample_cdf(w, u_final)
+    return a, tok, info
 
 
 def top1_prob(logits: np.ndarray) -> float:

@@ -121,6 +121,13 @@ def gen_tokens(seed: int, count: int, vocab: int, stream: int = 0) -> torch.Tens
     return (_lsr(h, 11) % vocab).to(torch.int32)
 
 
+def gen_uniform(seed: int, count: int, stream: int = 0) -> torch.Tensor:
+    """Uniform numbers k / 2^24, k in [0, 2^24), float32 (exactly representable), on the CPU. These are the random
+    draws of stochastic decoding, handed to both the oracle and the device as inputs."""
+    h = hash_bits(seed, 2 << 20 | stream, 0, count)
+    return (_lsr(h, 40).to(torch.float64) / float(1 << 24)).to(torch.float32)
+
+
 # tensor ids inside a model's stream
 _EMBED, _LM_HEAD, _LAYER0, _PER_LAYER = 0, 1, 16, 8
 _MATS = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
