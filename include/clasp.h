@@ -148,6 +148,30 @@ int clasp_dp_select(clasp_ctx *ctx, const float *states, size_t layer_stride, in
 int clasp_draft_step(clasp_ctx *ctx, const uint8_t *mask, const int32_t *token, int pos, int32_t *next_token_out,
                      float *top1_prob_out, void *stream);
 
+/*
+ * Stochastic decoding (the Temperature = 1 setting of Sec. 4; the method stays speculative sampling, Sec. 4.1, so
+ * the output is distributed exactly as the full model's). Every random draw takes a uniform number in [0, 1) from
+ * the caller (dev fp32), so a run is reproducible from its inputs. temperature > 0 divides the logits.
+ *
+ * clasp_sample_token: token_out[0] ~ softmax(logits / temperature), by inverting the cumulative distribution in
+ *   index order with u[0].  logits dev fp32 [vocab].
+ * clasp_draft_sample: clasp_draft_step, but the next token is drawn from the draft model's distribution with u[0]
+ *   and the draft model's logits are kept for the acceptance test.  logits_out dev fp32 [vocab] (required).
+ * clasp_spec_accept: one round's acceptance. tokens dev int32 [n_draft+1] = pending token, drafts; p_logits dev fp32
+ *   rows 0..n_draft (full model, clasp_verify_forward's logits_out over the same rows), q_logits rows 0..n_draft-1
+ *   (clasp_draft_sample's), both with `ld` elements between rows (ld >= vocab). Draft i (token after row i) is kept
+ *   when u_accept[i] * q_i(x) < p_i(x); at the first rejection a the replacement is drawn from max(0, p_a - q_a)
+ *   renormalised, and when all are kept the bonus token is drawn from p_n; both draws use u_final[0].
+ *   n_accepted_out, next_token_out dev int32 [1].  1 <= n_draft <= max_rows - 1.
+ */
+int clasp_sample_token(clasp_ctx *ctx, const float *logits, float temperature, const float *u, int32_t *token_out,
+                       void *stream);
+int clasp_draft_sample(clasp_ctx *ctx, const uint8_t *mask, const int32_t *token, int pos, float temperature,
+                       const float *u, float *logits_out, int32_t *next_token_out, void *stream);
+int clasp_spec_accept(clasp_ctx *ctx, const float *p_logits, const float *q_logits, size_t ld, const int32_t *tokens,
+                      int n_draft, float temperature, const float *u_accept, const float *u_final,
+                      int32_t *n_accepted_out, int32_t *next_token_out, void *stream);
+
 /* Installs cache contents for one layer: K, V dev fp32 [n_tokens][n_kv_heads][head_dim] (keys already rotated) are
  * converted to the cache dtype and layout at positions 0..n_tokens-1. For callers that hold a cache from elsewhere
  * (and for tests that feed synthetic cache contents). */

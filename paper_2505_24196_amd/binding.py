@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libclasp_hip.so")
 CLASP_F32, CLASP_BF16 = 0, 1
 EXPORTS = ("clasp_strerror", "clasp_packed_bytes", "clasp_pack_matrix", "clasp_pack_gate_up", "clasp_workspace_bytes",
            "clasp_kv_cache_bytes", "clasp_create", "clasp_destroy", "clasp_verify_forward", "clasp_dp_select",
-           "clasp_draft_step", "clasp_kv_load", "clasp_kernel_timer_begin", "clasp_kernel_timer_end")
+           "clasp_draft_step", "clasp_sample_token", "clasp_draft_sample", "clasp_spec_accept", "clasp_kv_load",
+           "clasp_kernel_timer_begin", "clasp_kernel_timer_end")
 
 KERNEL_KINDS = {"qkv": 0, "attention": 1, "o_proj": 2, "gate_up": 3, "down": 4, "lm_head": 5}
 
@@ -65,6 +66,9 @@ def lib():
         l.clasp_verify_forward.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp]
         l.clasp_dp_select.argtypes = [vp, vp, sz, i32, i32, vp, vp, vp, vp, vp]
         l.clasp_draft_step.argtypes = [vp, vp, vp, i32, vp, vp, vp]
+        l.clasp_sample_token.argtypes = [vp, vp, C.c_float, vp, vp, vp]
+        l.clasp_draft_sample.argtypes = [vp, vp, vp, i32, C.c_float, vp, vp, vp, vp]
+        l.clasp_spec_accept.argtypes = [vp, vp, vp, sz, vp, i32, C.c_float, vp, vp, vp, vp, vp]
         l.clasp_kv_load.argtypes = [vp, i32, vp, vp, i32, vp]
         l.clasp_kernel_timer_begin.argtypes = [vp, i32, i32, i32]
         l.clasp_kernel_timer_end.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int)]
@@ -257,6 +261,46 @@ class Engine:
         _check(lib().clasp_draft_step(self._ctx, mp, token.data_ptr(), pos, next_token_out.data_ptr(),
                                       None if top1_prob_out is None else top1_prob_out.data_ptr(), _stream()),
                "clasp_draft_step")
+
+    def _mask_ptr(self, mask):
+        if mask is None:
+            return None
+        mb = (C.c_uint8 * self.shape.n_layers)(*[int(x) for x in mask])
+        return C.cast(mb, C.c_void_p), mb
+
+    def clasp_sample_token(self, logits: torch.Tensor, temperature: float, u: torch.Tensor, token_out: torch.Tensor):
+        """logits device fp32 [vocab] (contiguous), u device fp32 [1], token_out device int32 [1]."""
+        assert logits.dtype == torch.float32 and logits.is_contiguous() and logits.numel() == self.shape.vocab
+        assert u.dtype == torch.float32 and token_out.dtype == torch.int32
+        _check(lib().clasp_sample_token(self._ctx, logits.data_ptr(), float(temperature), u.data_ptr(),
+                                        token_out.data_ptr(), _stream()), "clasp_sample_token")
+
+    def clasp_draft_sample(self, mask: Optional[Sequence[int]], token: torch.Tensor, pos: int, temperature: float,
+                           u: torch.Tensor, logits_out: torch.Tensor, next_token_out: torch.Tensor):
+        """As clasp_draft_step, drawing the next token with u (device fp32 [1]); logits_out device fp32 [vocab]."""
+        assert logits_out.dtype == torch.float32 and logits_out.is_contiguous() and logits_out.numel() == self.shape.vocab
+        assert u.dtype == torch.float32 and next_token_out.dtype == torch.int32 and token.dtype == torch.int32
+        mp = self._mask_ptr(mask)
+        _check(lib().clasp_draft_sample(self._ctx, None if mp is None else mp[0], token.data_ptr(), pos,
+                                        float(temperature), u.data_ptr(), logits_out.data_ptr(),
+                                        next_token_out.data_ptr(), _stream()), "clasp_draft_sample")
+
+    def clasp_spec_accept(self, p_logits: torch.Tensor, q_logits: torch.Tensor, tokens: torch.Tensor, n_draft: int,
+                          temperature: float, u_accept: torch.Tensor, u_final: torch.Tensor,
+                          n_accepted_out: torch.Tensor, next_token_out: torch.Tensor):
+        """p_logits [>= n_draft+1][vocab], q_logits [>= n_draft][vocab] device fp32 with unit inner stride;
+        tokens device int32 [n_draft+1]; u_accept device fp32 [n_draft]; u_final device fp32 [1]."""
+        V = self.shape.vocab
+        for t, rows in ((p_logits, n_draft + 1), (q_logits, n_draft)):
+            assert t.dtype == torch.float32 and t.dim() == 2 and t.shape[1] == V and t.stride(1) == 1 and t.shape[0] >= rows
+        assert p_logits.stride(0) == q_logits.stride(0)
+        assert tokens.dtype == torch.int32 and tokens.numel() >= n_draft + 1 and u_accept.numel() >= n_draft
+        assert u_accept.dtype == torch.float32 and u_final.dtype == torch.float32
+        assert n_accepted_out.dtype == torch.int32 and next_token_out.dtype == torch.int32
+        _check(lib().clasp_spec_accept(self._ctx, p_logits.data_ptr(), q_logits.data_ptr(), p_logits.stride(0),
+                                       tokens.data_ptr(), n_draft, float(temperature), u_accept.data_ptr(),
+                                       u_final.data_ptr(), n_accepted_out.data_ptr(), next_token_out.data_ptr(),
+                                       _stream()), "clasp_spec_accept")
 
     # ---- measurement aid ------------------------------------------------------------------------------------------
     def kernel_timer_begin(self, kind: str, capacity: int = 1 << 16, every: int = 1):

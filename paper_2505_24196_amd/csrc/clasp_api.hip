@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "clasp_attn.h"
+#include "clasp_sample.h"
 #include "clasp_common.h"
 #include "clasp_gemm.h"
 #include "clasp_misc.h"
@@ -644,12 +645,11 @@ int clasp_verify_forward(clasp_ctx* ctx, const int32_t* tokens, int n_tokens, in
     return CLASP_OK;
 }
 
-int clasp_draft_step(clasp_ctx* ctx, const uint8_t* mask, const int32_t* token, int pos, int32_t* next_token_out,
-                     float* top1_prob_out, void* stream) {
-    if (!ctx || !token || !next_token_out) return CLASP_E_INVALID_ARG;
+// The layers a skip set keeps on one row at position `pos`, then the head: greedy token (+ top-1 probability) and / or
+// the logits.
+static int draft_forward(clasp_ctx* ctx, const uint8_t* mask, const int32_t* token, int pos, float* logits_out,
+                         int32_t* argmax_out, float* top1_prob_out, hipStream_t st) {
     const clasp_config& c = ctx->cfg;
-    if (pos < 0 || pos >= c.max_seq) return CLASP_E_INVALID_ARG;
-    hipStream_t st = static_cast<hipStream_t>(stream);
     const int L = c.n_layers;
     std::vector<int> kept;
     for (int l = 0; l < L; ++l)
@@ -663,7 +663,48 @@ int clasp_draft_step(clasp_ctx* ctx, const uint8_t* mask, const int32_t* token, 
                             nullptr, st)))
             return rc;
     }
-    return run_head(ctx, 1, 1, nullptr, next_token_out, nullptr, top1_prob_out, st);
+    return run_head(ctx, 1, 1, logits_out, argmax_out, nullptr, top1_prob_out, st);
+}
+
+int clasp_draft_step(clasp_ctx* ctx, const uint8_t* mask, const int32_t* token, int pos, int32_t* next_token_out,
+                     float* top1_prob_out, void* stream) {
+    if (!ctx || !token || !next_token_out) return CLASP_E_INVALID_ARG;
+    if (pos < 0 || pos >= ctx->cfg.max_seq) return CLASP_E_INVALID_ARG;
+    return draft_forward(ctx, mask, token, pos, nullptr, next_token_out, top1_prob_out, static_cast<hipStream_t>(stream));
+}
+
+int clasp_sample_token(clasp_ctx* ctx, const float* logits, float temperature, const float* u, int32_t* token_out,
+                       void* stream) {
+    if (!ctx || !logits || !u || !token_out || !(temperature > 0.f)) return CLASP_E_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(sample_kernel, dim3(1), dim3(kSampleThreads), 0, st, logits, ctx->cfg.vocab, 1.0f / temperature, u,
+                       token_out);
+    CLASP_LAUNCH_CHECK();
+    return CLASP_OK;
+}
+
+int clasp_draft_sample(clasp_ctx* ctx, const uint8_t* mask, const int32_t* token, int pos, float temperature,
+                       const float* u, float* logits_out, int32_t* next_token_out, void* stream) {
+    if (!ctx || !token || !next_token_out || !u || !logits_out || !(temperature > 0.f)) return CLASP_E_INVALID_ARG;
+    if (pos < 0 || pos >= ctx->cfg.max_seq) return CLASP_E_INVALID_ARG;
+    int rc;
+    if ((rc = draft_forward(ctx, mask, token, pos, logits_out, nullptr, nullptr, static_cast<hipStream_t>(stream))))
+        return rc;
+    return clasp_sample_token(ctx, logits_out, temperature, u, next_token_out, stream);
+}
+
+int clasp_spec_accept(clasp_ctx* ctx, const float* p_logits, const float* q_logits, size_t ld, const int32_t* tokens,
+                      int n_draft, float temperature, const float* u_accept, const float* u_final,
+                      int32_t* n_accepted_out, int32_t* next_token_out, void* stream) {
+    if (!ctx || !p_logits || !q_logits || !tokens || !u_accept || !u_final || !n_accepted_out || !next_token_out)
+        return CLASP_E_INVALID_ARG;
+    if (!(temperature > 0.f) || n_draft < 1 || n_draft > ctx->cfg.max_rows - 1 || ld < (size_t)ctx->cfg.vocab)
+        return CLASP_E_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(spec_accept_kernel, dim3(1), dim3(kSampleThreads), 0, st, p_logits, q_logits, ld, tokens, n_draft,
+                       ctx->cfg.vocab, 1.0f / temperature, u_accept, u_final, n_accepted_out, next_token_out);
+    CLASP_LAUNCH_CHECK();
+    return CLASP_OK;
 }
 
 int clasp_dp_select(clasp_ctx* ctx, const float* states, size_t layer_stride, int pos, int M, uint8_t* mask_out,

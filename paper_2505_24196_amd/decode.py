@@ -87,3 +87,54 @@ def clasp_generate(engine: Engine, prompt: Sequence[int], n_gen: int, M: int, K:
         tok[0:1].copy_(ver["argmax"][a:a + 1])
         pos += a + 1
     return {"tokens": out[:n_gen], "rounds": rounds}
+
+
+def clasp_sample_generate(engine: Engine, prompt: Sequence[int], n_gen: int, M: int, K: int,
+                          uniforms: Dict[str, torch.Tensor], temperature: float = 1.0,
+                          trace: bool = False) -> Dict[str, object]:
+    """Stochastic self-speculative decoding (the Temperature = 1 setting of Sec. 4): drafts are drawn from the
+    layer-skipped model's distribution, one verify pass gives the full model's logits for all of them, and the
+    speculative-sampling rule keeps a prefix of the drafts and draws the next token, so the output is distributed as
+    the full model's own sampling. The layer optimisation runs on the last accepted row as in the greedy loop.
+
+    uniforms: device fp32 tensors "first" [1], "draft" [rounds*K], "accept" [rounds*K], "final" [rounds] in [0, 1);
+    round r consumes draft/accept indices r*K .. r*K+K-1 and final index r. Per round one 8-byte device-to-host copy
+    (accepted count, next token) plus the mask bytes."""
+    dev = engine.device
+    V = engine.shape.vocab
+    toks = torch.as_tensor(list(prompt), dtype=torch.int32, device=dev)
+    n, step = toks.numel(), engine.max_rows
+    for s in range(0, n, step):
+        last = engine.clasp_verify_forward(toks[s:s + step], s, want_hidden=(s + step >= n), want_logits=(s + step >= n))
+    rows_last = last["argmax"].numel() - 1
+    tok = torch.empty(K + 1, dtype=torch.int32, device=dev)
+    engine.clasp_sample_token(last["logits"][rows_last], temperature, uniforms["first"][0:1], tok[0:1])
+    pos = len(prompt)
+    dp = engine.clasp_dp_select(last["hidden"][:, rows_last, :], pos - 1, M)
+    mask = dp["mask"].cpu().tolist()
+    out: List[int] = [int(tok[0].item())]
+    q_logits = torch.empty(K, V, dtype=torch.float32, device=dev)
+    res = torch.empty(2, dtype=torch.int32, device=dev)
+    rounds = []
+    r = 0
+    while len(out) < n_gen:
+        for k in range(K):
+            engine.clasp_draft_sample(mask, tok[k:k + 1], pos + k, temperature, uniforms["draft"][r * K + k:r * K + k + 1],
+                                      q_logits[k], tok[k + 1:k + 2])
+        ver = engine.clasp_verify_forward(tok, pos, want_hidden=True, want_logits=True)
+        engine.clasp_spec_accept(ver["logits"], q_logits, tok, K, temperature, uniforms["accept"][r * K:(r + 1) * K],
+                                 uniforms["final"][r:r + 1], res[0:1], res[1:2])
+        a, nxt = res.cpu().tolist()
+        drafts = tok[1:].cpu().tolist()
+        out.extend(drafts[:a] + [nxt])
+        rec = {"pos": pos, "accepted": a, "next": nxt, "drafts": drafts, "mask": list(mask)}
+        if trace:
+            rec["p_logits"], rec["q_logits"] = ver["logits"].cpu(), q_logits.cpu()
+        rounds.append(rec)
+        if len(out) < n_gen:
+            dp = engine.clasp_dp_select(ver["hidden"][:, a, :], pos + a, M)
+            mask = dp["mask"].cpu().tolist()
+        tok[0:1].copy_(res[1:2])
+        pos += a + 1
+        r += 1
+    return {"tokens": out[:n_gen], "rounds": rounds}

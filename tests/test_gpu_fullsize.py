@@ -58,3 +58,40 @@ def test_8b_verify_dp_and_draft(setup_8b):
     ref_tok, ref_margin = oc.argmax_margin(dl)
     if ref_margin > HID_TOL["bf16"] * np.abs(dl).max() * 2:
         assert int(nxt) == ref_tok
+
+
+def test_8b_vocab_sampling_and_acceptance(setup_8b):
+    """Inverse-CDF draws and one acceptance round at the full vocabulary (128256 entries, 126 per thread with a ragged
+    last chunk), on synthetic logits, against the fp64 oracle, with the margins of tests/test_gpu_sampling.py."""
+    shape, T, eng, om, cache = setup_8b
+    V = shape.vocab
+    n = 4
+    p_lg = si.gen_matrix(21, 900, n + 1, V, 2.0, "f32").numpy()
+    q_lg = (p_lg[:n] + 0.3 * si.gen_matrix(22, 901, n, V, 2.0, "f32").numpy()).astype(np.float32)
+    us = si.gen_uniform(23, 40, 0)
+    d_tok = torch.zeros(1, dtype=torch.int32, device="cuda")
+    d_lg, d_u = dev(p_lg[0]), us.cuda()
+    w = oc.softmax_t(p_lg[0])
+    checked = 0
+    for i in range(24):
+        eng.clasp_sample_token(d_lg, 1.0, d_u[i:i + 1], d_tok)
+        ref, margin = oc.sample_cdf(w, float(us[i]))
+        if margin > 2e-7:  # token probabilities are ~1e-5 here; fp32 running sums hold ~1e-7 of the total
+            assert int(d_tok) == ref
+            checked += 1
+    assert checked > 12
+    res = torch.zeros(2, dtype=torch.int32, device="cuda")
+    compared = 0
+    for trial in range(6):
+        u = si.gen_uniform(30 + trial, 2 * n + 1, 3).numpy()
+        drafts = [oc.sample_cdf(oc.softmax_t(q_lg[i]), float(u[i]))[0] for i in range(n)]
+        a_ref, tok_ref, info = oc.spec_accept(p_lg, q_lg, drafts, u[n:2 * n], float(u[2 * n]))
+        eng.clasp_spec_accept(dev(p_lg), dev(q_lg), dev([1] + drafts, torch.int32), n, 1.0, dev(u[n:2 * n]),
+                              dev(u[2 * n:]), res[0:1], res[1:2])
+        a, tok = res.cpu().tolist()
+        if min(info["ratio_margin"]) > 1e-4:
+            assert a == a_ref
+            if info["cdf_margin"] > 2e-7:
+                assert tok == tok_ref
+                compared += 1
+    assert compared >= 3
