@@ -126,6 +126,10 @@ def main():
     ap.add_argument("--resid-scale", type=float, default=1.0,
                     help="closed loop only: std multiplier of wo / w_down (0.05 = slow-drift variant whose drafts get "
                          "accepted; 1.0 = the plain N(0, 0.02) init of the benchmark configurations)")
+    ap.add_argument("--dp-interval", type=int, default=1,
+                    help="closed loop only: re-optimise the skip set every this many verify steps (Sec. 3.7)")
+    ap.add_argument("--det-threshold", type=float, default=None,
+                    help="closed loop only: draft-exiting threshold on the draft token's top-1 probability (Sec. 5.3.3)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="only run plain device copies of a known size (1 GiB read + 1 GiB written per copy), to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -161,7 +165,8 @@ def main():
         torch.cuda.synchronize()
         t_plain = time.perf_counter() - t0
         t0 = time.perf_counter()
-        spec = decode.clasp_generate(eng, prompt, n_gen, M, K)
+        spec = decode.clasp_generate(eng, prompt, n_gen, M, K, dp_interval=args.dp_interval,
+                                     det_threshold=args.det_threshold)
         torch.cuda.synchronize()
         t_spec = time.perf_counter() - t0
         first_diff = next((i for i, (a, b) in enumerate(zip(plain, spec["tokens"])) if a != b), None)
@@ -170,6 +175,9 @@ def main():
                           "plain_greedy_tokens_per_s": round(n_gen / t_plain, 2),
                           "clasp_tokens_per_s": round(n_gen / t_spec, 2), "speedup": round(t_plain / t_spec, 3),
                           "rounds": len(acc), "mean_tokens_per_round": round(n_gen / max(1, len(acc)), 3),
+                          "dp_interval": args.dp_interval, "det_threshold": args.det_threshold,
+                          "skip_set_jaccard_by_round_gap": [round(x, 3) for x in decode.skip_set_jaccard(
+                              [r["mask"] for r in spec["rounds"]][::args.dp_interval], 8)],
                           "tokens_equal": first_diff is None, "first_difference_at": first_diff,
                           "plain_margin_at_difference": None if first_diff is None else margins[first_diff]}))
         return

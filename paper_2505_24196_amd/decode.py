@@ -80,7 +80,7 @@ def clasp_generate(engine: Engine, prompt: Sequence[int], n_gen: int, M: int, K:
                            "draft_conf": conf[:n_draft].cpu().tolist(),
                            "states": ver["hidden"][:, a, :].cpu()})
         else:
-            rounds.append({"pos": pos, "accepted": a})
+            rounds.append({"pos": pos, "accepted": a, "mask": list(mask)})
         if n_verify % dp_interval == 0 and len(out) < n_gen:
             dp = engine.clasp_dp_select(ver["hidden"][:, a, :], pos + a, M, want_tables=trace)
             mask = dp["mask"].cpu().tolist()
@@ -138,3 +138,17 @@ def clasp_sample_generate(engine: Engine, prompt: Sequence[int], n_gen: int, M: 
         pos += a + 1
         r += 1
     return {"tokens": out[:n_gen], "rounds": rounds}
+
+
+def skip_set_jaccard(masks: Sequence[Sequence[int]], max_gap: int = 8) -> List[float]:
+    """Sparse persistence (Sec. 3.7, Fig. 3a): mean Jaccard similarity |A & B| / |A | B| between the skip sets chosen
+    `gap` optimisations apart, for gap = 1..max_gap (two empty sets count as identical). masks: one 0/1 sequence of
+    length L per optimisation, in order. Gaps with no pair are left out."""
+    sets = [frozenset(i for i, m in enumerate(mask) if m) for mask in masks]
+    curve = []
+    for gap in range(1, max_gap + 1):
+        pairs = [(a, b) for a, b in zip(sets, sets[gap:])]
+        if not pairs:
+            break
+        curve.append(sum(1.0 if not (a | b) else len(a & b) / len(a | b) for a, b in pairs) / len(pairs))
+    return curve

@@ -61,3 +61,14 @@ def test_engine_refuses_to_run_without_a_gpu():
     import synth_inputs as si
     with pytest.raises(clasp.ClaspError):
         clasp.Engine(si.TINY_F32, max_seq=64)
+
+
+def test_skip_set_jaccard_curve_by_hand():
+    """Sparse persistence statistic (Sec. 3.7): Jaccard similarity of skip sets `gap` optimisations apart."""
+    from paper_2505_24196_amd import skip_set_jaccard
+    masks = [[1, 1, 0, 0], [1, 0, 1, 0], [1, 0, 1, 0], [0, 0, 0, 1]]
+    # gap 1: {0,1}~{0,2} = 1/3, {0,2}~{0,2} = 1, {0,2}~{3} = 0; gap 2: {0,1}~{0,2} = 1/3, {0,2}~{3} = 0; gap 3: 0
+    curve = skip_set_jaccard(masks, max_gap=8)
+    assert curve == pytest.approx([(1 / 3 + 1 + 0) / 3, (1 / 3 + 0) / 2, 0.0])
+    assert skip_set_jaccard([[0, 0], [0, 0]]) == [1.0]  # two empty sets are identical
+    assert skip_set_jaccard([[1, 0]]) == []
