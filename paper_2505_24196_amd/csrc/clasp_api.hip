@@ -70,6 +70,18 @@ namespace {
 #ifndef CLASP_DOWNP_KS
 #define CLASP_DOWNP_KS 4
 #endif
+#ifndef CLASP_GEMV_DEPTH
+#define CLASP_GEMV_DEPTH 4  // weight loads per register stage of the single-row kernel (deeper is slower: measured)
+#endif
+#ifndef CLASP_GEMV_KW_QKV
+#define CLASP_GEMV_KW_QKV 8
+#endif
+#ifndef CLASP_GEMV_KW_RESID
+#define CLASP_GEMV_KW_RESID 8
+#endif
+#ifndef CLASP_GEMV
+#define CLASP_GEMV 1  // single-row launches (draft steps) take the LDS-staged kernel
+#endif
 #ifndef CLASP_ACT_SPLIT
 #define CLASP_ACT_SPLIT 2  // 2: activations enter the MFMAs as bf16 hi + lo; 1: hi only
 #endif
@@ -118,7 +130,7 @@ struct clasp_ctx {
     float* logits;
     float* attn_partial;
     float* down_parts;  // [CLASP_DOWNP_KS][32][d] K-slices of the DP's down projection
-    void* head_parts;   // [vocab/16][32] x 16 bytes: per-tile pieces of the greedy head
+    void* head_parts;   // [32][vocab/16] x 16 bytes: per-tile pieces of the greedy head
     void *q_frag, *k_self, *v_self;
     uint8_t* choice;
     int32_t* tok_tmp;
@@ -217,6 +229,32 @@ struct TimerScope {
 #endif
 constexpr int kResidentKW = 8, kResidentKSW = 16;
 
+constexpr size_t kGemvMaxLds = 96 * 1024;
+
+// LDS bytes the single-row kernel needs for this contraction length with KWV wavefronts, 0 if it cannot take it.
+template <int KWV>
+size_t gemv_lds_bytes(int K) {
+    const int nks_max = (K / 32 + KWV - 1) / KWV;
+    if (nks_max * CLASP_ACT_SPLIT * 4 > kGemvLoads * 64) return 0;
+    const size_t lds = (size_t)KWV * nks_max * CLASP_ACT_SPLIT * 64;
+    return lds <= kGemvMaxLds ? lds : 0;
+}
+
+template <int EPI, int KWV>
+int launch_gemv(const GemmArgs& g, size_t lds, hipStream_t st) {
+    static bool opted_in = false;  // more than 64 KiB of LDS per workgroup has to be requested once per kernel
+    auto kernel = gemv_bf16_kernel<KWV, EPI, CLASP_GEMV_DEPTH, CLASP_ACT_SPLIT>;
+    if (!opted_in) {
+        if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemvMaxLds) !=
+            hipSuccess)
+            return CLASP_E_HIP;
+        opted_in = true;
+    }
+    hipLaunchKernelGGL(kernel, dim3(g.N / 16), dim3(KWV * 64), lds, st, g, (g.K / 32 + KWV - 1) / KWV);
+    CLASP_LAUNCH_CHECK();
+    return CLASP_OK;
+}
+
 template <int EPI, int CW, int KW>
 int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kind) {
     const int tiles = g.N / 16;
@@ -224,11 +262,16 @@ int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kin
     if (ctx->cfg.dtype == CLASP_BF16) {
         const bool resident = g.R == 1 && ((CLASP_RESIDENT_MASK >> kind) & 1) &&
                               (g.K / 32 + kResidentKW - 1) / kResidentKW <= kResidentKSW && tiles > ctx->n_cu;
+        constexpr int KWV = EPI == kEpiQkv ? CLASP_GEMV_KW_QKV : (EPI == kEpiResid ? CLASP_GEMV_KW_RESID : 8);
+        const size_t gemv_lds =
+            (CLASP_GEMV && g.n_rows == 1 && g.R == 1 && EPI != kEpiPartial) ? gemv_lds_bytes<KWV>(g.K) : 0;
         if (resident) {
             // every workgroup takes the same number of tiles (+-1): rounds = ceil(tiles / CUs), grid = ceil(tiles / rounds)
             const int rounds = (tiles + ctx->n_cu - 1) / ctx->n_cu, grid = (tiles + rounds - 1) / rounds;
             hipLaunchKernelGGL((gemm_bf16_resident_kernel<kResidentKSW, kResidentKW, EPI, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>),
                                dim3(grid), dim3(kResidentKW * 64), 0, st, g);
+        } else if (gemv_lds) {
+            return launch_gemv<EPI, KWV>(g, gemv_lds, st);
         } else {
             const dim3 grid((tiles + CW - 1) / CW);
             if (g.R == 1)
@@ -397,10 +440,10 @@ int launch_embed(const clasp_ctx* ctx, const int32_t* tokens, int n, int R, floa
                  float* capture, hipStream_t st) {
     const clasp_config& c = ctx->cfg;
     if (c.dtype == CLASP_BF16)
-        hipLaunchKernelGGL((embed_kernel<kDtBf16>), dim3(n), dim3(256), 0, st, tokens, ctx->embed, c.vocab, c.d_model, h,
+        hipLaunchKernelGGL((embed_kernel<kDtBf16>), dim3(n, (c.d_model + 255) / 256), dim3(256), 0, st, tokens, ctx->embed, c.vocab, c.d_model, h,
                            ctx->op_h, R, gain, ctx->ss_h, capture);
     else
-        hipLaunchKernelGGL((embed_kernel<kDtF32>), dim3(n), dim3(256), 0, st, tokens, ctx->embed, c.vocab, c.d_model, h,
+        hipLaunchKernelGGL((embed_kernel<kDtF32>), dim3(n, (c.d_model + 255) / 256), dim3(256), 0, st, tokens, ctx->embed, c.vocab, c.d_model, h,
                            ctx->op_h, R, gain, ctx->ss_h, capture);
     CLASP_LAUNCH_CHECK();
     return CLASP_OK;

@@ -64,7 +64,7 @@ struct GemmArgs {
     float* capture;          // optional copy of out, [rows][ldc]
     int ldc;
     QkvOut qkv;  // kEpiQkv only
-    f32x4* head_parts;  // kEpiHead: [N/16][32] (max, index bits, second max, sum exp)
+    f32x4* head_parts;  // kEpiHead: [32][N/16] (max, index bits, second max, sum exp)
 };
 
 // (largest, index, second largest) of two disjoint sets; equal maxima keep the lower index.
@@ -102,6 +102,45 @@ __device__ __forceinline__ void compute_rstd(const GemmArgs& g, float* rstd_s, f
         rstd_s[threadIdx.x] = 1.0f / sqrtf(t * g.inv_dim + g.eps);
     }
     __syncthreads();
+}
+
+// The same reduction in three steps, for kernels that hide the round trip of the partials behind their weight stream:
+// thread t adds the partials p = t/32 + u*nsub (nsub = blockDim/32, fixed order) of row t%32;
+//   rstd_issue  requests the first NLD of them (all of them when n_parts <= NLD * nsub);
+//   rstd_stash  adds them up (fetching any remaining ones the slow way) and leaves the thread's sum in tmp[t];
+//   rstd_finish, run by one whole wavefront after a workgroup barrier that follows rstd_stash, adds the nsub sums of
+//   each row in order and writes rstd_s; the same wavefront may read rstd_s right after it.
+template <int NLD>
+__device__ __forceinline__ void rstd_issue(const GemmArgs& g, float (&v)[NLD]) {
+    const int row = threadIdx.x & 31, sub = threadIdx.x >> 5, nsub = blockDim.x >> 5;
+#pragma unroll
+    for (int u = 0; u < NLD; ++u) {
+        const int p = sub + u * nsub;
+        v[u] = (p < g.n_parts && row < g.n_rows) ? g.ss_parts[(size_t)p * kMaxRows + row] : 0.f;
+    }
+}
+template <int NLD>
+__device__ __forceinline__ void rstd_stash(const GemmArgs& g, const float (&v)[NLD], float* tmp /* [blockDim] */) {
+    const int row = threadIdx.x & 31, sub = threadIdx.x >> 5, nsub = blockDim.x >> 5;
+    float s = 0.f;
+#pragma unroll
+    for (int u = 0; u < NLD; ++u) s += v[u];
+    for (int p = sub + NLD * nsub; p < g.n_parts; p += nsub)
+        if (row < g.n_rows) s += g.ss_parts[(size_t)p * kMaxRows + row];
+    tmp[threadIdx.x] = s;
+}
+__device__ __forceinline__ void rstd_finish(const GemmArgs& g, const float* tmp, float* rstd_s) {
+    const int lane = threadIdx.x & 63, nsub = blockDim.x >> 5;
+    if (lane < 32) {
+        float t = 0.f;
+        for (int u = 0; u < nsub; ++u) t += tmp[u * 32 + lane];
+        rstd_s[lane] = 1.0f / sqrtf(t * g.inv_dim + g.eps);
+    }
+    // LDS operations of one wavefront complete in program order; the fences keep the compiler from moving the
+    // readers of rstd_s above the store
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 template <int R, int NACC, int P, int SPLIT>
@@ -252,7 +291,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, int tile, int l
                 top2_merge(v1, i1, v2, b1, bi, b2);
             }
             const float se = sum16(expf(x - v1));
-            if ((lane & 15) == 0) g.head_parts[(size_t)tile * kMaxRows + row] = f32x4{v1, __int_as_float(i1), v2, se};
+            if ((lane & 15) == 0) g.head_parts[(size_t)row * (g.N >> 4) + tile] = f32x4{v1, __int_as_float(i1), v2, se};
         }
     } else if constexpr (EPI == kEpiPartial) {
         float* slab = g.out + (size_t)blockIdx.y * g.ldr;  // ldr = elements per slab
@@ -388,6 +427,98 @@ __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
         for (int x = 0; x < NACC; ++x) fin[x] = sum[x][rg];
         gemm_epilogue<EPI, NACC>(g, tile, lane, rg, fin, rstd_s, pre[rg]);
     }
+}
+
+// Single-row variant (draft steps, plain decoding): with one live row an activation fragment is the same 16 bytes in all
+// 16 lanes of a lane group, and fetching it with per-lane global loads (two per weight load: hi and lo plane) costs the
+// load pipeline more than the weights do. Here every wavefront first copies row 0 of ITS k-slice (64 bytes per plane
+// and k-step) into a private LDS region, one 16-byte piece per lane and load, and the main loop reads the fragments
+// back with broadcast LDS reads, which run beside the weight stream instead of inside it. One column tile per
+// workgroup, KW wavefronts split K; the register stages hold weights only. `nks_max` = LDS k-steps reserved per
+// wavefront (>= ceil(K/32/KW), <= 16*kGemvLoads/SPLIT); dynamic LDS = KW * nks_max * SPLIT * 64 bytes.
+constexpr int kGemvLoads = 8;
+template <int KW, int EPI, int P, int SPLIT>
+__global__ __launch_bounds__(KW * 64) void gemv_bf16_kernel(GemmArgs g, int nks_max) {
+    extern __shared__ u32x4 a_lds[];
+    __shared__ f32x4 red[KW][64];
+    __shared__ float rstd_s[kMaxRows];
+    __shared__ float tmp_s[KW * 64];
+    constexpr bool kNeedsRstd = EPI != kEpiResid && EPI != kEpiPartial;
+    const int kw = threadIdx.x >> 6, lane = threadIdx.x & 63, q = lane >> 4;
+    const int tile = blockIdx.x, KS = g.K >> 5;
+    const int ks0 = (KS * kw) / KW, ks1 = (KS * (kw + 1)) / KW, nks = ks1 - ks0;
+
+    int mi = 0, tl = tile;
+    if constexpr (EPI == kEpiScale || EPI == kEpiQkv) {
+        if (tile >= g.tile_end[0]) { mi = 1; tl = tile - g.tile_end[0]; }
+        if (tile >= g.tile_end[1]) { mi = 2; tl = tile - g.tile_end[1]; }
+    }
+    const u32x4* w0 = reinterpret_cast<const u32x4*>(g.W[mi]) + (size_t)tl * KS * 64 + lane;
+    u32x4 wb[2][P];
+    auto issue = [&](u32x4 (&buf)[P], int s) {
+#pragma unroll
+        for (int u = 0; u < P; ++u) buf[u] = load_stream(w0 + (size_t)min(s + u, ks1 - 1) * 64);
+    };
+    int s = ks0;
+    if (s < ks1) issue(wb[0], s);  // weights first: independent of everything else
+
+    // piece e of the slice = (k-step e / (4*SPLIT), plane (e / 4) % SPLIT, 16-byte quarter e % 4) of row 0
+    const int n_el = nks * SPLIT * 4;
+    u32x4 av[kGemvLoads];
+    {
+        const u32x4* A = reinterpret_cast<const u32x4*>(g.A);
+#pragma unroll
+        for (int i = 0; i < kGemvLoads; ++i) {
+            const int e = min(lane + i * 64, max(n_el - 1, 0));
+            av[i] = A[((size_t)(ks0 + e / (4 * SPLIT)) * 2 + (e / 4) % SPLIT) * 64 + (e & 3)];
+        }
+    }
+    EpiPre pre;
+    if (kw == 0) epi_prefetch<EPI>(g, tile, lane, 0, pre);
+    float ssv[16];
+    if constexpr (kNeedsRstd) rstd_issue(g, ssv);
+    if (s + P < ks1) issue(wb[1], s + P);
+
+    u32x4* mine = a_lds + (size_t)kw * nks_max * SPLIT * 4;
+#pragma unroll
+    for (int i = 0; i < kGemvLoads; ++i)
+        if (lane + i * 64 < n_el) mine[lane + i * 64] = av[i];
+    if constexpr (kNeedsRstd) rstd_stash(g, ssv, tmp_s);
+    // the region is private to this wavefront and its LDS operations complete in program order
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    auto compute = [&](const u32x4 (&buf)[P], int s0) {
+#pragma unroll
+        for (int u = 0; u < P; ++u) {
+            if (s0 + u < ks1) {
+#pragma unroll
+                for (int h = 0; h < SPLIT; ++h)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(mine[((s0 + u - ks0) * SPLIT + h) * 4 + q]),
+                                                                  as_bf16x8(buf[u]), acc, 0, 0, 0);
+            }
+        }
+    };
+    while (s < ks1) {  // two register stages: one being consumed, the other in flight
+        compute(wb[0], s);
+        s += P;
+        if (s >= ks1) break;
+        if (s + P < ks1) issue(wb[0], s + P);
+        compute(wb[1], s);
+        s += P;
+        if (s + P < ks1) issue(wb[1], s + P);
+    }
+
+    red[kw][lane] = acc;
+    __syncthreads();
+    if (kw != 0) return;
+    if constexpr (kNeedsRstd) rstd_finish(g, tmp_s, rstd_s);
+    f32x4 fin[1];
+    fin[0] = red[0][lane];
+    for (int k = 1; k < KW; ++k) fin[0] += red[k][lane];
+    gemm_epilogue<EPI, 1>(g, tile, lane, 0, fin, rstd_s, pre);
 }
 
 // Resident-activation variant for one row group (rows <= 16) and K/32 <= KW*KSW: wavefront kw keeps ITS k-slice of the

@@ -64,37 +64,24 @@ __global__ void fill_zero_kernel(u32x4* p, size_t n_vec) {
         p[i] = u32x4{0u, 0u, 0u, 0u};
 }
 
-// ---- emit one row for the next layer: fp32 copy, GEMM operand (row * gain), per-16-column sums of squares --------
-// Called by all threads of a workgroup; d % 16 == 0 and blockDim % 16 == 0 so a 16-column tile sits in 16 lanes.
-template <int DT, class F>
-__device__ __forceinline__ void emit_row(F value_at, int d, float* dst_f32, void* op, int R, int op_row,
-                                         const float* gain, float* ss /* [d/16][32] */) {
-    for (int c = threadIdx.x; c < d; c += blockDim.x) {
-        const float v = value_at(c);
-        if (dst_f32) dst_f32[c] = v;
-        if (op) {
-            store_operand<DT>(op, R, d, op_row, c, v * (gain ? gain[c] : 1.0f));
-            const float sq = sum16(v * v);
-            if ((c & 15) == 0) ss[(size_t)(c >> 4) * kMaxRows + op_row] = sq;
-        }
-    }
-}
-
 // ---- embedding gather: h_0 of each row, plus everything layer 0 consumes ------------------------------------------
+// Grid (rows, ceil(d / 256)): one column per thread, so the token -> table -> store chain is walked once.
 template <int DT>
 __global__ __launch_bounds__(256) void embed_kernel(const int32_t* tokens, const void* table, int vocab, int d,
                                                     float* h, void* op, int R, const float* gain, float* ss,
                                                     float* capture) {
-    const int row = blockIdx.x;
+    const int row = blockIdx.x, c = blockIdx.y * 256 + threadIdx.x;  // d % 16 == 0: a 16-column tile is all in or out
+    if (c >= d) return;
     int tok = tokens[row];
     tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
-    auto val = [&](int c) -> float {
-        if constexpr (DT == kDtBf16) return from_bf16(reinterpret_cast<const bf16*>(table)[(size_t)tok * d + c]);
-        else return reinterpret_cast<const float*>(table)[(size_t)tok * d + c];
-    };
-    emit_row<DT>(val, d, h + (size_t)row * d, op, R, row, gain, ss);
-    if (capture)
-        for (int c = threadIdx.x; c < d; c += blockDim.x) capture[(size_t)row * d + c] = val(c);
+    float v;
+    if constexpr (DT == kDtBf16) v = from_bf16(reinterpret_cast<const bf16*>(table)[(size_t)tok * d + c]);
+    else v = reinterpret_cast<const float*>(table)[(size_t)tok * d + c];
+    h[(size_t)row * d + c] = v;
+    if (capture) capture[(size_t)row * d + c] = v;
+    store_operand<DT>(op, R, d, row, c, v * (gain ? gain[c] : 1.0f));
+    const float sq = sum16(v * v);
+    if ((c & 15) == 0) ss[(size_t)(c >> 4) * kMaxRows + row] = sq;
 }
 
 // ---- install cache contents given as fp32 [T][n_kv][hd] -----------------------------------------------------------
@@ -249,7 +236,7 @@ __global__ void dp_backtrack_kernel(const uint8_t* choice, int L, int M, uint8_t
 }
 
 // ---- greedy head ----------------------------------------------------------------------------------------------
-// bf16 path: merges the per-tile pieces the lm_head epilogue left behind ([tiles][32] x (max, index, second max, sum of
+// bf16 path: merges the per-tile pieces the lm_head epilogue left behind ([32][tiles] x (max, index, second max, sum of
 // exp(logit - max))) into argmax (lowest index on ties), top-1 minus top-2 logit and the softmax probability of the
 // top-1. One workgroup per row.
 __global__ __launch_bounds__(1024) void head_reduce_kernel(const f32x4* parts, int n_tiles, int32_t* argmax_out,
@@ -272,7 +259,7 @@ __global__ __launch_bounds__(1024) void head_reduce_kernel(const f32x4* parts, i
         }
     };
     for (int t = threadIdx.x; t < n_tiles; t += blockDim.x) {
-        const f32x4 p = parts[(size_t)t * kMaxRows + row];
+        const f32x4 p = parts[(size_t)row * n_tiles + t];
         merge(v1, i1, v2, se, p[0], __float_as_int(p[1]), p[2], p[3]);
     }
     for (int o = 1; o < 64; o <<= 1) {
