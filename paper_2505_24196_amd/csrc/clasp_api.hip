@@ -62,13 +62,25 @@ namespace {
 #endif
 // the DP's down projection: K split over CLASP_DOWNP_KS workgroups per group of CLASP_DOWNP_CW column tiles
 #ifndef CLASP_DOWNP_CW
-#define CLASP_DOWNP_CW 4
+#define CLASP_DOWNP_CW 2
 #endif
 #ifndef CLASP_DOWNP_KW
-#define CLASP_DOWNP_KW 2
+#define CLASP_DOWNP_KW 4
 #endif
 #ifndef CLASP_DOWNP_KS
 #define CLASP_DOWNP_KS 4
+#endif
+#ifndef CLASP_QKV_NACC
+#define CLASP_QKV_NACC 1  // column tiles per wavefront in the several-row streaming kernel
+#endif
+#ifndef CLASP_OPROJ_NACC
+#define CLASP_OPROJ_NACC 1
+#endif
+#ifndef CLASP_DOWN_NACC
+#define CLASP_DOWN_NACC 1
+#endif
+#ifndef CLASP_DOWNP_NACC
+#define CLASP_DOWNP_NACC 2
 #endif
 #ifndef CLASP_GEMV_DEPTH
 #define CLASP_GEMV_DEPTH 4  // weight loads per register stage of the single-row kernel (deeper is slower: measured)
@@ -255,7 +267,7 @@ int launch_gemv(const GemmArgs& g, size_t lds, hipStream_t st) {
     return CLASP_OK;
 }
 
-template <int EPI, int CW, int KW>
+template <int EPI, int CW, int KW, int NACC = 1>
 int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kind) {
     const int tiles = g.N / 16;
     TimerScope timer(ctx, kind, st);
@@ -273,11 +285,14 @@ int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kin
         } else if (gemv_lds) {
             return launch_gemv<EPI, KWV>(g, gemv_lds, st);
         } else {
-            const dim3 grid((tiles + CW - 1) / CW);
-            if (g.R == 1)
-                hipLaunchKernelGGL((gemm_bf16_kernel<1, CW, KW, EPI, CLASP_STREAM_DEPTH, CLASP_ACT_SPLIT>), grid, dim3(CW * KW * 64), 0, st, g);
-            else
+            if (g.R == 1) {  // NACC tiles per wavefront share the activation fragments; the stage depth shrinks to match
+                const dim3 grid((tiles + CW * NACC - 1) / (CW * NACC));
+                hipLaunchKernelGGL((gemm_bf16_kernel<1, CW, KW, EPI, CLASP_STREAM_DEPTH / NACC, CLASP_ACT_SPLIT, NACC>), grid,
+                                   dim3(CW * KW * 64), 0, st, g);
+            } else {
+                const dim3 grid((tiles + CW - 1) / CW);
                 hipLaunchKernelGGL((gemm_bf16_kernel<2, CW, KW, EPI, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>), grid, dim3(CW * KW * 64), 0, st, g);
+            }
         }
     } else {
         if constexpr (EPI == kEpiQkv || EPI == kEpiHead || EPI == kEpiPartial) return CLASP_E_UNSUPPORTED;
@@ -383,7 +398,7 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
             o.k_cache = ctx->k_cache + (size_t)l * ctx->kv_layer_bytes;
             o.v_cache = ctx->v_cache + (size_t)l * ctx->kv_layer_bytes;
             o.k_self = ctx->k_self; o.v_self = ctx->v_self;
-            if ((rc = launch_gemm<kEpiQkv, CLASP_QKV_CW, CLASP_QKV_KW>(ctx, g, st, CLASP_KERNEL_QKV))) return rc;
+            if ((rc = launch_gemm<kEpiQkv, CLASP_QKV_CW, CLASP_QKV_KW, CLASP_QKV_NACC>(ctx, g, st, CLASP_KERNEL_QKV))) return rc;
         } else {
             if ((rc = launch_gemm<kEpiScale, 1, 1>(ctx, g, st, CLASP_KERNEL_QKV))) return rc;
         }
@@ -395,7 +410,7 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
         g.A = ctx->op_attn; g.n_rows = n; g.N = d; g.K = ctx->q_dim; g.R = R;
         g.out = ctx->a_buf; g.ldo = d; g.resid = h_in; g.ldr = d;
         g.next_op = ctx->op_a; g.next_gain = ctx->mlp_norm[l]; g.next_ss = ctx->ss_a;
-        if ((rc = launch_gemm<kEpiResid, CLASP_OPROJ_CW, CLASP_OPROJ_KW>(ctx, g, st, CLASP_KERNEL_O_PROJ))) return rc;
+        if ((rc = launch_gemm<kEpiResid, CLASP_OPROJ_CW, CLASP_OPROJ_KW, CLASP_OPROJ_NACC>(ctx, g, st, CLASP_KERNEL_O_PROJ))) return rc;
     }
     {
         GemmArgs g{};
@@ -418,8 +433,10 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
         TimerScope timer(ctx, CLASP_KERNEL_DOWN, st);
         const dim3 grid((d / 16 + CLASP_DOWNP_CW - 1) / CLASP_DOWNP_CW, down_split);
         if (R == 1)
-            hipLaunchKernelGGL((gemm_bf16_kernel<1, CLASP_DOWNP_CW, CLASP_DOWNP_KW, kEpiPartial, CLASP_STREAM_DEPTH, CLASP_ACT_SPLIT>),
-                               grid, dim3(CLASP_DOWNP_CW * CLASP_DOWNP_KW * 64), 0, st, g);
+            hipLaunchKernelGGL((gemm_bf16_kernel<1, CLASP_DOWNP_CW, CLASP_DOWNP_KW, kEpiPartial, CLASP_STREAM_DEPTH / CLASP_DOWNP_NACC,
+                                                 CLASP_ACT_SPLIT, CLASP_DOWNP_NACC>),
+                               dim3((d / 16 + CLASP_DOWNP_CW * CLASP_DOWNP_NACC - 1) / (CLASP_DOWNP_CW * CLASP_DOWNP_NACC), down_split),
+                               dim3(CLASP_DOWNP_CW * CLASP_DOWNP_KW * 64), 0, st, g);
         else
             hipLaunchKernelGGL((gemm_bf16_kernel<2, CLASP_DOWNP_CW, CLASP_DOWNP_KW, kEpiPartial, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>),
                                grid, dim3(CLASP_DOWNP_CW * CLASP_DOWNP_KW * 64), 0, st, g);
@@ -431,7 +448,7 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
         g.out = h_out; g.ldo = d; g.resid = ctx->a_buf; g.ldr = d;
         g.next_op = next_op; g.next_gain = next_gain; g.next_ss = next_ss;
         g.capture = capture; g.ldc = d;
-        if ((rc = launch_gemm<kEpiResid, CLASP_DOWN_CW, CLASP_DOWN_KW>(ctx, g, st, CLASP_KERNEL_DOWN))) return rc;
+        if ((rc = launch_gemm<kEpiResid, CLASP_DOWN_CW, CLASP_DOWN_KW, CLASP_DOWN_NACC>(ctx, g, st, CLASP_KERNEL_DOWN))) return rc;
     }
     return CLASP_OK;
 }
@@ -760,7 +777,7 @@ int clasp_dp_select(clasp_ctx* ctx, const float* states, size_t layer_stride, in
     if ((reinterpret_cast<uintptr_t>(states) & 15) || (layer_stride & 3)) return CLASP_E_INVALID_ARG;  // float4 loads
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int R = M > 16 ? 2 : 1;
-    const int down_split = (c.dtype == CLASP_BF16 && c.d_ffn / 32 >= CLASP_DOWNP_KS * CLASP_DOWNP_KW * 8) ? CLASP_DOWNP_KS : 1;
+    const int down_split = (c.dtype == CLASP_BF16 && c.d_ffn / 32 >= CLASP_DOWNP_KS * CLASP_DOWNP_KW * 4) ? CLASP_DOWNP_KS : 1;
     uint8_t* choice = choice_out ? choice_out : ctx->choice;
     const int cells = (L + 1) * (M + 1);
     hipLaunchKernelGGL(dp_table_init_kernel, dim3((cells + 255) / 256), dim3(256), 0, st, score_out, choice, cells);

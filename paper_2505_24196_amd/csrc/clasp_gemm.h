@@ -154,13 +154,13 @@ struct GemmStage {
 // never stored, and unconditional loads keep the load stream free of exec-mask merges, which would make every stage
 // wait for the previous one.
 template <int R, int NACC, int P, int SPLIT>
-__device__ __forceinline__ void gemm_issue(GemmStage<R, NACC, P, SPLIT>& st, const u32x4* w0, const u32x4* w1,
+__device__ __forceinline__ void gemm_issue(GemmStage<R, NACC, P, SPLIT>& st, const u32x4* const (&w)[NACC],
                                            const u32x4* const (&af)[R], int s, int ks1) {
 #pragma unroll
     for (int u = 0; u < P; ++u) {
         const int ss = min(s + u, ks1 - 1);
-        st.b[0][u] = load_stream(w0 + (size_t)ss * 64);
-        if constexpr (NACC == 2) st.b[1][u] = load_stream(w1 + (size_t)ss * 64);
+#pragma unroll
+        for (int a = 0; a < NACC; ++a) st.b[a][u] = load_stream(w[a] + (size_t)ss * 64);
 #pragma unroll
         for (int rg = 0; rg < R; ++rg)
 #pragma unroll
@@ -332,35 +332,39 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, int tile, int l
     }
 }
 
-// Workgroup = CW x KW wavefronts: wavefront (cw, kw) streams column tile blockIdx.x*CW + cw over k-slice kw of KW
-// equal slices. The CW wavefronts that share a k-slice read the same activation fragments at about the same time
-// (one L2 fetch, the rest hit in L1); the KW partial tiles of a column tile are summed through LDS in slice order.
+// Workgroup = CW x KW wavefronts: wavefront (cw, kw) streams NACC neighbouring column tiles, starting at tile
+// (blockIdx.x*CW + cw)*NACC, over k-slice kw of KW equal slices; with NACC = 2 one activation fragment feeds two weight
+// fragments, which halves the activation loads per weight byte. The CW wavefronts that share a k-slice read the same
+// activation fragments at about the same time (one L2 fetch, the rest hit in L1); the KW partial tiles of a column
+// tile are summed through LDS in slice order.
 // (Cross-workgroup split-K inside one kernel is not used: agent-scope release fences cost far more than they save
 // on this part, every one of them writes the whole L2 back.)
-template <int R, int CW, int KW, int EPI, int P, int SPLIT>
+template <int R, int CW, int KW, int EPI, int P, int SPLIT, int NACC = 1>
 __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
     constexpr int NW = CW * KW;
-    constexpr int NACC = 1;
     __shared__ f32x4 red[KW][CW][NACC][R][64];
     __shared__ float rstd_s[kMaxRows];
     __shared__ float tmp_s[NW * 64];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int cw = wave % CW, kw = wave / CW;
     const int n_tiles = g.N >> 4;
-    const int tile_raw = blockIdx.x * CW + cw;
-    const bool live = tile_raw < n_tiles;
-    const int tile = live ? tile_raw : n_tiles - 1;  // idle wavefronts shadow the last tile, their result is dropped
+    const int tile0 = (blockIdx.x * CW + cw) * NACC;
     const int KS = g.K >> 5;
     const int nslice = gridDim.y * KW, slice = blockIdx.y * KW + kw;  // gridDim.y > 1 only with kEpiPartial
     const int ks0 = (int)(((long long)KS * slice) / nslice), ks1 = (int)(((long long)KS * (slice + 1)) / nslice);
 
-    int mi = 0, tl = tile;
-    if constexpr (EPI == kEpiScale || EPI == kEpiQkv) {
-        if (tile >= g.tile_end[0]) { mi = 1; tl = tile - g.tile_end[0]; }
-        if (tile >= g.tile_end[1]) { mi = 2; tl = tile - g.tile_end[1]; }
+    int tile[NACC];
+    const u32x4* w[NACC];
+#pragma unroll
+    for (int a = 0; a < NACC; ++a) {
+        tile[a] = min(tile0 + a, n_tiles - 1);  // tiles beyond the last shadow it, their result is dropped
+        int mi = 0, tl = tile[a];
+        if constexpr (EPI == kEpiScale || EPI == kEpiQkv) {
+            if (tile[a] >= g.tile_end[0]) { mi = 1; tl = tile[a] - g.tile_end[0]; }
+            if (tile[a] >= g.tile_end[1]) { mi = 2; tl = tile[a] - g.tile_end[1]; }
+        }
+        w[a] = reinterpret_cast<const u32x4*>(g.W[mi]) + (size_t)tl * KS * 64 + lane;
     }
-    const u32x4* w0 = reinterpret_cast<const u32x4*>(g.W[mi]) + (size_t)tl * KS * 64 + lane;
-    const u32x4* w1 = (NACC == 2) ? reinterpret_cast<const u32x4*>(g.W[1]) + (size_t)tl * KS * 64 + lane : nullptr;
     const u32x4* af[R];
 #pragma unroll
     for (int rg = 0; rg < R; ++rg) {  // row of this lane, clamped to the last live row; may sit in an earlier group
@@ -376,21 +380,23 @@ __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
 
     GemmStage<R, NACC, P, SPLIT> st0, st1;
     int s = ks0;
-    if (s < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w0, w1, af, s, ks1);  // weights first: independent of rstd
+    if (s < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w, af, s, ks1);  // weights first: independent of rstd
 
-    EpiPre pre[R];
+    EpiPre pre[NACC][R];
     if (kw == 0) {
 #pragma unroll
-        for (int rg = 0; rg < R; ++rg) epi_prefetch<EPI>(g, tile, lane, rg, pre[rg]);
+        for (int a = 0; a < NACC; ++a)
+#pragma unroll
+            for (int rg = 0; rg < R; ++rg) epi_prefetch<EPI>(g, tile[a], lane, rg, pre[a][rg]);
     }
     if constexpr (EPI != kEpiResid && EPI != kEpiPartial) compute_rstd(g, rstd_s, tmp_s);
 
     while (s < ks1) {
-        if (s + P < ks1) gemm_issue<R, NACC, P, SPLIT>(st1, w0, w1, af, s + P, ks1);
+        if (s + P < ks1) gemm_issue<R, NACC, P, SPLIT>(st1, w, af, s + P, ks1);
         gemm_compute<R, NACC, P, SPLIT>(st0, acc, s, ks1);
         s += P;
         if (s >= ks1) break;
-        if (s + P < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w0, w1, af, s + P, ks1);
+        if (s + P < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w, af, s + P, ks1);
         gemm_compute<R, NACC, P, SPLIT>(st1, acc, s, ks1);
         s += P;
     }
@@ -418,14 +424,17 @@ __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
             for (int rg = 0; rg < R; ++rg) sum[a][rg] = acc[a][rg];
     }
 
-    if (kw != 0 || !live) return;
+    if (kw != 0) return;
 
 #pragma unroll
-    for (int rg = 0; rg < R; ++rg) {
-        f32x4 fin[NACC];
+    for (int a = 0; a < NACC; ++a) {
+        if (tile0 + a >= n_tiles) continue;
 #pragma unroll
-        for (int x = 0; x < NACC; ++x) fin[x] = sum[x][rg];
-        gemm_epilogue<EPI, NACC>(g, tile, lane, rg, fin, rstd_s, pre[rg]);
+        for (int rg = 0; rg < R; ++rg) {
+            f32x4 fin[1];
+            fin[0] = sum[a][rg];
+            gemm_epilogue<EPI, 1>(g, tile[a], lane, rg, fin, rstd_s, pre[a][rg]);
+        }
     }
 }
 
