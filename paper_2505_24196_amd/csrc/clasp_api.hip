@@ -82,6 +82,9 @@ namespace {
 #ifndef CLASP_DOWNP_NACC
 #define CLASP_DOWNP_NACC 2
 #endif
+#ifndef CLASP_ATTN_DEFER
+#define CLASP_ATTN_DEFER 1  // one-row launches: the output projection merges the attention's prefix splits
+#endif
 #ifndef CLASP_GEMV_DEPTH
 #define CLASP_GEMV_DEPTH 4  // weight loads per register stage of the single-row kernel (deeper is slower: measured)
 #endif
@@ -252,10 +255,10 @@ size_t gemv_lds_bytes(int K) {
     return lds <= kGemvMaxLds ? lds : 0;
 }
 
-template <int EPI, int KWV>
+template <int EPI, int KWV, int ASRC = 0>
 int launch_gemv(const GemmArgs& g, size_t lds, hipStream_t st) {
     static bool opted_in = false;  // more than 64 KiB of LDS per workgroup has to be requested once per kernel
-    auto kernel = gemv_bf16_kernel<KWV, EPI, CLASP_GEMV_DEPTH, CLASP_ACT_SPLIT>;
+    auto kernel = gemv_bf16_kernel<KWV, EPI, CLASP_GEMV_DEPTH, CLASP_ACT_SPLIT, ASRC>;
     if (!opted_in) {
         if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemvMaxLds) !=
             hipSuccess)
@@ -283,6 +286,9 @@ int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kin
             hipLaunchKernelGGL((gemm_bf16_resident_kernel<kResidentKSW, kResidentKW, EPI, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>),
                                dim3(grid), dim3(kResidentKW * 64), 0, st, g);
         } else if (gemv_lds) {
+            if constexpr (EPI == kEpiResid) {
+                if (g.attn_partial) return launch_gemv<EPI, KWV, 1>(g, gemv_lds, st);
+            }
             return launch_gemv<EPI, KWV>(g, gemv_lds, st);
         } else {
             if (g.R == 1) {  // NACC tiles per wavefront share the activation fragments; the stage depth shrinks to match
@@ -329,7 +335,22 @@ int launch_attn_bf16(const AttnArgs& a, bool short_prefix, int nt, dim3 grid, hi
     }
 }
 
-int launch_attention(const clasp_ctx* ctx, int layer, int n, int R, int mode, int pos0, hipStream_t st) {
+// Prefix splits of a one-row launch whose merge the output projection takes over (0 = merge here as usual): the
+// single-row projection kernel stages its input through LDS anyway and can merge up to kGemvMaxSplit pieces per
+// query while doing so, which saves the combine launch of long prefixes and lets short prefixes use several
+// workgroups per KV head (one workgroup cannot pull its 256 KiB at T = 512 faster than ~50 GB/s).
+int attn_deferred_splits(const clasp_ctx* ctx, int n, int R, int mode, int pos0) {
+    const clasp_config& c = ctx->cfg;
+    if (!CLASP_GEMV || !CLASP_ATTN_DEFER || c.dtype != CLASP_BF16 || n != 1 || R != 1 || c.head_dim % 8) return 0;
+    if (!gemv_lds_bytes<CLASP_GEMV_KW_RESID>(ctx->q_dim)) return 0;
+    const int nblk = (pos0 + (mode ? n : 0) + 31) / 32;
+    const int per = nblk <= CLASP_ATTN_SHORT_BLOCKS ? CLASP_ATTN_SHORT_WAVES : CLASP_ATTN_BLOCKS_PER_SPLIT;
+    const int split = (nblk + per - 1) / per;
+    return (split >= 2 && split <= kGemvMaxSplit) ? split : 0;
+}
+
+int launch_attention(const clasp_ctx* ctx, int layer, int n, int R, int mode, int pos0, hipStream_t st,
+                     int deferred_splits = 0) {
     const clasp_config& c = ctx->cfg;
     AttnArgs a{};
     a.qkv = ctx->qkv; a.ld_qkv = ctx->qkv_dim;
@@ -359,12 +380,13 @@ int launch_attention(const clasp_ctx* ctx, int layer, int n, int R, int mode, in
     const int nt = short_prefix ? 1 : (ntq < 4 ? ntq : 4), qgroups = (ntq + nt - 1) / nt;
     int split = short_prefix ? 1 : (nblk + CLASP_ATTN_BLOCKS_PER_SPLIT - 1) / CLASP_ATTN_BLOCKS_PER_SPLIT;
     split = split < 1 ? 1 : (split > kMaxSplit ? kMaxSplit : split);
+    if (deferred_splits) split = deferred_splits;
     a.n_split = split;
     const dim3 grid(c.n_kv_heads, qgroups, split);
     const int rc = c.head_dim == 64 ? launch_attn_bf16<64>(a, short_prefix, nt, grid, st)
                                     : launch_attn_bf16<128>(a, short_prefix, nt, grid, st);
     if (rc) return rc;
-    if (split > 1) {
+    if (split > 1 && !deferred_splits) {
         hipLaunchKernelGGL(attn_combine_kernel, dim3(c.n_kv_heads, nQ), dim3(c.head_dim), 0, st, a, nt, qgroups);
         CLASP_LAUNCH_CHECK();
     }
@@ -403,11 +425,15 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
             if ((rc = launch_gemm<kEpiScale, 1, 1>(ctx, g, st, CLASP_KERNEL_QKV))) return rc;
         }
     }
-    if ((rc = launch_attention(ctx, l, n, R, mode, pos0, st))) return rc;
+    const int deferred = attn_deferred_splits(ctx, n, R, mode, pos0);
+    if ((rc = launch_attention(ctx, l, n, R, mode, pos0, st, deferred))) return rc;
     {
         GemmArgs g{};
         g.W[0] = ctx->wo[l]; g.tile_end[0] = g.tile_end[1] = g.tile_end[2] = d / 16;
         g.A = ctx->op_attn; g.n_rows = n; g.N = d; g.K = ctx->q_dim; g.R = R;
+        if (deferred) {
+            g.attn_partial = ctx->attn_partial; g.attn_split = deferred; g.attn_group = ctx->group; g.attn_hd = c.head_dim;
+        }
         g.out = ctx->a_buf; g.ldo = d; g.resid = h_in; g.ldr = d;
         g.next_op = ctx->op_a; g.next_gain = ctx->mlp_norm[l]; g.next_ss = ctx->ss_a;
         if ((rc = launch_gemm<kEpiResid, CLASP_OPROJ_CW, CLASP_OPROJ_KW, CLASP_OPROJ_NACC>(ctx, g, st, CLASP_KERNEL_O_PROJ))) return rc;

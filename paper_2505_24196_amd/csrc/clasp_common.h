@@ -49,6 +49,7 @@ __device__ __forceinline__ bf16 to_bf16(float x) { return static_cast<bf16>(x); 
 __device__ __forceinline__ float from_bf16(bf16 x) { return static_cast<float>(x); }
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ __forceinline__ u32x4 as_u32x4(bf16x8 v) { return __builtin_bit_cast(u32x4, v); }
 
 // Streaming (no-reuse) 16-byte load: weights and KV are read once per launch, keep them out of the way of the
 // small activation working set that every workgroup re-reads from L2.

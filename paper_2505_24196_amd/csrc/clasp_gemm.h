@@ -65,6 +65,11 @@ struct GemmArgs {
     int ldc;
     QkvOut qkv;  // kEpiQkv only
     f32x4* head_parts;  // kEpiHead: [32][N/16] (max, index bits, second max, sum exp)
+    // single-row kernel fed by split attention (A unused): row 0's input features are the merged attention outputs,
+    // feature x belongs to head x / attn_hd; query j of KV head v left `attn_split` pieces
+    // (O^T[attn_hd], max, sum) at attn_partial + ((v * attn_split + s) * 16 + j) * (attn_hd + 2)
+    const float* attn_partial;
+    int attn_split, attn_group, attn_hd;
 };
 
 // (largest, index, second largest) of two disjoint sets; equal maxima keep the lower index.
@@ -445,8 +450,12 @@ __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
 // back with broadcast LDS reads, which run beside the weight stream instead of inside it. One column tile per
 // workgroup, KW wavefronts split K; the register stages hold weights only. `nks_max` = LDS k-steps reserved per
 // wavefront (>= ceil(K/32/KW), <= 16*kGemvLoads/SPLIT); dynamic LDS = KW * nks_max * SPLIT * 64 bytes.
+// ASRC = 1 (output projection of a draft step): the row is not read from an operand but merged here from the pieces
+// that split attention left per (KV head, prefix split, query): same arithmetic and order as attn_combine_kernel, so
+// the attention kernel needs neither a second launch nor a single workgroup per KV head.
 constexpr int kGemvLoads = 8;
-template <int KW, int EPI, int P, int SPLIT>
+constexpr int kGemvMaxSplit = 8;
+template <int KW, int EPI, int P, int SPLIT, int ASRC = 0>
 __global__ __launch_bounds__(KW * 64) void gemv_bf16_kernel(GemmArgs g, int nks_max) {
     extern __shared__ u32x4 a_lds[];
     __shared__ f32x4 red[KW][64];
@@ -473,25 +482,82 @@ __global__ __launch_bounds__(KW * 64) void gemv_bf16_kernel(GemmArgs g, int nks_
 
     // piece e of the slice = (k-step e / (4*SPLIT), plane (e / 4) % SPLIT, 16-byte quarter e % 4) of row 0
     const int n_el = nks * SPLIT * 4;
-    u32x4 av[kGemvLoads];
-    {
+    u32x4* mine = a_lds + (size_t)kw * nks_max * SPLIT * 4;
+    EpiPre pre;
+    float ssv[16];
+    if constexpr (ASRC == 0) {
+        u32x4 av[kGemvLoads];
         const u32x4* A = reinterpret_cast<const u32x4*>(g.A);
 #pragma unroll
         for (int i = 0; i < kGemvLoads; ++i) {
             const int e = min(lane + i * 64, max(n_el - 1, 0));
             av[i] = A[((size_t)(ks0 + e / (4 * SPLIT)) * 2 + (e / 4) % SPLIT) * 64 + (e & 3)];
         }
-    }
-    EpiPre pre;
-    if (kw == 0) epi_prefetch<EPI>(g, tile, lane, 0, pre);
-    float ssv[16];
-    if constexpr (kNeedsRstd) rstd_issue(g, ssv);
-    if (s + P < ks1) issue(wb[1], s + P);
-
-    u32x4* mine = a_lds + (size_t)kw * nks_max * SPLIT * 4;
+        if (kw == 0) epi_prefetch<EPI>(g, tile, lane, 0, pre);
+        if constexpr (kNeedsRstd) rstd_issue(g, ssv);
+        if (s + P < ks1) issue(wb[1], s + P);
 #pragma unroll
-    for (int i = 0; i < kGemvLoads; ++i)
-        if (lane + i * 64 < n_el) mine[lane + i * 64] = av[i];
+        for (int i = 0; i < kGemvLoads; ++i)
+            if (lane + i * 64 < n_el) mine[lane + i * 64] = av[i];
+    } else {
+        // (k-step, quarter) pp of the slice = 8 consecutive features of one head; lane takes pp = lane, lane + 64, ..
+        const int HD = g.attn_hd, S = g.attn_split;
+        const size_t sstride = (size_t)16 * (HD + 2);
+        struct Piece { float2 ml[kGemvMaxSplit], ov[kGemvMaxSplit][4]; };
+        auto fetch = [&](Piece& pc, int pp) {  // requests of the pieces that exist; nothing is added yet
+            const int x0 = (ks0 + (pp >> 2)) * 32 + (pp & 3) * 8, head = x0 / HD, e0 = x0 - head * HD;
+            const int kvh = head / g.attn_group, qi = head - kvh * g.attn_group;
+            const float* base = g.attn_partial + ((size_t)kvh * S * 16 + qi) * (HD + 2);
+#pragma unroll
+            for (int sp = 0; sp < kGemvMaxSplit; ++sp) {
+                if (sp < S) {
+                    pc.ml[sp] = *reinterpret_cast<const float2*>(base + sp * sstride + HD);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) pc.ov[sp][i] = reinterpret_cast<const float2*>(base + sp * sstride + e0)[i];
+                }
+            }
+        };
+        auto merge_store = [&](const Piece& pc, int pp) {  // attn_combine_kernel's arithmetic, then hi/lo into LDS
+            float mstar = -INFINITY;
+#pragma unroll
+            for (int sp = 0; sp < kGemvMaxSplit; ++sp)
+                if (sp < S) mstar = fmaxf(mstar, pc.ml[sp].x);
+            float L = 0.f, O[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) O[i] = 0.f;
+#pragma unroll
+            for (int sp = 0; sp < kGemvMaxSplit; ++sp) {
+                if (sp < S) {
+                    const float f = (pc.ml[sp].x == -INFINITY) ? 0.f : exp2f(pc.ml[sp].x - mstar);
+                    L += f * pc.ml[sp].y;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        O[2 * i] += f * pc.ov[sp][i].x;
+                        O[2 * i + 1] += f * pc.ov[sp][i].y;
+                    }
+                }
+            }
+            bf16x8 hi, lo;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float v = O[i] / L;
+                hi[i] = to_bf16(v);
+                lo[i] = to_bf16(v - from_bf16(hi[i]));
+            }
+            const int sl = pp >> 2, qq = pp & 3;
+            mine[(sl * SPLIT) * 4 + qq] = as_u32x4(hi);
+            if constexpr (SPLIT == 2) mine[(sl * SPLIT + 1) * 4 + qq] = as_u32x4(lo);
+        };
+        Piece pc;
+        if (lane < nks * 4) fetch(pc, lane);  // ahead of the second weight stage, like the operand loads above
+        if (kw == 0) epi_prefetch<EPI>(g, tile, lane, 0, pre);
+        if (s + P < ks1) issue(wb[1], s + P);
+        if (lane < nks * 4) merge_store(pc, lane);
+        for (int pp = lane + 64; pp < nks * 4; pp += 64) {
+            fetch(pc, pp);
+            merge_store(pc, pp);
+        }
+    }
     if constexpr (kNeedsRstd) rstd_stash(g, ssv, tmp_s);
     // the region is private to this wavefront and its LDS operations complete in program order
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");

@@ -206,6 +206,38 @@ def test_long_prefix_split_and_ragged_blocks(T):
     check_dp(om, eng, ost[:, 2], T + 2, c, 3)
 
 
+@pytest.mark.parametrize("name,T", [("small-bf16", 300), ("small-bf16", 700), ("small-bf16", 1500),
+                                    ("small-bf16-hd128", 2601)])
+def test_single_row_forward_over_long_prefix(name, T):
+    """One-row launches (draft steps, plain decoding) split the prefix over several workgroups per KV head and let
+    the output projection merge the pieces (2, 3, 2 and 3 pieces here); hidden states and the chained draft token are
+    compared with the oracle, and the row must agree with the same row inside a several-row launch."""
+    shape = si.SHAPES[name]
+    om, eng = oracle_model(name), engine(name, max_seq=2688)
+    K, V = si.gen_kv(shape, 4, shape.n_layers, T)
+    cache = oc.KVCache(shape, T + 8)
+    cache.load(K.numpy().astype(np.float64), V.numpy().astype(np.float64))
+    for l in range(shape.n_layers):
+        eng.clasp_kv_load(l, K[l], V[l])
+    toks = prompt(shape, 2, seed=6)
+    st, lg = om.token(toks[0], T, cache, want_states=True)
+    one = eng.clasp_verify_forward(dev(toks[:1], torch.int32), T, want_hidden=True, want_logits=True)
+    assert relerr(one["hidden"][:, 0].cpu().numpy(), st) <= HID_TOL["bf16"]
+    assert relerr(one["logits"][0].cpu().numpy(), lg) <= HID_TOL["bf16"]
+    two = eng.clasp_verify_forward(dev(toks, torch.int32), T, want_hidden=True)
+    # (the softmax weights enter the MFMA as bf16 and the two launches scale them against different running maxima)
+    assert relerr(one["hidden"][:, 0].cpu().numpy(), two["hidden"][:, 0].cpu().numpy()) <= 5e-3
+    # a draft step with a skip set at the next position
+    mask = np.zeros(shape.n_layers, dtype=np.uint8)
+    mask[1] = 1
+    nxt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    eng.clasp_draft_step(mask.tolist(), dev(toks[1:2], torch.int32), T + 1, nxt)
+    _, dl = om.token(toks[1], T + 1, cache, skip=mask)
+    ref_tok, ref_margin = oc.argmax_margin(dl)
+    if ref_margin > HID_TOL["bf16"] * np.abs(dl).max() * 2:
+        assert int(nxt) == ref_tok
+
+
 def test_two_row_groups_32_rows_and_budget_above_16():
     """max_rows = 32: a 32-row verify launch and a DP with M = 20 use two 16-row MFMA groups."""
     name = "small-bf16-deep"
