@@ -85,6 +85,12 @@ namespace {
 #ifndef CLASP_ATTN_DEFER
 #define CLASP_ATTN_DEFER 1  // one-row launches: the output projection merges the attention's prefix splits
 #endif
+#ifndef CLASP_R2_NACC
+#define CLASP_R2_NACC 4  // column tiles per wavefront when a launch has two 16-row groups
+#endif
+#ifndef CLASP_R2_DEPTH
+#define CLASP_R2_DEPTH 2  // k-steps per register stage of those launches
+#endif
 #ifndef CLASP_GEMV_DEPTH
 #define CLASP_GEMV_DEPTH 4  // weight loads per register stage of the single-row kernel (deeper is slower: measured)
 #endif
@@ -296,8 +302,9 @@ int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kin
                 hipLaunchKernelGGL((gemm_bf16_kernel<1, CW, KW, EPI, CLASP_STREAM_DEPTH / NACC, CLASP_ACT_SPLIT, NACC>), grid,
                                    dim3(CW * KW * 64), 0, st, g);
             } else {
-                const dim3 grid((tiles + CW - 1) / CW);
-                hipLaunchKernelGGL((gemm_bf16_kernel<2, CW, KW, EPI, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>), grid, dim3(CW * KW * 64), 0, st, g);
+                const dim3 grid((tiles + CW * CLASP_R2_NACC - 1) / (CW * CLASP_R2_NACC));
+                hipLaunchKernelGGL((gemm_bf16_kernel<2, CW, KW, EPI, CLASP_R2_DEPTH, CLASP_ACT_SPLIT, CLASP_R2_NACC>),
+                                   grid, dim3(CW * KW * 64), 0, st, g);
             }
         }
     } else {
@@ -464,8 +471,10 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
                                dim3((d / 16 + CLASP_DOWNP_CW * CLASP_DOWNP_NACC - 1) / (CLASP_DOWNP_CW * CLASP_DOWNP_NACC), down_split),
                                dim3(CLASP_DOWNP_CW * CLASP_DOWNP_KW * 64), 0, st, g);
         else
-            hipLaunchKernelGGL((gemm_bf16_kernel<2, CLASP_DOWNP_CW, CLASP_DOWNP_KW, kEpiPartial, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>),
-                               grid, dim3(CLASP_DOWNP_CW * CLASP_DOWNP_KW * 64), 0, st, g);
+            hipLaunchKernelGGL((gemm_bf16_kernel<2, CLASP_DOWNP_CW, CLASP_DOWNP_KW, kEpiPartial, CLASP_R2_DEPTH,
+                                                 CLASP_ACT_SPLIT, CLASP_R2_NACC>),
+                               dim3((d / 16 + CLASP_DOWNP_CW * CLASP_R2_NACC - 1) / (CLASP_DOWNP_CW * CLASP_R2_NACC), down_split),
+                               dim3(CLASP_DOWNP_CW * CLASP_DOWNP_KW * 64), 0, st, g);
         CLASP_LAUNCH_CHECK();
     } else {
         GemmArgs g{};
