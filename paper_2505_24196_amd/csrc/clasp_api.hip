@@ -91,6 +91,9 @@ namespace {
 #ifndef CLASP_R2_DEPTH
 #define CLASP_R2_DEPTH 2  // k-steps per register stage of those launches
 #endif
+#ifndef CLASP_ATTN_NT2_BLOCKS
+#define CLASP_ATTN_NT2_BLOCKS 512  // head_dim 128: prefixes from this many 32-key blocks on put two query tiles in a workgroup
+#endif
 #ifndef CLASP_GEMV_DEPTH
 #define CLASP_GEMV_DEPTH 4  // weight loads per register stage of the single-row kernel (deeper is slower: measured)
 #endif
@@ -384,8 +387,19 @@ int launch_attention(const clasp_ctx* ctx, int layer, int n, int R, int mode, in
     const int nQ = n * ctx->group, ntq = (nQ + 15) / 16;
     const int nblk = (pos0 + (mode ? n : 0) + 31) / 32;
     const bool short_prefix = nblk <= CLASP_ATTN_SHORT_BLOCKS;
-    const int nt = short_prefix ? 1 : (ntq < 4 ? ntq : 4), qgroups = (ntq + nt - 1) / nt;
+    // query tiles per workgroup: what the register file holds without spilling (O^T alone is head_dim/4 registers
+    // per tile); further tiles go to sibling workgroups, launched next to each other so that their key reads meet in L2
+    const int max_nt = c.head_dim > 64 ? (nblk >= CLASP_ATTN_NT2_BLOCKS ? 2 : 1) : 4;
+    const int nt = short_prefix ? 1 : (ntq < max_nt ? ntq : max_nt), qgroups = (ntq + nt - 1) / nt;
     int split = short_prefix ? 1 : (nblk + CLASP_ATTN_BLOCKS_PER_SPLIT - 1) / CLASP_ATTN_BLOCKS_PER_SPLIT;
+    {   // a CU holds one of these workgroups: a launch a little above a whole number of rounds would leave most CUs
+        // idle for its last round, so the split count is trimmed to fill whole rounds
+        const int per_split = c.n_kv_heads * qgroups, wgs = per_split * split;
+        if (wgs > ctx->n_cu) {
+            const int rounds = (wgs + ctx->n_cu / 2) / ctx->n_cu, trimmed = rounds * ctx->n_cu / per_split;
+            if (trimmed >= 1 && trimmed < split) split = trimmed;
+        }
+    }
     split = split < 1 ? 1 : (split > kMaxSplit ? kMaxSplit : split);
     if (deferred_splits) split = deferred_splits;
     a.n_split = split;

@@ -40,6 +40,10 @@ struct AttnArgs {
     const void* v_self;
 };
 
+#ifndef CLASP_ATTN_DOUBLE_NT
+#define CLASP_ATTN_DOUBLE_NT 1  // query tiles up to which a workgroup keeps two whole fragment sets
+#endif
+
 constexpr float kLog2e = 1.4426950408889634f;
 
 template <int HD, int NT>
@@ -67,14 +71,16 @@ __device__ __forceinline__ void attn_load(AttnFrags<HD>& f, KF kf, VF vf) {
     for (int c = 0; c < HD / 16; ++c) f.v[c] = vf(c);
 }
 
-// One 32-key block: scores for NT query tiles, online softmax update, O^T accumulation.
+// One 32-key block in two steps, so that a pipelined loop can re-use the key registers for the next block's keys as
+// soon as the scores exist, and the value registers as soon as the block is accumulated.
+// attn_scores: S^T = K Q^T for NT query tiles, online softmax update (running max / sum, rescaling of O^T), leaves the
+//              exponentiated scores as the B fragments pf[t] of the second product.
 //   valid(u, r, t) -> whether key (lane/16)*8 + u*4 + r of the block is visible to query t*16 + lane%16
+// attn_pv:     O^T += V^T P^T.
 template <int HD, int NT, class VALID>
-__device__ __forceinline__ void attn_compute(AttnState<HD, NT>& st, const bf16x8 (&qf)[NT][HD / 32],
-                                             const AttnFrags<HD>& f, VALID valid) {
+__device__ __forceinline__ void attn_scores(AttnState<HD, NT>& st, const bf16x8 (&qf)[NT][HD / 32],
+                                            const bf16x8 (&kfr)[2][HD / 32], VALID valid, bf16x8 (&pf)[NT]) {
     constexpr int KK = HD / 32, CT = HD / 16;
-    const bf16x8 (&kfr)[2][KK] = f.k;
-    const bf16x8 (&vfr)[CT] = f.v;
     f32x4 s[2][NT];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
@@ -87,7 +93,6 @@ __device__ __forceinline__ void attn_compute(AttnState<HD, NT>& st, const bf16x8
                 s[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr[u][kk], qf[t][kk], s[u][t], 0, 0, 0);
         }
     }
-    bf16x8 pf[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         float mx = -INFINITY;
@@ -117,12 +122,24 @@ __device__ __forceinline__ void attn_compute(AttnState<HD, NT>& st, const bf16x8
 #pragma unroll
         for (int c = 0; c < CT; ++c) st.o[t][c] *= alpha;
     }
+}
+
+template <int HD, int NT>
+__device__ __forceinline__ void attn_pv(AttnState<HD, NT>& st, const bf16x8 (&vfr)[HD / 16], const bf16x8 (&pf)[NT]) {
 #pragma unroll
-    for (int c = 0; c < CT; ++c) {
+    for (int c = 0; c < HD / 16; ++c) {
 #pragma unroll
         for (int t = 0; t < NT; ++t)
             st.o[t][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vfr[c], pf[t], st.o[t][c], 0, 0, 0);
     }
+}
+
+template <int HD, int NT, class VALID>
+__device__ __forceinline__ void attn_compute(AttnState<HD, NT>& st, const bf16x8 (&qf)[NT][HD / 32],
+                                             const AttnFrags<HD>& f, VALID valid) {
+    bf16x8 pf[NT];
+    attn_scores<HD, NT>(st, qf, f.k, valid, pf);
+    attn_pv<HD, NT>(st, f.v, pf);
 }
 
 // q_frag: queries of one KV head (query index qi = row*group + head%group) as MFMA B fragments,
@@ -187,7 +204,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(AttnArgs a) {
         attn_compute<HD, NT>(st, qf, f, [&](int u, int r, int t) { return kb + q4 * 8 + u * 4 + r <= limit[t]; });
     };
     int blk = b0 + wave;
-    if constexpr (NT <= 2) {  // registers allow a second fragment set: the next block is in flight during the MFMAs
+    if constexpr (NT <= CLASP_ATTN_DOUBLE_NT) {  // registers allow a second fragment set: the next block is in flight during the MFMAs
         AttnFrags<HD> f0, f1;
         if (blk < b1) load_blk(f0, blk);
         while (blk < b1) {
@@ -200,10 +217,32 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(AttnArgs a) {
             blk += NW;
         }
     } else {
+        // one fragment set, re-used in flight: the next block's keys are requested as soon as this block's scores
+        // exist (they land during the softmax and the second product), its values as soon as the block is accumulated
         AttnFrags<HD> f;
+        auto load_k = [&](int b) {
+            const u32x4* kp = Kh + (size_t)b * (2 * KK * 64);
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int kk = 0; kk < KK; ++kk) f.k[u][kk] = as_bf16x8(load_stream(kp + (u * KK + kk) * 64));
+        };
+        auto load_v = [&](int b) {
+            const u32x4* vp = Vh + (size_t)b * (CT * 64);
+#pragma unroll
+            for (int c = 0; c < CT; ++c) f.v[c] = as_bf16x8(load_stream(vp + c * 64));
+        };
+        if (blk < b1) {
+            load_k(blk);
+            load_v(blk);
+        }
         for (; blk < b1; blk += NW) {
-            load_blk(f, blk);
-            compute_blk(f, blk);
+            const int kb = blk << 5;
+            bf16x8 pf[NT];
+            attn_scores<HD, NT>(st, qf, f.k, [&](int u, int r, int t) { return kb + q4 * 8 + u * 4 + r <= limit[t]; }, pf);
+            if (blk + NW < b1) load_k(blk + NW);
+            attn_pv<HD, NT>(st, f.v, pf);
+            if (blk + NW < b1) load_v(blk + NW);
         }
     }
     if (!a.mode && split == a.n_split - 1 && wave == (b1 - b0) % NW) {  // DP candidates: own key/value only
