@@ -152,9 +152,11 @@ __global__ __launch_bounds__(1024) void dp_select_kernel(SelectArgs a) {
         return v;
     };
     float acc[5] = {0.f, 0.f, 0.f, 0.f, 0.f};  // x.x, s.x, s.s, c.x, c.c
+    f32x4 s_first = f32x4{0.f, 0.f, 0.f, 0.f}, g_first = s_first;  // the thread's first chunk stays in registers
     for (int c = threadIdx.x; c < d / 4; c += blockDim.x) {
         const f32x4 x = x4[c], s = skip4[c];
         const f32x4 g = has_comp ? load_comp(c) : f32x4{0.f, 0.f, 0.f, 0.f};
+        if (c == (int)threadIdx.x) { s_first = s; g_first = g; }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             acc[0] = fmaf(x[e], x[e], acc[0]);
@@ -191,7 +193,7 @@ __global__ __launch_bounds__(1024) void dp_select_kernel(SelectArgs a) {
     }
     const f32x4* gain4 = reinterpret_cast<const f32x4*>(a.gain);
     for (int c = threadIdx.x; c < d / 4; c += blockDim.x) {
-        const f32x4 v = keep_comp ? load_comp(c) : skip4[c];
+        const f32x4 v = c == (int)threadIdx.x ? (keep_comp ? g_first : s_first) : (keep_comp ? load_comp(c) : skip4[c]);
         reinterpret_cast<f32x4*>(dst)[c] = v;
         if (a.op) {
             const f32x4 gn = gain4 ? gain4[c] : f32x4{1.f, 1.f, 1.f, 1.f};
