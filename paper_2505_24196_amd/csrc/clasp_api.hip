@@ -21,14 +21,18 @@ using namespace clasp;
 
 namespace {
 
-// Launch shapes of the bf16 GEMMs, per projection: a workgroup has CW x KW wavefronts (CW column tiles that share
-// their activation fragments, KW slices of K reduced through LDS). P = fragments per register stage (two stages in
-// flight).
+// Tuning constants (each can be overridden on the compiler command line for sweeps; the values are the measured best
+// on MI355X at the LLaMA-3-8B and -70B shapes).
+// --- several-row streaming GEMM: a workgroup has CW x KW wavefronts (CW column-tile groups that share their activation
+//     fragments, KW slices of K reduced through LDS); NACC = column tiles per wavefront
 #ifndef CLASP_QKV_CW
 #define CLASP_QKV_CW 1
 #endif
 #ifndef CLASP_QKV_KW
 #define CLASP_QKV_KW 4
+#endif
+#ifndef CLASP_QKV_NACC
+#define CLASP_QKV_NACC 1
 #endif
 #ifndef CLASP_OPROJ_CW
 #define CLASP_OPROJ_CW 1
@@ -36,8 +40,11 @@ namespace {
 #ifndef CLASP_OPROJ_KW
 #define CLASP_OPROJ_KW 8
 #endif
+#ifndef CLASP_OPROJ_NACC
+#define CLASP_OPROJ_NACC 1
+#endif
 #ifndef CLASP_GATEUP_CW
-#define CLASP_GATEUP_CW 4
+#define CLASP_GATEUP_CW 4  // gate|up and lm_head only take this kernel when they have no more tiles than the GPU has CUs
 #endif
 #ifndef CLASP_GATEUP_KW
 #define CLASP_GATEUP_KW 2
@@ -48,19 +55,17 @@ namespace {
 #ifndef CLASP_DOWN_KW
 #define CLASP_DOWN_KW 8
 #endif
+#ifndef CLASP_DOWN_NACC
+#define CLASP_DOWN_NACC 1
+#endif
 #ifndef CLASP_HEAD_CW
 #define CLASP_HEAD_CW 4
 #endif
 #ifndef CLASP_HEAD_KW
 #define CLASP_HEAD_KW 2
 #endif
-#ifndef CLASP_STREAM_DEPTH
-#define CLASP_STREAM_DEPTH 8  // streaming kernel with one row group
-#endif
-#ifndef CLASP_GEMM_DEPTH
-#define CLASP_GEMM_DEPTH 4
-#endif
-// the DP's down projection: K split over CLASP_DOWNP_KS workgroups per group of CLASP_DOWNP_CW column tiles
+// the DP's down projection: K split over CLASP_DOWNP_KS workgroups per group of column tiles, slices added by the
+// select kernel
 #ifndef CLASP_DOWNP_CW
 #define CLASP_DOWNP_CW 2
 #endif
@@ -70,32 +75,32 @@ namespace {
 #ifndef CLASP_DOWNP_KS
 #define CLASP_DOWNP_KS 4
 #endif
-#ifndef CLASP_QKV_NACC
-#define CLASP_QKV_NACC 1  // column tiles per wavefront in the several-row streaming kernel
-#endif
-#ifndef CLASP_OPROJ_NACC
-#define CLASP_OPROJ_NACC 1
-#endif
-#ifndef CLASP_DOWN_NACC
-#define CLASP_DOWN_NACC 1
-#endif
 #ifndef CLASP_DOWNP_NACC
 #define CLASP_DOWNP_NACC 2
 #endif
-#ifndef CLASP_ATTN_DEFER
-#define CLASP_ATTN_DEFER 1  // one-row launches: the output projection merges the attention's prefix splits
-#endif
+// launches with two 16-row groups (17..32 rows): four activation loads per k-step, shared by this many column tiles
 #ifndef CLASP_R2_NACC
-#define CLASP_R2_NACC 4  // column tiles per wavefront when a launch has two 16-row groups
+#define CLASP_R2_NACC 4
 #endif
 #ifndef CLASP_R2_DEPTH
 #define CLASP_R2_DEPTH 2  // k-steps per register stage of those launches
 #endif
-#ifndef CLASP_ATTN_NT2_BLOCKS
-#define CLASP_ATTN_NT2_BLOCKS 512  // head_dim 128: prefixes from this many 32-key blocks on put two query tiles in a workgroup
+// k-steps per register stage (two stages in flight)
+#ifndef CLASP_STREAM_DEPTH
+#define CLASP_STREAM_DEPTH 8  // several-row streaming kernel, one row group
+#endif
+#ifndef CLASP_GEMM_DEPTH
+#define CLASP_GEMM_DEPTH 4  // resident-activation kernel
+#endif
+#ifndef CLASP_ACT_SPLIT
+#define CLASP_ACT_SPLIT 2  // 2: activations enter the MFMAs as bf16 hi + lo; 1: hi only
+#endif
+// --- single-row kernel (draft steps, plain decoding)
+#ifndef CLASP_GEMV
+#define CLASP_GEMV 1  // 0: single-row launches take the several-row kernel
 #endif
 #ifndef CLASP_GEMV_DEPTH
-#define CLASP_GEMV_DEPTH 4  // weight loads per register stage of the single-row kernel (deeper is slower: measured)
+#define CLASP_GEMV_DEPTH 4  // more loads in flight than HBM latency x bandwidth needs only queue (16 is 5 % slower)
 #endif
 #ifndef CLASP_GEMV_KW_QKV
 #define CLASP_GEMV_KW_QKV 8
@@ -103,11 +108,9 @@ namespace {
 #ifndef CLASP_GEMV_KW_RESID
 #define CLASP_GEMV_KW_RESID 8
 #endif
-#ifndef CLASP_GEMV
-#define CLASP_GEMV 1  // single-row launches (draft steps) take the LDS-staged kernel
-#endif
-#ifndef CLASP_ACT_SPLIT
-#define CLASP_ACT_SPLIT 2  // 2: activations enter the MFMAs as bf16 hi + lo; 1: hi only
+// --- attention
+#ifndef CLASP_ATTN_DEFER
+#define CLASP_ATTN_DEFER 1  // one-row launches: the output projection merges the attention's prefix splits
 #endif
 #ifndef CLASP_ATTN_SHORT_WAVES
 #define CLASP_ATTN_SHORT_WAVES 8
@@ -115,10 +118,13 @@ namespace {
 #ifndef CLASP_ATTN_SHORT_BLOCKS
 #define CLASP_ATTN_SHORT_BLOCKS 40  // prefixes of up to this many 32-key blocks take the latency-oriented launch
 #endif
-constexpr int kMaxSplit = 64;   // most workgroups that share one KV head's prefix
 #ifndef CLASP_ATTN_BLOCKS_PER_SPLIT
 #define CLASP_ATTN_BLOCKS_PER_SPLIT 32  // 32-key blocks per workgroup before the prefix is split further
 #endif
+#ifndef CLASP_ATTN_NT2_BLOCKS
+#define CLASP_ATTN_NT2_BLOCKS 512  // head_dim 128: from this many blocks on a workgroup takes two query tiles
+#endif
+constexpr int kMaxSplit = 64;  // most workgroups that share one KV head's prefix
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
