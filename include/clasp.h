@@ -177,9 +177,10 @@ int clasp_spec_accept(clasp_ctx *ctx, const float *p_logits, const float *q_logi
  * (and for tests that feed synthetic cache contents). */
 int clasp_kv_load(clasp_ctx *ctx, int layer, const float *K, const float *V, int n_tokens, void *stream);
 
-/* Measurement aid: between begin and end, every `every`-th launch of the chosen kernel kind inside the three calls
- * above is bracketed by a pair of HIP events on the call's stream (up to `capacity` launches; host-side event objects
- * only; each pair costs the stream a few microseconds, hence the sampling). clasp_kernel_timer_end waits for them and
+/* Measurement aid: between begin and end, every `every`-th launch of the chosen kernel kind inside the calls above
+ * gets a pair of HIP events (up to `capacity` launches; host-side event objects only). The GEMM kinds attach the pair
+ * to the launch itself, so it holds the kernel's own begin and end time stamps; attention (which may be two launches)
+ * is bracketed by two recorded events, which adds a few microseconds. clasp_kernel_timer_end waits for the events and
  * returns the summed elapsed time and the number of launches timed. */
 enum {
     CLASP_KERNEL_QKV = 0,      /* RMSNorm-scaled q/k/v projection                      */

@@ -4,6 +4,7 @@
 #include "../../include/clasp.h"
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <cmath>
@@ -236,20 +237,36 @@ int check_config(const clasp_config* c) {
         if (hipGetLastError() != hipSuccess) return CLASP_E_HIP; \
     } while (0)
 
-// ---- per-kernel timer: brackets the launches of one kernel kind with event pairs ------------------------------
+// ---- per-kernel timer ----------------------------------------------------------------------------------------------
+// Every `timer_every`-th launch of the chosen kernel kind gets an event pair. Where a scope holds exactly one launch
+// the pair is attached to the launch itself (launch_timed: the events then carry the kernel's own begin and end time
+// stamps, no extra packets on the stream); a scope with several launches is bracketed by two recorded events.
 struct TimerScope {
     clasp_ctx* ctx;
     hipStream_t st;
-    bool on;
-    TimerScope(const clasp_ctx* c, int kind, hipStream_t s) : ctx(const_cast<clasp_ctx*>(c)), st(s) {
+    bool on, bracket;
+    TimerScope(const clasp_ctx* c, int kind, hipStream_t s, bool bracket_launches)
+        : ctx(const_cast<clasp_ctx*>(c)), st(s), bracket(bracket_launches) {
         on = ctx->timer_kind == kind && ctx->timer_used < ctx->timer_start.size() &&
              (ctx->timer_seen++ % ctx->timer_every) == 0;
-        if (on) (void)hipEventRecord(ctx->timer_start[ctx->timer_used], st);
+        if (on && bracket) (void)hipEventRecord(start(), st);
     }
+    hipEvent_t start() const { return ctx->timer_start[ctx->timer_used]; }
+    hipEvent_t stop() const { return ctx->timer_stop[ctx->timer_used]; }
     ~TimerScope() {
-        if (on) (void)hipEventRecord(ctx->timer_stop[ctx->timer_used++], st);
+        if (!on) return;
+        if (bracket) (void)hipEventRecord(stop(), st);
+        ++ctx->timer_used;
     }
 };
+
+template <class K, class... Args>
+void launch_timed(const TimerScope& t, K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, Args... args) {
+    if (t.on && !t.bracket)
+        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, st, t.start(), t.stop(), 0, args...);
+    else
+        hipLaunchKernelGGL(kernel, grid, block, lds, st, args...);
+}
 
 // ---- GEMM dispatch ---------------------------------------------------------------------------------------------
 // Which projections may use the resident-activation kernel (bit = CLASP_KERNEL_* kind) when it applies (one row group
@@ -271,7 +288,7 @@ size_t gemv_lds_bytes(int K) {
 }
 
 template <int EPI, int KWV, int ASRC = 0>
-int launch_gemv(const GemmArgs& g, size_t lds, hipStream_t st) {
+int launch_gemv(const TimerScope& timer, const GemmArgs& g, size_t lds, hipStream_t st) {
     static bool opted_in = false;  // more than 64 KiB of LDS per workgroup has to be requested once per kernel
     auto kernel = gemv_bf16_kernel<KWV, EPI, CLASP_GEMV_DEPTH, CLASP_ACT_SPLIT, ASRC>;
     if (!opted_in) {
@@ -280,7 +297,7 @@ int launch_gemv(const GemmArgs& g, size_t lds, hipStream_t st) {
             return CLASP_E_HIP;
         opted_in = true;
     }
-    hipLaunchKernelGGL(kernel, dim3(g.N / 16), dim3(KWV * 64), lds, st, g, (g.K / 32 + KWV - 1) / KWV);
+    launch_timed(timer, kernel, dim3(g.N / 16), dim3(KWV * 64), lds, st, g, (g.K / 32 + KWV - 1) / KWV);
     CLASP_LAUNCH_CHECK();
     return CLASP_OK;
 }
@@ -288,7 +305,7 @@ int launch_gemv(const GemmArgs& g, size_t lds, hipStream_t st) {
 template <int EPI, int CW, int KW, int NACC = 1>
 int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kind) {
     const int tiles = g.N / 16;
-    TimerScope timer(ctx, kind, st);
+    TimerScope timer(ctx, kind, st, false);
     if (ctx->cfg.dtype == CLASP_BF16) {
         const bool resident = g.R == 1 && ((CLASP_RESIDENT_MASK >> kind) & 1) &&
                               (g.K / 32 + kResidentKW - 1) / kResidentKW <= kResidentKSW && tiles > ctx->n_cu;
@@ -298,27 +315,27 @@ int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kin
         if (resident) {
             // every workgroup takes the same number of tiles (+-1): rounds = ceil(tiles / CUs), grid = ceil(tiles / rounds)
             const int rounds = (tiles + ctx->n_cu - 1) / ctx->n_cu, grid = (tiles + rounds - 1) / rounds;
-            hipLaunchKernelGGL((gemm_bf16_resident_kernel<kResidentKSW, kResidentKW, EPI, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>),
-                               dim3(grid), dim3(kResidentKW * 64), 0, st, g);
+            launch_timed(timer, gemm_bf16_resident_kernel<kResidentKSW, kResidentKW, EPI, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>,
+                         dim3(grid), dim3(kResidentKW * 64), 0, st, g);
         } else if (gemv_lds) {
             if constexpr (EPI == kEpiResid) {
-                if (g.attn_partial) return launch_gemv<EPI, KWV, 1>(g, gemv_lds, st);
+                if (g.attn_partial) return launch_gemv<EPI, KWV, 1>(timer, g, gemv_lds, st);
             }
-            return launch_gemv<EPI, KWV>(g, gemv_lds, st);
+            return launch_gemv<EPI, KWV>(timer, g, gemv_lds, st);
         } else {
             if (g.R == 1) {  // NACC tiles per wavefront share the activation fragments; the stage depth shrinks to match
                 const dim3 grid((tiles + CW * NACC - 1) / (CW * NACC));
-                hipLaunchKernelGGL((gemm_bf16_kernel<1, CW, KW, EPI, CLASP_STREAM_DEPTH / NACC, CLASP_ACT_SPLIT, NACC>), grid,
-                                   dim3(CW * KW * 64), 0, st, g);
+                launch_timed(timer, gemm_bf16_kernel<1, CW, KW, EPI, CLASP_STREAM_DEPTH / NACC, CLASP_ACT_SPLIT, NACC>, grid,
+                             dim3(CW * KW * 64), 0, st, g);
             } else {
                 const dim3 grid((tiles + CW * CLASP_R2_NACC - 1) / (CW * CLASP_R2_NACC));
-                hipLaunchKernelGGL((gemm_bf16_kernel<2, CW, KW, EPI, CLASP_R2_DEPTH, CLASP_ACT_SPLIT, CLASP_R2_NACC>),
-                                   grid, dim3(CW * KW * 64), 0, st, g);
+                launch_timed(timer, gemm_bf16_kernel<2, CW, KW, EPI, CLASP_R2_DEPTH, CLASP_ACT_SPLIT, CLASP_R2_NACC>, grid,
+                             dim3(CW * KW * 64), 0, st, g);
             }
         }
     } else {
         if constexpr (EPI == kEpiQkv || EPI == kEpiHead || EPI == kEpiPartial) return CLASP_E_UNSUPPORTED;
-        else hipLaunchKernelGGL((gemm_f32_kernel<EPI>), dim3(tiles), dim3(256), 0, st, g);
+        else launch_timed(timer, gemm_f32_kernel<EPI>, dim3(tiles), dim3(256), 0, st, g);
     }
     CLASP_LAUNCH_CHECK();
     return CLASP_OK;
@@ -379,7 +396,7 @@ int launch_attention(const clasp_ctx* ctx, int layer, int n, int R, int mode, in
     a.scale = 1.0f / sqrtf((float)c.head_dim);
     a.q_frag = ctx->q_frag; a.k_self = ctx->k_self; a.v_self = ctx->v_self;
     a.n_split = 1;
-    TimerScope timer(ctx, CLASP_KERNEL_ATTENTION, st);
+    TimerScope timer(ctx, CLASP_KERNEL_ATTENTION, st, true);
     if (c.dtype == CLASP_F32) {
         const size_t lds = (size_t)(c.head_dim + pos0 + 32) * sizeof(float);
         hipLaunchKernelGGL(attn_f32_kernel, dim3(c.n_heads, n), dim3(256), lds, st, a);
@@ -483,18 +500,18 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
         g.W[0] = ctx->w_down[l]; g.tile_end[0] = g.tile_end[1] = g.tile_end[2] = d / 16;
         g.A = ctx->op_act; g.n_rows = n; g.N = d; g.K = F; g.R = R;
         g.out = ctx->down_parts; g.ldo = d; g.ldr = kMaxRows * d;
-        TimerScope timer(ctx, CLASP_KERNEL_DOWN, st);
-        const dim3 grid((d / 16 + CLASP_DOWNP_CW - 1) / CLASP_DOWNP_CW, down_split);
+        TimerScope timer(ctx, CLASP_KERNEL_DOWN, st, false);
+        const dim3 block(CLASP_DOWNP_CW * CLASP_DOWNP_KW * 64);
         if (R == 1)
-            hipLaunchKernelGGL((gemm_bf16_kernel<1, CLASP_DOWNP_CW, CLASP_DOWNP_KW, kEpiPartial, CLASP_STREAM_DEPTH / CLASP_DOWNP_NACC,
-                                                 CLASP_ACT_SPLIT, CLASP_DOWNP_NACC>),
-                               dim3((d / 16 + CLASP_DOWNP_CW * CLASP_DOWNP_NACC - 1) / (CLASP_DOWNP_CW * CLASP_DOWNP_NACC), down_split),
-                               dim3(CLASP_DOWNP_CW * CLASP_DOWNP_KW * 64), 0, st, g);
+            launch_timed(timer, gemm_bf16_kernel<1, CLASP_DOWNP_CW, CLASP_DOWNP_KW, kEpiPartial,
+                                                 CLASP_STREAM_DEPTH / CLASP_DOWNP_NACC, CLASP_ACT_SPLIT, CLASP_DOWNP_NACC>,
+                         dim3((d / 16 + CLASP_DOWNP_CW * CLASP_DOWNP_NACC - 1) / (CLASP_DOWNP_CW * CLASP_DOWNP_NACC), down_split),
+                         block, 0, st, g);
         else
-            hipLaunchKernelGGL((gemm_bf16_kernel<2, CLASP_DOWNP_CW, CLASP_DOWNP_KW, kEpiPartial, CLASP_R2_DEPTH,
-                                                 CLASP_ACT_SPLIT, CLASP_R2_NACC>),
-                               dim3((d / 16 + CLASP_DOWNP_CW * CLASP_R2_NACC - 1) / (CLASP_DOWNP_CW * CLASP_R2_NACC), down_split),
-                               dim3(CLASP_DOWNP_CW * CLASP_DOWNP_KW * 64), 0, st, g);
+            launch_timed(timer, gemm_bf16_kernel<2, CLASP_DOWNP_CW, CLASP_DOWNP_KW, kEpiPartial, CLASP_R2_DEPTH,
+                                                 CLASP_ACT_SPLIT, CLASP_R2_NACC>,
+                         dim3((d / 16 + CLASP_DOWNP_CW * CLASP_R2_NACC - 1) / (CLASP_DOWNP_CW * CLASP_R2_NACC), down_split),
+                         block, 0, st, g);
         CLASP_LAUNCH_CHECK();
     } else {
         GemmArgs g{};
