@@ -312,7 +312,7 @@ int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kin
         constexpr int KWV = EPI == kEpiQkv ? CLASP_GEMV_KW_QKV : (EPI == kEpiResid ? CLASP_GEMV_KW_RESID : 8);
         const size_t gemv_lds =
             (CLASP_GEMV && g.n_rows == 1 && g.R == 1 && EPI != kEpiPartial) ? gemv_lds_bytes<KWV>(g.K) : 0;
-        if (resident) {
+        if (resident && !(gemv_lds && kind == CLASP_KERNEL_LM_HEAD)) {  // one-row lm_head: the single-row kernel is 3 % faster
             // every workgroup takes the same number of tiles (+-1): rounds = ceil(tiles / CUs), grid = ceil(tiles / rounds)
             const int rounds = (tiles + ctx->n_cu - 1) / ctx->n_cu, grid = (tiles + rounds - 1) / rounds;
             launch_timed(timer, gemm_bf16_resident_kernel<kResidentKSW, kResidentKW, EPI, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>,
