@@ -570,6 +570,27 @@ int run_head(const clasp_ctx* ctx, int n, int R, float* logits_out, int32_t* arg
     return CLASP_OK;
 }
 
+// The layers a skip set keeps on one row at position `pos`, then the head: greedy token (+ top-1 probability) and / or
+// the logits.
+int draft_forward(clasp_ctx* ctx, const uint8_t* mask, const int32_t* token, int pos, float* logits_out,
+                         int32_t* argmax_out, float* top1_prob_out, hipStream_t st) {
+    const clasp_config& c = ctx->cfg;
+    const int L = c.n_layers;
+    std::vector<int> kept;
+    for (int l = 0; l < L; ++l)
+        if (!mask || !mask[l]) kept.push_back(l);
+    int rc;
+    const float* gain0 = kept.empty() ? ctx->final_norm : ctx->attn_norm[kept[0]];
+    if ((rc = launch_embed(ctx, token, 1, 1, ctx->h[0], gain0, nullptr, st))) return rc;
+    for (size_t k = 0; k < kept.size(); ++k) {
+        const float* gain = (k + 1 < kept.size()) ? ctx->attn_norm[kept[k + 1]] : ctx->final_norm;
+        if ((rc = run_layer(ctx, kept[k], 1, 1, 1, pos, ctx->h[k & 1], ctx->h[(k + 1) & 1], ctx->op_h, gain, ctx->ss_h,
+                            nullptr, st)))
+            return rc;
+    }
+    return run_head(ctx, 1, 1, logits_out, argmax_out, nullptr, top1_prob_out, st);
+}
+
 }  // namespace
 
 extern "C" {
@@ -775,27 +796,6 @@ int clasp_verify_forward(clasp_ctx* ctx, const int32_t* tokens, int n_tokens, in
     if (argmax_out || margin_out || logits_out)
         return run_head(ctx, n, R, logits_out, argmax_out, margin_out, nullptr, st);
     return CLASP_OK;
-}
-
-// The layers a skip set keeps on one row at position `pos`, then the head: greedy token (+ top-1 probability) and / or
-// the logits.
-static int draft_forward(clasp_ctx* ctx, const uint8_t* mask, const int32_t* token, int pos, float* logits_out,
-                         int32_t* argmax_out, float* top1_prob_out, hipStream_t st) {
-    const clasp_config& c = ctx->cfg;
-    const int L = c.n_layers;
-    std::vector<int> kept;
-    for (int l = 0; l < L; ++l)
-        if (!mask || !mask[l]) kept.push_back(l);
-    int rc;
-    const float* gain0 = kept.empty() ? ctx->final_norm : ctx->attn_norm[kept[0]];
-    if ((rc = launch_embed(ctx, token, 1, 1, ctx->h[0], gain0, nullptr, st))) return rc;
-    for (size_t k = 0; k < kept.size(); ++k) {
-        const float* gain = (k + 1 < kept.size()) ? ctx->attn_norm[kept[k + 1]] : ctx->final_norm;
-        if ((rc = run_layer(ctx, kept[k], 1, 1, 1, pos, ctx->h[k & 1], ctx->h[(k + 1) & 1], ctx->op_h, gain, ctx->ss_h,
-                            nullptr, st)))
-            return rc;
-    }
-    return run_head(ctx, 1, 1, logits_out, argmax_out, nullptr, top1_prob_out, st);
 }
 
 int clasp_draft_step(clasp_ctx* ctx, const uint8_t* mask, const int32_t* token, int pos, int32_t* next_token_out,
