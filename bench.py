@@ -71,7 +71,8 @@ def algorithmic_bytes(shape, T, M):
     head = shape.vocab * shape.d_model * eb
     L = shape.n_layers
     return {"dp_select": (L - 1) * (wl + kv), "draft_step": (L - M) * (wl + kv) + head,
-            "verify_forward": L * (wl + kv) + head, "gate_up_kernel": 2 * shape.d_model * shape.d_ffn * eb}
+            "verify_forward": L * (wl + kv) + head, "gate_up_kernel": 2 * shape.d_model * shape.d_ffn * eb,
+            "kv_share_per_layer": kv / (wl + kv)}
 
 
 def cpu_baseline(shape, host_model, T, M, budget_s=30.0):
@@ -130,6 +131,9 @@ def main():
                     help="closed loop only: re-optimise the skip set every this many verify steps (Sec. 3.7)")
     ap.add_argument("--det-threshold", type=float, default=None,
                     help="closed loop only: draft-exiting threshold on the draft token's top-1 probability (Sec. 5.3.3)")
+    ap.add_argument("--temperature", type=float, default=None,
+                    help="closed loop only: stochastic decoding at this temperature (speculative sampling with seeded "
+                         "uniform numbers) instead of greedy decoding; reports rounds and acceptance, no token comparison")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="only run plain device copies of a known size (1 GiB read + 1 GiB written per copy), to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -160,6 +164,20 @@ def main():
         eng, _ = build_engine(shape, 1, max_seq, 32 if M > 16 else 16, resid_scale=args.resid_scale)
         prompt = [int(t) for t in si.gen_tokens(2, T, shape.vocab)]
         torch.cuda.synchronize()
+        if args.temperature is not None:
+            un = {"first": si.gen_uniform(5, 1, 10).cuda(), "draft": si.gen_uniform(5, n_gen * K, 11).cuda(),
+                  "accept": si.gen_uniform(5, n_gen * K, 12).cuda(), "final": si.gen_uniform(5, n_gen, 13).cuda()}
+            t0 = time.perf_counter()
+            spec = decode.clasp_sample_generate(eng, prompt, n_gen, M, K, un, args.temperature)
+            torch.cuda.synchronize()
+            t_spec = time.perf_counter() - t0
+            acc = [r["accepted"] for r in spec["rounds"]]
+            print(json.dumps({"closed_loop": args.workload, "temperature": args.temperature, "resid_scale": args.resid_scale,
+                              "generated": n_gen, "includes_prefill": True, "clasp_tokens_per_s": round(n_gen / t_spec, 2),
+                              "rounds": len(acc), "mean_accepted_drafts": round(sum(acc) / max(1, len(acc)), 3),
+                              "skip_set_jaccard_by_round_gap": [round(x, 3) for x in decode.skip_set_jaccard(
+                                  [r["mask"] for r in spec["rounds"]], 8)]}))
+            return
         t0 = time.perf_counter()
         plain, margins = decode.greedy_generate(eng, prompt, n_gen)
         torch.cuda.synchronize()
@@ -253,6 +271,7 @@ def main():
         "mean_accepted": round(accepted / n, 3), "tokens_per_s_closed_loop": round((accepted + n) / t_total, 2),
         "hbm_frac_of_8TBs": {"dp_select": frac(ab["dp_select"], dp_ms), "draft_step": frac(ab["draft_step"], draft_ms),
                              "verify_forward": frac(ab["verify_forward"], verify_ms)},
+        "kv_share_of_layer_bytes": round(ab["kv_share_per_layer"], 4),
     }
     if kt_n:
         avg_ms = kt_ms / kt_n
