@@ -369,3 +369,40 @@ def test_closed_loop_with_draft_exiting_threshold(thr):
                 break
             assert rg["mask"] == ro["mask"].tolist() and len(rg["drafts"]) == len(ro["drafts"])
             np.testing.assert_allclose(rg["draft_conf"], ro["draft_conf"], rtol=5e-3)
+
+
+def test_budget_equal_to_depth_and_last_cache_position():
+    """Degenerate ends of the ranges: M = L skips every layer (the draft model is embedding -> final norm -> lm_head),
+    and the last position of the cache (pos = max_seq - 1) is usable by every call."""
+    name = "tiny-f32"
+    shape = si.SHAPES[name]
+    L = shape.n_layers
+    om, eng = oracle_model(name), engine(name, max_seq=64, max_rows=16)
+    toks = prompt(shape, 63)
+    cache, ost, olg = oracle_prefill(om, toks, 64)
+    tt = dev(toks, torch.int32)
+    for s in range(0, 63, 16):
+        out = eng.clasp_verify_forward(tt[s:s + 16], s, want_hidden=True, want_logits=True)
+    # rows 48..62: the last one sits at position 62; one more row at position 63 = max_seq - 1
+    assert relerr(out["hidden"][:, -1].cpu().numpy(), ost[:, -1]) <= HID_TOL["f32"]
+    last_tok = int(np.argmax(olg[-1]))
+    st, lg = om.token(last_tok, 63, cache, want_states=True)
+    one = eng.clasp_verify_forward(dev([last_tok], torch.int32), 63, want_hidden=True, want_logits=True)
+    assert relerr(one["hidden"][:, 0].cpu().numpy(), st) <= HID_TOL["f32"]
+    assert relerr(one["logits"][0].cpu().numpy(), lg) <= HID_TOL["f32"]
+    # DP at the last position with M = L: every layer skipped, g(L, L) = x_0
+    gpu, ref = check_dp(om, eng, st, 63, cache, L)
+    assert gpu["mask"].cpu().numpy().tolist() == [1] * L == ref["mask"].tolist()
+    assert relerr(gpu["g_final"].cpu().numpy(), st[0]) <= 1e-6
+    # draft step that skips everything, at the last position
+    nxt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    prob = torch.zeros(1, dtype=torch.float32, device="cuda")
+    eng.clasp_draft_step([1] * L, dev([last_tok], torch.int32), 63, nxt, prob)
+    _, dl = om.token(last_tok, 63, cache, skip=np.ones(L, dtype=np.uint8))
+    ref_tok, ref_margin = oc.argmax_margin(dl)
+    if ref_margin > 1e-3:
+        assert int(nxt) == ref_tok
+    assert abs(float(prob) - oc.top1_prob(dl)) <= 1e-3 * oc.top1_prob(dl)
+    import paper_2505_24196_amd as clasp
+    with pytest.raises(clasp.ClaspError):
+        eng.clasp_verify_forward(dev([1, 2], torch.int32), 63)  # second row would sit at max_seq
