@@ -341,30 +341,30 @@ int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kin
     return CLASP_OK;
 }
 
-template <int HD, int NT, int NW>
+template <int HD, int NT, int NW, bool STREAM>
 int launch_attn_one(const AttnArgs& a, dim3 grid, hipStream_t st) {
     constexpr size_t lds = (size_t)NW * HD * 17 * sizeof(float);
     static bool opted_in = false;  // more than 64 KiB of LDS per workgroup has to be requested once per kernel
     if (!opted_in) {
-        if (hipFuncSetAttribute((const void*)attn_bf16_kernel<HD, NT, NW>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        if (hipFuncSetAttribute((const void*)attn_bf16_kernel<HD, NT, NW, STREAM>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds) != hipSuccess)
             return CLASP_E_HIP;
         opted_in = true;
     }
-    hipLaunchKernelGGL((attn_bf16_kernel<HD, NT, NW>), grid, dim3(NW * 64), lds, st, a);
+    hipLaunchKernelGGL((attn_bf16_kernel<HD, NT, NW, STREAM>), grid, dim3(NW * 64), lds, st, a);
     CLASP_LAUNCH_CHECK();
     return CLASP_OK;
 }
 
-// short = latency-oriented launch: one query tile per workgroup, 16 wavefronts
+// short = latency-oriented launch: one query tile per workgroup, keys and values through plain (cached) loads
 template <int HD>
 int launch_attn_bf16(const AttnArgs& a, bool short_prefix, int nt, dim3 grid, hipStream_t st) {
-    if (short_prefix) return launch_attn_one<HD, 1, CLASP_ATTN_SHORT_WAVES>(a, grid, st);
+    if (short_prefix) return launch_attn_one<HD, 1, CLASP_ATTN_SHORT_WAVES, false>(a, grid, st);
     switch (nt) {
-        case 1: return launch_attn_one<HD, 1, 8>(a, grid, st);
-        case 2: return launch_attn_one<HD, 2, 8>(a, grid, st);
-        case 3: return launch_attn_one<HD, 3, 8>(a, grid, st);
-        default: return launch_attn_one<HD, 4, 8>(a, grid, st);
+        case 1: return launch_attn_one<HD, 1, 8, true>(a, grid, st);
+        case 2: return launch_attn_one<HD, 2, 8, true>(a, grid, st);
+        case 3: return launch_attn_one<HD, 3, 8, true>(a, grid, st);
+        default: return launch_attn_one<HD, 4, 8, true>(a, grid, st);
     }
 }
 
