@@ -108,9 +108,9 @@ def cpu_baseline(shape, host_model, T, M, budget_s=30.0):
     if M_s != M:
         t_draft *= (L - M) / L
     return {"value": round(1.0 / t_draft, 3), "unit": "draft tokens/s", "cores": oc.num_threads(), "kind": "oracle",
-            "dp_select_ms": round(t_dp * scale * 1e3, 1),
-            "sample": f"one oracle DP with M={M_s} (scaled x{scale:.2f} to M={M}) and one draft step at T={T} on "
-                      f"synthetic KV, {shape.name}"}
+            "dp_select_ms": round(t_dp * scale * 1e3, 1), "verify_row_ms": round(t_verify_row * 1e3, 1),
+            "sample": f"one oracle DP with M={M_s} (scaled x{scale:.2f} to M={M}), one draft step and one verify row "
+                      f"(the full model on one token; a verify pass is K+1 of them) at T={T} on synthetic KV, {shape.name}"}
 
 
 def main():
