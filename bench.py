@@ -25,11 +25,11 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC = {"llama3-8b-shape": 236.8e6 + 1.84e6}
 
 WORKLOADS = {
-    # BASELINE config 2: the configuration the metric is quoted on
+    # benchmark configuration 2: the one the metric is quoted on
     "llama3-8b-shape/T512/M12/K4": dict(shape="llama3-8b-shape", T=512, M=12, K=4),
-    # BASELINE config 1: small case the oracle finishes in seconds
+    # benchmark configuration 1: small case the oracle finishes in seconds
     "tiny-f32/T64/M3/K4": dict(shape="tiny-f32", T=64, M=3, K=4),
-    # BASELINE config 5 (closed loop shape) and config 3 (context sweep), config 4 (70B shape)
+    # benchmark configurations 5 (closed loop shape), 3 (context sweep) and 4 (70B shape)
     "llama3-8b-shape/T4096/M12/K6": dict(shape="llama3-8b-shape", T=4096, M=12, K=6),
     "llama3-8b-shape/T2048/M12/K4": dict(shape="llama3-8b-shape", T=2048, M=12, K=4),
     "llama3-8b-shape/T8192/M12/K4": dict(shape="llama3-8b-shape", T=8192, M=12, K=4),

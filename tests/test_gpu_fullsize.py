@@ -1,4 +1,4 @@
-"""Parity at BASELINE's full size (LLaMA-3-8B shape, bf16, T = 512, M = 12), in the launch configuration bench.py
+"""Parity at the benchmark's full size (LLaMA-3-8B shape, bf16, T = 512, M = 12), in the launch configuration bench.py
 times. The oracle cannot afford a 512-token prefill at this size, so a seeded synthetic KV prefix (shared input)
 stands in for it on both sides; the verify rows, the DP and a draft step are then compared call by call."""
 import numpy as np

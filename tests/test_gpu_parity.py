@@ -306,7 +306,7 @@ def test_invalid_arguments_are_rejected_on_the_host():
 
 @pytest.mark.parametrize("resid_scale,M", [(1.0, 3), (0.05, 3), (1.0, 0)])
 def test_closed_loop_tiny_matches_oracle_and_is_lossless(resid_scale, M):
-    """BASELINE configuration 1: 64 random context tokens, M = 3, draft length 4, 32 generated tokens."""
+    """Benchmark configuration 1: 64 random context tokens, M = 3, draft length 4, 32 generated tokens."""
     import paper_2505_24196_amd as clasp
     name = "tiny-f32"
     shape = si.SHAPES[name]
