@@ -371,6 +371,44 @@ def test_closed_loop_with_draft_exiting_threshold(thr):
             np.testing.assert_allclose(rg["draft_conf"], ro["draft_conf"], rtol=5e-3)
 
 
+def test_two_row_groups_head_dim_128():
+    """A 32-row verify launch and a DP with M = 20 on the head_dim-128 model (two 16-row MFMA groups, four column
+    tiles per wavefront, 8 query tiles per KV head)."""
+    name = "small-bf16-hd128"
+    shape = si.SHAPES[name]
+    om, eng = oracle_model(name, 1, 0.3), engine(name, 1, 0.3, max_seq=128, max_rows=32)
+    toks = prompt(shape, 35)
+    cache, ost, olg = oracle_prefill(om, toks, 64)
+    tt = dev(toks, torch.int32)
+    o1 = eng.clasp_verify_forward(tt[:32], 0, want_hidden=True, want_logits=True)
+    o2 = eng.clasp_verify_forward(tt[32:], 32, want_hidden=True, want_logits=True)
+    hid = torch.cat([o1["hidden"], o2["hidden"]], 1).cpu().numpy()
+    for l in range(shape.n_layers + 1):
+        assert relerr(hid[l], ost[l]) <= HID_TOL["bf16"], f"layer {l}"
+    lg = torch.cat([o1["logits"], o2["logits"]], 0).cpu().numpy()
+    assert relerr(lg, olg) <= HID_TOL["bf16"]
+    check_dp(om, eng, ost[:, -1], 34, cache, 4)
+
+
+def test_lower_optimisation_frequency_on_the_device():
+    """dp_interval = 3 (Sec. 3.7): the skip set is kept for three verify steps; output still equals the device's own
+    plain greedy decoding, and the masks change only at every third round."""
+    import paper_2505_24196_amd as clasp
+    name = "tiny-f32"
+    shape = si.SHAPES[name]
+    eng = engine(name, 1, 0.05)
+    pr = [int(t) for t in si.gen_tokens(2, 40, shape.vocab)]
+    plain, _ = clasp.greedy_generate(eng, pr, 24)
+    spec = clasp.clasp_generate(eng, pr, 24, 3, 2, dp_interval=3)
+    assert spec["tokens"] == plain
+    masks = [r["mask"] for r in spec["rounds"]]
+    for a, b, c in zip(masks[0::3], masks[1::3], masks[2::3]):
+        assert a == b == c
+    assert all(sum(m) == 3 for m in masks)
+    curve = clasp.skip_set_jaccard(masks[::3], 4)
+    assert all(0.0 <= x <= 1.0 for x in curve)
+
+
 def test_budget_equal_to_depth_and_last_cache_position():
     """Degenerate ends of the ranges: M = L skips every layer (the draft model is embedding -> final norm -> lm_head),
     and the last position of the cache (pos = max_seq - 1) is usable by every call."""

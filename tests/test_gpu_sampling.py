@@ -59,8 +59,8 @@ def _accept_case(seed, n, V, noise):
     return p_lg, q_lg, drafts, u[n:2 * n].astype(np.float32), u[2 * n:].astype(np.float32)
 
 
-@pytest.mark.parametrize("name", ["tiny-f32", "small-bf16"])
-def test_spec_accept_matches_oracle(name):
+@pytest.mark.parametrize("name,temperature", [("tiny-f32", 1.0), ("small-bf16", 1.0), ("small-bf16", 0.6)])
+def test_spec_accept_matches_oracle(name, temperature):
     eng = engine(name)
     V = si.SHAPES[name].vocab
     n_acc = torch.zeros(1, dtype=torch.int32, device="cuda")
@@ -70,9 +70,9 @@ def test_spec_accept_matches_oracle(name):
         n = 1 + seed % 4
         noise = [0.0, 0.05, 0.3, 1.0][(seed // 4) % 4]
         p_lg, q_lg, drafts, u_acc, u_fin = _accept_case(100 + seed, n, V, noise)
-        a_ref, tok_ref, info = oc.spec_accept(p_lg, q_lg, drafts, u_acc, float(u_fin[0]))
-        eng.clasp_spec_accept(dev(p_lg), dev(q_lg), dev([7] + drafts, torch.int32), n, 1.0, dev(u_acc), dev(u_fin),
-                              n_acc, nxt)
+        a_ref, tok_ref, info = oc.spec_accept(p_lg, q_lg, drafts, u_acc, float(u_fin[0]), temperature)
+        eng.clasp_spec_accept(dev(p_lg), dev(q_lg), dev([7] + drafts, torch.int32), n, temperature, dev(u_acc),
+                              dev(u_fin), n_acc, nxt)
         a, tok = int(n_acc), int(nxt)
         assert 0 <= a <= n and 0 <= tok < V
         if noise == 0.0:
