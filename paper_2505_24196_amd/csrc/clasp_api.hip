@@ -100,6 +100,15 @@ namespace {
 #ifndef CLASP_GEMV
 #define CLASP_GEMV 1  // 0: single-row launches take the several-row kernel
 #endif
+#ifndef CLASP_GEMV_PERSISTENT
+#define CLASP_GEMV_PERSISTENT 1  // one-row gate|up and lm_head take the persistent single-row kernel
+#endif
+#ifndef CLASP_FEW_ROWS
+#define CLASP_FEW_ROWS 8  // launches of up to this many rows (<= kFewRows) take it
+#endif
+#ifndef CLASP_GEMVP_DEPTH
+#define CLASP_GEMVP_DEPTH 4
+#endif
 #ifndef CLASP_GEMV_DEPTH
 #define CLASP_GEMV_DEPTH 4  // more loads in flight than HBM latency x bandwidth needs only queue (16 is 5 % slower)
 #endif
@@ -312,7 +321,20 @@ int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kin
         constexpr int KWV = EPI == kEpiQkv ? CLASP_GEMV_KW_QKV : (EPI == kEpiResid ? CLASP_GEMV_KW_RESID : 8);
         const size_t gemv_lds =
             (CLASP_GEMV && g.n_rows == 1 && g.R == 1 && EPI != kEpiPartial) ? gemv_lds_bytes<KWV>(g.K) : 0;
-        if (resident && !(gemv_lds && kind == CLASP_KERNEL_LM_HEAD)) {  // one-row lm_head: the single-row kernel is 3 % faster
+        if (resident && CLASP_GEMV_PERSISTENT && g.n_rows <= CLASP_FEW_ROWS) {
+            // few rows: they sit in LDS, the registers hold a whole tile slice of weights per wavefront
+            auto kernel = gemv_persistent_bf16_kernel<kResidentKSW, kResidentKW, EPI, CLASP_GEMVP_DEPTH, CLASP_ACT_SPLIT>;
+            static bool opted_in = false;  // more than 64 KiB of LDS per workgroup has to be requested once per kernel
+            if (!opted_in) {
+                if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        kResidentKW * kResidentKSW * CLASP_ACT_SPLIT * 64 * kFewRows) != hipSuccess)
+                    return CLASP_E_HIP;
+                opted_in = true;
+            }
+            const int rounds = (tiles + ctx->n_cu - 1) / ctx->n_cu, grid = (tiles + rounds - 1) / rounds;
+            launch_timed(timer, kernel, dim3(grid), dim3((kResidentKW + 1) * 64),
+                         (size_t)kResidentKW * kResidentKSW * CLASP_ACT_SPLIT * 64 * g.n_rows, st, g);
+        } else if (resident && !(gemv_lds && kind == CLASP_KERNEL_LM_HEAD)) {  // one-row lm_head: the single-row kernel is 3 % faster
             // every workgroup takes the same number of tiles (+-1): rounds = ceil(tiles / CUs), grid = ceil(tiles / rounds)
             const int rounds = (tiles + ctx->n_cu - 1) / ctx->n_cu, grid = (tiles + rounds - 1) / rounds;
             launch_timed(timer, gemm_bf16_resident_kernel<kResidentKSW, kResidentKW, EPI, CLASP_GEMM_DEPTH, CLASP_ACT_SPLIT>,

@@ -596,6 +596,114 @@ __global__ __launch_bounds__(KW * 64) void gemv_bf16_kernel(GemmArgs g, int nks_
     gemm_epilogue<EPI, 1>(g, tile, lane, 0, fin, rstd_s, pre);
 }
 
+// Few-row kernel (1..kFewRows rows) for projections with more column tiles than the GPU has CUs (gate|up, lm_head):
+// persistent workgroups walk over tiles blockIdx.x, blockIdx.x + gridDim.x, ..; the live rows of every wavefront's
+// k-slice sit in a private LDS region (dynamic LDS: KW * KSW * SPLIT * 64 * rows bytes; lanes of rows that do not exist
+// read the last live row), so the registers are free for NST = KSW/P weight stages, a whole tile slice per wavefront: the
+// stage just consumed is refilled with the same stage of the NEXT tile, which keeps NST-1 stages in flight across the
+// per-tile reduction barrier. KW wavefronts stream; one more wavefront does nothing but the epilogues (it is always
+// early at the barrier, so no streaming wavefront ever waits for an epilogue; the partial tiles are double-buffered in
+// LDS, and an epilogue has two tile times to finish). Needs K/32 <= KW*KSW.
+constexpr int kFewRows = 8;
+template <int KSW, int KW, int EPI, int P, int SPLIT>
+__global__ __launch_bounds__((KW + 1) * 64) void gemv_persistent_bf16_kernel(GemmArgs g) {
+    static_assert(KSW % P == 0, "a tile slice is a whole number of stages");
+    constexpr int NST = KSW / P;
+    extern __shared__ u32x4 a_s[];  // [KW][KSW * SPLIT * 4 * rows]
+    __shared__ f32x4 red[2][KW][64];
+    __shared__ float rstd_s[kMaxRows];
+    __shared__ float tmp_s[(KW + 1) * 64];
+    constexpr bool kNeedsRstd = EPI != kEpiResid && EPI != kEpiPartial;
+    const int kw = threadIdx.x >> 6, lane = threadIdx.x & 63, q = lane >> 4;
+    const int n_tiles = g.N >> 4, KS = g.K >> 5;
+    float ssv[16];
+    if constexpr (kNeedsRstd) rstd_issue(g, ssv);
+
+    if (kw == KW) {  // the epilogue wavefront
+        if constexpr (kNeedsRstd) rstd_stash(g, ssv, tmp_s);
+        int it = 0;
+        for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x, ++it) {
+            EpiPre pre;
+            epi_prefetch<EPI>(g, tile, lane, 0, pre);
+            __syncthreads();  // the KW partial tiles of `tile` are in red[it & 1]
+            if constexpr (kNeedsRstd) {
+                if (it == 0) rstd_finish(g, tmp_s, rstd_s);
+            }
+            f32x4(&rb)[KW][64] = red[it & 1];
+            f32x4 fin[1];
+            fin[0] = rb[0][lane];
+            for (int k = 1; k < KW; ++k) fin[0] += rb[k][lane];
+            gemm_epilogue<EPI, 1>(g, tile, lane, 0, fin, rstd_s, pre);
+        }
+        return;
+    }
+
+    const int ks0 = (KS * kw) / KW, nks = (KS * (kw + 1)) / KW - ks0;  // nks <= KSW (checked on the host)
+    auto wptr = [&](int tile) -> const u32x4* {
+        int mi = 0, tl = tile;
+        if constexpr (EPI == kEpiScale || EPI == kEpiQkv) {
+            if (tile >= g.tile_end[0]) { mi = 1; tl = tile - g.tile_end[0]; }
+            if (tile >= g.tile_end[1]) { mi = 2; tl = tile - g.tile_end[1]; }
+        }
+        return reinterpret_cast<const u32x4*>(g.W[mi]) + ((size_t)tl * KS + ks0) * 64 + lane;
+    };
+    u32x4 wb[NST][P];
+    auto issue = [&](u32x4 (&buf)[P], int tile, int j) {  // stage j of `tile`: k-steps j*P .. j*P+P-1 of the slice
+        const u32x4* w = wptr(tile);
+#pragma unroll
+        for (int u = 0; u < P; ++u) buf[u] = load_stream(w + (size_t)min(j * P + u, max(nks - 1, 0)) * 64);
+    };
+    int tile = blockIdx.x;
+    if (tile < n_tiles) {
+#pragma unroll
+        for (int j = 0; j < NST; ++j) issue(wb[j], tile, j);  // the whole first slice
+    }
+    // the live rows of this wavefront's k-slice into its LDS region: piece e = ((k-step, plane, 16-byte quarter), row),
+    // row fastest, so that the 16 lanes of a quarter read 16 consecutive pieces
+    const int nr = g.n_rows;
+    u32x4* mine = a_s + (size_t)kw * (KSW * SPLIT * 4) * nr;
+    {
+        const int n_el = nks * SPLIT * 4 * nr;
+        const u32x4* A = reinterpret_cast<const u32x4*>(g.A);
+        constexpr int NLD = (KSW * SPLIT * 4 * kFewRows + 63) / 64;
+        u32x4 av[NLD];
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int e = min(lane + i * 64, max(n_el - 1, 0)), row = e % nr, t = e / nr;
+            if (i == 0 || lane + i * 64 < n_el)
+                av[i] = A[((size_t)(ks0 + t / (4 * SPLIT)) * 2 + (t / 4) % SPLIT) * 64 + row * 4 + (t & 3)];
+        }
+#pragma unroll
+        for (int i = 0; i < NLD; ++i)
+            if (lane + i * 64 < n_el) mine[lane + i * 64] = av[i];
+        if constexpr (kNeedsRstd) rstd_stash(g, ssv, tmp_s);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // the region is private to this wavefront
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    const u32x4* mine_r = mine + q * nr + min(lane & 15, nr - 1);  // this lane's quarter and (clamped) row
+
+    for (int it = 0; tile < n_tiles; tile += gridDim.x, ++it) {
+        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+        const int next_tile = tile + gridDim.x;
+#pragma unroll
+        for (int j = 0; j < NST; ++j) {
+#pragma unroll
+            for (int u = 0; u < P; ++u) {
+                if (j * P + u < nks) {
+#pragma unroll
+                    for (int h = 0; h < SPLIT; ++h)
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(mine_r[((j * P + u) * SPLIT + h) * 4 * nr]),
+                                                                      as_bf16x8(wb[j][u]), acc, 0, 0, 0);
+                }
+            }
+            if (next_tile < n_tiles) issue(wb[j], next_tile, j);  // refill what was just consumed
+        }
+        red[it & 1][kw][lane] = acc;
+        __syncthreads();
+    }
+}
+
 // Resident-activation variant for one row group (rows <= 16) and K/32 <= KW*KSW: wavefront kw keeps ITS k-slice of the
 // activation fragments (hi and lo) in registers for the whole kernel, and the workgroup walks over column tiles
 // blockIdx.x, blockIdx.x + gridDim.x, ... streaming nothing but weights: one 16-byte load per lane per MFMA pair.
