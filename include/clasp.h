@@ -120,6 +120,26 @@ int clasp_verify_forward(clasp_ctx *ctx, const int32_t *tokens, int n_tokens, in
                          int32_t *argmax_out, float *margin_out, float *logits_out, void *stream);
 
 /*
+ * Prompt processing with many rows per pass (the full-model forward of Sec. 3.1 over the prompt, whose lasting
+ * product is the KV cache that verification, layer optimisation (Sec. 3.4) and drafting read): the full model over
+ * n_tokens rows at positions pos0..pos0+n_tokens-1, causal among themselves, attending cache positions 0..pos0-1,
+ * in passes of chunk_rows rows through compute-bound MFMA GEMMs and causal flash attention. Writes the rows'
+ * keys/values into every layer's cache and nothing else; the states and the next token of the prompt's last token
+ * come from clasp_verify_forward on that token (or on the last few) afterwards. bf16 models only
+ * (CLASP_E_UNSUPPORTED otherwise); arithmetic as in clasp_verify_forward (bf16 weights, hi + lo bf16 activation
+ * operands, fp32 accumulation), so the cache equals the one clasp_verify_forward leaves up to rounding order.
+ *   tokens       dev int32 [n_tokens]; ids outside [0, vocab) are clamped
+ *   n_tokens     >= 1;  pos0 >= 0, pos0 + n_tokens <= max_seq
+ *   chunk_rows   rows per pass: a multiple of 128 in 128..8192 (larger = fewer passes over the weights)
+ *   workspace    dev, 256-byte aligned, >= clasp_prefill_workspace_bytes(cfg, chunk_rows) bytes, caller-owned, only
+ *                used during the call (on `stream`)
+ * clasp_prefill_workspace_bytes returns 0 for an unsupported configuration or chunk_rows.
+ */
+size_t clasp_prefill_workspace_bytes(const clasp_config *cfg, int chunk_rows);
+int clasp_prefill(clasp_ctx *ctx, const int32_t *tokens, int n_tokens, int pos0, int chunk_rows, void *workspace,
+                  size_t workspace_bytes, void *stream);
+
+/*
  * Layer optimisation (Sec. 3.4, Eq. 2, Algorithm 1; batching of the candidates of one layer: Sec. 3.6).
  * For the token at position `pos` with stored verify states x_0..x_L, runs the dynamic program
  *   D(i,j) = max{ cos(x_i, g(i-1,j-1)), cos(x_i, f_{i-1}(g(i-1,j))) },  i = 1..L, j = 1..min(i, M)
@@ -176,6 +196,11 @@ int clasp_spec_accept(clasp_ctx *ctx, const float *p_logits, const float *q_logi
  * converted to the cache dtype and layout at positions 0..n_tokens-1. For callers that hold a cache from elsewhere
  * (and for tests that feed synthetic cache contents). */
 int clasp_kv_load(clasp_ctx *ctx, int layer, const float *K, const float *V, int n_tokens, void *stream);
+
+/* The inverse: cache positions pos0..pos0+n_tokens-1 of one layer as dev fp32 [n_tokens][n_kv_heads][head_dim]
+ * (keys as stored, i.e. rotated; values of the cache dtype widened exactly). For callers that move a cache elsewhere
+ * and for tests that compare cache contents. */
+int clasp_kv_read(clasp_ctx *ctx, int layer, int pos0, int n_tokens, float *K, float *V, void *stream);
 
 /* Measurement aid: between begin and end, every `every`-th launch of the chosen kernel kind inside the calls above
  * gets a pair of HIP events (up to `capacity` launches; host-side event objects only). The GEMM kinds attach the pair

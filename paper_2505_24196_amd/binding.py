@@ -18,6 +18,7 @@ CLASP_F32, CLASP_BF16 = 0, 1
 EXPORTS = ("clasp_strerror", "clasp_packed_bytes", "clasp_pack_matrix", "clasp_pack_gate_up", "clasp_workspace_bytes",
            "clasp_kv_cache_bytes", "clasp_create", "clasp_destroy", "clasp_verify_forward", "clasp_dp_select",
            "clasp_draft_step", "clasp_sample_token", "clasp_draft_sample", "clasp_spec_accept", "clasp_kv_load",
+           "clasp_kv_read", "clasp_prefill_workspace_bytes", "clasp_prefill",
            "clasp_kernel_timer_begin", "clasp_kernel_timer_end")
 
 KERNEL_KINDS = {"qkv": 0, "attention": 1, "o_proj": 2, "gate_up": 3, "down": 4, "lm_head": 5}
@@ -70,6 +71,10 @@ def lib():
         l.clasp_draft_sample.argtypes = [vp, vp, vp, i32, C.c_float, vp, vp, vp, vp]
         l.clasp_spec_accept.argtypes = [vp, vp, vp, sz, vp, i32, C.c_float, vp, vp, vp, vp, vp]
         l.clasp_kv_load.argtypes = [vp, i32, vp, vp, i32, vp]
+        l.clasp_kv_read.argtypes = [vp, i32, i32, i32, vp, vp, vp]
+        l.clasp_prefill_workspace_bytes.restype = sz
+        l.clasp_prefill_workspace_bytes.argtypes = [C.POINTER(Config), i32]
+        l.clasp_prefill.argtypes = [vp, vp, i32, i32, i32, vp, sz, vp]
         l.clasp_kernel_timer_begin.argtypes = [vp, i32, i32, i32]
         l.clasp_kernel_timer_end.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int)]
         _lib = l
@@ -214,6 +219,26 @@ class Engine:
         K = K.to(self.device, torch.float32).contiguous()
         V = V.to(self.device, torch.float32).contiguous()
         _check(lib().clasp_kv_load(self._ctx, layer, _ptr(K), _ptr(V), K.shape[0], _stream()), "clasp_kv_load")
+
+    def clasp_kv_read(self, layer: int, pos0: int, n_tokens: int):
+        """Cache positions pos0..pos0+n_tokens-1 of `layer` as fp32 (K, V), each [n_tokens][n_kv_heads][head_dim]."""
+        s = self.shape
+        K = torch.empty(n_tokens, s.n_kv_heads, s.head_dim, dtype=torch.float32, device=self.device)
+        V = torch.empty_like(K)
+        _check(lib().clasp_kv_read(self._ctx, layer, pos0, n_tokens, _ptr(K), _ptr(V), _stream()), "clasp_kv_read")
+        return K, V
+
+    def clasp_prefill(self, tokens: torch.Tensor, pos0: int, chunk_rows: int = 1024):
+        """tokens: device int32 [n] -> their keys/values in every layer's cache at pos0.. (bf16 models). The workspace
+        for `chunk_rows` rows per pass is allocated on first use and kept."""
+        need = lib().clasp_prefill_workspace_bytes(C.byref(self.cfg), chunk_rows)
+        if need == 0:
+            raise ClaspError("clasp_prefill: unsupported model dtype or chunk_rows (multiple of 128 in 128..8192)")
+        ws = getattr(self, "_prefill_ws", None)
+        if ws is None or ws.numel() < need:
+            ws = self._prefill_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        _check(lib().clasp_prefill(self._ctx, _ptr(tokens, torch.int32), tokens.numel(), pos0, chunk_rows, ws.data_ptr(),
+                                   ws.numel(), _stream()), "clasp_prefill")
 
     def clasp_verify_forward(self, tokens: torch.Tensor, pos0: int, want_hidden: bool = False, want_logits: bool = False,
                              want_margin: bool = False):

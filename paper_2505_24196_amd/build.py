@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libclasp_hip.so")
 SOURCES = [os.path.join(CSRC, "clasp_api.hip")]
-HEADERS = [os.path.join(CSRC, f) for f in ("clasp_common.h", "clasp_gemm.h", "clasp_attn.h", "clasp_misc.h", "clasp_sample.h")] + [
+HEADERS = [os.path.join(CSRC, f) for f in ("clasp_common.h", "clasp_gemm.h", "clasp_attn.h", "clasp_misc.h", "clasp_sample.h", "clasp_prefill.h")] + [
     os.path.join(os.path.dirname(HERE), "include", "clasp.h")]
 
 

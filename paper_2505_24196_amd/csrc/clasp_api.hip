@@ -17,6 +17,7 @@
 #include "clasp_common.h"
 #include "clasp_gemm.h"
 #include "clasp_misc.h"
+#include "clasp_prefill.h"
 
 using namespace clasp;
 
@@ -613,6 +614,132 @@ int draft_forward(clasp_ctx* ctx, const uint8_t* mask, const int32_t* token, int
     return run_head(ctx, 1, 1, logits_out, argmax_out, nullptr, top1_prob_out, st);
 }
 
+// ---- prompt processing with many rows per pass ---------------------------------------------------------------------
+constexpr int kPrefillMaxChunk = 8192;
+
+struct PrefillWs {
+    float *h, *a_buf, *ss_h, *ss_a, *rstd_h, *rstd_a;
+    void *op_h, *op_a, *op_attn, *op_act, *q_frag;
+};
+
+size_t carve_prefill(const clasp_config& c, int chunk, char* base, PrefillWs* ws) {
+    Carver w{base};
+    const size_t C = chunk, d = c.d_model, qd = (size_t)c.n_heads * c.head_dim;
+    PrefillWs t;
+    t.h = w.take<float>(C * d * 4);
+    t.a_buf = w.take<float>(C * d * 4);
+    t.ss_h = w.take<float>((d / 16) * C * 4);
+    t.ss_a = w.take<float>((d / 16) * C * 4);
+    t.rstd_h = w.take<float>(C * 4);
+    t.rstd_a = w.take<float>(C * 4);
+    t.op_h = w.take<void>(C * d * 4);
+    t.op_a = w.take<void>(C * d * 4);
+    t.op_attn = w.take<void>(C * qd * 4);
+    t.op_act = w.take<void>(C * (size_t)c.d_ffn * 4);
+    t.q_frag = w.take<void>(C * qd * 2);
+    if (ws) *ws = t;
+    return w.off;
+}
+
+// Fewer, fatter workgroups (256 feature columns) when they still fill the chip, else 128 columns.
+template <int EPI>
+int launch_prefill_gemm(const clasp_ctx* ctx, const PrefillGemmArgs& p, hipStream_t st) {
+    const int nrb = (p.g.R * 16 + kPrefillRows - 1) / kPrefillRows, tiles = p.g.N / 16;
+    const bool wide = nrb * ((tiles + 15) / 16) >= ctx->n_cu;
+    static bool opted_in[2] = {false, false};  // more than 64 KiB of LDS per workgroup has to be requested once per kernel
+    auto launch = [&](auto kernel, size_t lds, int col_tiles, bool& opted) -> int {
+        if (!opted) {
+            if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+                return CLASP_E_HIP;
+            opted = true;
+        }
+        const int total = nrb * ((tiles + col_tiles - 1) / col_tiles);
+        hipLaunchKernelGGL(kernel, dim3((total + 7) / 8 * 8), dim3(256), lds, st, p);
+        CLASP_LAUNCH_CHECK();
+        return CLASP_OK;
+    };
+    if (wide) return launch(prefill_gemm_kernel<EPI, 8>, prefill_gemm_lds_bytes<8>(), 16, opted_in[0]);
+    return launch(prefill_gemm_kernel<EPI, 4>, prefill_gemm_lds_bytes<4>(), 8, opted_in[1]);
+}
+
+// The full model over n rows at positions pos0.. (n <= the chunk the workspace was carved for): leaves their keys and
+// values in the cache. The last layer stops after its q/k/v projection: nothing after it feeds the cache.
+int prefill_chunk(const clasp_ctx* ctx, const PrefillWs& ws, int ld, const int32_t* tokens, int n, int pos0,
+                  hipStream_t st) {
+    const clasp_config& c = ctx->cfg;
+    const int d = c.d_model, F = c.d_ffn, L = c.n_layers, R = (n + 15) / 16;
+    int rc;
+    hipLaunchKernelGGL(prefill_embed_kernel, dim3(n, (d + 255) / 256), dim3(256), 0, st, tokens,
+                       static_cast<const bf16*>(ctx->embed), c.vocab, d, ws.h, ws.op_h, R, ctx->attn_norm[0], ws.ss_h, ld);
+    CLASP_LAUNCH_CHECK();
+    for (int l = 0; l < L; ++l) {
+        hipLaunchKernelGGL(prefill_rstd_kernel, dim3((n + 255) / 256), dim3(256), 0, st, ws.ss_h, d / 16, ld, n, 1.0f / d,
+                           c.rms_eps, ws.rstd_h);
+        CLASP_LAUNCH_CHECK();
+        {
+            PrefillGemmArgs p{};
+            GemmArgs& g = p.g;
+            g.W[0] = ctx->wq[l]; g.W[1] = ctx->wk[l]; g.W[2] = ctx->wv[l];
+            g.tile_end[0] = ctx->q_dim / 16; g.tile_end[1] = (ctx->q_dim + ctx->kv_dim) / 16; g.tile_end[2] = ctx->qkv_dim / 16;
+            g.A = ws.op_h; g.n_rows = n; g.N = ctx->qkv_dim; g.K = d; g.R = R;
+            p.rstd = ws.rstd_h;
+            QkvOut& o = g.qkv;
+            o.n_heads = c.n_heads; o.n_kv_heads = c.n_kv_heads; o.head_dim = c.head_dim;
+            o.pos0 = pos0; o.mode = 1; o.t_max = c.max_seq; o.rope = ctx->rope;
+            o.q_scale = 1.4426950408889634f / sqrtf((float)c.head_dim);
+            o.q_frag = ws.q_frag;
+            o.k_cache = ctx->k_cache + (size_t)l * ctx->kv_layer_bytes;
+            o.v_cache = ctx->v_cache + (size_t)l * ctx->kv_layer_bytes;
+            if ((rc = launch_prefill_gemm<kEpiQkv>(ctx, p, st))) return rc;
+        }
+        if (l == L - 1) break;
+        {
+            PrefillAttnArgs a{};
+            a.q_frag = ws.q_frag;
+            a.Kc = ctx->k_cache + (size_t)l * ctx->kv_layer_bytes;
+            a.Vt = ctx->v_cache + (size_t)l * ctx->kv_layer_bytes;
+            a.out_op = ws.op_attn;
+            a.n_rows = n; a.R = R; a.n_heads = c.n_heads; a.n_kv_heads = c.n_kv_heads; a.pos0 = pos0; a.t_max = c.max_seq;
+            const int per_wg = kPrefillAttnWaves * kPrefillAttnNT;
+            const dim3 grid(c.n_kv_heads, (R * ctx->group + per_wg - 1) / per_wg);
+            if (c.head_dim == 64) hipLaunchKernelGGL(prefill_attn_kernel<64>, grid, dim3(kPrefillAttnWaves * 64), 0, st, a);
+            else hipLaunchKernelGGL(prefill_attn_kernel<128>, grid, dim3(kPrefillAttnWaves * 64), 0, st, a);
+            CLASP_LAUNCH_CHECK();
+        }
+        {
+            PrefillGemmArgs p{};
+            GemmArgs& g = p.g;
+            g.W[0] = ctx->wo[l]; g.tile_end[0] = g.tile_end[1] = g.tile_end[2] = d / 16;
+            g.A = ws.op_attn; g.n_rows = n; g.N = d; g.K = ctx->q_dim; g.R = R;
+            g.out = ws.a_buf; g.ldo = d; g.resid = ws.h; g.ldr = d;
+            g.next_op = ws.op_a; g.next_gain = ctx->mlp_norm[l]; g.next_ss = ws.ss_a; p.ld_ss = ld;
+            if ((rc = launch_prefill_gemm<kEpiResid>(ctx, p, st))) return rc;
+        }
+        hipLaunchKernelGGL(prefill_rstd_kernel, dim3((n + 255) / 256), dim3(256), 0, st, ws.ss_a, d / 16, ld, n, 1.0f / d,
+                           c.rms_eps, ws.rstd_a);
+        CLASP_LAUNCH_CHECK();
+        {
+            PrefillGemmArgs p{};
+            GemmArgs& g = p.g;
+            g.W[0] = ctx->w_gate_up[l]; g.N = 2 * F; g.tile_end[0] = g.tile_end[1] = g.tile_end[2] = g.N / 16;
+            g.A = ws.op_a; g.n_rows = n; g.K = d; g.R = R;
+            p.rstd = ws.rstd_a;
+            g.next_op = ws.op_act;
+            if ((rc = launch_prefill_gemm<kEpiSwiglu>(ctx, p, st))) return rc;
+        }
+        {
+            PrefillGemmArgs p{};
+            GemmArgs& g = p.g;
+            g.W[0] = ctx->w_down[l]; g.tile_end[0] = g.tile_end[1] = g.tile_end[2] = d / 16;
+            g.A = ws.op_act; g.n_rows = n; g.N = d; g.K = F; g.R = R;
+            g.out = ws.h; g.ldo = d; g.resid = ws.a_buf; g.ldr = d;
+            g.next_op = ws.op_h; g.next_gain = ctx->attn_norm[l + 1]; g.next_ss = ws.ss_h; p.ld_ss = ld;
+            if ((rc = launch_prefill_gemm<kEpiResid>(ctx, p, st))) return rc;
+        }
+    }
+    return CLASP_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -798,6 +925,25 @@ int clasp_kv_load(clasp_ctx* ctx, int layer, const float* K, const float* V, int
     return CLASP_OK;
 }
 
+int clasp_kv_read(clasp_ctx* ctx, int layer, int pos0, int n_tokens, float* K, float* V, void* stream) {
+    if (!ctx || !K || !V) return CLASP_E_INVALID_ARG;
+    const clasp_config& c = ctx->cfg;
+    if (layer < 0 || layer >= c.n_layers || pos0 < 0 || n_tokens < 0 || (long long)pos0 + n_tokens > c.max_seq)
+        return CLASP_E_INVALID_ARG;
+    if (n_tokens == 0) return CLASP_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const void* Kc = ctx->k_cache + (size_t)layer * ctx->kv_layer_bytes;
+    const void* Vt = ctx->v_cache + (size_t)layer * ctx->kv_layer_bytes;
+    if (c.dtype == CLASP_BF16)
+        hipLaunchKernelGGL((kv_read_kernel<kDtBf16>), dim3(1024), dim3(256), 0, st, Kc, Vt, K, V, pos0, n_tokens,
+                           c.n_kv_heads, c.head_dim, c.max_seq);
+    else
+        hipLaunchKernelGGL((kv_read_kernel<kDtF32>), dim3(1024), dim3(256), 0, st, Kc, Vt, K, V, pos0, n_tokens,
+                           c.n_kv_heads, c.head_dim, c.max_seq);
+    CLASP_LAUNCH_CHECK();
+    return CLASP_OK;
+}
+
 int clasp_verify_forward(clasp_ctx* ctx, const int32_t* tokens, int n_tokens, int pos0, float* hidden_out,
                          int32_t* argmax_out, float* margin_out, float* logits_out, void* stream) {
     if (!ctx || !tokens) return CLASP_E_INVALID_ARG;
@@ -817,6 +963,32 @@ int clasp_verify_forward(clasp_ctx* ctx, const int32_t* tokens, int n_tokens, in
     }
     if (argmax_out || margin_out || logits_out)
         return run_head(ctx, n, R, logits_out, argmax_out, margin_out, nullptr, st);
+    return CLASP_OK;
+}
+
+size_t clasp_prefill_workspace_bytes(const clasp_config* cfg, int chunk_rows) {
+    if (check_config(cfg) != CLASP_OK || cfg->dtype != CLASP_BF16) return 0;
+    if (chunk_rows < kPrefillRows || chunk_rows > kPrefillMaxChunk || chunk_rows % kPrefillRows) return 0;
+    return carve_prefill(*cfg, chunk_rows, nullptr, nullptr);
+}
+
+int clasp_prefill(clasp_ctx* ctx, const int32_t* tokens, int n_tokens, int pos0, int chunk_rows, void* workspace,
+                  size_t workspace_bytes, void* stream) {
+    if (!ctx || !tokens || !workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return CLASP_E_INVALID_ARG;
+    const clasp_config& c = ctx->cfg;
+    if (c.dtype != CLASP_BF16) return CLASP_E_UNSUPPORTED;
+    if (n_tokens < 1 || pos0 < 0 || (long long)pos0 + n_tokens > c.max_seq) return CLASP_E_INVALID_ARG;
+    const size_t need = clasp_prefill_workspace_bytes(&c, chunk_rows);
+    if (!need) return CLASP_E_INVALID_ARG;
+    if (workspace_bytes < need) return CLASP_E_WORKSPACE;
+    PrefillWs ws;
+    carve_prefill(c, chunk_rows, static_cast<char*>(workspace), &ws);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    for (int s = 0; s < n_tokens; s += chunk_rows) {
+        const int n = n_tokens - s < chunk_rows ? n_tokens - s : chunk_rows;
+        const int rc = prefill_chunk(ctx, ws, chunk_rows, tokens + s, n, pos0 + s, st);
+        if (rc) return rc;
+    }
     return CLASP_OK;
 }
 

@@ -104,6 +104,26 @@ __global__ void kv_load_kernel(const float* K, const float* V, void* Kc, void* V
     }
 }
 
+// ---- read cache contents back as fp32 [T][n_kv][hd] (positions pos0 .. pos0+T-1) ------------------------------------
+template <int DT>
+__global__ void kv_read_kernel(const void* Kc, const void* Vt, float* K, float* V, int pos0, int T, int nkv, int hd,
+                               int t_max) {
+    const size_t total = (size_t)T * nkv * hd;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const int e = (int)(i % hd);
+        const int kvh = (int)((i / hd) % nkv);
+        const size_t t = pos0 + i / ((size_t)hd * nkv);
+        if constexpr (DT == kDtBf16) {
+            const size_t head = (size_t)kvh * t_max * hd;
+            K[i] = from_bf16(reinterpret_cast<const bf16*>(Kc)[head + kfrag_offset(hd, (int)t, e)]);
+            V[i] = from_bf16(reinterpret_cast<const bf16*>(Vt)[head + vfrag_offset(hd, (int)t, e)]);
+        } else {
+            K[i] = reinterpret_cast<const float*>(Kc)[((size_t)kvh * t_max + t) * hd + e];
+            V[i] = reinterpret_cast<const float*>(Vt)[((size_t)kvh * hd + e) * t_max + t];
+        }
+    }
+}
+
 // ---- the DP's score / select step for layer index i (Algorithm 1, Eq. 2) -------------------------------------------
 // Workgroup j = blockIdx.x handles cell (i, j), j = 0..min(i, M):
 //   j = 0          g(i,0) = x_i

@@ -1,0 +1,320 @@
+// Prompt processing ("prefill") with many rows per pass: the full model over hundreds of prompt tokens at once, whose
+// only lasting product is the KV cache that verification, the layer-skip search and drafting (Sec. 3.1, 3.6 of the
+// paper) read afterwards. With C rows per pass the GEMMs do C flop per weight byte, beyond the ridge of the part
+// (~310) from a few hundred rows on, so unlike the decode-time kernels these are organised around the matrix cores:
+//   * prefill_gemm_kernel: workgroup tile 128 rows x (128 | 256) features, 2 x 2 wavefronts, each holding a
+//     64 x (64 | 128) accumulator tile; both operands arrive in MFMA fragment order already (weights as packed for
+//     the decode kernels, activations as the hi/lo operand planes every producer writes), so staging is a copy of
+//     whole KiB fragments: global -> registers -> LDS two k-steps ahead, three LDS stages, one barrier per k-step.
+//     The activations keep the decode path's hi + lo split (two MFMAs per fragment pair), so that the cache a prompt
+//     leaves behind does not depend on how many rows went through at once beyond rounding order.
+//   * prefill_attn_kernel: causal flash attention; a wavefront owns two tiles of 16 queries (row x head of one KV
+//     group) and walks the visible prefix in 32-key blocks on its own (no merging), key / value fragments straight
+//     from the fragment-order cache with a register double buffer; sibling wavefronts read the same blocks from L2.
+// Epilogues write exactly what the decode kernels' epilogues write (rotated, scaled query fragments; keys and values
+// into the cache; residual stream, next operand, sum-of-squares partials; SwiGLU operand).
+#pragma once
+#include "clasp_attn.h"
+#include "clasp_common.h"
+#include "clasp_gemm.h"
+
+namespace clasp {
+
+struct PrefillGemmArgs {
+    GemmArgs g;          // W, tile_end, A, n_rows, N, K, R, out/ldo, resid/ldr, next_op, next_gain, next_ss, qkv
+    const float* rstd;   // [n_rows] 1/rms of the input rows (projections that follow a norm), else null
+    int ld_ss;           // row capacity of next_ss: next_ss[tile][ld_ss]
+};
+
+// rstd[row] = 1 / sqrt(sum_p ss[p][row] / dim + eps), parts added in index order.
+__global__ void prefill_rstd_kernel(const float* ss, int n_parts, int ld, int n_rows, float inv_dim, float eps,
+                                    float* rstd) {
+    const int row = blockIdx.x * blockDim.x + threadIdx.x;
+    if (row >= n_rows) return;
+    float s = 0.f;
+    for (int p = 0; p < n_parts; ++p) s += ss[(size_t)p * ld + row];
+    rstd[row] = 1.0f / sqrtf(s * inv_dim + eps);
+}
+
+// Embedding gather for a chunk: h_0, the first layer's operand (times its norm gains) and sum-of-squares partials.
+// Grid (rows, ceil(d / 256)).
+__global__ __launch_bounds__(256) void prefill_embed_kernel(const int32_t* tokens, const bf16* table, int vocab, int d,
+                                                            float* h, void* op, int R, const float* gain, float* ss,
+                                                            int ld_ss) {
+    const int row = blockIdx.x, c = blockIdx.y * 256 + threadIdx.x;
+    if (c >= d) return;
+    int tok = tokens[row];
+    tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
+    const float v = from_bf16(table[(size_t)tok * d + c]);
+    h[(size_t)row * d + c] = v;
+    store_operand<kDtBf16>(op, R, d, row, c, v * gain[c]);
+    const float sq = sum16(v * v);
+    if ((c & 15) == 0) ss[(size_t)(c >> 4) * ld_ss + row] = sq;
+}
+
+// One finished 16 x 16 accumulator tile (row tile rt, feature tile `tile`): lane holds rows rt*16 + (lane/16)*4 + r,
+// feature tile*16 + lane%16. Every lane runs the same shuffles; only stores are predicated.
+template <int EPI>
+__device__ __forceinline__ void prefill_epilogue(const PrefillGemmArgs& p, int rt, int tile, int lane, const f32x4& acc) {
+    const GemmArgs& g = p.g;
+    const int c = lane & 15, col = tile * 16 + c, row0 = rt * 16 + (lane >> 4) * 4;
+    if constexpr (EPI == kEpiQkv) {
+        const QkvOut& o = g.qkv;
+        const int HD = o.head_dim, HALF = HD >> 1, tph = HD >> 4, KK = HD >> 5;
+        const int G = o.n_heads / o.n_kv_heads;
+        const int which = tile < g.tile_end[0] ? 0 : (tile < g.tile_end[1] ? 1 : 2);
+        const int tl = tile - (which == 0 ? 0 : (which == 1 ? g.tile_end[0] : g.tile_end[1]));
+        const int head = tl / tph, u = tl % tph;
+        bf16* kc = reinterpret_cast<bf16*>(o.k_cache) + (size_t)head * o.t_max * HD;
+        bf16* vc = reinterpret_cast<bf16*>(o.v_cache) + (size_t)head * o.t_max * HD;
+        const int e = u * 8 + (c & 7), x = e + ((c & 8) ? HALF : 0);  // q / k: rotary pair (e, e + HALF) in one tile
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = row0 + r;
+            const bool live = row < g.n_rows;
+            const float own = acc[r] * (live ? p.rstd[row] : 0.f);
+            const float partner = __shfl_xor(own, 8);
+            if (!live) continue;
+            const int pos = o.pos0 + row;
+            if (which == 2) {
+                vc[vfrag_offset(HD, pos, u * 16 + c)] = to_bf16(own);
+                continue;
+            }
+            const float2 cs = o.rope[(size_t)pos * HALF + e];
+            const float rot = own * cs.x + ((c & 8) ? partner : -partner) * cs.y;
+            if (which == 0) {
+                // query index inside its KV head: row * G + head % G; g.R * G tiles of 16 queries per KV head
+                const int kvh = head / G, qi = row * G + head % G;
+                const size_t off = (((((size_t)kvh * (g.R * G) + (qi >> 4)) * KK + (x >> 5)) * 64) +
+                                    ((x >> 3) & 3) * 16 + (qi & 15)) * 8 + (x & 7);
+                reinterpret_cast<bf16*>(o.q_frag)[off] = to_bf16(rot * o.q_scale);
+            } else {
+                kc[kfrag_offset(HD, pos, x)] = to_bf16(rot);
+            }
+        }
+    } else if constexpr (EPI == kEpiResid) {
+        const float gain = g.next_gain ? g.next_gain[col] : 1.0f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = row0 + r;
+            const bool live = row < g.n_rows;
+            float v = 0.f;
+            if (live) {
+                v = g.resid[(size_t)row * g.ldr + col] + acc[r];
+                g.out[(size_t)row * g.ldo + col] = v;
+            }
+            if (g.next_op) store_operand<kDtBf16>(g.next_op, g.R, 0, row, col, v * gain);  // dead rows of the tile: zeros
+            const float sq = sum16(v * v);
+            if (g.next_ss && c == 0 && live) g.next_ss[(size_t)tile * p.ld_ss + row] = sq;
+        }
+    } else {  // kEpiSwiglu: lanes 0..7 hold gate features 8*tile .., lanes 8..15 the matching up features
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = row0 + r;
+            const bool live = row < g.n_rows;
+            const float own = acc[r] * (live ? p.rstd[row] : 0.f);
+            const float up = __shfl_xor(own, 8);
+            const float v = live ? own / (1.0f + expf(-own)) * up : 0.f;
+            if (c < 8) store_operand<kDtBf16>(g.next_op, g.R, 0, row, tile * 8 + c, v);
+        }
+    }
+}
+
+constexpr int kPrefillRM = 4;      // 16-row tiles per wavefront
+constexpr int kPrefillStages = 3;  // LDS stages (k-steps)
+constexpr int kPrefillRows = 2 * kPrefillRM * 16;  // rows of a workgroup tile
+
+template <int RN>
+constexpr size_t prefill_gemm_lds_bytes() {
+    return (size_t)kPrefillStages * (2 * 2 * kPrefillRM + 2 * RN) * 1024;
+}
+
+// Workgroup = 2 x 2 wavefronts; wavefront (wm, wn) accumulates row tiles wm*4 .. +3 times feature tiles wn*RN .. +RN-1
+// of the workgroup tile. Per k-step the workgroup stages 16 activation fragments (8 row tiles x hi/lo) and 2*RN weight
+// fragments of 1 KiB each. Workgroups are numbered so that the ones resident on an XCD at the same time share weight
+// columns: the XCD's L2 then sees each weight fragment from HBM once and serves the sibling row blocks.
+template <int EPI, int RN>
+__global__ __launch_bounds__(256) void prefill_gemm_kernel(PrefillGemmArgs p) {
+    constexpr int RM = kPrefillRM, NSTAGE = kPrefillStages;
+    constexpr int A_FR = 2 * 2 * RM, B_FR = 2 * RN, FR = A_FR + B_FR, NL = FR / 4;
+    static_assert(FR % 4 == 0, "fragments are dealt to four wavefronts");
+    extern __shared__ u32x4 prefill_lds[];  // [NSTAGE][FR][64]
+    const GemmArgs& g = p.g;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, wm = w >> 1, wn = w & 1;
+    const int KS = g.K >> 5, n_tiles = g.N >> 4;
+    const int nrb = (g.R * 16 + kPrefillRows - 1) / kPrefillRows, ncb = (n_tiles + B_FR - 1) / B_FR;
+    // block id -> (row block, column block): ids congruent mod 8 run on one XCD; give each XCD a contiguous range
+    const int total = nrb * ncb, per_xcd = (total + 7) >> 3;
+    const int pid = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (pid >= total) return;
+    const int rb = pid % nrb, cb = pid / nrb;
+
+    // loader role: fragments w, w + 4, .. of the stage
+    const u32x4* src[NL];
+    size_t step[NL];
+#pragma unroll
+    for (int j = 0; j < NL; ++j) {
+        const int f = w + 4 * j;
+        if (f < A_FR) {  // activation fragment: row tile f/2, plane f%2; fetched in the order the MFMA lanes want it
+            const int rg = min(rb * (2 * RM) + (f >> 1), g.R - 1);
+            src[j] = reinterpret_cast<const u32x4*>(g.A) + ((size_t)rg * 2 + (f & 1)) * 64 + (lane & 15) * 4 + (lane >> 4);
+            step[j] = (size_t)g.R * 2 * 64;
+        } else {
+            const int tile = min(cb * B_FR + (f - A_FR), n_tiles - 1);
+            int mi = 0, tl = tile;
+            if (tile >= g.tile_end[0]) { mi = 1; tl = tile - g.tile_end[0]; }
+            if (tile >= g.tile_end[1]) { mi = 2; tl = tile - g.tile_end[1]; }
+            src[j] = reinterpret_cast<const u32x4*>(g.W[mi]) + (size_t)tl * KS * 64 + lane;
+            step[j] = 64;
+        }
+    }
+    auto issue = [&](u32x4 (&r)[NL], int s) {
+#pragma unroll
+        for (int j = 0; j < NL; ++j) r[j] = src[j][(size_t)s * step[j]];
+    };
+    auto commit = [&](const u32x4 (&r)[NL], int buf) {
+#pragma unroll
+        for (int j = 0; j < NL; ++j) prefill_lds[((size_t)buf * FR + (w + 4 * j)) * 64 + lane] = r[j];
+    };
+
+    f32x4 acc[RM][RN];
+#pragma unroll
+    for (int i = 0; i < RM; ++i)
+#pragma unroll
+        for (int j = 0; j < RN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    auto compute = [&](int buf) {
+        const u32x4* L = prefill_lds + (size_t)buf * FR * 64 + lane;
+        u32x4 bf[RN];
+#pragma unroll
+        for (int j = 0; j < RN; ++j) bf[j] = L[(A_FR + wn * RN + j) * 64];
+#pragma unroll
+        for (int i = 0; i < RM; ++i) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const u32x4 af = L[((wm * RM + i) * 2 + h) * 64];
+#pragma unroll
+                for (int j = 0; j < RN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(af), as_bf16x8(bf[j]), acc[i][j], 0, 0, 0);
+            }
+        }
+    };
+
+    // stage s is requested at the top of iteration s-3, committed to LDS at the bottom of iteration s-2 and consumed
+    // in iteration s; two register sets alternate
+    u32x4 r0[NL], r1[NL];
+    issue(r0, 0);
+    if (KS > 1) issue(r1, 1);
+    commit(r0, 0);
+    if (KS > 1) commit(r1, 1);
+    if (KS > 2) issue(r0, 2);
+    __syncthreads();
+    int buf = 0;
+    auto iteration = [&](int s, u32x4 (&cur)[NL], u32x4 (&nxt)[NL]) {  // cur holds stage s+2, nxt is free
+        if (s + 3 < KS) issue(nxt, s + 3);
+        compute(buf);
+        if (s + 2 < KS) commit(cur, buf == 0 ? NSTAGE - 1 : buf - 1);  // (s + 2) % 3 == (s - 1) % 3
+        __syncthreads();
+        buf = buf == NSTAGE - 1 ? 0 : buf + 1;
+    };
+    for (int s = 0; s < KS; s += 2) {
+        iteration(s, r0, r1);
+        if (s + 1 < KS) iteration(s + 1, r1, r0);
+    }
+
+#pragma unroll
+    for (int i = 0; i < RM; ++i) {
+        const int rt = rb * (2 * RM) + wm * RM + i;
+        if (rt >= g.R) continue;
+#pragma unroll
+        for (int j = 0; j < RN; ++j) {
+            const int tile = cb * B_FR + wn * RN + j;
+            if (tile < n_tiles) prefill_epilogue<EPI>(p, rt, tile, lane, acc[i][j]);
+        }
+    }
+}
+
+// ---- causal attention over the cache for a chunk of rows ----------------------------------------------------------
+struct PrefillAttnArgs {
+    const void* q_frag;  // [n_kv_heads][R*G tiles][head_dim/32][64][8], rotated and scaled by the q/k/v epilogue
+    const void* Kc;      // this layer's cache, fragment order; the chunk's own keys / values are already in it
+    const void* Vt;
+    void* out_op;        // operand of the output projection, R row groups
+    int n_rows, R, n_heads, n_kv_heads, pos0, t_max;
+};
+
+constexpr int kPrefillAttnNT = 2, kPrefillAttnWaves = 4;
+
+// Grid (n_kv_heads, ceil(query tiles / 8)). Query qi = row * G + head % G of KV head kvh sees cache positions
+// 0 .. pos0 + row.
+template <int HD>
+__global__ __launch_bounds__(kPrefillAttnWaves * 64) void prefill_attn_kernel(PrefillAttnArgs a) {
+    constexpr int NT = kPrefillAttnNT, KK = HD / 32, CT = HD / 16;
+    const int kvh = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int G = a.n_heads / a.n_kv_heads, nQ = a.n_rows * G, n_qt = a.R * G;
+    const int t0 = ((int)blockIdx.y * kPrefillAttnWaves + wave) * NT;  // first query tile of this wavefront
+    if (t0 * 16 >= nQ) return;
+    const int m16 = lane & 15, q4 = lane >> 4;
+
+    bf16x8 qf[NT][KK];
+    int limit[NT];
+    {
+        const u32x4* qp = reinterpret_cast<const u32x4*>(a.q_frag) + (size_t)kvh * n_qt * KK * 64 + lane;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int qt = min(t0 + t, n_qt - 1), qi = (t0 + t) * 16 + m16;
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) qf[t][kk] = as_bf16x8(qp[((size_t)qt * KK + kk) * 64]);
+            limit[t] = qi < nQ ? a.pos0 + qi / G : -1;
+        }
+    }
+    // last position any query of the wavefront sees (queries ascend with the tile index)
+    const int last_q = min((t0 + NT) * 16, nQ) - 1;
+    const int nblk = ((a.pos0 + last_q / G) >> 5) + 1;
+
+    AttnState<HD, NT> st;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        st.m[t] = -INFINITY;
+        st.l[t] = 0.f;
+#pragma unroll
+        for (int c = 0; c < CT; ++c) st.o[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const u32x4* Kh = reinterpret_cast<const u32x4*>(reinterpret_cast<const bf16*>(a.Kc) + (size_t)kvh * a.t_max * HD) + lane;
+    const u32x4* Vh = reinterpret_cast<const u32x4*>(reinterpret_cast<const bf16*>(a.Vt) + (size_t)kvh * a.t_max * HD) + lane;
+    auto load_blk = [&](AttnFrags<HD>& f, int blk) {
+        const u32x4* kp = Kh + (size_t)blk * (2 * KK * 64);
+        const u32x4* vp = Vh + (size_t)blk * (CT * 64);
+        attn_load<HD>(f, [&](int u, int kk) { return as_bf16x8(kp[(u * KK + kk) * 64]); },
+                      [&](int c) { return as_bf16x8(vp[c * 64]); });
+    };
+    auto compute_blk = [&](const AttnFrags<HD>& f, int blk) {
+        const int kb = blk << 5;
+        attn_compute<HD, NT>(st, qf, f, [&](int u, int r, int t) { return kb + q4 * 8 + u * 4 + r <= limit[t]; });
+    };
+    AttnFrags<HD> f0, f1;
+    load_blk(f0, 0);
+    for (int blk = 0; blk < nblk; blk += 2) {
+        if (blk + 1 < nblk) load_blk(f1, blk + 1);
+        compute_blk(f0, blk);
+        if (blk + 1 >= nblk) break;
+        if (blk + 2 < nblk) load_blk(f0, blk + 2);
+        compute_blk(f1, blk + 1);
+    }
+
+    // O^T tile: lane holds features c*16 + q4*4 + r of query m16
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        float l = st.l[t];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        const int qi = (t0 + t) * 16 + m16;
+        if (qi >= nQ) continue;
+        const float inv = 1.0f / l;
+        const int row = qi / G, h = kvh * G + qi % G;
+#pragma unroll
+        for (int c = 0; c < CT; ++c)
+            store_operand4<kDtBf16>(a.out_op, a.R, 0, row, h * HD + c * 16 + q4 * 4, st.o[t][c] * inv);
+    }
+}
+
+}  // namespace clasp
