@@ -615,6 +615,12 @@ int draft_forward(clasp_ctx* ctx, const uint8_t* mask, const int32_t* token, int
 }
 
 // ---- prompt processing with many rows per pass ---------------------------------------------------------------------
+#ifndef CLASP_PREFILL_WIDE
+#define CLASP_PREFILL_WIDE 1  // 0: every GEMM takes the 128-column workgroup tile
+#endif
+#ifndef CLASP_PREFILL_NARROW_DEPTH
+#define CLASP_PREFILL_NARROW_DEPTH 2  // k-steps the 128-column kernel requests its operands ahead
+#endif
 constexpr int kPrefillMaxChunk = 8192;
 
 struct PrefillWs {
@@ -641,11 +647,12 @@ size_t carve_prefill(const clasp_config& c, int chunk, char* base, PrefillWs* ws
     return w.off;
 }
 
-// Fewer, fatter workgroups (256 feature columns) when they still fill the chip, else 128 columns.
+// Workgroup tile 128 rows x 128 columns, except the gate|up projection when 256-column tiles still give every CU its
+// two workgroups: its long N makes the fatter tile pay (measured at the 8B shape, 2048 rows: 848 vs 1070 us), while
+// the projections onto d_model lose with it (375 vs 338 us) and the q/k/v epilogue does not fit its register budget.
 template <int EPI>
 int launch_prefill_gemm(const clasp_ctx* ctx, const PrefillGemmArgs& p, hipStream_t st) {
     const int nrb = (p.g.R * 16 + kPrefillRows - 1) / kPrefillRows, tiles = p.g.N / 16;
-    const bool wide = nrb * ((tiles + 15) / 16) >= ctx->n_cu;
     static bool opted_in[2] = {false, false};  // more than 64 KiB of LDS per workgroup has to be requested once per kernel
     auto launch = [&](auto kernel, size_t lds, int col_tiles, bool& opted) -> int {
         if (!opted) {
@@ -658,8 +665,12 @@ int launch_prefill_gemm(const clasp_ctx* ctx, const PrefillGemmArgs& p, hipStrea
         CLASP_LAUNCH_CHECK();
         return CLASP_OK;
     };
-    if (wide) return launch(prefill_gemm_kernel<EPI, 8>, prefill_gemm_lds_bytes<8>(), 16, opted_in[0]);
-    return launch(prefill_gemm_kernel<EPI, 4>, prefill_gemm_lds_bytes<4>(), 8, opted_in[1]);
+    if constexpr (EPI == kEpiSwiglu) {
+        if (CLASP_PREFILL_WIDE && nrb * ((tiles + 15) / 16) >= 2 * ctx->n_cu)
+            return launch(prefill_gemm_kernel<EPI, 8, 1>, prefill_gemm_lds_bytes<8, 1>(), 16, opted_in[0]);
+    }
+    return launch(prefill_gemm_kernel<EPI, 4, CLASP_PREFILL_NARROW_DEPTH>, prefill_gemm_lds_bytes<4, CLASP_PREFILL_NARROW_DEPTH>(), 8,
+                  opted_in[1]);
 }
 
 // The full model over n rows at positions pos0.. (n <= the chunk the workspace was carved for): leaves their keys and
@@ -673,7 +684,7 @@ int prefill_chunk(const clasp_ctx* ctx, const PrefillWs& ws, int ld, const int32
                        static_cast<const bf16*>(ctx->embed), c.vocab, d, ws.h, ws.op_h, R, ctx->attn_norm[0], ws.ss_h, ld);
     CLASP_LAUNCH_CHECK();
     for (int l = 0; l < L; ++l) {
-        hipLaunchKernelGGL(prefill_rstd_kernel, dim3((n + 255) / 256), dim3(256), 0, st, ws.ss_h, d / 16, ld, n, 1.0f / d,
+        hipLaunchKernelGGL(prefill_rstd_kernel, dim3((n + 63) / 64), dim3(64, 4), 0, st, ws.ss_h, d / 16, ld, n, 1.0f / d,
                            c.rms_eps, ws.rstd_h);
         CLASP_LAUNCH_CHECK();
         {
@@ -715,7 +726,7 @@ int prefill_chunk(const clasp_ctx* ctx, const PrefillWs& ws, int ld, const int32
             g.next_op = ws.op_a; g.next_gain = ctx->mlp_norm[l]; g.next_ss = ws.ss_a; p.ld_ss = ld;
             if ((rc = launch_prefill_gemm<kEpiResid>(ctx, p, st))) return rc;
         }
-        hipLaunchKernelGGL(prefill_rstd_kernel, dim3((n + 255) / 256), dim3(256), 0, st, ws.ss_a, d / 16, ld, n, 1.0f / d,
+        hipLaunchKernelGGL(prefill_rstd_kernel, dim3((n + 63) / 64), dim3(64, 4), 0, st, ws.ss_a, d / 16, ld, n, 1.0f / d,
                            c.rms_eps, ws.rstd_a);
         CLASP_LAUNCH_CHECK();
         {

@@ -5,7 +5,8 @@
 //   * prefill_gemm_kernel: workgroup tile 128 rows x (128 | 256) features, 2 x 2 wavefronts, each holding a
 //     64 x (64 | 128) accumulator tile; both operands arrive in MFMA fragment order already (weights as packed for
 //     the decode kernels, activations as the hi/lo operand planes every producer writes), so staging is a copy of
-//     whole KiB fragments: global -> registers -> LDS two k-steps ahead, three LDS stages, one barrier per k-step.
+//     whole KiB fragments: global -> registers -> LDS one k-step ahead, two LDS stages, one barrier per k-step, two
+//     workgroups per CU.
 //     The activations keep the decode path's hi + lo split (two MFMAs per fragment pair), so that the cache a prompt
 //     leaves behind does not depend on how many rows went through at once beyond rounding order.
 //   * prefill_attn_kernel: causal flash attention; a wavefront owns two tiles of 16 queries (row x head of one KV
@@ -26,14 +27,21 @@ struct PrefillGemmArgs {
     int ld_ss;           // row capacity of next_ss: next_ss[tile][ld_ss]
 };
 
-// rstd[row] = 1 / sqrt(sum_p ss[p][row] / dim + eps), parts added in index order.
-__global__ void prefill_rstd_kernel(const float* ss, int n_parts, int ld, int n_rows, float inv_dim, float eps,
-                                    float* rstd) {
-    const int row = blockIdx.x * blockDim.x + threadIdx.x;
-    if (row >= n_rows) return;
+// rstd[row] = 1 / sqrt(sum_p ss[p][row] / dim + eps). Block (64, 4): thread (x, y) adds parts y, y + 4, .. of row
+// blockIdx.x*64 + x (coalesced over rows), the four sums are added in y order.
+__global__ __launch_bounds__(256) void prefill_rstd_kernel(const float* ss, int n_parts, int ld, int n_rows, float inv_dim,
+                                                           float eps, float* rstd) {
+    __shared__ float part[4][64];
+    const int row = blockIdx.x * 64 + threadIdx.x, y = threadIdx.y;
     float s = 0.f;
-    for (int p = 0; p < n_parts; ++p) s += ss[(size_t)p * ld + row];
-    rstd[row] = 1.0f / sqrtf(s * inv_dim + eps);
+    if (row < n_rows)
+        for (int p = y; p < n_parts; p += 4) s += ss[(size_t)p * ld + row];
+    part[y][threadIdx.x] = s;
+    __syncthreads();
+    if (y == 0 && row < n_rows) {
+        const float t = ((part[0][threadIdx.x] + part[1][threadIdx.x]) + part[2][threadIdx.x]) + part[3][threadIdx.x];
+        rstd[row] = 1.0f / sqrtf(t * inv_dim + eps);
+    }
 }
 
 // Embedding gather for a chunk: h_0, the first layer's operand (times its norm gains) and sum-of-squares partials.
@@ -121,23 +129,27 @@ __device__ __forceinline__ void prefill_epilogue(const PrefillGemmArgs& p, int r
 }
 
 constexpr int kPrefillRM = 4;      // 16-row tiles per wavefront
-constexpr int kPrefillStages = 3;  // LDS stages (k-steps)
 constexpr int kPrefillRows = 2 * kPrefillRM * 16;  // rows of a workgroup tile
 
-template <int RN>
+// D = k-steps a stage is requested ahead of its use (register sets in flight); D + 1 LDS stages
+template <int RN, int D>
 constexpr size_t prefill_gemm_lds_bytes() {
-    return (size_t)kPrefillStages * (2 * 2 * kPrefillRM + 2 * RN) * 1024;
+    return (size_t)(D + 1) * (2 * 2 * kPrefillRM + 2 * RN) * 1024;
 }
 
 // Workgroup = 2 x 2 wavefronts; wavefront (wm, wn) accumulates row tiles wm*4 .. +3 times feature tiles wn*RN .. +RN-1
 // of the workgroup tile. Per k-step the workgroup stages 16 activation fragments (8 row tiles x hi/lo) and 2*RN weight
-// fragments of 1 KiB each. Workgroups are numbered so that the ones resident on an XCD at the same time share weight
-// columns: the XCD's L2 then sees each weight fragment from HBM once and serves the sibling row blocks.
-template <int EPI, int RN>
-__global__ __launch_bounds__(256) void prefill_gemm_kernel(PrefillGemmArgs p) {
-    constexpr int RM = kPrefillRM, NSTAGE = kPrefillStages;
+// fragments of 1 KiB each: requested into registers at the top of a k-step, written to a free LDS stage after the
+// MFMAs of the D-th k-step from there (D register sets alternate, D + 1 LDS stages), one barrier per k-step. Two
+// workgroups share a CU (<= 256 registers per lane, <= 80 KiB of LDS each), so one computes while the other waits for
+// LDS, memory or its barrier.
+// Workgroups are numbered so that the ones resident on an XCD at the same time share weight columns: the XCD's L2
+// then sees each weight fragment from HBM once and serves the sibling row blocks.
+template <int EPI, int RN, int D>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_gemm_kernel(PrefillGemmArgs p) {
+    constexpr int RM = kPrefillRM, NSTAGE = D + 1;
     constexpr int A_FR = 2 * 2 * RM, B_FR = 2 * RN, FR = A_FR + B_FR, NL = FR / 4;
-    static_assert(FR % 4 == 0, "fragments are dealt to four wavefronts");
+    static_assert(FR % 4 == 0 && (D == 1 || D == 2), "fragments are dealt to four wavefronts");
     extern __shared__ u32x4 prefill_lds[];  // [NSTAGE][FR][64]
     const GemmArgs& g = p.g;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, wm = w >> 1, wn = w & 1;
@@ -168,9 +180,12 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(PrefillGemmArgs p) {
             step[j] = 64;
         }
     }
-    auto issue = [&](u32x4 (&r)[NL], int s) {
+    auto issue = [&](u32x4 (&r)[NL]) {
 #pragma unroll
-        for (int j = 0; j < NL; ++j) r[j] = src[j][(size_t)s * step[j]];
+        for (int j = 0; j < NL; ++j) {
+            r[j] = *src[j];
+            src[j] += step[j];
+        }
     };
     auto commit = [&](const u32x4 (&r)[NL], int buf) {
 #pragma unroll
@@ -187,38 +202,55 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(PrefillGemmArgs p) {
         u32x4 bf[RN];
 #pragma unroll
         for (int j = 0; j < RN; ++j) bf[j] = L[(A_FR + wn * RN + j) * 64];
+        // the hi / lo pair of the next row tile is requested before this tile's MFMAs are issued (the scheduling
+        // fences keep the compiler from sinking the reads below them): LDS latency hides behind 16 MFMAs
+        u32x4 a_hi = L[(wm * RM * 2) * 64], a_lo = L[(wm * RM * 2 + 1) * 64];
 #pragma unroll
         for (int i = 0; i < RM; ++i) {
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const u32x4 af = L[((wm * RM + i) * 2 + h) * 64];
-#pragma unroll
-                for (int j = 0; j < RN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(af), as_bf16x8(bf[j]), acc[i][j], 0, 0, 0);
+            const u32x4 c_hi = a_hi, c_lo = a_lo;
+            if (i + 1 < RM) {
+                a_hi = L[((wm * RM + i + 1) * 2) * 64];
+                a_lo = L[((wm * RM + i + 1) * 2 + 1) * 64];
             }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < RN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(c_hi), as_bf16x8(bf[j]), acc[i][j], 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < RN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(c_lo), as_bf16x8(bf[j]), acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    // stage s is requested at the top of iteration s-3, committed to LDS at the bottom of iteration s-2 and consumed
-    // in iteration s; two register sets alternate
-    u32x4 r0[NL], r1[NL];
-    issue(r0, 0);
-    if (KS > 1) issue(r1, 1);
+    // stage s is requested at the top of k-step s - D, committed to LDS stage s % (D + 1) after the MFMAs of k-step
+    // s - 1 (the barrier that ended k-step s - 2 freed that stage) and consumed in k-step s
+    u32x4 r0[NL], r1[D == 2 ? NL : 1];
+    issue(r0);
     commit(r0, 0);
-    if (KS > 1) commit(r1, 1);
-    if (KS > 2) issue(r0, 2);
-    __syncthreads();
-    int buf = 0;
-    auto iteration = [&](int s, u32x4 (&cur)[NL], u32x4 (&nxt)[NL]) {  // cur holds stage s+2, nxt is free
-        if (s + 3 < KS) issue(nxt, s + 3);
-        compute(buf);
-        if (s + 2 < KS) commit(cur, buf == 0 ? NSTAGE - 1 : buf - 1);  // (s + 2) % 3 == (s - 1) % 3
+    if constexpr (D == 1) {
         __syncthreads();
-        buf = buf == NSTAGE - 1 ? 0 : buf + 1;
-    };
-    for (int s = 0; s < KS; s += 2) {
-        iteration(s, r0, r1);
-        if (s + 1 < KS) iteration(s + 1, r1, r0);
+        for (int s = 0; s < KS; ++s) {
+            if (s + 1 < KS) issue(r0);
+            compute(s & 1);
+            if (s + 1 < KS) commit(r0, (s + 1) & 1);
+            __syncthreads();
+        }
+    } else {
+        if (KS > 1) issue(r0);  // stage 1
+        __syncthreads();
+        int buf = 0;
+        auto iteration = [&](int s, u32x4 (&cur)[NL], u32x4 (&nxt)[NL]) {  // cur holds stage s + 1, nxt is free
+            if (s + 2 < KS) issue(nxt);
+            compute(buf);
+            buf = buf == NSTAGE - 1 ? 0 : buf + 1;
+            if (s + 1 < KS) commit(cur, buf);
+            __syncthreads();
+        };
+        for (int s = 0; s < KS; s += 2) {
+            iteration(s, r0, r1);
+            if (s + 1 < KS) iteration(s + 1, r1, r0);
+        }
     }
 
 #pragma unroll
