@@ -135,6 +135,10 @@ def main():
     ap.add_argument("--temperature", type=float, default=None,
                     help="closed loop only: stochastic decoding at this temperature (speculative sampling with seeded "
                          "uniform numbers) instead of greedy decoding; reports rounds and acceptance, no token comparison")
+    ap.add_argument("--prefill", type=int, default=0, metavar="N_TOKENS",
+                    help="only time the prompt pass (clasp_prefill) over N_TOKENS synthetic tokens of the workload's "
+                         "model; prints its own JSON line (tokens/s, algorithmic TFLOP/s against the bf16 MFMA peak)")
+    ap.add_argument("--prefill-chunk", type=int, default=2048, help="rows per pass of --prefill (multiple of 128)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="only run plain device copies of a known size (1 GiB read + 1 GiB written per copy), to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -159,6 +163,38 @@ def main():
     wl = WORKLOADS[args.workload]
     shape = si.SHAPES[wl["shape"]]
     T, M, K = wl["T"], wl["M"], wl["K"]
+    if args.prefill:
+        n = args.prefill
+        eng, _ = build_engine(shape, 1, ((n + 31) // 32) * 32, 16)
+        toks = si.gen_tokens(2, n, shape.vocab).cuda()
+        for _ in range(max(1, args.warmup)):
+            eng.clasp_prefill(toks, 0, args.prefill_chunk)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        steps = max(1, args.steps)
+        e0.record()
+        for _ in range(steps):
+            eng.clasp_prefill(toks, 0, args.prefill_chunk)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        # algorithmic flops: every projection of layers 0..L-2 plus the last layer's q/k/v (nothing after it feeds the
+        # cache), 2 flop per weight and row; causal attention 4 * q_dim flop per (query, visible key) pair
+        L, d, F = shape.n_layers, shape.d_model, shape.d_ffn
+        qd, kvd = shape.n_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
+        p_qkv = d * (qd + 2 * kvd)
+        p_layer = p_qkv + qd * d + 3 * d * F
+        flops = 2.0 * n * ((L - 1) * p_layer + p_qkv) + (L - 1) * 4.0 * qd * n * (n + 1) / 2
+        tf = flops / ms / 1e9
+        print(json.dumps({"metric": "prefill_tokens_per_s", "value": round(n / ms * 1e3, 1), "unit": "tokens/s", "n_gpus": 1,
+                          "steps": steps, "warmup": max(1, args.warmup), "ms_per_step": round(ms, 3),
+                          "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": f"{shape.name}/prefill{n}/chunk{args.prefill_chunk}"},
+                          "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                                       "frac": round(tf / 2500.0, 4), "traffic": None,
+                                       "note": "algorithmic flops; activations enter as bf16 hi + lo, so the matrix "
+                                               "cores execute twice the GEMM flops counted here"}}))
+        return
     if args.closed_loop:
         n_gen = args.closed_loop
         max_seq = ((T + n_gen + K + 2 + 31) // 32) * 32
