@@ -135,6 +135,10 @@ def main():
     ap.add_argument("--temperature", type=float, default=None,
                     help="closed loop only: stochastic decoding at this temperature (speculative sampling with seeded "
                          "uniform numbers) instead of greedy decoding; reports rounds and acceptance, no token comparison")
+    ap.add_argument("--markov-study", action="store_true",
+                    help="only run the comparison of the paper's Sec. 3.5 on the workload's model: first and last 10/32 "
+                         "of the layers fixed, skip sets of the layers between chosen by brute force, at random and by "
+                         "the dynamic program; cosine of the resulting last hidden state with the full model's")
     ap.add_argument("--prefill", type=int, default=0, metavar="N_TOKENS",
                     help="only time the prompt pass (clasp_prefill) over N_TOKENS synthetic tokens of the workload's "
                          "model; prints its own JSON line (tokens/s, algorithmic TFLOP/s against the bf16 MFMA peak)")
@@ -163,6 +167,22 @@ def main():
     wl = WORKLOADS[args.workload]
     shape = si.SHAPES[wl["shape"]]
     T, M, K = wl["T"], wl["M"], wl["K"]
+    if args.markov_study:
+        eng, _ = build_engine(shape, 1, ((T + 64 + 31) // 32) * 32, 16, resid_scale=args.resid_scale)
+        Kp, Vp = si.gen_kv(shape, 3, 1, T, "cuda")
+        for l in range(shape.n_layers):
+            eng.clasp_kv_load(l, Kp[0], Vp[0])
+        tok = si.gen_tokens(2, 1, shape.vocab, stream=9).cuda()
+        states = eng.clasp_verify_forward(tok, T, want_hidden=True)["hidden"][:, 0].contiguous()
+        lo = 10 * shape.n_layers // 32
+        hi = shape.n_layers - lo
+        budgets = [m for m in (2, 4, 6, 8, 10) if m < hi - lo]
+        t0 = time.perf_counter()
+        rows = decode.markov_study(eng, states, tok, T, lo, hi, budgets)
+        torch.cuda.synchronize()
+        print(json.dumps({"markov_study": args.workload, "resid_scale": args.resid_scale, "window": [lo, hi],
+                          "seconds": round(time.perf_counter() - t0, 2), "rows": rows}))
+        return
     if args.prefill:
         n = args.prefill
         eng, _ = build_engine(shape, 1, ((n + 31) // 32) * 32, 16)

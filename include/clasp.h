@@ -159,6 +159,28 @@ int clasp_dp_select(clasp_ctx *ctx, const float *states, size_t layer_stride, in
                     float *score_out, uint8_t *choice_out, float *g_final_out, void *stream);
 
 /*
+ * The same search restricted to the layers layer_lo .. layer_hi-1 (Sec. 3.5 fixes the first and last layers of the
+ * model and searches the ones between): layers outside the window are always kept, the dynamic program starts from
+ * state layer_lo and matches states layer_lo+1 .. layer_hi; M <= layer_hi - layer_lo. mask_out covers all n_layers;
+ * score_out / choice_out are [(layer_hi-layer_lo+1)][(M+1)]([2]) tables indexed from the window's first layer.
+ * clasp_dp_select is this call with the window 0 .. n_layers.
+ */
+int clasp_dp_select_window(clasp_ctx *ctx, const float *states, size_t layer_stride, int pos, int M, int layer_lo,
+                           int layer_hi, uint8_t *mask_out, float *score_out, uint8_t *choice_out, float *g_final_out,
+                           void *stream);
+
+/*
+ * The objective of Eq. 1 for given skip sets (what Sec. 3.5 compares between brute-force search, random choice and
+ * the dynamic program): for each of n_masks masks, the token goes through the layers the mask keeps at position
+ * `pos` (as in clasp_draft_step, including the write of its key/value at `pos` in the kept layers), and the cosine
+ * of the resulting last hidden state (before the final norm) with `target` is stored.
+ *   masks    host uint8 [n_masks][n_layers], 1 = skip;  token dev int32 [1];  target dev fp32 [d_model]
+ *   cos_out  dev fp32 [n_masks]: <h, target> / (max(|h|, 1e-12) max(|target|, 1e-12))
+ */
+int clasp_skip_cosine(clasp_ctx *ctx, const uint8_t *masks, int n_masks, const int32_t *token, int pos,
+                      const float *target, float *cos_out, void *stream);
+
+/*
  * Drafting (Sec. 3.1 stage 1, Sec. 3.3): one token through the layers the skip set keeps, at position `pos`,
  * attending cache positions 0..pos-1; writes the token's key/value at `pos` into the kept layers' caches only.
  *   mask           host uint8 [n_layers], 1 = skip (NULL = keep all)

@@ -73,6 +73,12 @@ def cosine(a: np.ndarray, b: np.ndarray) -> float:
 class KVCache:
     """The full model's keys (rotated) and values: float64 [n_layers][t_max][n_kv_heads][head_dim]."""
 
+    def window(self, lo: int, hi: int) -> "KVCache":
+        """View of the layers lo..hi-1 (shares memory), for OracleModel.window."""
+        v = KVCache.__new__(KVCache)
+        v.K, v.V, v.t_max = self.K[lo:hi], self.V[lo:hi], self.t_max
+        return v
+
     def __init__(self, shape, t_max: int):
         dims = (shape.n_layers, t_max, shape.n_kv_heads, shape.head_dim)
         self.K = np.zeros(dims, dtype=np.float64)
@@ -170,6 +176,30 @@ class OracleModel:
         if rc:
             raise ValueError("clasp_oracle_dp: bad argument")
         return {"sigma_c": sc, "sigma_s": ss, "choice": ch, "g_final": gf, "mask": mask}
+
+    # ---- the search restricted to a window of layers, and the objective of a given skip set (Sec. 3.5) ------------
+    def window(self, lo: int, hi: int) -> "OracleModel":
+        """The layers lo..hi-1 as a model of their own (same weights): its dp() is Algorithm 1 with every layer outside
+        the window kept, on states X[lo..hi] and the cache of those layers (cache_window)."""
+        if not (0 <= lo < hi <= self.shape.n_layers):
+            raise ValueError("window out of range")
+        import dataclasses
+        w = dict(self.w)
+        w["layers"] = self.w["layers"][lo:hi]
+        return OracleModel(dataclasses.replace(self.shape, n_layers=hi - lo), w)
+
+    def masked_state(self, x0: np.ndarray, pos: int, cache: KVCache, mask: Sequence[int]) -> np.ndarray:
+        """x_0 through the layers a skip set keeps, each attending the cache rows 0..pos-1 of its layer plus its own
+        key/value (the context of the candidates in Algorithm 1): the state the draft model would hand to the head."""
+        h = np.array(x0, dtype=np.float64)
+        for l in range(self.shape.n_layers):
+            if not mask[l]:
+                h, _, _ = self.layer(l, h, pos, pos, cache.K[l], cache.V[l])
+        return h
+
+    def skip_cosine(self, x0: np.ndarray, pos: int, cache: KVCache, mask: Sequence[int], target: np.ndarray) -> float:
+        """Eq. 1's objective for one skip set: cosine of masked_state with the full model's last hidden state."""
+        return cosine(self.masked_state(x0, pos, cache, mask), np.asarray(target, dtype=np.float64))
 
     # ---- loops --------------------------------------------------------------------------------------------
     def prefill(self, tokens: Sequence[int], cache: KVCache, pos0: int = 0):

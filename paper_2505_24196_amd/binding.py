@@ -18,7 +18,7 @@ CLASP_F32, CLASP_BF16 = 0, 1
 EXPORTS = ("clasp_strerror", "clasp_packed_bytes", "clasp_pack_matrix", "clasp_pack_gate_up", "clasp_workspace_bytes",
            "clasp_kv_cache_bytes", "clasp_create", "clasp_destroy", "clasp_verify_forward", "clasp_dp_select",
            "clasp_draft_step", "clasp_sample_token", "clasp_draft_sample", "clasp_spec_accept", "clasp_kv_load",
-           "clasp_kv_read", "clasp_prefill_workspace_bytes", "clasp_prefill",
+           "clasp_kv_read", "clasp_prefill_workspace_bytes", "clasp_prefill", "clasp_dp_select_window", "clasp_skip_cosine",
            "clasp_kernel_timer_begin", "clasp_kernel_timer_end")
 
 KERNEL_KINDS = {"qkv": 0, "attention": 1, "o_proj": 2, "gate_up": 3, "down": 4, "lm_head": 5}
@@ -66,6 +66,8 @@ def lib():
         l.clasp_destroy.argtypes = [vp]
         l.clasp_verify_forward.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp]
         l.clasp_dp_select.argtypes = [vp, vp, sz, i32, i32, vp, vp, vp, vp, vp]
+        l.clasp_dp_select_window.argtypes = [vp, vp, sz, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+        l.clasp_skip_cosine.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp]
         l.clasp_draft_step.argtypes = [vp, vp, vp, i32, vp, vp, vp]
         l.clasp_sample_token.argtypes = [vp, vp, C.c_float, vp, vp, vp]
         l.clasp_draft_sample.argtypes = [vp, vp, vp, i32, C.c_float, vp, vp, vp, vp]
@@ -274,6 +276,36 @@ class Engine:
         _check(lib().clasp_dp_select(self._ctx, states.data_ptr(), states.stride(0), pos, M, _ptr(out["mask"]),
                                      _ptr(out.get("scores")), _ptr(out.get("choice")), _ptr(out.get("g_final")),
                                      _stream()), "clasp_dp_select")
+        return out
+
+    def clasp_dp_select_window(self, states: torch.Tensor, pos: int, M: int, layer_lo: int, layer_hi: int,
+                               want_tables: bool = False):
+        """clasp_dp_select over the layers layer_lo..layer_hi-1 only. states: device fp32 [L+1][d]. Returns dict(mask
+        [L], scores?, choice? ([layer_hi-layer_lo+1][M+1]), g_final?)."""
+        s = self.shape
+        L, Lw = s.n_layers, layer_hi - layer_lo
+        if states.dtype != torch.float32 or not states.is_cuda or states.stride(1) != 1 or states.shape != (L + 1, s.d_model):
+            raise ClaspError("states must be device fp32 [L+1][d] with unit inner stride")
+        out = {"mask": torch.empty(L, dtype=torch.uint8, device=self.device)}
+        if want_tables and Lw > 0:
+            out["scores"] = torch.empty(Lw + 1, M + 1, 2, dtype=torch.float32, device=self.device)
+            out["choice"] = torch.empty(Lw + 1, M + 1, dtype=torch.uint8, device=self.device)
+            out["g_final"] = torch.empty(s.d_model, dtype=torch.float32, device=self.device)
+        _check(lib().clasp_dp_select_window(self._ctx, states.data_ptr(), states.stride(0), pos, M, layer_lo, layer_hi,
+                                            _ptr(out["mask"]), _ptr(out.get("scores")), _ptr(out.get("choice")),
+                                            _ptr(out.get("g_final")), _stream()), "clasp_dp_select_window")
+        return out
+
+    def clasp_skip_cosine(self, masks, token: torch.Tensor, pos: int, target: torch.Tensor) -> torch.Tensor:
+        """masks: host array-like [n][L] of 0/1 (1 = skip); token: device int32 [1]; target: device fp32 [d]. Returns
+        the device fp32 [n] cosines of the masked forwards' last hidden states with target."""
+        import numpy as np
+        m = np.ascontiguousarray(np.asarray(masks, dtype=np.uint8))
+        if m.ndim != 2 or m.shape[1] != self.shape.n_layers or m.shape[0] < 1:
+            raise ClaspError("masks must be [n][n_layers]")
+        out = torch.empty(m.shape[0], dtype=torch.float32, device=self.device)
+        _check(lib().clasp_skip_cosine(self._ctx, m.ctypes.data, m.shape[0], _ptr(token, torch.int32), pos,
+                                       _ptr(target, torch.float32), _ptr(out), _stream()), "clasp_skip_cosine")
         return out
 
     def clasp_draft_step(self, mask: Optional[Sequence[int]], token: torch.Tensor, pos: int,

@@ -593,12 +593,10 @@ int run_head(const clasp_ctx* ctx, int n, int R, float* logits_out, int32_t* arg
     return CLASP_OK;
 }
 
-// The layers a skip set keeps on one row at position `pos`, then the head: greedy token (+ top-1 probability) and / or
-// the logits.
-int draft_forward(clasp_ctx* ctx, const uint8_t* mask, const int32_t* token, int pos, float* logits_out,
-                         int32_t* argmax_out, float* top1_prob_out, hipStream_t st) {
-    const clasp_config& c = ctx->cfg;
-    const int L = c.n_layers;
+// The layers a skip set keeps on one row at position `pos`. Returns the index of the ctx->h buffer that holds the
+// result (the state before the final norm); op_h / ss_h hold its operand for the head.
+int masked_layers(clasp_ctx* ctx, const uint8_t* mask, const int32_t* token, int pos, hipStream_t st, int* h_index) {
+    const int L = ctx->cfg.n_layers;
     std::vector<int> kept;
     for (int l = 0; l < L; ++l)
         if (!mask || !mask[l]) kept.push_back(l);
@@ -611,7 +609,65 @@ int draft_forward(clasp_ctx* ctx, const uint8_t* mask, const int32_t* token, int
                             nullptr, st)))
             return rc;
     }
+    *h_index = (int)(kept.size() & 1);
+    return CLASP_OK;
+}
+
+// ... then the head: greedy token (+ top-1 probability) and / or the logits.
+int draft_forward(clasp_ctx* ctx, const uint8_t* mask, const int32_t* token, int pos, float* logits_out,
+                  int32_t* argmax_out, float* top1_prob_out, hipStream_t st) {
+    int h_index = 0;
+    const int rc = masked_layers(ctx, mask, token, pos, st, &h_index);
+    if (rc) return rc;
     return run_head(ctx, 1, 1, logits_out, argmax_out, nullptr, top1_prob_out, st);
+}
+
+// Algorithm 1 over the layers lo .. hi-1 (tables indexed from the window's first layer), everything outside kept.
+int dp_select_window(clasp_ctx* ctx, const float* states, size_t layer_stride, int pos, int M, int lo, int hi,
+                     uint8_t* mask_out, float* score_out, uint8_t* choice_out, float* g_final_out, hipStream_t st) {
+    const clasp_config& c = ctx->cfg;
+    const int L = hi - lo, d = c.d_model;
+    const int R = M > 16 ? 2 : 1;
+    const int down_split = (c.dtype == CLASP_BF16 && c.d_ffn / 32 >= CLASP_DOWNP_KS * CLASP_DOWNP_KW * 4) ? CLASP_DOWNP_KS : 1;
+    uint8_t* choice = choice_out ? choice_out : ctx->choice;
+    const int cells = (L + 1) * (M + 1);
+    hipLaunchKernelGGL(dp_table_init_kernel, dim3((cells + 255) / 256), dim3(256), 0, st, score_out, choice, cells);
+    CLASP_LAUNCH_CHECK();
+    const float* x0 = states + (size_t)lo * layer_stride;
+    int rc;
+    for (int i = 1; i <= L; ++i) {
+        const int ell = (i - 1 < M) ? i - 1 : M;
+        const float* g_prev = (i == 1) ? x0 : ctx->g[(i - 1) & 1];
+        float* g_cur = ctx->g[i & 1];
+        if (ell > 0) {  // candidates g(i-1, 1..ell) through the window's layer i-1, all at position `pos`
+            if ((rc = run_layer(ctx, lo + i - 1, ell, R, 0, pos, g_prev + d, ctx->G, nullptr, nullptr, nullptr, nullptr, st,
+                                down_split)))
+                return rc;
+        }
+        SelectArgs s{};
+        s.i = i; s.M = M; s.d = d; s.R = R;
+        s.x_i = x0 + (size_t)i * layer_stride;
+        s.g_prev = g_prev; s.g_cur = g_cur;
+        if (down_split > 1) {  // candidates = residual rows (a_buf) + the K-slices the down projection left behind
+            s.G = ctx->a_buf; s.parts = ctx->down_parts; s.n_parts = down_split; s.part_stride = (size_t)kMaxRows * d;
+        } else {
+            s.G = ctx->G;
+        }
+        s.op = (i < L) ? ctx->op_h : nullptr;
+        s.gain = (i < L) ? ctx->attn_norm[lo + i] : nullptr;
+        s.ss = ctx->ss_h;
+        s.scores = score_out; s.choice = choice;
+        const int cells_i = ((i < M) ? i : M) + 1;
+        if (c.dtype == CLASP_BF16)
+            hipLaunchKernelGGL((dp_select_kernel<kDtBf16>), dim3(cells_i), dim3(1024), 0, st, s);
+        else
+            hipLaunchKernelGGL((dp_select_kernel<kDtF32>), dim3(cells_i), dim3(1024), 0, st, s);
+        CLASP_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(dp_backtrack_kernel, dim3(2), dim3(256), 0, st, choice, L, M, mask_out, lo, c.n_layers,
+                       ctx->g[L & 1], g_final_out, d);
+    CLASP_LAUNCH_CHECK();
+    return CLASP_OK;
 }
 
 // ---- prompt processing with many rows per pass ---------------------------------------------------------------------
@@ -1044,54 +1100,39 @@ int clasp_spec_accept(clasp_ctx* ctx, const float* p_logits, const float* q_logi
     return CLASP_OK;
 }
 
-int clasp_dp_select(clasp_ctx* ctx, const float* states, size_t layer_stride, int pos, int M, uint8_t* mask_out,
-                    float* score_out, uint8_t* choice_out, float* g_final_out, void* stream) {
+int clasp_dp_select_window(clasp_ctx* ctx, const float* states, size_t layer_stride, int pos, int M, int layer_lo,
+                           int layer_hi, uint8_t* mask_out, float* score_out, uint8_t* choice_out, float* g_final_out,
+                           void* stream) {
     if (!ctx || !states || !mask_out) return CLASP_E_INVALID_ARG;
     const clasp_config& c = ctx->cfg;
-    const int L = c.n_layers, d = c.d_model;
-    if (M < 0 || M > L || M > c.max_rows || pos < 0 || pos >= c.max_seq || layer_stride < (size_t)d)
+    if (layer_lo < 0 || layer_hi > c.n_layers || layer_lo >= layer_hi) return CLASP_E_INVALID_ARG;
+    if (M < 0 || M > layer_hi - layer_lo || M > c.max_rows || pos < 0 || pos >= c.max_seq || layer_stride < (size_t)c.d_model)
         return CLASP_E_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(states) & 15) || (layer_stride & 3)) return CLASP_E_INVALID_ARG;  // float4 loads
+    return dp_select_window(ctx, states, layer_stride, pos, M, layer_lo, layer_hi, mask_out, score_out, choice_out,
+                            g_final_out, static_cast<hipStream_t>(stream));
+}
+
+int clasp_dp_select(clasp_ctx* ctx, const float* states, size_t layer_stride, int pos, int M, uint8_t* mask_out,
+                    float* score_out, uint8_t* choice_out, float* g_final_out, void* stream) {
+    if (!ctx) return CLASP_E_INVALID_ARG;
+    return clasp_dp_select_window(ctx, states, layer_stride, pos, M, 0, ctx->cfg.n_layers, mask_out, score_out, choice_out,
+                                  g_final_out, stream);
+}
+
+int clasp_skip_cosine(clasp_ctx* ctx, const uint8_t* masks, int n_masks, const int32_t* token, int pos, const float* target,
+                      float* cos_out, void* stream) {
+    if (!ctx || !masks || !token || !target || !cos_out || n_masks < 1) return CLASP_E_INVALID_ARG;
+    if (pos < 0 || pos >= ctx->cfg.max_seq) return CLASP_E_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int R = M > 16 ? 2 : 1;
-    const int down_split = (c.dtype == CLASP_BF16 && c.d_ffn / 32 >= CLASP_DOWNP_KS * CLASP_DOWNP_KW * 4) ? CLASP_DOWNP_KS : 1;
-    uint8_t* choice = choice_out ? choice_out : ctx->choice;
-    const int cells = (L + 1) * (M + 1);
-    hipLaunchKernelGGL(dp_table_init_kernel, dim3((cells + 255) / 256), dim3(256), 0, st, score_out, choice, cells);
-    CLASP_LAUNCH_CHECK();
-    int rc;
-    for (int i = 1; i <= L; ++i) {
-        const int ell = (i - 1 < M) ? i - 1 : M;
-        const float* g_prev = (i == 1) ? states : ctx->g[(i - 1) & 1];
-        float* g_cur = ctx->g[i & 1];
-        if (ell > 0) {  // candidates g(i-1, 1..ell) through layer i-1, all at position `pos`
-            if ((rc = run_layer(ctx, i - 1, ell, R, 0, pos, g_prev + d, ctx->G, nullptr, nullptr, nullptr, nullptr, st,
-                                down_split)))
-                return rc;
-        }
-        SelectArgs s{};
-        s.i = i; s.M = M; s.d = d; s.R = R;
-        s.x_i = states + (size_t)i * layer_stride;
-        s.g_prev = g_prev; s.g_cur = g_cur;
-        if (down_split > 1) {  // candidates = residual rows (a_buf) + the K-slices the down projection left behind
-            s.G = ctx->a_buf; s.parts = ctx->down_parts; s.n_parts = down_split; s.part_stride = (size_t)kMaxRows * d;
-        } else {
-            s.G = ctx->G;
-        }
-        s.op = (i < L) ? ctx->op_h : nullptr;
-        s.gain = (i < L) ? ctx->attn_norm[i] : nullptr;
-        s.ss = ctx->ss_h;
-        s.scores = score_out; s.choice = choice;
-        const int cells_i = ((i < M) ? i : M) + 1;
-        if (c.dtype == CLASP_BF16)
-            hipLaunchKernelGGL((dp_select_kernel<kDtBf16>), dim3(cells_i), dim3(1024), 0, st, s);
-        else
-            hipLaunchKernelGGL((dp_select_kernel<kDtF32>), dim3(cells_i), dim3(1024), 0, st, s);
+    const int L = ctx->cfg.n_layers;
+    for (int m = 0; m < n_masks; ++m) {
+        int h_index = 0;
+        const int rc = masked_layers(ctx, masks + (size_t)m * L, token, pos, st, &h_index);
+        if (rc) return rc;
+        hipLaunchKernelGGL(cosine_kernel, dim3(1), dim3(1024), 0, st, ctx->h[h_index], target, ctx->cfg.d_model, cos_out + m);
         CLASP_LAUNCH_CHECK();
     }
-    hipLaunchKernelGGL(dp_backtrack_kernel, dim3(2), dim3(256), 0, st, choice, L, M, mask_out, ctx->g[L & 1],
-                       g_final_out, d);
-    CLASP_LAUNCH_CHECK();
     return CLASP_OK;
 }
 

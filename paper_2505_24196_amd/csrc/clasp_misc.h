@@ -237,16 +237,18 @@ __global__ void dp_table_init_kernel(float* scores, uint8_t* choice, int cells) 
 }
 
 // Backtracking from (L, M): a kept skip candidate at (i, j) means layer i-1 is skipped.
-__global__ void dp_backtrack_kernel(const uint8_t* choice, int L, int M, uint8_t* mask, const float* g_last,
-                                    float* g_final, int d) {
+// The tables cover the L layers of the searched window, which starts at layer `lo` of the model's L_all layers; the
+// mask covers all of them (layers outside the window are never skipped).
+__global__ void dp_backtrack_kernel(const uint8_t* choice, int L, int M, uint8_t* mask, int lo, int L_all,
+                                    const float* g_last, float* g_final, int d) {
     if (blockIdx.x == 0) {
-        for (int l = threadIdx.x; l < L; l += blockDim.x) mask[l] = 0;
+        for (int l = threadIdx.x; l < L_all; l += blockDim.x) mask[l] = 0;
         __syncthreads();
         if (threadIdx.x == 0) {
             int i = L, j = M;
             while (i > 0 && j > 0) {
                 if (choice[(size_t)i * (M + 1) + j] == 1) {
-                    mask[i - 1] = 1;
+                    mask[lo + i - 1] = 1;
                     --j;
                 }
                 --i;
@@ -255,6 +257,23 @@ __global__ void dp_backtrack_kernel(const uint8_t* choice, int L, int M, uint8_t
     } else if (g_final) {
         for (int c = threadIdx.x; c < d; c += blockDim.x) g_final[c] = g_last[(size_t)M * d + c];
     }
+}
+
+// ---- cosine of two vectors (the DP's objective, Eq. 1, for a given skip set) ------------------------------------------
+// out[0] = <a, b> / (max(|a|, 1e-12) max(|b|, 1e-12)), fixed-order sums. One workgroup.
+__global__ __launch_bounds__(1024) void cosine_kernel(const float* a, const float* b, int d, float* out) {
+    __shared__ float red[16];
+    float ab = 0.f, aa = 0.f, bb = 0.f;
+    for (int c = threadIdx.x; c < d; c += 1024) {
+        const float x = a[c], y = b[c];
+        ab += x * y;
+        aa += x * x;
+        bb += y * y;
+    }
+    ab = block_sum(ab, red);
+    aa = block_sum(aa, red);
+    bb = block_sum(bb, red);
+    if (threadIdx.x == 0) out[0] = ab / (fmaxf(sqrtf(aa), 1e-12f) * fmaxf(sqrtf(bb), 1e-12f));
 }
 
 // ---- greedy head ----------------------------------------------------------------------------------------------

@@ -165,3 +165,31 @@ def skip_set_jaccard(masks: Sequence[Sequence[int]], max_gap: int = 8) -> List[f
             break
         curve.append(sum(1.0 if not (a | b) else len(a & b) / len(a | b) for a, b in pairs) / len(pairs))
     return curve
+
+
+def markov_study(engine: Engine, states: torch.Tensor, token: torch.Tensor, pos: int, layer_lo: int, layer_hi: int,
+                 budgets: Sequence[int], n_random: int = 32, seed: int = 0) -> List[Dict[str, object]]:
+    """The comparison of Sec. 3.5 (approximate Markov property): with the layers outside layer_lo..layer_hi-1 fixed,
+    the cosine between the full model's last hidden state (states[L]) and the one a skip set of size M produces, for
+    the set the dynamic program selects, for the best of all C(window, M) sets (brute force) and for random sets.
+    states: device fp32 [L+1][d] of the token (device int32 [1]) at position pos. Host side: enumeration only."""
+    import itertools
+    import random
+    L = engine.shape.n_layers
+    target = states[L].contiguous()
+    rng = random.Random(seed)
+    rows = []
+    for M in budgets:
+        combos = list(itertools.combinations(range(layer_lo, layer_hi), M))
+        masks = [[1 if l in c else 0 for l in range(L)] for c in map(set, combos)]
+        cos = engine.clasp_skip_cosine(masks, token, pos, target).cpu()
+        best = int(torch.argmax(cos))
+        dp_mask = engine.clasp_dp_select_window(states, pos, M, layer_lo, layer_hi)["mask"].cpu().tolist()
+        dp_cos = float(engine.clasp_skip_cosine([dp_mask], token, pos, target).cpu()[0])
+        picks = [rng.randrange(len(combos)) for _ in range(n_random)]
+        rnd = cos[picks]
+        rows.append({"M": M, "sets": len(combos), "brute_force_cos": float(cos[best]), "brute_force_set": list(combos[best]),
+                     "dp_cos": dp_cos, "dp_set": [l for l in range(L) if dp_mask[l]],
+                     "dp_rank": int((cos > dp_cos + 1e-7).sum()) + 1,
+                     "random_mean_cos": float(rnd.mean()), "random_min_cos": float(rnd.min())})
+    return rows

@@ -444,3 +444,60 @@ def test_budget_equal_to_depth_and_last_cache_position():
     import paper_2505_24196_amd as clasp
     with pytest.raises(clasp.ClaspError):
         eng.clasp_verify_forward(dev([1, 2], torch.int32), 63)  # second row would sit at max_seq
+
+
+# ---- window search and the objective of given skip sets (Sec. 3.5) -----------------------------------------------
+@pytest.mark.parametrize("name,resid_scale,lo,hi,M", [("tiny-f32", 0.05, 2, 6, 2), ("small-bf16-deep", 0.05, 8, 16, 4),
+                                                     ("small-bf16-deep", 1.0, 6, 18, 5)])
+def test_window_search_matches_oracle(name, resid_scale, lo, hi, M):
+    shape = si.SHAPES[name]
+    om, eng = oracle_model(name, 1, resid_scale), engine(name, 1, resid_scale)
+    toks = prompt(shape, 12)
+    cache, ost, _ = oracle_prefill(om, toks, 16)
+    tt = dev(toks, torch.int32)
+    eng.clasp_verify_forward(tt, 0)
+    pos, X = 11, ost[:, 11]
+    gpu = eng.clasp_dp_select_window(dev(X), pos, M, lo, hi, want_tables=True)
+    omw, cw = om.window(lo, hi), cache.window(lo, hi)
+    g_choice = gpu["choice"].cpu().numpy()
+    ov = np.full((hi - lo + 1, M + 1), -1, dtype=np.int8)
+    for _ in range(16):
+        ref = omw.dp(X[lo:hi + 1], pos, cw, M, override=ov)
+        diff = np.argwhere(ref["choice"] != g_choice)
+        if diff.size == 0:
+            break
+        for i, j in diff:
+            assert abs(ref["sigma_c"][i, j] - ref["sigma_s"][i, j]) <= COS_MARGIN, f"choice differs at ({i},{j})"
+            ov[i, j] = g_choice[i, j]
+    else:
+        raise AssertionError("device and oracle choices do not converge")
+    sc = gpu["scores"].cpu().numpy().astype(np.float64)
+    for k, key in enumerate(("sigma_c", "sigma_s")):
+        assert np.array_equal(np.isnan(sc[..., k]), np.isnan(ref[key])), key
+        assert np.nanmax(np.abs(sc[..., k] - ref[key])) <= COS_TOL, key
+    mask = gpu["mask"].cpu().numpy()
+    assert mask[lo:hi].tolist() == ref["mask"].tolist() and mask.sum() == M
+    assert not mask[:lo].any() and not mask[hi:].any()
+    assert relerr(gpu["g_final"].cpu().numpy(), ref["g_final"]) <= HID_TOL[shape.dtype]
+
+
+@pytest.mark.parametrize("name,resid_scale", [("tiny-f32", 1.0), ("small-bf16", 0.05), ("small-bf16-hd128", 1.0)])
+def test_skip_cosine_matches_oracle(name, resid_scale):
+    """Every skip set of two layers, the empty set and the full set: cosines of the masked forward's last state."""
+    import itertools
+    shape = si.SHAPES[name]
+    L = shape.n_layers
+    om, eng = oracle_model(name, 1, resid_scale), engine(name, 1, resid_scale)
+    toks = prompt(shape, 10)
+    cache, ost, _ = oracle_prefill(om, toks, 16)
+    tt = dev(toks, torch.int32)
+    eng.clasp_verify_forward(tt, 0)
+    pos, X = 9, ost[:, 9]
+    masks = [[0] * L, [1] * L] + [[1 if l in c else 0 for l in range(L)] for c in itertools.combinations(range(L), 2)]
+    got = eng.clasp_skip_cosine(masks, tt[9:10], pos, dev(X[L])).cpu().numpy()
+    ref = np.array([om.skip_cosine(X[0], pos, cache, m, X[L]) for m in masks])
+    assert np.abs(got - ref).max() <= COS_TOL, np.abs(got - ref).max()
+    assert abs(got[0] - 1.0) <= COS_TOL
+    # the masked forward leaves the full model's cache rows below pos alone: the verify states are reproduced after it
+    out = eng.clasp_verify_forward(tt[9:10], pos, want_hidden=True)
+    assert relerr(out["hidden"][:, 0].cpu().numpy(), X) <= HID_TOL[shape.dtype]

@@ -242,3 +242,61 @@ def test_draft_exiting_threshold_shortens_rounds_and_stays_lossless(thr):
     if thr == 0.0026:  # about the median confidence of this random-init model (vocab 1024): rounds of mixed length
         lens = [len(r["drafts"]) for r in spec["rounds"]]
         assert min(lens) < K and max(lens) > 1
+
+
+# ---- the search restricted to a window of layers, and the objective of a given skip set (Sec. 3.5) -------------------
+def test_window_over_all_layers_is_the_plain_search():
+    T, M = 7, 3
+    om, shape, cache, X = _setup("tiny-f32", T, 0.05)
+    a = om.dp(X, T - 1, cache, M)
+    b = om.window(0, shape.n_layers).dp(X, T - 1, cache.window(0, shape.n_layers), M)
+    for k in ("sigma_c", "sigma_s", "choice", "g_final", "mask"):
+        assert np.array_equal(a[k], b[k], equal_nan=True), k
+
+
+@pytest.mark.parametrize("resid_scale", [1.0, 0.05])
+def test_window_search_replays_and_is_bounded_by_brute_force(resid_scale):
+    """Window 2..6 of the 8 layers: the window's skip set replayed from x_2 reproduces g; pushing it on through the
+    kept layers 6, 7 gives the state whose cosine with x_L brute force over the window's C(4, 2) sets can only beat
+    when it is evaluated on the same objective (cosine at the end of the window)."""
+    T, M, lo, hi = 6, 2, 2, 6
+    om, shape, cache, X = _setup("tiny-f32", T, resid_scale)
+    L, pos = shape.n_layers, T - 1
+    res = om.window(lo, hi).dp(X[lo:hi + 1], pos, cache.window(lo, hi), M)
+    assert int(res["mask"].sum()) == M and res["mask"].shape == (hi - lo,)
+    full_mask = np.zeros(L, dtype=np.uint8)
+    full_mask[lo:hi] = res["mask"]
+    h = X[lo].copy()
+    for l in range(lo, hi):
+        if not full_mask[l]:
+            h, _, _ = om.layer(l, h, pos, pos, cache.K[l], cache.V[l])
+    assert np.array_equal(h, res["g_final"])
+    d_win = np.nanmax([res["sigma_c"][hi - lo, M], res["sigma_s"][hi - lo, M]])
+    assert _np_cos(h, X[hi]) == pytest.approx(d_win, abs=1e-12)
+    # masked_state from x_0 passes through the kept layers 0, 1 (reproducing x_2), the window, then 6, 7
+    end = om.masked_state(X[0], pos, cache, full_mask)
+    tail = h.copy()
+    for l in range(hi, L):
+        tail, _, _ = om.layer(l, tail, pos, pos, cache.K[l], cache.V[l])
+    np.testing.assert_allclose(end, tail, rtol=1e-12, atol=1e-13)
+    assert om.skip_cosine(X[0], pos, cache, full_mask, X[L]) == pytest.approx(_np_cos(end, X[L]), abs=1e-12)
+    best = -2.0
+    for comb in itertools.combinations(range(lo, hi), M):
+        m = np.zeros(L, dtype=np.uint8)
+        m[list(comb)] = 1
+        g = X[lo].copy()
+        for l in range(lo, hi):
+            if not m[l]:
+                g, _, _ = om.layer(l, g, pos, pos, cache.K[l], cache.V[l])
+        best = max(best, _np_cos(g, X[hi]))
+    assert best >= d_win - 1e-12
+
+
+def test_skip_cosine_closed_forms():
+    T = 5
+    om, shape, cache, X = _setup("tiny-f32", T)
+    L, pos = shape.n_layers, T - 1
+    none, every = np.zeros(L, dtype=np.uint8), np.ones(L, dtype=np.uint8)
+    assert om.skip_cosine(X[0], pos, cache, none, X[L]) == pytest.approx(1.0, abs=1e-12)   # nothing skipped: x_L itself
+    assert om.skip_cosine(X[0], pos, cache, every, X[L]) == pytest.approx(_np_cos(X[0], X[L]), abs=1e-12)
+    np.testing.assert_allclose(om.masked_state(X[0], pos, cache, none), X[L], rtol=1e-12, atol=1e-13)
