@@ -1,5 +1,5 @@
-"""Parity at the benchmark's full size (LLaMA-3-8B shape, bf16, T = 512, M = 12), in the launch configuration bench.py
-times. The oracle cannot afford a 512-token prefill at this size, so a seeded synthetic KV prefix (shared input)
+"""Parity at the benchmark's full size (LLaMA-3-8B shape, bf16, M = 12; T = 512 and the long prefixes of the context
+sweep), in the launch configuration bench.py times. The oracle cannot afford a 512-token prefill at this size, so a seeded synthetic KV prefix (shared input)
 stands in for it on both sides; the verify rows, the DP and a draft step are then compared call by call."""
 import numpy as np
 import pytest
@@ -12,12 +12,15 @@ from tests.test_gpu_parity import HID_TOL, check_dp, dev, relerr
 pytestmark = pytest.mark.gpu
 
 
+MAX_T = 32768
+
+
 @pytest.fixture(scope="module")
 def setup_8b():
     import bench
     shape = si.LLAMA3_8B
     T = 512
-    eng, host = bench.build_engine(shape, 1, 1024, 16, keep_host=True)
+    eng, host = bench.build_engine(shape, 1, MAX_T + 64, 16, keep_host=True)
     om = oc.OracleModel(shape, host)
     K, V = si.gen_kv(shape, 3, shape.n_layers, T)
     cache = oc.KVCache(shape, T + 8)
@@ -28,8 +31,8 @@ def setup_8b():
     eng.close()
 
 
-def test_8b_verify_dp_and_draft(setup_8b):
-    shape, T, eng, om, cache = setup_8b
+def verify_dp_draft(shape, T, eng, om, cache):
+    """Two verify rows at positions T, T+1 on top of a T-token prefix, the DP on row 1 (M = 12), one draft step."""
     toks = [int(t) for t in si.gen_tokens(2, 3, shape.vocab, stream=9)]
     st, lg = [], []
     for r, tk in enumerate(toks):
@@ -44,20 +47,65 @@ def test_8b_verify_dp_and_draft(setup_8b):
     assert relerr(out["logits"].cpu().numpy(), olg) <= HID_TOL["bf16"]
     # DP on row 1 (position T+1): cache rows 0..T of the oracle are the synthetic prefix plus row 0's own k/v
     print("oracle dp", flush=True)
-    c = oc.KVCache(shape, T + 8)
-    c.K[:, :T + 1] = cache.K[:, :T + 1]
-    c.V[:, :T + 1] = cache.V[:, :T + 1]
-    gpu, ref = check_dp(om, eng, ost[:, 1], T + 1, c, 12)
+    gpu, ref = check_dp(om, eng, ost[:, 1], T + 1, cache, 12)
     # one draft step with the selected skip set, from row 2's token at position T+2
     print("oracle draft", flush=True)
     nxt = torch.zeros(1, dtype=torch.int32, device="cuda")
     eng.clasp_draft_step(ref["mask"].tolist(), dev(toks[2:3], torch.int32), T + 2, nxt)
-    c.K[:, T + 1] = cache.K[:, T + 1]
-    c.V[:, T + 1] = cache.V[:, T + 1]
-    _, dl = om.token(toks[2], T + 2, c, skip=ref["mask"])
+    _, dl = om.token(toks[2], T + 2, cache, skip=ref["mask"])
     ref_tok, ref_margin = oc.argmax_margin(dl)
     if ref_margin > HID_TOL["bf16"] * np.abs(dl).max() * 2:
         assert int(nxt) == ref_tok
+
+
+def test_8b_verify_dp_and_draft(setup_8b):
+    shape, T, eng, om, cache = setup_8b
+    verify_dp_draft(shape, T, eng, om, cache)
+
+
+def load_prefix(shape, eng, cache, T, n_layers):
+    """Synthetic prefix of T tokens for the first n_layers layers, drawn layer by layer with the shared generator (on
+    the device, where a billion draws take seconds) and handed to both sides."""
+    for l in range(n_layers):
+        K, V = si.gen_kv(shape, 1000 + l, 1, T, "cuda")
+        eng.clasp_kv_load(l, K[0], V[0])
+        cache.K[l, :T] = K[0].cpu().numpy()
+        cache.V[l, :T] = V[0].cpu().numpy()
+    print(f"prefix of {T} tokens loaded", flush=True)
+
+
+def test_8b_long_prefix_verify_dp_and_draft(setup_8b):
+    """The same calls on an 8192-token prefix of the benchmark's context sweep (split attention and its merge)."""
+    shape, _, eng, om, _ = setup_8b
+    T = 8192
+    cache = oc.KVCache(shape, T + 8)
+    load_prefix(shape, eng, cache, T, shape.n_layers)
+    verify_dp_draft(shape, T, eng, om, cache)
+
+
+def test_8b_longest_prefix_first_layers(setup_8b):
+    """32768-token prefix (two query tiles per workgroup, 64-way split, merge kernel). The oracle's plain attention
+    loop takes ~0.7 s per row and layer here, so the comparison covers the first 8 layers: two verify rows' states
+    0..8 and the search restricted to those layers (M = 6, up to 6 candidate rows per layer)."""
+    shape, _, eng, om, _ = setup_8b
+    T, Lw, M = MAX_T, 8, 6
+    omw = om.window(0, Lw)
+    cache = oc.KVCache(omw.shape, T + 8)
+    load_prefix(shape, eng, cache, T, Lw)
+    toks = [int(t) for t in si.gen_tokens(2, 2, shape.vocab, stream=9)]
+    st = []
+    for r, tk in enumerate(toks):
+        print(f"oracle verify row {r}, {Lw} layers", flush=True)
+        s, _ = omw.token(tk, T + r, cache, want_states=True, want_logits=False)
+        st.append(s)
+    ost = np.stack(st, 1)
+    out = eng.clasp_verify_forward(dev(toks, torch.int32), T, want_hidden=True)
+    for l in range(Lw + 1):
+        assert relerr(out["hidden"][l].cpu().numpy(), ost[l]) <= HID_TOL["bf16"], f"layer {l}"
+    print("oracle dp, window of 8 layers", flush=True)
+    X = np.zeros((shape.n_layers + 1, shape.d_model))
+    X[:Lw + 1] = ost[:, 1]
+    check_dp(om, eng, X, T + 1, cache, M, 0, Lw)   # the cache holds exactly the window's layers
 
 
 def test_8b_vocab_sampling_and_acceptance(setup_8b):

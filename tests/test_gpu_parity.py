@@ -51,14 +51,23 @@ def oracle_prefill(om, toks, t_max):
     return cache, np.stack(st, 1), np.stack(lg)
 
 
-def check_dp(om, eng, X, pos, cache, M):
-    """Margin-aware comparison of one DP call. Returns (device result, oracle result)."""
-    L = om.shape.n_layers
-    gpu = eng.clasp_dp_select(dev(X), pos, M, want_tables=True)
+def check_dp(om, eng, X, pos, cache, M, lo=0, hi=None):
+    """Margin-aware comparison of one DP call (restricted to the layers lo..hi-1 when given; X then still holds all
+    L+1 states, of which lo..hi are read). Returns (device result, oracle result)."""
+    L_all = om.shape.n_layers
+    hi = L_all if hi is None else hi
+    L = hi - lo
+    windowed = (lo, hi) != (0, L_all)
+    if windowed:
+        gpu = eng.clasp_dp_select_window(dev(X), pos, M, lo, hi, want_tables=True)
+        om, cache, Xw = om.window(lo, hi), cache.window(lo, hi), X[lo:hi + 1]
+    else:
+        gpu = eng.clasp_dp_select(dev(X), pos, M, want_tables=True)
+        Xw = X
     g_choice = gpu["choice"].cpu().numpy()
     ov = np.full((L + 1, M + 1), -1, dtype=np.int8)
     for _ in range(16):
-        ref = om.dp(X, pos, cache, M, override=ov)
+        ref = om.dp(Xw, pos, cache, M, override=ov)
         diff = np.argwhere(ref["choice"] != g_choice)
         if diff.size == 0:
             break
@@ -74,8 +83,9 @@ def check_dp(om, eng, X, pos, cache, M):
         assert np.array_equal(np.isnan(sc[..., k]), np.isnan(ref[key])), key
         if not np.isnan(ref[key]).all():
             assert np.nanmax(np.abs(sc[..., k] - ref[key])) <= COS_TOL, key
-    assert gpu["mask"].cpu().numpy().tolist() == ref["mask"].tolist()
-    assert int(gpu["mask"].sum()) == M
+    mask = gpu["mask"].cpu().numpy()
+    assert mask[lo:hi].tolist() == ref["mask"].tolist()
+    assert int(mask.sum()) == M and not mask[:lo].any() and not mask[hi:].any()
     assert relerr(gpu["g_final"].cpu().numpy(), ref["g_final"]) <= HID_TOL[om.shape.dtype]
     return gpu, ref
 
@@ -457,28 +467,7 @@ def test_window_search_matches_oracle(name, resid_scale, lo, hi, M):
     tt = dev(toks, torch.int32)
     eng.clasp_verify_forward(tt, 0)
     pos, X = 11, ost[:, 11]
-    gpu = eng.clasp_dp_select_window(dev(X), pos, M, lo, hi, want_tables=True)
-    omw, cw = om.window(lo, hi), cache.window(lo, hi)
-    g_choice = gpu["choice"].cpu().numpy()
-    ov = np.full((hi - lo + 1, M + 1), -1, dtype=np.int8)
-    for _ in range(16):
-        ref = omw.dp(X[lo:hi + 1], pos, cw, M, override=ov)
-        diff = np.argwhere(ref["choice"] != g_choice)
-        if diff.size == 0:
-            break
-        for i, j in diff:
-            assert abs(ref["sigma_c"][i, j] - ref["sigma_s"][i, j]) <= COS_MARGIN, f"choice differs at ({i},{j})"
-            ov[i, j] = g_choice[i, j]
-    else:
-        raise AssertionError("device and oracle choices do not converge")
-    sc = gpu["scores"].cpu().numpy().astype(np.float64)
-    for k, key in enumerate(("sigma_c", "sigma_s")):
-        assert np.array_equal(np.isnan(sc[..., k]), np.isnan(ref[key])), key
-        assert np.nanmax(np.abs(sc[..., k] - ref[key])) <= COS_TOL, key
-    mask = gpu["mask"].cpu().numpy()
-    assert mask[lo:hi].tolist() == ref["mask"].tolist() and mask.sum() == M
-    assert not mask[:lo].any() and not mask[hi:].any()
-    assert relerr(gpu["g_final"].cpu().numpy(), ref["g_final"]) <= HID_TOL[shape.dtype]
+    check_dp(om, eng, X, pos, cache, M, lo, hi)
 
 
 @pytest.mark.parametrize("name,resid_scale", [("tiny-f32", 1.0), ("small-bf16", 0.05), ("small-bf16-hd128", 1.0)])
