@@ -39,7 +39,8 @@ def check_cache(eng, cache, lo, hi, what=""):
 
 
 @pytest.mark.parametrize("name,T,chunk", [("small-bf16", 203, 128), ("small-bf16-hd128", 333, 256),
-                                           ("small-bf16-deep", 150, 128), ("small-bf16-hd128", 1700, 2048)])
+                                           ("small-bf16-deep", 150, 128), ("small-bf16", 130, 128),
+                                           ("small-bf16-hd128", 1700, 2048)])
 def test_prefill_cache_and_last_token_match_oracle(name, T, chunk):
     shape = si.SHAPES[name]
     max_seq = (T + 31) // 32 * 32
