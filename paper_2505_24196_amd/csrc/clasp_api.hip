@@ -723,10 +723,14 @@ int launch_prefill_gemm(const clasp_ctx* ctx, const PrefillGemmArgs& p, hipStrea
     };
     if constexpr (EPI == kEpiSwiglu) {
         if (CLASP_PREFILL_WIDE && nrb * ((tiles + 15) / 16) >= 2 * ctx->n_cu)
-            return launch(prefill_gemm_kernel<EPI, 8, 1>, prefill_gemm_lds_bytes<8, 1>(), 16, opted_in[0]);
+            return launch(prefill_gemm_kernel<EPI, 8, 1, 2>, prefill_gemm_lds_bytes<8, 1>(), 16, opted_in[0]);
     }
-    return launch(prefill_gemm_kernel<EPI, 4, CLASP_PREFILL_NARROW_DEPTH>, prefill_gemm_lds_bytes<4, CLASP_PREFILL_NARROW_DEPTH>(), 8,
-                  opted_in[1]);
+    if constexpr (EPI == kEpiQkv) {  // three lighter workgroups per CU: 272 -> 221 us at the 8B shape, 2048 rows (768 workgroups)
+        return launch(prefill_gemm_kernel<EPI, 4, 1, 3>, prefill_gemm_lds_bytes<4, 1>(), 8, opted_in[1]);
+    } else {
+        return launch(prefill_gemm_kernel<EPI, 4, CLASP_PREFILL_NARROW_DEPTH, 2>,
+                      prefill_gemm_lds_bytes<4, CLASP_PREFILL_NARROW_DEPTH>(), 8, opted_in[1]);
+    }
 }
 
 // The full model over n rows at positions pos0.. (n <= the chunk the workspace was carved for): leaves their keys and
@@ -740,7 +744,7 @@ int prefill_chunk(const clasp_ctx* ctx, const PrefillWs& ws, int ld, const int32
                        static_cast<const bf16*>(ctx->embed), c.vocab, d, ws.h, ws.op_h, R, ctx->attn_norm[0], ws.ss_h, ld);
     CLASP_LAUNCH_CHECK();
     for (int l = 0; l < L; ++l) {
-        hipLaunchKernelGGL(prefill_rstd_kernel, dim3((n + 63) / 64), dim3(64, 4), 0, st, ws.ss_h, d / 16, ld, n, 1.0f / d,
+        hipLaunchKernelGGL(prefill_rstd_kernel, dim3((n + 63) / 64), dim3(64, 16), 0, st, ws.ss_h, d / 16, ld, n, 1.0f / d,
                            c.rms_eps, ws.rstd_h);
         CLASP_LAUNCH_CHECK();
         {
@@ -782,7 +786,7 @@ int prefill_chunk(const clasp_ctx* ctx, const PrefillWs& ws, int ld, const int32
             g.next_op = ws.op_a; g.next_gain = ctx->mlp_norm[l]; g.next_ss = ws.ss_a; p.ld_ss = ld;
             if ((rc = launch_prefill_gemm<kEpiResid>(ctx, p, st))) return rc;
         }
-        hipLaunchKernelGGL(prefill_rstd_kernel, dim3((n + 63) / 64), dim3(64, 4), 0, st, ws.ss_a, d / 16, ld, n, 1.0f / d,
+        hipLaunchKernelGGL(prefill_rstd_kernel, dim3((n + 63) / 64), dim3(64, 16), 0, st, ws.ss_a, d / 16, ld, n, 1.0f / d,
                            c.rms_eps, ws.rstd_a);
         CLASP_LAUNCH_CHECK();
         {

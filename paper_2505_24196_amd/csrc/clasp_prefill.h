@@ -27,19 +27,27 @@ struct PrefillGemmArgs {
     int ld_ss;           // row capacity of next_ss: next_ss[tile][ld_ss]
 };
 
-// rstd[row] = 1 / sqrt(sum_p ss[p][row] / dim + eps). Block (64, 4): thread (x, y) adds parts y, y + 4, .. of row
-// blockIdx.x*64 + x (coalesced over rows), the four sums are added in y order.
-__global__ __launch_bounds__(256) void prefill_rstd_kernel(const float* ss, int n_parts, int ld, int n_rows, float inv_dim,
-                                                           float eps, float* rstd) {
-    __shared__ float part[4][64];
+// rstd[row] = 1 / sqrt(sum_p ss[p][row] / dim + eps). Block (64, 16): thread (x, y) adds parts y, y + 16, .. of row
+// blockIdx.x*64 + x (coalesced over rows, loads issued eight at a time), the sixteen sums are added in y order.
+__global__ __launch_bounds__(1024) void prefill_rstd_kernel(const float* ss, int n_parts, int ld, int n_rows, float inv_dim,
+                                                            float eps, float* rstd) {
+    __shared__ float part[16][64];
     const int row = blockIdx.x * 64 + threadIdx.x, y = threadIdx.y;
     float s = 0.f;
-    if (row < n_rows)
-        for (int p = y; p < n_parts; p += 4) s += ss[(size_t)p * ld + row];
+    if (row < n_rows) {
+        for (int p0 = y; p0 < n_parts; p0 += 16 * 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = (p0 + 16 * u < n_parts) ? ss[(size_t)(p0 + 16 * u) * ld + row] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+    }
     part[y][threadIdx.x] = s;
     __syncthreads();
     if (y == 0 && row < n_rows) {
-        const float t = ((part[0][threadIdx.x] + part[1][threadIdx.x]) + part[2][threadIdx.x]) + part[3][threadIdx.x];
+        float t = 0.f;
+        for (int k = 0; k < 16; ++k) t += part[k][threadIdx.x];
         rstd[row] = 1.0f / sqrtf(t * inv_dim + eps);
     }
 }
@@ -142,11 +150,12 @@ constexpr size_t prefill_gemm_lds_bytes() {
 // fragments of 1 KiB each: requested into registers at the top of a k-step, written to a free LDS stage after the
 // MFMAs of the D-th k-step from there (D register sets alternate, D + 1 LDS stages), one barrier per k-step. Two
 // workgroups share a CU (<= 256 registers per lane, <= 80 KiB of LDS each), so one computes while the other waits for
-// LDS, memory or its barrier.
+// LDS, memory or its barrier; WPS = wavefronts per SIMD the register budget is cut for (3 with RN = 4, D = 1: 48 KiB of
+// LDS and 152 registers, three workgroups per CU).
 // Workgroups are numbered so that the ones resident on an XCD at the same time share weight columns: the XCD's L2
 // then sees each weight fragment from HBM once and serves the sibling row blocks.
-template <int EPI, int RN, int D>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_gemm_kernel(PrefillGemmArgs p) {
+template <int EPI, int RN, int D, int WPS>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WPS, WPS))) void prefill_gemm_kernel(PrefillGemmArgs p) {
     constexpr int RM = kPrefillRM, NSTAGE = D + 1;
     constexpr int A_FR = 2 * 2 * RM, B_FR = 2 * RN, FR = A_FR + B_FR, NL = FR / 4;
     static_assert(FR % 4 == 0 && (D == 1 || D == 2), "fragments are dealt to four wavefronts");
