@@ -490,3 +490,35 @@ def test_skip_cosine_matches_oracle(name, resid_scale):
     # the masked forward leaves the full model's cache rows below pos alone: the verify states are reproduced after it
     out = eng.clasp_verify_forward(tt[9:10], pos, want_hidden=True)
     assert relerr(out["hidden"][:, 0].cpu().numpy(), X) <= HID_TOL[shape.dtype]
+
+
+def test_markov_study_rows_match_oracle():
+    """decode.markov_study on a window of 6 layers (M = 2, 15 sets): brute-force optimum, the DP's set and its rank
+    against the oracle's own enumeration."""
+    import itertools
+    from paper_2505_24196_amd import decode
+    name, lo, hi, M = "small-bf16-deep", 9, 15, 2
+    shape = si.SHAPES[name]
+    L = shape.n_layers
+    om, eng = oracle_model(name, 1, 0.05), engine(name, 1, 0.05)
+    toks = prompt(shape, 10)
+    cache, ost, _ = oracle_prefill(om, toks, 16)
+    tt = dev(toks, torch.int32)
+    eng.clasp_verify_forward(tt, 0)
+    pos, X = 9, ost[:, 9]
+    row = decode.markov_study(eng, dev(X), tt[9:10], pos, lo, hi, [M], n_random=8)[0]
+    combos = list(itertools.combinations(range(lo, hi), M))
+    ref = np.array([om.skip_cosine(X[0], pos, cache, [1 if l in c else 0 for l in range(L)], X[L]) for c in combos])
+    assert row["sets"] == len(combos) == 15
+    assert abs(row["brute_force_cos"] - ref.max()) <= COS_TOL
+    order = np.sort(ref)[::-1]
+    if order[0] - order[1] > COS_MARGIN:
+        assert tuple(row["brute_force_set"]) == combos[int(ref.argmax())]
+    dp_ref = om.window(lo, hi).dp(X[lo:hi + 1], pos, cache.window(lo, hi), M)
+    margins = np.abs(dp_ref["sigma_c"] - dp_ref["sigma_s"])
+    if np.nanmin(margins[1:, 1:]) > COS_MARGIN:
+        assert row["dp_set"] == [lo + int(i) for i in np.flatnonzero(dp_ref["mask"])]
+        k = combos.index(tuple(row["dp_set"]))
+        assert abs(row["dp_cos"] - ref[k]) <= COS_TOL
+    assert row["random_min_cos"] <= row["random_mean_cos"] <= row["brute_force_cos"] + 1e-6
+    assert row["dp_cos"] <= row["brute_force_cos"] + 1e-6
