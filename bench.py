@@ -142,7 +142,7 @@ def main():
     ap.add_argument("--prefill", type=int, default=0, metavar="N_TOKENS",
                     help="only time the prompt pass (clasp_prefill) over N_TOKENS synthetic tokens of the workload's "
                          "model; prints its own JSON line (tokens/s, algorithmic TFLOP/s against the bf16 MFMA peak)")
-    ap.add_argument("--prefill-chunk", type=int, default=2048, help="rows per pass of --prefill (multiple of 128)")
+    ap.add_argument("--prefill-chunk", type=int, default=4096, help="rows per pass of --prefill (multiple of 128)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="only run plain device copies of a known size (1 GiB read + 1 GiB written per copy), to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters")

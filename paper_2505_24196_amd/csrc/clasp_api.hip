@@ -671,11 +671,8 @@ int dp_select_window(clasp_ctx* ctx, const float* states, size_t layer_stride, i
 }
 
 // ---- prompt processing with many rows per pass ---------------------------------------------------------------------
-#ifndef CLASP_PREFILL_WIDE
-#define CLASP_PREFILL_WIDE 1  // 0: every GEMM takes the 128-column workgroup tile
-#endif
-#ifndef CLASP_PREFILL_NARROW_DEPTH
-#define CLASP_PREFILL_NARROW_DEPTH 2  // k-steps the 128-column kernel requests its operands ahead
+#ifndef CLASP_PREFILL_BIG
+#define CLASP_PREFILL_BIG 1  // 256 x 256 tiles fed by direct global -> LDS loads where the grid is large enough
 #endif
 constexpr int kPrefillMaxChunk = 8192;
 
@@ -703,34 +700,44 @@ size_t carve_prefill(const clasp_config& c, int chunk, char* base, PrefillWs* ws
     return w.off;
 }
 
-// Workgroup tile 128 rows x 128 columns, except the gate|up projection when 256-column tiles still give every CU its
-// two workgroups: its long N makes the fatter tile pay (measured at the 8B shape, 2048 rows: 848 vs 1070 us), while
-// the projections onto d_model lose with it (375 vs 338 us) and the q/k/v epilogue does not fit its register budget.
+// Which GEMM kernel a projection of the prompt pass takes (measured at the 8B shape):
+//  * o_proj, gate|up, down: 256 x 256 tiles fed by direct global -> LDS loads when they give every CU a workgroup
+//    (gate|up from 513 rows on, the projections onto d_model from 3841 rows on: 4096 rows, gate|up 1.51 ms against
+//    1.63 with 128 x 256 tiles, o_proj + down 1.03 ms against 1.32), else 128 x 128 tiles, two workgroups per CU;
+//  * q/k/v: 128 x 128 tiles with three lighter workgroups per CU (its epilogue does not fit the larger tiles' register
+//    budget, and 24 column blocks of 256 would leave half of a second round of CUs idle).
 template <int EPI>
 int launch_prefill_gemm(const clasp_ctx* ctx, const PrefillGemmArgs& p, hipStream_t st) {
-    const int nrb = (p.g.R * 16 + kPrefillRows - 1) / kPrefillRows, tiles = p.g.N / 16;
-    static bool opted_in[2] = {false, false};  // more than 64 KiB of LDS per workgroup has to be requested once per kernel
-    auto launch = [&](auto kernel, size_t lds, int col_tiles, bool& opted) -> int {
-        if (!opted) {
-            if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-                return CLASP_E_HIP;
-            opted = true;
+    const int tiles = p.g.N / 16;
+    if constexpr (EPI != kEpiQkv) {
+        const int nrb = (p.g.R * 16 + kPrefillBigRows - 1) / kPrefillBigRows, total = nrb * ((tiles + 15) / 16);
+        if (CLASP_PREFILL_BIG && total >= ctx->n_cu) {
+            static bool opted_in = false;  // more than 64 KiB of LDS per workgroup has to be requested once per kernel
+            auto kernel = prefill_gemm256_kernel<EPI>;
+            if (!opted_in) {
+                if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPrefillBigLds) !=
+                    hipSuccess)
+                    return CLASP_E_HIP;
+                opted_in = true;
+            }
+            hipLaunchKernelGGL(kernel, dim3((total + 7) / 8 * 8), dim3(512), kPrefillBigLds, st, p);
+            CLASP_LAUNCH_CHECK();
+            return CLASP_OK;
         }
-        const int total = nrb * ((tiles + col_tiles - 1) / col_tiles);
-        hipLaunchKernelGGL(kernel, dim3((total + 7) / 8 * 8), dim3(256), lds, st, p);
-        CLASP_LAUNCH_CHECK();
-        return CLASP_OK;
-    };
-    if constexpr (EPI == kEpiSwiglu) {
-        if (CLASP_PREFILL_WIDE && nrb * ((tiles + 15) / 16) >= 2 * ctx->n_cu)
-            return launch(prefill_gemm_kernel<EPI, 8, 1, 2>, prefill_gemm_lds_bytes<8, 1>(), 16, opted_in[0]);
     }
-    if constexpr (EPI == kEpiQkv) {  // three lighter workgroups per CU: 272 -> 221 us at the 8B shape, 2048 rows (768 workgroups)
-        return launch(prefill_gemm_kernel<EPI, 4, 1, 3>, prefill_gemm_lds_bytes<4, 1>(), 8, opted_in[1]);
-    } else {
-        return launch(prefill_gemm_kernel<EPI, 4, CLASP_PREFILL_NARROW_DEPTH, 2>,
-                      prefill_gemm_lds_bytes<4, CLASP_PREFILL_NARROW_DEPTH>(), 8, opted_in[1]);
+    constexpr int D = EPI == kEpiQkv ? 1 : 2, WPS = EPI == kEpiQkv ? 3 : 2;
+    const int nrb = (p.g.R * 16 + kPrefillRows - 1) / kPrefillRows, total = nrb * ((tiles + 7) / 8);
+    constexpr size_t lds = prefill_gemm_lds_bytes<4, D>();
+    static bool opted_in = false;
+    auto kernel = prefill_gemm_kernel<EPI, 4, D, WPS>;
+    if (!opted_in) {
+        if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return CLASP_E_HIP;
+        opted_in = true;
     }
+    hipLaunchKernelGGL(kernel, dim3((total + 7) / 8 * 8), dim3(256), lds, st, p);
+    CLASP_LAUNCH_CHECK();
+    return CLASP_OK;
 }
 
 // The full model over n rows at positions pos0.. (n <= the chunk the workspace was carved for): leaves their keys and

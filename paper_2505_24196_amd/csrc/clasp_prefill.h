@@ -274,6 +274,123 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WPS, WPS)))
     }
 }
 
+// ---- 256 x 256 tile fed by direct global -> LDS loads ---------------------------------------------------------------
+// What binds the kernel above is operand delivery: a 128 x 256 tile pulls 32 KiB per k-step through L2 for 4 MFLOP, most
+// of it with Infinity-Cache / HBM latency, and registers + LDS keep only one or two k-steps in flight. Here a workgroup
+// of 4 x 2 wavefronts (64 x 128 accumulators each) owns a 256 x 256 tile (48 KiB per k-step for 8 MFLOP), and the
+// fragments go straight from global memory into a ring of three LDS stages with global_load_lds_dwordx4 (per lane a
+// global address, destination = wave-uniform LDS base + lane * 16, which is exactly a fragment): no staging registers,
+// two k-steps (96 KiB per CU) in flight while the third is consumed. The loads are written as inline assembly
+// because their completion has to be awaited stage by stage (s_waitcnt vmcnt(6): the six loads of the next stage may
+// stay in flight); nothing else in the loop touches global memory, and the counter is drained before the epilogue.
+// (The same loop on 32 x 32 x 16 MFMAs, whose operands a lane can gather from two neighbouring fragments, measured 12 %
+// slower.)
+constexpr int kPrefillBigRows = 256, kPrefillBigStages = 3;
+constexpr int kPrefillBigFrags = 4 * kPrefillRM * 2 + 2 * 8;  // 32 activation + 16 weight fragments per k-step
+constexpr size_t kPrefillBigLds = (size_t)kPrefillBigStages * kPrefillBigFrags * 1024;
+
+__device__ __forceinline__ void load_to_lds_16(const u32x4* g, unsigned lds_byte_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_byte_addr), "v"(g) : "memory");
+}
+
+template <int EPI>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_gemm256_kernel(PrefillGemmArgs p) {
+    constexpr int RM = kPrefillRM, RN = 8, A_FR = 4 * RM * 2, B_FR = 2 * RN, FR = A_FR + B_FR, NL = FR / 8;
+    constexpr int NSTAGE = kPrefillBigStages;
+    static_assert(FR == kPrefillBigFrags && FR % 8 == 0, "fragments are dealt to eight wavefronts");
+    extern __shared__ u32x4 prefill_lds[];  // [NSTAGE][FR][64]
+    const GemmArgs& g = p.g;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6), wm = w >> 1, wn = w & 1;
+    const int KS = g.K >> 5, n_tiles = g.N >> 4;
+    const int nrb = (g.R * 16 + kPrefillBigRows - 1) / kPrefillBigRows, ncb = (n_tiles + B_FR - 1) / B_FR;
+    const int total = nrb * ncb, per_xcd = (total + 7) >> 3;
+    const int pid = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (pid >= total) return;
+    const int rb = pid % nrb, cb = pid / nrb;
+
+    const u32x4* src[NL];
+    size_t step[NL];
+#pragma unroll
+    for (int j = 0; j < NL; ++j) {
+        const int f = w + 8 * j;
+        if (f < A_FR) {
+            const int rg = min(rb * (A_FR / 2) + (f >> 1), g.R - 1);
+            src[j] = reinterpret_cast<const u32x4*>(g.A) + ((size_t)rg * 2 + (f & 1)) * 64 + (lane & 15) * 4 + (lane >> 4);
+            step[j] = (size_t)g.R * 2 * 64;
+        } else {
+            const int tile = min(cb * B_FR + (f - A_FR), n_tiles - 1);
+            int mi = 0, tl = tile;
+            if (tile >= g.tile_end[0]) { mi = 1; tl = tile - g.tile_end[0]; }
+            if (tile >= g.tile_end[1]) { mi = 2; tl = tile - g.tile_end[1]; }
+            src[j] = reinterpret_cast<const u32x4*>(g.W[mi]) + (size_t)tl * KS * 64 + lane;
+            step[j] = 64;
+        }
+    }
+    const unsigned lds_base = (unsigned)(uintptr_t)((__attribute__((address_space(3))) char*)prefill_lds);
+    auto issue = [&](int buf) {  // this wavefront's six fragments of the next stage in line
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            load_to_lds_16(src[j], lds_base + (unsigned)((buf * FR + w + 8 * j) * 1024));
+            src[j] += step[j];
+        }
+    };
+
+    f32x4 acc[RM][RN];
+#pragma unroll
+    for (int i = 0; i < RM; ++i)
+#pragma unroll
+        for (int j = 0; j < RN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    auto compute = [&](int buf) {
+        const u32x4* L = prefill_lds + (size_t)buf * FR * 64 + lane;
+        u32x4 bf[RN];
+#pragma unroll
+        for (int j = 0; j < RN; ++j) bf[j] = L[(A_FR + wn * RN + j) * 64];
+        u32x4 a_hi = L[(wm * RM * 2) * 64], a_lo = L[(wm * RM * 2 + 1) * 64];
+#pragma unroll
+        for (int i = 0; i < RM; ++i) {
+            const u32x4 c_hi = a_hi, c_lo = a_lo;
+            if (i + 1 < RM) {
+                a_hi = L[((wm * RM + i + 1) * 2) * 64];
+                a_lo = L[((wm * RM + i + 1) * 2 + 1) * 64];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < RN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(c_hi), as_bf16x8(bf[j]), acc[i][j], 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < RN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(c_lo), as_bf16x8(bf[j]), acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // stage s lives in LDS stage s % 3; it is requested two k-steps before its use, right after the barrier that
+    // tells that every wavefront has finished reading the stage it replaces
+    issue(0);
+    if (KS > 1) issue(1);
+    int buf = 0;
+    for (int s = 0; s < KS; ++s) {
+        if (s + 1 < KS) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");  // own loads of stage s have landed
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();  // everybody's have, and stage s - 1 is no longer read
+        if (s + 2 < KS) issue(buf == 0 ? 2 : buf - 1);  // (s + 2) % 3
+        compute(buf);
+        buf = buf == NSTAGE - 1 ? 0 : buf + 1;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+#pragma unroll
+    for (int i = 0; i < RM; ++i) {
+        const int rt = rb * (A_FR / 2) + wm * RM + i;
+        if (rt >= g.R) continue;
+#pragma unroll
+        for (int j = 0; j < RN; ++j) {
+            const int tile = cb * B_FR + wn * RN + j;
+            if (tile < n_tiles) prefill_epilogue<EPI>(p, rt, tile, lane, acc[i][j]);
+        }
+    }
+}
 // ---- causal attention over the cache for a chunk of rows ----------------------------------------------------------
 struct PrefillAttnArgs {
     const void* q_frag;  // [n_kv_heads][R*G tiles][head_dim/32][64][8], rotated and scaled by the q/k/v epilogue

@@ -182,13 +182,14 @@ def test_8b_prefill_short_prompt_against_oracle(setup_8b):
         assert relerr(hid[l], ost[l]) <= deep_tol(l), f"layer {l}"
 
 
-def test_8b_prefill_in_the_timed_configuration(setup_8b):
-    """700 prompt tokens (ragged; 1024 rows per pass, which takes the 256-column gate|up tile and several row blocks):
-    layer 0's keys / values at sampled positions against the oracle (they need no prefix), and every layer's cache
-    against the one clasp_verify_forward leaves for the same prompt in chunks of max_rows, which
-    test_8b_verify_dp_and_draft ties to the oracle at this shape."""
+@pytest.mark.parametrize("n,chunk", [(700, 1024), (4100, 4096)])
+def test_8b_prefill_in_the_timed_configuration(setup_8b, n, chunk):
+    """Ragged prompts in passes of 1024 rows (256 x 256 tiles for gate|up, 128 x 128 elsewhere) and of 4096 rows (the
+    timed configuration: 256 x 256 tiles for o_proj, gate|up and down). Against the oracle: layer 0's keys / values at
+    sampled positions (they need no prefix) and layer 1's at the first 16 positions (they go through all of layer 0:
+    attention over a short prefix, o_proj, gate|up, down). Every layer's cache against the one clasp_verify_forward
+    leaves for the same prompt in chunks of max_rows, which test_8b_verify_dp_and_draft ties to the oracle."""
     shape, T, eng, om, _ = setup_8b
-    n = 700
     toks = si.gen_tokens(2, n, shape.vocab, stream=12)
     tt = toks.to("cuda")
     for s in range(0, n, eng.max_rows):
@@ -197,14 +198,21 @@ def test_8b_prefill_in_the_timed_configuration(setup_8b):
     for l in range(shape.n_layers):
         K, V = eng.clasp_kv_read(l, 0, n)
         ref.append((K.cpu().numpy(), V.cpu().numpy()))
-    eng.clasp_prefill(tt, 0, 1024)
+    eng.clasp_prefill(tt, 0, chunk)
     embed = om.w["embed"]
-    for pos in (0, 1, 127, 128, 333, 699):
+    for pos in (0, 1, 127, 128, 333, n - 1):
         row = (embed[int(toks[pos])].astype(np.uint32) << 16).view(np.float32).astype(np.float64)
         _, kn, vn = om.layer(0, row, pos, 0, np.zeros((1, shape.kv_dim)), np.zeros((1, shape.kv_dim)))
         K, V = eng.clasp_kv_read(0, pos, 1)
         assert relerr(K.cpu().numpy().ravel(), kn) <= HID_TOL["bf16"], f"K position {pos}"
         assert relerr(V.cpu().numpy().ravel(), vn) <= HID_TOL["bf16"], f"V position {pos}"
+    om2 = om.window(0, 2)
+    c2 = oc.KVCache(om2.shape, 16)
+    for pos in range(16):
+        om2.token(int(toks[pos]), pos, c2, want_logits=False)
+    K, V = eng.clasp_kv_read(1, 0, 16)
+    assert relerr(K.cpu().numpy(), c2.K[1]) <= HID_TOL["bf16"]
+    assert relerr(V.cpu().numpy(), c2.V[1]) <= HID_TOL["bf16"]
     for l in range(shape.n_layers):
         K, V = eng.clasp_kv_read(l, 0, n)
         assert relerr(K.cpu().numpy(), ref[l][0]) <= HID_TOL["bf16"], f"K layer {l}"
