@@ -740,6 +740,43 @@ int launch_prefill_gemm(const clasp_ctx* ctx, const PrefillGemmArgs& p, hipStrea
     return CLASP_OK;
 }
 
+// Attention of a chunk: long prefixes share the key / value blocks of a workgroup through LDS, short ones (a few blocks
+// per query, the ring would stay mostly empty) let every wavefront read them itself.
+#ifndef CLASP_PREFILL_ATTN_LDS_WAVES
+#define CLASP_PREFILL_ATTN_LDS_WAVES 8
+#endif
+#ifndef CLASP_PREFILL_ATTN_LDS_MIN_BLOCKS
+#define CLASP_PREFILL_ATTN_LDS_MIN_BLOCKS 32
+#endif
+int launch_prefill_attn(const clasp_ctx* ctx, const PrefillAttnArgs& a, hipStream_t st) {
+    const clasp_config& c = ctx->cfg;
+    const int n_qt = a.R * ctx->group;
+    const int nblk = (a.pos0 + a.n_rows + 31) / 32;
+    if (CLASP_PREFILL_ATTN_LDS_WAVES && nblk >= CLASP_PREFILL_ATTN_LDS_MIN_BLOCKS) {
+        constexpr int NW = CLASP_PREFILL_ATTN_LDS_WAVES ? CLASP_PREFILL_ATTN_LDS_WAVES : 4;
+        const dim3 grid(c.n_kv_heads, (n_qt + NW * kPrefillAttnNT - 1) / (NW * kPrefillAttnNT));
+        static bool opted_in[2] = {false, false};
+        auto launch = [&](auto kernel, size_t lds, bool& opted) -> int {
+            if (!opted) {
+                if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+                    return CLASP_E_HIP;
+                opted = true;
+            }
+            hipLaunchKernelGGL(kernel, grid, dim3(NW * 64), lds, st, a);
+            CLASP_LAUNCH_CHECK();
+            return CLASP_OK;
+        };
+        if (c.head_dim == 64) return launch(prefill_attn_lds_kernel<64, NW>, (size_t)kPrefillAttnStages * 8 * 1024, opted_in[0]);
+        return launch(prefill_attn_lds_kernel<128, NW>, (size_t)kPrefillAttnStages * 16 * 1024, opted_in[1]);
+    }
+    const int per_wg = kPrefillAttnWaves * kPrefillAttnNT;
+    const dim3 grid(c.n_kv_heads, (n_qt + per_wg - 1) / per_wg);
+    if (c.head_dim == 64) hipLaunchKernelGGL(prefill_attn_kernel<64>, grid, dim3(kPrefillAttnWaves * 64), 0, st, a);
+    else hipLaunchKernelGGL(prefill_attn_kernel<128>, grid, dim3(kPrefillAttnWaves * 64), 0, st, a);
+    CLASP_LAUNCH_CHECK();
+    return CLASP_OK;
+}
+
 // The full model over n rows at positions pos0.. (n <= the chunk the workspace was carved for): leaves their keys and
 // values in the cache. The last layer stops after its q/k/v projection: nothing after it feeds the cache.
 int prefill_chunk(const clasp_ctx* ctx, const PrefillWs& ws, int ld, const int32_t* tokens, int n, int pos0,
@@ -778,11 +815,7 @@ int prefill_chunk(const clasp_ctx* ctx, const PrefillWs& ws, int ld, const int32
             a.Vt = ctx->v_cache + (size_t)l * ctx->kv_layer_bytes;
             a.out_op = ws.op_attn;
             a.n_rows = n; a.R = R; a.n_heads = c.n_heads; a.n_kv_heads = c.n_kv_heads; a.pos0 = pos0; a.t_max = c.max_seq;
-            const int per_wg = kPrefillAttnWaves * kPrefillAttnNT;
-            const dim3 grid(c.n_kv_heads, (R * ctx->group + per_wg - 1) / per_wg);
-            if (c.head_dim == 64) hipLaunchKernelGGL(prefill_attn_kernel<64>, grid, dim3(kPrefillAttnWaves * 64), 0, st, a);
-            else hipLaunchKernelGGL(prefill_attn_kernel<128>, grid, dim3(kPrefillAttnWaves * 64), 0, st, a);
-            CLASP_LAUNCH_CHECK();
+            if ((rc = launch_prefill_attn(ctx, a, st))) return rc;
         }
         {
             PrefillGemmArgs p{};

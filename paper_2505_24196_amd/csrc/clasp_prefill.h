@@ -289,8 +289,10 @@ constexpr int kPrefillBigRows = 256, kPrefillBigStages = 3;
 constexpr int kPrefillBigFrags = 4 * kPrefillRM * 2 + 2 * 8;  // 32 activation + 16 weight fragments per k-step
 constexpr size_t kPrefillBigLds = (size_t)kPrefillBigStages * kPrefillBigFrags * 1024;
 
+// lds_byte_addr must be the same in every lane (the hardware takes it from M0); lane l's 16 bytes land at + l * 16.
 __device__ __forceinline__ void load_to_lds_16(const u32x4* g, unsigned lds_byte_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_byte_addr), "v"(g) : "memory");
+    const unsigned base = __builtin_amdgcn_readfirstlane(lds_byte_addr);
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(g) : "memory");
 }
 
 template <int EPI>
@@ -475,4 +477,123 @@ __global__ __launch_bounds__(kPrefillAttnWaves * 64) void prefill_attn_kernel(Pr
     }
 }
 
+// ---- the same attention with the key / value blocks shared through LDS ----------------------------------------------
+// In the kernel above every wavefront streams the whole visible prefix of its KV head from L2 for its 32 queries; at
+// long prefixes that is what binds it (4096 rows x 32k tokens: 34 GB through L2 per layer). Here the NW wavefronts of a
+// workgroup (NW x 32 queries) walk the prefix together: each 32-key block goes from global memory straight into a
+// ring of eight LDS stages (global_load_lds_dwordx4, a quarter or an eighth of the block's fragments per wavefront,
+// six blocks in flight) and every wavefront reads its fragments from there, one block ahead of the one it multiplies.
+// One barrier per block; the ring is kept full to the end by re-requesting the last block, so the number of loads
+// to wait for is the same in every step.
+constexpr int kPrefillAttnStages = 8;
+
+template <int HD, int NW>
+__global__ __launch_bounds__(NW * 64) void prefill_attn_lds_kernel(PrefillAttnArgs a) {
+    constexpr int NT = kPrefillAttnNT, KK = HD / 32, CT = HD / 16, FRB = 2 * KK + CT, PER = FRB / NW;
+    constexpr int NSTAGE = kPrefillAttnStages;
+    static_assert(FRB % NW == 0 && (NSTAGE - 2) * PER <= 63, "loads per wavefront and block; vmcnt holds 6 bits");
+    extern __shared__ u32x4 attn_lds[];  // [NSTAGE][FRB][64]
+    const int kvh = blockIdx.x, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int G = a.n_heads / a.n_kv_heads, nQ = a.n_rows * G, n_qt = a.R * G;
+    const int t_wg = (int)blockIdx.y * NW * NT;  // first query tile of the workgroup
+    if (t_wg * 16 >= nQ) return;
+    const int t0 = t_wg + wave * NT;
+    const int m16 = lane & 15, q4 = lane >> 4;
+
+    bf16x8 qf[NT][KK];
+    int limit[NT];
+    {
+        const u32x4* qp = reinterpret_cast<const u32x4*>(a.q_frag) + (size_t)kvh * n_qt * KK * 64 + lane;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int qt = min(t0 + t, n_qt - 1), qi = (t0 + t) * 16 + m16;
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) qf[t][kk] = as_bf16x8(qp[((size_t)qt * KK + kk) * 64]);
+            limit[t] = qi < nQ ? a.pos0 + qi / G : -1;
+        }
+    }
+    // blocks any query of the workgroup sees (queries ascend with the tile index)
+    const int last_q = min((t_wg + NW * NT) * 16, nQ) - 1;
+    const int nblk = ((a.pos0 + last_q / G) >> 5) + 1;
+
+    AttnState<HD, NT> st;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        st.m[t] = -INFINITY;
+        st.l[t] = 0.f;
+#pragma unroll
+        for (int c = 0; c < CT; ++c) st.o[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const u32x4* Kh = reinterpret_cast<const u32x4*>(reinterpret_cast<const bf16*>(a.Kc) + (size_t)kvh * a.t_max * HD) + lane;
+    const u32x4* Vh = reinterpret_cast<const u32x4*>(reinterpret_cast<const bf16*>(a.Vt) + (size_t)kvh * a.t_max * HD) + lane;
+    const unsigned lds_base = (unsigned)(uintptr_t)((__attribute__((address_space(3))) char*)attn_lds);
+    auto issue = [&](int blk, int stage) {  // this wavefront's PER fragments of block min(blk, nblk - 1)
+        const int b = min(blk, nblk - 1);
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int f = wave + NW * j;  // fragments 0 .. 2*KK-1: keys, then values
+            const u32x4* src = f < 2 * KK ? Kh + ((size_t)b * (2 * KK) + f) * 64 : Vh + ((size_t)b * CT + (f - 2 * KK)) * 64;
+            load_to_lds_16(src, lds_base + (unsigned)((stage * FRB + f) * 1024));
+        }
+    };
+    // Steady state of step blk: the fragments of block blk are in registers (read from LDS during step blk - 1), block
+    // blk + 1 is awaited and read into the other register set while block blk is multiplied, blocks blk + 2 ..
+    // blk + NSTAGE - 1 are in flight (the newest requested right after the barrier, into the stage of block blk - 1).
+    auto wait_oldest = [&](int ahead) {  // until at most `ahead` blocks' worth of this wavefront's loads are pending
+        if (ahead == NSTAGE - 2) {
+            if constexpr ((NSTAGE - 2) * PER == 24) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+            else if constexpr ((NSTAGE - 2) * PER == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        } else {
+            if constexpr ((NSTAGE - 3) * PER == 20) asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
+            else if constexpr ((NSTAGE - 3) * PER == 10) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+        }
+    };
+    static_assert(NSTAGE == 8 && (PER == 1 || PER == 2 || PER == 4), "the wait counts above are spelled out for these");
+    auto read_frags = [&](AttnFrags<HD>& f, int stage) {
+        const u32x4* L = attn_lds + (size_t)stage * FRB * 64 + lane;
+        attn_load<HD>(f, [&](int u, int kk) { return as_bf16x8(L[(u * KK + kk) * 64]); },
+                      [&](int c) { return as_bf16x8(L[(2 * KK + c) * 64]); });
+    };
+#pragma unroll 1
+    for (int b = 0; b < NSTAGE - 1; ++b) issue(b, b);
+    AttnFrags<HD> f0, f1;
+    wait_oldest(NSTAGE - 2);
+    __syncthreads();
+    read_frags(f0, 0);
+    int stage = 0;  // of block blk
+    auto step = [&](int blk, const AttnFrags<HD>& cur, AttnFrags<HD>& nxt) {
+        wait_oldest(NSTAGE - 3);
+        __syncthreads();  // block blk + 1 is complete in LDS, and every wavefront is done with block blk - 1
+        issue(blk + NSTAGE - 1, stage == 0 ? NSTAGE - 1 : stage - 1);
+        stage = stage == NSTAGE - 1 ? 0 : stage + 1;
+        read_frags(nxt, stage);
+        const int kb = blk << 5;
+        attn_compute<HD, NT>(st, qf, cur, [&](int u, int r, int t) { return kb + q4 * 8 + u * 4 + r <= limit[t]; });
+    };
+#pragma unroll 1
+    for (int blk = 0; blk < nblk; blk += 2) {
+        step(blk, f0, f1);
+        if (blk + 1 < nblk) step(blk + 1, f1, f0);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        float l = st.l[t];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        const int qi = (t0 + t) * 16 + m16;
+        if (qi >= nQ) continue;
+        const float inv = 1.0f / l;
+        const int row = qi / G, h = kvh * G + qi % G;
+#pragma unroll
+        for (int c = 0; c < CT; ++c)
+            store_operand4<kDtBf16>(a.out_op, a.R, 0, row, h * HD + c * 16 + q4 * 4, st.o[t][c] * inv);
+    }
+}
+
 }  // namespace clasp
+

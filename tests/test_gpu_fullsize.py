@@ -31,8 +31,8 @@ def setup_8b():
     eng.close()
 
 
-def verify_dp_draft(shape, T, eng, om, cache):
-    """Two verify rows at positions T, T+1 on top of a T-token prefix, the DP on row 1 (M = 12), one draft step."""
+def verify_dp_draft(shape, T, eng, om, cache, M=12):
+    """Two verify rows at positions T, T+1 on top of a T-token prefix, the DP on row 1, one draft step."""
     toks = [int(t) for t in si.gen_tokens(2, 3, shape.vocab, stream=9)]
     st, lg = [], []
     for r, tk in enumerate(toks):
@@ -47,7 +47,7 @@ def verify_dp_draft(shape, T, eng, om, cache):
     assert relerr(out["logits"].cpu().numpy(), olg) <= HID_TOL["bf16"]
     # DP on row 1 (position T+1): cache rows 0..T of the oracle are the synthetic prefix plus row 0's own k/v
     print("oracle dp", flush=True)
-    gpu, ref = check_dp(om, eng, ost[:, 1], T + 1, cache, 12)
+    gpu, ref = check_dp(om, eng, ost[:, 1], T + 1, cache, M)
     # one draft step with the selected skip set, from row 2's token at position T+2
     print("oracle draft", flush=True)
     nxt = torch.zeros(1, dtype=torch.int32, device="cuda")
@@ -75,12 +75,13 @@ def load_prefix(shape, eng, cache, T, n_layers):
 
 
 def test_8b_long_prefix_verify_dp_and_draft(setup_8b):
-    """The same calls on an 8192-token prefix of the benchmark's context sweep (split attention and its merge)."""
+    """The same calls on an 8192-token prefix of the benchmark's context sweep (split attention and its merge), with the
+    sweep's smaller skip budget M = 8 (the oracle's search costs ~0.2 s per candidate row and layer at this length)."""
     shape, _, eng, om, _ = setup_8b
     T = 8192
     cache = oc.KVCache(shape, T + 8)
     load_prefix(shape, eng, cache, T, shape.n_layers)
-    verify_dp_draft(shape, T, eng, om, cache)
+    verify_dp_draft(shape, T, eng, om, cache, M=8)
 
 
 def test_8b_longest_prefix_first_layers(setup_8b):
