@@ -522,3 +522,23 @@ def test_markov_study_rows_match_oracle():
         assert abs(row["dp_cos"] - ref[k]) <= COS_TOL
     assert row["random_min_cos"] <= row["random_mean_cos"] <= row["brute_force_cos"] + 1e-6
     assert row["dp_cos"] <= row["brute_force_cos"] + 1e-6
+
+
+def test_window_and_skip_cosine_reject_bad_arguments():
+    from paper_2505_24196_amd.binding import ClaspError
+    name = "small-bf16"
+    shape = si.SHAPES[name]
+    L = shape.n_layers
+    eng = engine(name)
+    X = dev(np.zeros((L + 1, shape.d_model)))
+    tok = dev([1], torch.int32)
+    for lo, hi, M in ((3, 3, 0), (4, 2, 1), (-1, 3, 1), (0, L + 1, 1), (1, 4, 4)):   # empty / reversed / outside / M > window
+        with pytest.raises(ClaspError):
+            eng.clasp_dp_select_window(X, 5, M, lo, hi)
+    with pytest.raises(ClaspError):
+        eng.clasp_skip_cosine([[0] * (L - 1)], tok, 5, X[L])          # mask of the wrong length
+    with pytest.raises(ClaspError):
+        eng.clasp_skip_cosine([[0] * L], tok, 256, X[L])              # position beyond max_seq
+    # M = window: every layer of the window skipped, nothing outside it
+    res = eng.clasp_dp_select_window(X, 5, 3, 1, 4)
+    assert res["mask"].cpu().tolist() == [0, 1, 1, 1] + [0] * (L - 4)
