@@ -330,6 +330,21 @@ def main():
                              "verify_forward": frac(ab["verify_forward"], verify_ms)},
         "kv_share_of_layer_bytes": round(ab["kv_share_per_layer"], 4),
     }
+    # achievable ceiling next to the nominal 8 TB/s: a plain device copy (1 GiB read + 1 GiB written per copy), untimed region
+    src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(10):
+        dst.copy_(src)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 10 * 2 * src.numel() * 2 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del src, dst
+    out["device_copy_GBs"] = round(copy_gbs, 1)
+    out["frac_of_device_copy"] = {k: round(v * 8000.0 / copy_gbs, 4) for k, v in out["hbm_frac_of_8TBs"].items()}
     if kt_n:
         avg_ms = kt_ms / kt_n
         ach = ab["gate_up_kernel"] / (avg_ms * 1e-3) / 1e9
