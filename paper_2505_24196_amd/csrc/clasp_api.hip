@@ -677,9 +677,10 @@ int dp_select_window(clasp_ctx* ctx, const float* states, size_t layer_stride, i
 constexpr int kPrefillMaxChunk = 8192;
 
 struct PrefillWs {
-    float *h, *a_buf, *ss_h, *ss_a, *rstd_h, *rstd_a;
+    float *h, *a_buf, *ss_h, *ss_a, *rstd_h, *rstd_a, *parts;
     void *op_h, *op_a, *op_attn, *op_act, *q_frag;
 };
+constexpr int kPrefillSplitRows = 1024, kPrefillMaxSplit = 4;  // K-split of short passes: rows it applies to, slices
 
 size_t carve_prefill(const clasp_config& c, int chunk, char* base, PrefillWs* ws) {
     Carver w{base};
@@ -696,6 +697,7 @@ size_t carve_prefill(const clasp_config& c, int chunk, char* base, PrefillWs* ws
     t.op_attn = w.take<void>(C * qd * 4);
     t.op_act = w.take<void>(C * (size_t)c.d_ffn * 4);
     t.q_frag = w.take<void>(C * qd * 2);
+    t.parts = w.take<float>((size_t)kPrefillMaxSplit * std::min<size_t>(C, kPrefillSplitRows) * d * 4);
     if (ws) *ws = t;
     return w.off;
 }
@@ -705,9 +707,10 @@ size_t carve_prefill(const clasp_config& c, int chunk, char* base, PrefillWs* ws
 //    (gate|up from 513 rows on, the projections onto d_model from 3841 rows on: 4096 rows, gate|up 1.51 ms against
 //    1.63 with 128 x 256 tiles, o_proj + down 1.03 ms against 1.32), else 128 x 128 tiles, two workgroups per CU;
 //  * q/k/v: 128 x 128 tiles with three lighter workgroups per CU (its epilogue does not fit the larger tiles' register
-//    budget, and 24 column blocks of 256 would leave half of a second round of CUs idle).
+//    budget, and 24 column blocks of 256 would leave half of a second round of CUs idle);
+//  * any of them: 64 x 128 tiles when even the 128 x 128 grid has fewer workgroups than CUs.
 template <int EPI>
-int launch_prefill_gemm(const clasp_ctx* ctx, const PrefillGemmArgs& p, hipStream_t st) {
+int launch_prefill_gemm(const clasp_ctx* ctx, const PrefillGemmArgs& p, hipStream_t st, float* parts = nullptr) {
     const int tiles = p.g.N / 16;
     if constexpr (EPI != kEpiQkv) {
         const int nrb = (p.g.R * 16 + kPrefillBigRows - 1) / kPrefillBigRows, total = nrb * ((tiles + 15) / 16);
@@ -725,19 +728,54 @@ int launch_prefill_gemm(const clasp_ctx* ctx, const PrefillGemmArgs& p, hipStrea
             return CLASP_OK;
         }
     }
-    constexpr int D = EPI == kEpiQkv ? 1 : 2, WPS = EPI == kEpiQkv ? 3 : 2;
-    const int nrb = (p.g.R * 16 + kPrefillRows - 1) / kPrefillRows, total = nrb * ((tiles + 7) / 8);
-    constexpr size_t lds = prefill_gemm_lds_bytes<4, D>();
-    static bool opted_in = false;
-    auto kernel = prefill_gemm_kernel<EPI, 4, D, WPS>;
-    if (!opted_in) {
-        if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return CLASP_E_HIP;
-        opted_in = true;
+    auto launch = [&](auto kernel, size_t lds, int rows, bool& opted) -> int {
+        if (!opted) {  // more than 64 KiB of LDS per workgroup has to be requested once per kernel
+            if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+                return CLASP_E_HIP;
+            opted = true;
+        }
+        const int total = ((p.g.R * 16 + rows - 1) / rows) * ((tiles + 7) / 8);
+        hipLaunchKernelGGL(kernel, dim3((total + 7) / 8 * 8), dim3(256), lds, st, p);
+        CLASP_LAUNCH_CHECK();
+        return CLASP_OK;
+    };
+    static bool opted_in[2] = {false, false};
+    // 64-row tiles when 128-row tiles would not give every CU a workgroup (prompts of a few hundred tokens)
+    const int total128 = ((p.g.R * 16 + kPrefillRows - 1) / kPrefillRows) * ((tiles + 7) / 8);
+    if (total128 < ctx->n_cu || (EPI == kEpiResid && p.g.n_rows <= kPrefillSplitRows && total128 < 2 * ctx->n_cu)) {
+        if constexpr (EPI == kEpiResid) {
+            // ... and when even those leave most of the three workgroup slots per CU empty, the contraction is split over
+            // gridDim.y workgroups as well (o_proj and down at 512 rows: 256 workgroups of 128 / 448 k-steps otherwise);
+            // the slices are summed in order by a second kernel that also runs the epilogue
+            const int total = ((p.g.R * 16 + 63) / 64) * ((tiles + 7) / 8);
+            int split = (3 * ctx->n_cu) / (total > 0 ? total : 1);
+            split = split > kPrefillMaxSplit ? kPrefillMaxSplit : split;
+            while (split >= 2 && p.g.K / 32 < 16 * split) --split;  // at least 16 k-steps per slice
+            if (parts && split >= 2 && p.g.n_rows <= kPrefillSplitRows) {
+                static bool split_opted_in = false;
+                auto kernel = prefill_gemm_kernel<kEpiPartial, 2, 4, 2, 3>;
+                constexpr size_t lds = prefill_gemm_lds_bytes<2, 4, 2>();
+                if (!split_opted_in) {
+                    if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+                        return CLASP_E_HIP;
+                    split_opted_in = true;
+                }
+                PrefillGemmArgs q = p;
+                q.k_split = split;
+                q.slab = (size_t)p.g.n_rows * p.g.ldo;
+                q.g.out = parts;
+                hipLaunchKernelGGL(kernel, dim3((total + 7) / 8 * 8, split), dim3(256), lds, st, q);
+                CLASP_LAUNCH_CHECK();
+                q.g.out = p.g.out;
+                hipLaunchKernelGGL(prefill_reduce_kernel, dim3(p.g.n_rows, (p.g.N + 255) / 256), dim3(256), 0, st, q, parts);
+                CLASP_LAUNCH_CHECK();
+                return CLASP_OK;
+            }
+        }
+        return launch(prefill_gemm_kernel<EPI, 2, 4, 2, 3>, prefill_gemm_lds_bytes<2, 4, 2>(), 64, opted_in[0]);
     }
-    hipLaunchKernelGGL(kernel, dim3((total + 7) / 8 * 8), dim3(256), lds, st, p);
-    CLASP_LAUNCH_CHECK();
-    return CLASP_OK;
+    constexpr int D = EPI == kEpiQkv ? 1 : 2, WPS = EPI == kEpiQkv ? 3 : 2;
+    return launch(prefill_gemm_kernel<EPI, 4, 4, D, WPS>, prefill_gemm_lds_bytes<4, 4, D>(), kPrefillRows, opted_in[1]);
 }
 
 // Attention of a chunk: long prefixes share the key / value blocks of a workgroup through LDS, short ones (a few blocks
@@ -824,7 +862,7 @@ int prefill_chunk(const clasp_ctx* ctx, const PrefillWs& ws, int ld, const int32
             g.A = ws.op_attn; g.n_rows = n; g.N = d; g.K = ctx->q_dim; g.R = R;
             g.out = ws.a_buf; g.ldo = d; g.resid = ws.h; g.ldr = d;
             g.next_op = ws.op_a; g.next_gain = ctx->mlp_norm[l]; g.next_ss = ws.ss_a; p.ld_ss = ld;
-            if ((rc = launch_prefill_gemm<kEpiResid>(ctx, p, st))) return rc;
+            if ((rc = launch_prefill_gemm<kEpiResid>(ctx, p, st, ws.parts))) return rc;
         }
         hipLaunchKernelGGL(prefill_rstd_kernel, dim3((n + 63) / 64), dim3(64, 16), 0, st, ws.ss_a, d / 16, ld, n, 1.0f / d,
                            c.rms_eps, ws.rstd_a);
@@ -845,7 +883,7 @@ int prefill_chunk(const clasp_ctx* ctx, const PrefillWs& ws, int ld, const int32
             g.A = ws.op_act; g.n_rows = n; g.N = d; g.K = F; g.R = R;
             g.out = ws.h; g.ldo = d; g.resid = ws.a_buf; g.ldr = d;
             g.next_op = ws.op_h; g.next_gain = ctx->attn_norm[l + 1]; g.next_ss = ws.ss_h; p.ld_ss = ld;
-            if ((rc = launch_prefill_gemm<kEpiResid>(ctx, p, st))) return rc;
+            if ((rc = launch_prefill_gemm<kEpiResid>(ctx, p, st, ws.parts))) return rc;
         }
     }
     return CLASP_OK;

@@ -25,6 +25,10 @@ struct PrefillGemmArgs {
     GemmArgs g;          // W, tile_end, A, n_rows, N, K, R, out/ldo, resid/ldr, next_op, next_gain, next_ss, qkv
     const float* rstd;   // [n_rows] 1/rms of the input rows (projections that follow a norm), else null
     int ld_ss;           // row capacity of next_ss: next_ss[tile][ld_ss]
+    // kEpiPartial (prefill_gemm_kernel with gridDim.y = k_split > 1): slice y of the contraction leaves its raw sums in
+    // g.out + y * slab ([rows][g.ldo]); prefill_reduce_kernel adds the slices in order and runs the residual epilogue
+    int k_split;
+    size_t slab;
 };
 
 // rstd[row] = 1 / sqrt(sum_p ss[p][row] / dim + eps). Block (64, 16): thread (x, y) adds parts y, y + 16, .. of row
@@ -108,6 +112,11 @@ __device__ __forceinline__ void prefill_epilogue(const PrefillGemmArgs& p, int r
                 kc[kfrag_offset(HD, pos, x)] = to_bf16(rot);
             }
         }
+    } else if constexpr (EPI == kEpiPartial) {
+        float* slab = g.out + (size_t)blockIdx.y * p.slab;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            if (row0 + r < g.n_rows) slab[(size_t)(row0 + r) * g.ldo + col] = acc[r];
     } else if constexpr (EPI == kEpiResid) {
         const float gain = g.next_gain ? g.next_gain[col] : 1.0f;
 #pragma unroll
@@ -136,17 +145,18 @@ __device__ __forceinline__ void prefill_epilogue(const PrefillGemmArgs& p, int r
     }
 }
 
-constexpr int kPrefillRM = 4;      // 16-row tiles per wavefront
-constexpr int kPrefillRows = 2 * kPrefillRM * 16;  // rows of a workgroup tile
+constexpr int kPrefillRM = 4;                      // 16-row tiles per wavefront (2 in the small-tile variant)
+constexpr int kPrefillRows = 2 * kPrefillRM * 16;  // rows of the 128-row workgroup tile; chunk sizes are multiples of it
 
 // D = k-steps a stage is requested ahead of its use (register sets in flight); D + 1 LDS stages
-template <int RN, int D>
+template <int RM, int RN, int D>
 constexpr size_t prefill_gemm_lds_bytes() {
-    return (size_t)(D + 1) * (2 * 2 * kPrefillRM + 2 * RN) * 1024;
+    return (size_t)(D + 1) * (2 * 2 * RM + 2 * RN) * 1024;
 }
 
-// Workgroup = 2 x 2 wavefronts; wavefront (wm, wn) accumulates row tiles wm*4 .. +3 times feature tiles wn*RN .. +RN-1
-// of the workgroup tile. Per k-step the workgroup stages 16 activation fragments (8 row tiles x hi/lo) and 2*RN weight
+// Workgroup = 2 x 2 wavefronts; wavefront (wm, wn) accumulates row tiles wm*RM .. +RM-1 times feature tiles wn*RN ..
+// +RN-1 of the workgroup tile (RM = 4: 128 rows; RM = 2: 64 rows, for passes so short that 128-row tiles would leave
+// CUs without a workgroup). Per k-step the workgroup stages 4*RM activation fragments (row tiles x hi/lo) and 2*RN weight
 // fragments of 1 KiB each: requested into registers at the top of a k-step, written to a free LDS stage after the
 // MFMAs of the D-th k-step from there (D register sets alternate, D + 1 LDS stages), one barrier per k-step. Two
 // workgroups share a CU (<= 256 registers per lane, <= 80 KiB of LDS each), so one computes while the other waits for
@@ -154,16 +164,18 @@ constexpr size_t prefill_gemm_lds_bytes() {
 // LDS and 152 registers, three workgroups per CU).
 // Workgroups are numbered so that the ones resident on an XCD at the same time share weight columns: the XCD's L2
 // then sees each weight fragment from HBM once and serves the sibling row blocks.
-template <int EPI, int RN, int D, int WPS>
+template <int EPI, int RM, int RN, int D, int WPS>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WPS, WPS))) void prefill_gemm_kernel(PrefillGemmArgs p) {
-    constexpr int RM = kPrefillRM, NSTAGE = D + 1;
+    constexpr int NSTAGE = D + 1, ROWS = 2 * RM * 16;
     constexpr int A_FR = 2 * 2 * RM, B_FR = 2 * RN, FR = A_FR + B_FR, NL = FR / 4;
     static_assert(FR % 4 == 0 && (D == 1 || D == 2), "fragments are dealt to four wavefronts");
     extern __shared__ u32x4 prefill_lds[];  // [NSTAGE][FR][64]
     const GemmArgs& g = p.g;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, wm = w >> 1, wn = w & 1;
-    const int KS = g.K >> 5, n_tiles = g.N >> 4;
-    const int nrb = (g.R * 16 + kPrefillRows - 1) / kPrefillRows, ncb = (n_tiles + B_FR - 1) / B_FR;
+    const int KS_all = g.K >> 5, n_tiles = g.N >> 4;
+    // this workgroup's slice of the contraction (all of it unless gridDim.y > 1)
+    const int ks0 = (int)(((long long)KS_all * blockIdx.y) / gridDim.y), KS = (int)(((long long)KS_all * (blockIdx.y + 1)) / gridDim.y) - ks0;
+    const int nrb = (g.R * 16 + ROWS - 1) / ROWS, ncb = (n_tiles + B_FR - 1) / B_FR;
     // block id -> (row block, column block): ids congruent mod 8 run on one XCD; give each XCD a contiguous range
     const int total = nrb * ncb, per_xcd = (total + 7) >> 3;
     const int pid = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
@@ -185,9 +197,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WPS, WPS)))
             int mi = 0, tl = tile;
             if (tile >= g.tile_end[0]) { mi = 1; tl = tile - g.tile_end[0]; }
             if (tile >= g.tile_end[1]) { mi = 2; tl = tile - g.tile_end[1]; }
-            src[j] = reinterpret_cast<const u32x4*>(g.W[mi]) + (size_t)tl * KS * 64 + lane;
+            src[j] = reinterpret_cast<const u32x4*>(g.W[mi]) + (size_t)tl * KS_all * 64 + lane;
             step[j] = 64;
         }
+        src[j] += (size_t)ks0 * step[j];
     }
     auto issue = [&](u32x4 (&r)[NL]) {
 #pragma unroll
@@ -272,6 +285,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WPS, WPS)))
             if (tile < n_tiles) prefill_epilogue<EPI>(p, rt, tile, lane, acc[i][j]);
         }
     }
+}
+
+// Sum of the k_split slices a split contraction left behind, in slice order, plus the residual epilogue (output, next
+// operand, sum-of-squares partials). Grid (rows, ceil(N / 256)), one column per thread.
+__global__ __launch_bounds__(256) void prefill_reduce_kernel(PrefillGemmArgs p, const float* parts) {
+    const GemmArgs& g = p.g;
+    const int row = blockIdx.x, c = blockIdx.y * 256 + threadIdx.x;
+    if (c >= g.N) return;  // N % 16 == 0: a 16-column tile is all in or out
+    float v = g.resid[(size_t)row * g.ldr + c];
+    for (int s = 0; s < p.k_split; ++s) v += parts[(size_t)s * p.slab + (size_t)row * g.ldo + c];
+    g.out[(size_t)row * g.ldo + c] = v;
+    if (g.next_op) store_operand<kDtBf16>(g.next_op, g.R, 0, row, c, v * (g.next_gain ? g.next_gain[c] : 1.0f));
+    const float sq = sum16(v * v);
+    if (g.next_ss && (c & 15) == 0) g.next_ss[(size_t)(c >> 4) * p.ld_ss + row] = sq;
 }
 
 // ---- 256 x 256 tile fed by direct global -> LDS loads ---------------------------------------------------------------
