@@ -1,19 +1,21 @@
-// Prompt processing ("prefill") with many rows per pass: the full model over hundreds of prompt tokens at once, whose
-// only lasting product is the KV cache that verification, the layer-skip search and drafting (Sec. 3.1, 3.6 of the
-// paper) read afterwards. With C rows per pass the GEMMs do C flop per weight byte, beyond the ridge of the part
-// (~310) from a few hundred rows on, so unlike the decode-time kernels these are organised around the matrix cores:
-//   * prefill_gemm_kernel: workgroup tile 128 rows x (128 | 256) features, 2 x 2 wavefronts, each holding a
-//     64 x (64 | 128) accumulator tile; both operands arrive in MFMA fragment order already (weights as packed for
-//     the decode kernels, activations as the hi/lo operand planes every producer writes), so staging is a copy of
-//     whole KiB fragments: global -> registers -> LDS one k-step ahead, two LDS stages, one barrier per k-step, two
-//     workgroups per CU.
-//     The activations keep the decode path's hi + lo split (two MFMAs per fragment pair), so that the cache a prompt
-//     leaves behind does not depend on how many rows went through at once beyond rounding order.
-//   * prefill_attn_kernel: causal flash attention; a wavefront owns two tiles of 16 queries (row x head of one KV
-//     group) and walks the visible prefix in 32-key blocks on its own (no merging), key / value fragments straight
-//     from the fragment-order cache with a register double buffer; sibling wavefronts read the same blocks from L2.
-// Epilogues write exactly what the decode kernels' epilogues write (rotated, scaled query fragments; keys and values
-// into the cache; residual stream, next operand, sum-of-squares partials; SwiGLU operand).
+// Prompt processing ("prefill") with many rows per pass: the full model over hundreds or thousands of prompt tokens
+// at once, whose only lasting product is the KV cache that verification, the layer-skip search and drafting (Sec. 3.1,
+// 3.6 of the paper) read afterwards. With C rows per pass the GEMMs do C flop per weight byte, beyond the ridge of the
+// part (~310) from a few hundred rows on, so unlike the decode-time kernels these are organised around the matrix
+// cores and around getting operands to them:
+//   * prefill_gemm256_kernel: 256 x 256 workgroup tiles, 4 x 2 wavefronts with 64 x 128 accumulators; both operands
+//     are stored in MFMA fragment order already (weights as packed for the decode kernels, activations as the hi / lo
+//     operand planes every producer writes), so staging is a copy of whole KiB fragments, done by direct global -> LDS
+//     loads into a ring of three stages.
+//   * prefill_gemm_kernel: 128 x 128 or 64 x 128 tiles staged through registers, for the q/k/v projection and for
+//     passes too short for the big tile; prefill_reduce_kernel finishes a K-split of very short passes.
+//   * prefill_attn_lds_kernel / prefill_attn_kernel: causal flash attention over the fragment-order cache; a wavefront
+//     owns two tiles of 16 queries (row x head of one KV group); long prefixes share each 32-key block among the eight
+//     wavefronts of a workgroup through a ring of LDS stages, short ones are read by every wavefront itself.
+// The activations keep the decode path's hi + lo split (two MFMAs per fragment pair), so that the cache a prompt leaves
+// behind does not depend on how many rows went through at once beyond rounding order. Epilogues write exactly what the
+// decode kernels' epilogues write (rotated, scaled query fragments; keys and values into the cache; residual stream,
+// next operand, sum-of-squares partials; SwiGLU operand).
 #pragma once
 #include "clasp_attn.h"
 #include "clasp_common.h"
@@ -316,7 +318,8 @@ constexpr int kPrefillBigRows = 256, kPrefillBigStages = 3;
 constexpr int kPrefillBigFrags = 4 * kPrefillRM * 2 + 2 * 8;  // 32 activation + 16 weight fragments per k-step
 constexpr size_t kPrefillBigLds = (size_t)kPrefillBigStages * kPrefillBigFrags * 1024;
 
-// lds_byte_addr must be the same in every lane (the hardware takes it from M0); lane l's 16 bytes land at + l * 16.
+// lds_byte_addr must be the same in every lane (the hardware takes it from M0, a reserved register that the compiler
+// sets itself before each of its own uses); lane l's 16 bytes land at + l * 16.
 __device__ __forceinline__ void load_to_lds_16(const u32x4* g, unsigned lds_byte_addr) {
     const unsigned base = __builtin_amdgcn_readfirstlane(lds_byte_addr);
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(g) : "memory");
