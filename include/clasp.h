@@ -154,6 +154,10 @@ int clasp_prefill(clasp_ctx *ctx, const int32_t *tokens, int n_tokens, int pos0,
  *                candidate) per cell, NaN where a candidate does not exist
  *   choice_out   dev uint8 [(n_layers+1)][(M+1)] or NULL: 0 computed kept, 1 skip kept, 255 no such cell
  *   g_final_out  dev fp32 [d_model] or NULL: g(L, M)
+ * Without score_out and choice_out the cells from which (L, M) cannot be reached (j < M - (L - i)) are left out: they
+ * decide nothing, and the last M levels then push fewer candidates through their layer. g_final_out is the same up to
+ * fp32 rounding order (launches with fewer rows may take kernels that slice the contraction differently), mask_out is
+ * the same unless a comparison is tied within that rounding.
  */
 int clasp_dp_select(clasp_ctx *ctx, const float *states, size_t layer_stride, int pos, int M, uint8_t *mask_out,
                     float *score_out, uint8_t *choice_out, float *g_final_out, void *stream);

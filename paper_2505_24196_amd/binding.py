@@ -260,7 +260,7 @@ class Engine:
         return out
 
     def clasp_dp_select(self, states: torch.Tensor, pos: int, M: int, want_tables: bool = False,
-                        out: Optional[Dict[str, torch.Tensor]] = None):
+                        out: Optional[Dict[str, torch.Tensor]] = None, want_g_final: bool = False):
         """states: device fp32 [L+1][d] (may be a strided view along dim 0). Returns dict(mask, scores?, choice?,
         g_final?) of device tensors; `out` lets the caller reuse the output tensors of an earlier call."""
         s = self.shape
@@ -272,6 +272,8 @@ class Engine:
             if want_tables:
                 out["scores"] = torch.empty(L + 1, M + 1, 2, dtype=torch.float32, device=self.device)
                 out["choice"] = torch.empty(L + 1, M + 1, dtype=torch.uint8, device=self.device)
+                out["g_final"] = torch.empty(s.d_model, dtype=torch.float32, device=self.device)
+            elif want_g_final:  # g(L, M) without the tables: the library then skips the cells that cannot reach (L, M)
                 out["g_final"] = torch.empty(s.d_model, dtype=torch.float32, device=self.device)
         _check(lib().clasp_dp_select(self._ctx, states.data_ptr(), states.stride(0), pos, M, _ptr(out["mask"]),
                                      _ptr(out.get("scores")), _ptr(out.get("choice")), _ptr(out.get("g_final")),

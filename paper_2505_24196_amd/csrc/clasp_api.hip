@@ -634,18 +634,25 @@ int dp_select_window(clasp_ctx* ctx, const float* states, size_t layer_stride, i
     hipLaunchKernelGGL(dp_table_init_kernel, dim3((cells + 255) / 256), dim3(256), 0, st, score_out, choice, cells);
     CLASP_LAUNCH_CHECK();
     const float* x0 = states + (size_t)lo * layer_stride;
+    // Cells (i, j) from which (L, M) cannot be reached (j < M - (L - i): too few layers left to skip) decide nothing;
+    // they are computed only when the caller asked for the tables. first_cell(i) = first cell of level i that is needed.
+    const bool full_table = score_out || choice_out;
+    auto first_cell = [&](int i) { return full_table ? 0 : std::max(0, M - (L - i)); };
     int rc;
     for (int i = 1; i <= L; ++i) {
         const int ell = (i - 1 < M) ? i - 1 : M;
+        const int j0 = first_cell(i), jc0 = std::max(1, j0), n_comp = ell - jc0 + 1;
+        const int jn0 = std::max(1, first_cell(i + 1));  // first cell whose state the next level pushes through a layer
         const float* g_prev = (i == 1) ? x0 : ctx->g[(i - 1) & 1];
         float* g_cur = ctx->g[i & 1];
-        if (ell > 0) {  // candidates g(i-1, 1..ell) through the window's layer i-1, all at position `pos`
-            if ((rc = run_layer(ctx, lo + i - 1, ell, R, 0, pos, g_prev + d, ctx->G, nullptr, nullptr, nullptr, nullptr, st,
-                                down_split)))
+        if (n_comp > 0) {  // candidates g(i-1, jc0..ell) through the window's layer i-1, all at position `pos`
+            if ((rc = run_layer(ctx, lo + i - 1, n_comp, R, 0, pos, g_prev + (size_t)jc0 * d, ctx->G, nullptr, nullptr,
+                                nullptr, nullptr, st, down_split)))
                 return rc;
         }
         SelectArgs s{};
         s.i = i; s.M = M; s.d = d; s.R = R;
+        s.j0 = j0; s.jc0 = jc0; s.jn0 = jn0;
         s.x_i = x0 + (size_t)i * layer_stride;
         s.g_prev = g_prev; s.g_cur = g_cur;
         if (down_split > 1) {  // candidates = residual rows (a_buf) + the K-slices the down projection left behind
@@ -657,7 +664,7 @@ int dp_select_window(clasp_ctx* ctx, const float* states, size_t layer_stride, i
         s.gain = (i < L) ? ctx->attn_norm[lo + i] : nullptr;
         s.ss = ctx->ss_h;
         s.scores = score_out; s.choice = choice;
-        const int cells_i = ((i < M) ? i : M) + 1;
+        const int cells_i = ((i < M) ? i : M) + 1 - j0;
         if (c.dtype == CLASP_BF16)
             hipLaunchKernelGGL((dp_select_kernel<kDtBf16>), dim3(cells_i), dim3(1024), 0, st, s);
         else

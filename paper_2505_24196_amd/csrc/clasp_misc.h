@@ -146,6 +146,10 @@ struct SelectArgs {
     float* ss;
     float* scores;    // [(L+1)][(M+1)][2] or null
     uint8_t* choice;  // [(L+1)][(M+1)]
+    // cells of this launch: j = j0 + blockIdx.x. Row 0 of G belongs to cell jc0 (>= 1), row 0 of the next layer's operand
+    // to cell jn0 (>= 1; cells below it feed nothing). The full table has j0 = 0, jc0 = jn0 = 1; a search that only
+    // needs the skip set leaves out the cells from which (L, M) cannot be reached.
+    int j0, jc0, jn0;
 };
 
 // One workgroup of 1024 threads per cell; every thread owns 4 consecutive columns per pass, all loads of a pass are
@@ -153,7 +157,7 @@ struct SelectArgs {
 template <int DT>
 __global__ __launch_bounds__(1024) void dp_select_kernel(SelectArgs a) {
     __shared__ float red[16][5];
-    const int j = blockIdx.x, d = a.d;
+    const int j = a.j0 + blockIdx.x, d = a.d;
     const int ell = min(a.i - 1, a.M);
     float* dst = a.g_cur + (size_t)j * d;
     const f32x4* x4 = reinterpret_cast<const f32x4*>(a.x_i);
@@ -162,10 +166,10 @@ __global__ __launch_bounds__(1024) void dp_select_kernel(SelectArgs a) {
         return;
     }
     const f32x4* skip4 = reinterpret_cast<const f32x4*>(a.g_prev + (size_t)(j - 1) * d);
-    const bool has_comp = j <= ell;
-    const f32x4* comp4 = reinterpret_cast<const f32x4*>(a.G + (size_t)(j - 1) * d);
+    const bool has_comp = j <= ell;  // cells of a launch never lie below jc0
+    const f32x4* comp4 = reinterpret_cast<const f32x4*>(a.G + (size_t)(j - a.jc0) * d);
     // the computed candidate: a finished row, or residual + K-slices of the down projection added in slice order
-    const f32x4* part4 = reinterpret_cast<const f32x4*>(a.parts + (size_t)(j - 1) * d);
+    const f32x4* part4 = reinterpret_cast<const f32x4*>(a.parts + (size_t)(j - a.jc0) * d);
     auto load_comp = [&](int c) -> f32x4 {
         f32x4 v = comp4[c];
         for (int p = 0; p < a.n_parts; ++p) v += part4[p * (a.part_stride / 4) + c];
@@ -215,13 +219,13 @@ __global__ __launch_bounds__(1024) void dp_select_kernel(SelectArgs a) {
     for (int c = threadIdx.x; c < d / 4; c += blockDim.x) {
         const f32x4 v = c == (int)threadIdx.x ? (keep_comp ? g_first : s_first) : (keep_comp ? load_comp(c) : skip4[c]);
         reinterpret_cast<f32x4*>(dst)[c] = v;
-        if (a.op) {
+        if (a.op && j >= a.jn0) {
             const f32x4 gn = gain4 ? gain4[c] : f32x4{1.f, 1.f, 1.f, 1.f};
-            store_operand4<DT>(a.op, a.R, d, j - 1, c * 4, v * gn);
+            store_operand4<DT>(a.op, a.R, d, j - a.jn0, c * 4, v * gn);
             float sq = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];  // 4 lanes cover one 16-column tile
             sq += __shfl_xor(sq, 1);
             sq += __shfl_xor(sq, 2);
-            if ((c & 3) == 0) a.ss[(size_t)(c >> 2) * kMaxRows + (j - 1)] = sq;
+            if ((c & 3) == 0) a.ss[(size_t)(c >> 2) * kMaxRows + (j - a.jn0)] = sq;
         }
     }
 }

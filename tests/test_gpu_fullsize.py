@@ -48,6 +48,9 @@ def verify_dp_draft(shape, T, eng, om, cache, M=12):
     # DP on row 1 (position T+1): cache rows 0..T of the oracle are the synthetic prefix plus row 0's own k/v
     print("oracle dp", flush=True)
     gpu, ref = check_dp(om, eng, ost[:, 1], T + 1, cache, M)
+    # the call as bench.py issues it (no tables: cells that cannot reach (L, M) are left out) selects the same set
+    lean = eng.clasp_dp_select(dev(ost[:, 1]), T + 1, M)
+    assert torch.equal(lean["mask"], gpu["mask"])
     # one draft step with the selected skip set, from row 2's token at position T+2
     print("oracle draft", flush=True)
     nxt = torch.zeros(1, dtype=torch.int32, device="cuda")

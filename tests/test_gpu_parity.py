@@ -542,3 +542,30 @@ def test_window_and_skip_cosine_reject_bad_arguments():
     # M = window: every layer of the window skipped, nothing outside it
     res = eng.clasp_dp_select_window(X, 5, 3, 1, 4)
     assert res["mask"].cpu().tolist() == [0, 1, 1, 1] + [0] * (L - 4)
+
+
+@pytest.mark.parametrize("name,resid_scale,M", [("tiny-f32", 0.05, 3), ("tiny-f32", 1.0, 8), ("small-bf16", 1.0, 1),
+                                               ("small-bf16-deep", 0.05, 12), ("small-bf16-deep", 1.0, 16),
+                                               ("small-bf16-hd128", 0.05, 2)])
+def test_search_without_tables_gives_the_same_set(name, resid_scale, M):
+    """Without the tables the library leaves out the cells that cannot reach (L, M); the skip set must not change and
+    g(L, M) only by fp32 rounding order (launches with fewer rows may take kernels that slice K differently). Also
+    on a window of layers."""
+    shape = si.SHAPES[name]
+    L = shape.n_layers
+    om, eng = oracle_model(name, 1, resid_scale), engine(name, 1, resid_scale, max_rows=32)
+    toks = prompt(shape, 12)
+    _, ost, _ = oracle_prefill(om, toks, 16)
+    tt = dev(toks, torch.int32)
+    eng.clasp_verify_forward(tt, 0)
+    X = dev(ost[:, 11])
+    full = eng.clasp_dp_select(X, 11, M, want_tables=True)
+    lean = eng.clasp_dp_select(X, 11, M, want_g_final=True)
+    assert torch.equal(full["mask"], lean["mask"]) and int(lean["mask"].sum()) == M
+    assert relerr(lean["g_final"].cpu().numpy(), full["g_final"].cpu().numpy()) <= 1e-5
+    if L >= 6 and M <= L - 4:
+        lo, hi = 2, L - 2
+        Mw = min(M, hi - lo)
+        full = eng.clasp_dp_select_window(X, 11, Mw, lo, hi, want_tables=True)
+        lean = eng.clasp_dp_select_window(X, 11, Mw, lo, hi)
+        assert torch.equal(full["mask"], lean["mask"])
