@@ -130,7 +130,8 @@ int clasp_verify_forward(clasp_ctx *ctx, const int32_t *tokens, int n_tokens, in
  * operands, fp32 accumulation), so the cache equals the one clasp_verify_forward leaves up to rounding order.
  *   tokens       dev int32 [n_tokens]; ids outside [0, vocab) are clamped
  *   n_tokens     >= 1;  pos0 >= 0, pos0 + n_tokens <= max_seq
- *   chunk_rows   rows per pass: a multiple of 128 in 128..8192 (larger = fewer passes over the weights)
+ *   chunk_rows   rows per pass: a multiple of 128 in 128..8192 (larger = fewer passes over the weights; 4096 is what the
+ *                measurements use: from there on every projection of an 8B-shaped model fills the chip with 256 x 256 tiles)
  *   workspace    dev, 256-byte aligned, >= clasp_prefill_workspace_bytes(cfg, chunk_rows) bytes, caller-owned, only
  *                used during the call (on `stream`)
  * clasp_prefill_workspace_bytes returns 0 for an unsupported configuration or chunk_rows.

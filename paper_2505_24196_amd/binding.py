@@ -230,7 +230,7 @@ class Engine:
         _check(lib().clasp_kv_read(self._ctx, layer, pos0, n_tokens, _ptr(K), _ptr(V), _stream()), "clasp_kv_read")
         return K, V
 
-    def clasp_prefill(self, tokens: torch.Tensor, pos0: int, chunk_rows: int = 1024):
+    def clasp_prefill(self, tokens: torch.Tensor, pos0: int, chunk_rows: int = 4096):
         """tokens: device int32 [n] -> their keys/values in every layer's cache at pos0.. (bf16 models). The workspace
         for `chunk_rows` rows per pass is allocated on first use and kept."""
         need = lib().clasp_prefill_workspace_bytes(C.byref(self.cfg), chunk_rows)
