@@ -74,6 +74,20 @@ def test_prefill_continues_an_existing_prefix():
     check_cache(eng, cache, 0, T)
 
 
+def test_prefill_continues_a_long_prefix():
+    """1003 tokens in place, 300 more on top: the chunk's attention walks 41 blocks through the LDS ring, starting from a
+    position that is not a multiple of 32."""
+    name, T0, T = "small-bf16", 1003, 1303
+    shape = si.SHAPES[name]
+    om, eng = oracle_model(name), engine(name, max_seq=1312)
+    toks = prompt(shape, T)
+    cache, _, _ = oracle_cache(om, toks, 1312, want_last=False)
+    tt = dev(toks, torch.int32)
+    eng.clasp_prefill(tt[:T0], 0, 1024)
+    eng.clasp_prefill(tt[T0:], T0, 384)
+    check_cache(eng, cache, 0, T)
+
+
 def test_prefill_agrees_with_the_row_limited_path():
     """Same prompt through clasp_verify_forward in chunks of max_rows: the two caches agree to rounding."""
     name, T = "small-bf16-hd128", 300
