@@ -126,14 +126,20 @@ int clasp_verify_forward(clasp_ctx *ctx, const int32_t *tokens, int n_tokens, in
  * in passes of chunk_rows rows through compute-bound MFMA GEMMs and causal flash attention. Writes the rows'
  * keys/values into every layer's cache and nothing else; the states and the next token of the prompt's last token
  * come from clasp_verify_forward on that token (or on the last few) afterwards. bf16 models only
- * (CLASP_E_UNSUPPORTED otherwise); arithmetic as in clasp_verify_forward (bf16 weights, hi + lo bf16 activation
- * operands, fp32 accumulation), so the cache equals the one clasp_verify_forward leaves up to rounding order.
+ * (CLASP_E_UNSUPPORTED otherwise). Passes of fewer than 1024 rows compute as clasp_verify_forward does (bf16 weights,
+ * hi + lo bf16 activation operands, fp32 accumulation) and leave the same cache up to rounding order. Passes of 1024
+ * rows or more (chunk_rows >= 1024 and that many rows left) run their projections on fp16 matrix instructions: each
+ * activation is rounded to one fp16 number (11 significant bits instead of the pair's 16), the layer's weights are
+ * converted to fp16 into the workspace at the start of the layer (exact for every bf16 weight of magnitude >= 2^-17,
+ * rounding to multiples of 2^-24 below), accumulation stays fp32, keys / values / attention stay bf16 as elsewhere. That
+ * halves the matrix-core work of a pass; the cache then agrees with clasp_verify_forward's to ~1e-3 of its largest
+ * magnitude per layer, inside the 2e-2 every bf16 result of this library is held to.
  *   tokens       dev int32 [n_tokens]; ids outside [0, vocab) are clamped
  *   n_tokens     >= 1;  pos0 >= 0, pos0 + n_tokens <= max_seq
  *   chunk_rows   rows per pass: a multiple of 128 in 128..8192 (larger = fewer passes over the weights; 4096 is what the
  *                measurements use: from there on every projection of an 8B-shaped model fills the chip with 256 x 256 tiles)
  *   workspace    dev, 256-byte aligned, >= clasp_prefill_workspace_bytes(cfg, chunk_rows) bytes, caller-owned, only
- *                used during the call (on `stream`)
+ *                used during the call (on `stream`); for chunk_rows >= 1024 it includes room for one layer's weights
  * clasp_prefill_workspace_bytes returns 0 for an unsupported configuration or chunk_rows.
  */
 size_t clasp_prefill_workspace_bytes(const clasp_config *cfg, int chunk_rows);

@@ -10,6 +10,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include "clasp_attn.h"
@@ -682,11 +683,20 @@ int dp_select_window(clasp_ctx* ctx, const float* states, size_t layer_stride, i
 #define CLASP_PREFILL_BIG 1  // 256 x 256 tiles fed by direct global -> LDS loads where the grid is large enough
 #endif
 constexpr int kPrefillMaxChunk = 8192;
+// Passes of at least this many rows run their GEMMs on fp16 MFMAs: one fp16 plane per activation instead of the bf16
+// hi / lo pair (half the matrix-core work) against an fp16 copy of the layer's weights made at the start of the layer
+// (one more read and write of the layer per pass, which shorter passes would not earn back). 0 = never.
+#ifndef CLASP_PREFILL_F16_ROWS
+#define CLASP_PREFILL_F16_ROWS 1024
+#endif
 
 struct PrefillWs {
     float *h, *a_buf, *ss_h, *ss_a, *rstd_h, *rstd_a, *parts;
     void *op_h, *op_a, *op_attn, *op_act, *q_frag;
+    char* w16;  // fp16 copy of one layer's packed matrices (q, k, v, o, gate|up, down in this order), or null
 };
+
+bool prefill_uses_f16(int rows) { return CLASP_PREFILL_F16_ROWS > 0 && rows >= CLASP_PREFILL_F16_ROWS; }
 constexpr int kPrefillSplitRows = 1024, kPrefillMaxSplit = 4;  // K-split of short passes: rows it applies to, slices
 
 size_t carve_prefill(const clasp_config& c, int chunk, char* base, PrefillWs* ws) {
@@ -705,6 +715,8 @@ size_t carve_prefill(const clasp_config& c, int chunk, char* base, PrefillWs* ws
     t.op_act = w.take<void>(C * (size_t)c.d_ffn * 4);
     t.q_frag = w.take<void>(C * qd * 2);
     t.parts = w.take<float>((size_t)kPrefillMaxSplit * std::min<size_t>(C, kPrefillSplitRows) * d * 4);
+    const size_t kvd = (size_t)c.n_kv_heads * c.head_dim;
+    t.w16 = prefill_uses_f16(chunk) ? w.take<char>((2 * qd * d + 2 * kvd * d + 3 * d * (size_t)c.d_ffn) * 2) : nullptr;
     if (ws) *ws = t;
     return w.off;
 }
@@ -716,21 +728,24 @@ size_t carve_prefill(const clasp_config& c, int chunk, char* base, PrefillWs* ws
 //  * q/k/v: 128 x 128 tiles with three lighter workgroups per CU (its epilogue does not fit the larger tiles' register
 //    budget, and 24 column blocks of 256 would leave half of a second round of CUs idle);
 //  * any of them: 64 x 128 tiles when even the 128 x 128 grid has fewer workgroups than CUs.
-template <int EPI>
+//  F16: the pass runs on fp16 operands (p.g.A is an fp16 plane, p.g.W an fp16 copy of the weights).
+template <int EPI, bool F16>
 int launch_prefill_gemm(const clasp_ctx* ctx, const PrefillGemmArgs& p, hipStream_t st, float* parts = nullptr) {
     const int tiles = p.g.N / 16;
     if constexpr (EPI != kEpiQkv) {
         const int nrb = (p.g.R * 16 + kPrefillBigRows - 1) / kPrefillBigRows, total = nrb * ((tiles + 15) / 16);
-        if (CLASP_PREFILL_BIG && total >= ctx->n_cu) {
+        // (the fp16 variant of the big tile walks the contraction in pairs of k-steps)
+        if (CLASP_PREFILL_BIG && total >= ctx->n_cu && (!F16 || (p.g.K / 32) % 2 == 0)) {
             static bool opted_in = false;  // more than 64 KiB of LDS per workgroup has to be requested once per kernel
-            auto kernel = prefill_gemm256_kernel<EPI>;
+            auto kernel = prefill_gemm256_kernel<EPI, F16>;
+            constexpr size_t big_lds = prefill_big_lds<F16>();
             if (!opted_in) {
-                if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPrefillBigLds) !=
+                if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)big_lds) !=
                     hipSuccess)
                     return CLASP_E_HIP;
                 opted_in = true;
             }
-            hipLaunchKernelGGL(kernel, dim3((total + 7) / 8 * 8), dim3(512), kPrefillBigLds, st, p);
+            hipLaunchKernelGGL(kernel, dim3((total + 7) / 8 * 8), dim3(512), big_lds, st, p);
             CLASP_LAUNCH_CHECK();
             return CLASP_OK;
         }
@@ -760,8 +775,8 @@ int launch_prefill_gemm(const clasp_ctx* ctx, const PrefillGemmArgs& p, hipStrea
             while (split >= 2 && p.g.K / 32 < 16 * split) --split;  // at least 16 k-steps per slice
             if (parts && split >= 2 && p.g.n_rows <= kPrefillSplitRows) {
                 static bool split_opted_in = false;
-                auto kernel = prefill_gemm_kernel<kEpiPartial, 2, 4, 2, 3>;
-                constexpr size_t lds = prefill_gemm_lds_bytes<2, 4, 2>();
+                auto kernel = prefill_gemm_kernel<kEpiPartial, 2, 4, 2, 3, F16>;
+                constexpr size_t lds = prefill_gemm_lds_bytes<2, 4, 2, F16>();
                 if (!split_opted_in) {
                     if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
                         return CLASP_E_HIP;
@@ -779,10 +794,12 @@ int launch_prefill_gemm(const clasp_ctx* ctx, const PrefillGemmArgs& p, hipStrea
                 return CLASP_OK;
             }
         }
-        return launch(prefill_gemm_kernel<EPI, 2, 4, 2, 3>, prefill_gemm_lds_bytes<2, 4, 2>(), 64, opted_in[0]);
+        constexpr size_t lds64 = prefill_gemm_lds_bytes<2, 4, 2, F16>();
+        return launch(prefill_gemm_kernel<EPI, 2, 4, 2, 3, F16>, lds64, 64, opted_in[0]);
     }
     constexpr int D = EPI == kEpiQkv ? 1 : 2, WPS = EPI == kEpiQkv ? 3 : 2;
-    return launch(prefill_gemm_kernel<EPI, 4, 4, D, WPS>, prefill_gemm_lds_bytes<4, 4, D>(), kPrefillRows, opted_in[1]);
+    constexpr size_t lds128 = prefill_gemm_lds_bytes<4, 4, D, F16>();
+    return launch(prefill_gemm_kernel<EPI, 4, 4, D, WPS, F16>, lds128, kPrefillRows, opted_in[1]);
 }
 
 // Attention of a chunk: long prefixes share the key / value blocks of a workgroup through LDS, short ones (a few blocks
@@ -828,21 +845,45 @@ int prefill_chunk(const clasp_ctx* ctx, const PrefillWs& ws, int ld, const int32
                   hipStream_t st) {
     const clasp_config& c = ctx->cfg;
     const int d = c.d_model, F = c.d_ffn, L = c.n_layers, R = (n + 15) / 16;
+    const bool f16 = ws.w16 && prefill_uses_f16(n);
     int rc;
     hipLaunchKernelGGL(prefill_embed_kernel, dim3(n, (d + 255) / 256), dim3(256), 0, st, tokens,
-                       static_cast<const bf16*>(ctx->embed), c.vocab, d, ws.h, ws.op_h, R, ctx->attn_norm[0], ws.ss_h, ld);
+                       static_cast<const bf16*>(ctx->embed), c.vocab, d, ws.h, ws.op_h, R, ctx->attn_norm[0], ws.ss_h, ld,
+                       (int)f16);
     CLASP_LAUNCH_CHECK();
+    auto gemm = [&](auto epi, const PrefillGemmArgs& p, float* parts) -> int {
+        constexpr int EPI = decltype(epi)::value;
+        return f16 ? launch_prefill_gemm<EPI, true>(ctx, p, st, parts) : launch_prefill_gemm<EPI, false>(ctx, p, st, parts);
+    };
     for (int l = 0; l < L; ++l) {
+        // this layer's matrices, as packed or as the fp16 copy made here (the last layer only runs q/k/v)
+        const void* W[6] = {ctx->wq[l], ctx->wk[l], ctx->wv[l], ctx->wo[l], ctx->w_gate_up[l], ctx->w_down[l]};
+        if (f16) {
+            const size_t bytes[6] = {(size_t)ctx->q_dim * d * 2, (size_t)ctx->kv_dim * d * 2, (size_t)ctx->kv_dim * d * 2,
+                                     (size_t)d * ctx->q_dim * 2, (size_t)2 * F * d * 2,       (size_t)d * F * 2};
+            const int n_mat = l == L - 1 ? 3 : 6;
+            ConvertArgs cv{};
+            size_t off = 0;
+            for (int m = 0; m < 6; ++m) {
+                cv.src[m] = static_cast<const u32x4*>(W[m]);
+                cv.dst[m] = reinterpret_cast<u32x4*>(ws.w16 + off);
+                if (m < n_mat) off += bytes[m];
+                cv.end[m] = off / 16;
+                W[m] = cv.dst[m];
+            }
+            hipLaunchKernelGGL(prefill_convert_f16_kernel, dim3(ctx->n_cu * 8), dim3(256), 0, st, cv);
+            CLASP_LAUNCH_CHECK();
+        }
         hipLaunchKernelGGL(prefill_rstd_kernel, dim3((n + 63) / 64), dim3(64, 16), 0, st, ws.ss_h, d / 16, ld, n, 1.0f / d,
                            c.rms_eps, ws.rstd_h);
         CLASP_LAUNCH_CHECK();
         {
             PrefillGemmArgs p{};
             GemmArgs& g = p.g;
-            g.W[0] = ctx->wq[l]; g.W[1] = ctx->wk[l]; g.W[2] = ctx->wv[l];
+            g.W[0] = W[0]; g.W[1] = W[1]; g.W[2] = W[2];
             g.tile_end[0] = ctx->q_dim / 16; g.tile_end[1] = (ctx->q_dim + ctx->kv_dim) / 16; g.tile_end[2] = ctx->qkv_dim / 16;
             g.A = ws.op_h; g.n_rows = n; g.N = ctx->qkv_dim; g.K = d; g.R = R;
-            p.rstd = ws.rstd_h;
+            p.rstd = ws.rstd_h; p.op_f16 = f16;
             QkvOut& o = g.qkv;
             o.n_heads = c.n_heads; o.n_kv_heads = c.n_kv_heads; o.head_dim = c.head_dim;
             o.pos0 = pos0; o.mode = 1; o.t_max = c.max_seq; o.rope = ctx->rope;
@@ -850,7 +891,7 @@ int prefill_chunk(const clasp_ctx* ctx, const PrefillWs& ws, int ld, const int32
             o.q_frag = ws.q_frag;
             o.k_cache = ctx->k_cache + (size_t)l * ctx->kv_layer_bytes;
             o.v_cache = ctx->v_cache + (size_t)l * ctx->kv_layer_bytes;
-            if ((rc = launch_prefill_gemm<kEpiQkv>(ctx, p, st))) return rc;
+            if ((rc = gemm(std::integral_constant<int, kEpiQkv>{}, p, nullptr))) return rc;
         }
         if (l == L - 1) break;
         {
@@ -860,16 +901,17 @@ int prefill_chunk(const clasp_ctx* ctx, const PrefillWs& ws, int ld, const int32
             a.Vt = ctx->v_cache + (size_t)l * ctx->kv_layer_bytes;
             a.out_op = ws.op_attn;
             a.n_rows = n; a.R = R; a.n_heads = c.n_heads; a.n_kv_heads = c.n_kv_heads; a.pos0 = pos0; a.t_max = c.max_seq;
+            a.op_f16 = f16;
             if ((rc = launch_prefill_attn(ctx, a, st))) return rc;
         }
         {
             PrefillGemmArgs p{};
             GemmArgs& g = p.g;
-            g.W[0] = ctx->wo[l]; g.tile_end[0] = g.tile_end[1] = g.tile_end[2] = d / 16;
+            g.W[0] = W[3]; g.tile_end[0] = g.tile_end[1] = g.tile_end[2] = d / 16;
             g.A = ws.op_attn; g.n_rows = n; g.N = d; g.K = ctx->q_dim; g.R = R;
             g.out = ws.a_buf; g.ldo = d; g.resid = ws.h; g.ldr = d;
-            g.next_op = ws.op_a; g.next_gain = ctx->mlp_norm[l]; g.next_ss = ws.ss_a; p.ld_ss = ld;
-            if ((rc = launch_prefill_gemm<kEpiResid>(ctx, p, st, ws.parts))) return rc;
+            g.next_op = ws.op_a; g.next_gain = ctx->mlp_norm[l]; g.next_ss = ws.ss_a; p.ld_ss = ld; p.op_f16 = f16;
+            if ((rc = gemm(std::integral_constant<int, kEpiResid>{}, p, ws.parts))) return rc;
         }
         hipLaunchKernelGGL(prefill_rstd_kernel, dim3((n + 63) / 64), dim3(64, 16), 0, st, ws.ss_a, d / 16, ld, n, 1.0f / d,
                            c.rms_eps, ws.rstd_a);
@@ -877,20 +919,20 @@ int prefill_chunk(const clasp_ctx* ctx, const PrefillWs& ws, int ld, const int32
         {
             PrefillGemmArgs p{};
             GemmArgs& g = p.g;
-            g.W[0] = ctx->w_gate_up[l]; g.N = 2 * F; g.tile_end[0] = g.tile_end[1] = g.tile_end[2] = g.N / 16;
+            g.W[0] = W[4]; g.N = 2 * F; g.tile_end[0] = g.tile_end[1] = g.tile_end[2] = g.N / 16;
             g.A = ws.op_a; g.n_rows = n; g.K = d; g.R = R;
-            p.rstd = ws.rstd_a;
+            p.rstd = ws.rstd_a; p.op_f16 = f16;
             g.next_op = ws.op_act;
-            if ((rc = launch_prefill_gemm<kEpiSwiglu>(ctx, p, st))) return rc;
+            if ((rc = gemm(std::integral_constant<int, kEpiSwiglu>{}, p, nullptr))) return rc;
         }
         {
             PrefillGemmArgs p{};
             GemmArgs& g = p.g;
-            g.W[0] = ctx->w_down[l]; g.tile_end[0] = g.tile_end[1] = g.tile_end[2] = d / 16;
+            g.W[0] = W[5]; g.tile_end[0] = g.tile_end[1] = g.tile_end[2] = d / 16;
             g.A = ws.op_act; g.n_rows = n; g.N = d; g.K = F; g.R = R;
             g.out = ws.h; g.ldo = d; g.resid = ws.a_buf; g.ldr = d;
-            g.next_op = ws.op_h; g.next_gain = ctx->attn_norm[l + 1]; g.next_ss = ws.ss_h; p.ld_ss = ld;
-            if ((rc = launch_prefill_gemm<kEpiResid>(ctx, p, st, ws.parts))) return rc;
+            g.next_op = ws.op_h; g.next_gain = ctx->attn_norm[l + 1]; g.next_ss = ws.ss_h; p.ld_ss = ld; p.op_f16 = f16;
+            if ((rc = gemm(std::integral_constant<int, kEpiResid>{}, p, ws.parts))) return rc;
         }
     }
     return CLASP_OK;

@@ -121,4 +121,35 @@ __device__ __forceinline__ void store_operand4(void* buf, int R, int ld, int row
     }
 }
 
+// ---- fp16 activation operand layout (prompt passes of many rows) ----------------------------------------------
+// One KiB per (k-step, row group) holding 16 rows x 32 halves, a single fp16 value (11 significant bits) per element
+// instead of the hi / lo pair, read by v_mfma_f32_16x16x32_f16 against weights converted to fp16 (every bf16 weight of
+// magnitude >= 2^-17 is an fp16 number). Inside the KiB the order is the MFMA operand's own: lane q*16 + r owns the 16
+// bytes X[rg*16 + r][s*32 + q*8 .. +8] at byte offset lane * 16, so a wavefront fetches a fragment with consecutive
+// lanes on consecutive addresses, exactly like a weight fragment.
+typedef _Float16 f16;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+__device__ __forceinline__ size_t frag16_elem_offset(int R, int row, int k) {
+    const int s = k >> 5, rg = row >> 4, r = row & 15, q = (k >> 3) & 3;
+    return ((((size_t)s * R + rg) * 4 + q) * 16 + r) * 8 + (k & 7);
+}
+
+// Operand element in the format a prompt pass runs in: fp16 plane (f16 != 0) or the bf16 hi / lo planes.
+__device__ __forceinline__ void store_operand_fmt(void* buf, int R, int row, int k, float v, int f16_plane) {
+    if (f16_plane) reinterpret_cast<f16*>(buf)[frag16_elem_offset(R, row, k)] = (f16)v;
+    else store_operand<kDtBf16>(buf, R, 0, row, k, v);
+}
+
+__device__ __forceinline__ void store_operand4_fmt(void* buf, int R, int row, int k, f32x4 v, int f16_plane) {
+    if (f16_plane) {
+        typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
+        f16x4 h;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) h[i] = (f16)v[i];
+        *reinterpret_cast<f16x4*>(reinterpret_cast<f16*>(buf) + frag16_elem_offset(R, row, k)) = h;
+    } else {
+        store_operand4<kDtBf16>(buf, R, 0, row, k, v);
+    }
+}
+
 }  // namespace clasp

@@ -31,6 +31,7 @@ struct PrefillGemmArgs {
     // g.out + y * slab ([rows][g.ldo]); prefill_reduce_kernel adds the slices in order and runs the residual epilogue
     int k_split;
     size_t slab;
+    int op_f16;          // format of next_op: one fp16 plane (passes that run on fp16 MFMAs) or the bf16 hi / lo planes
 };
 
 // rstd[row] = 1 / sqrt(sum_p ss[p][row] / dim + eps). Block (64, 16): thread (x, y) adds parts y, y + 16, .. of row
@@ -62,22 +63,50 @@ __global__ __launch_bounds__(1024) void prefill_rstd_kernel(const float* ss, int
 // Grid (rows, ceil(d / 256)).
 __global__ __launch_bounds__(256) void prefill_embed_kernel(const int32_t* tokens, const bf16* table, int vocab, int d,
                                                             float* h, void* op, int R, const float* gain, float* ss,
-                                                            int ld_ss) {
+                                                            int ld_ss, int op_f16) {
     const int row = blockIdx.x, c = blockIdx.y * 256 + threadIdx.x;
     if (c >= d) return;
     int tok = tokens[row];
     tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
     const float v = from_bf16(table[(size_t)tok * d + c]);
     h[(size_t)row * d + c] = v;
-    store_operand<kDtBf16>(op, R, d, row, c, v * gain[c]);
+    store_operand_fmt(op, R, row, c, v * gain[c], op_f16);
     const float sq = sum16(v * v);
     if ((c & 15) == 0) ss[(size_t)(c >> 4) * ld_ss + row] = sq;
 }
 
+// What the epilogue of a row tile reads from memory, fetched for all of a wavefront's feature tiles before any of them
+// is stored: the compiler cannot move a load across the epilogue's stores (they might alias), so loads issued tile by
+// tile would each wait out a memory latency in turn (o_proj and down: 128 of them per wavefront).
+template <int EPI, int RN>
+struct PrefillEpilogueInputs {
+    float rstd[4];       // 1/rms of the lane's four rows (projections that follow a norm), 0 for rows that do not exist
+    float resid[RN][4];  // kEpiResid: the residual values of the lane's four rows in each feature tile
+};
+
+template <int EPI, int RN>
+__device__ __forceinline__ void prefill_epilogue_fetch(const PrefillGemmArgs& p, int rt, int tile0, int n_tiles, int lane,
+                                                       PrefillEpilogueInputs<EPI, RN>& in) {
+    const GemmArgs& g = p.g;
+    const int c = lane & 15, row0 = rt * 16 + (lane >> 4) * 4;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const bool live = row0 + r < g.n_rows;
+        in.rstd[r] = (EPI == kEpiQkv || EPI == kEpiSwiglu) && live ? p.rstd[row0 + r] : 0.f;
+        if constexpr (EPI == kEpiResid) {
+#pragma unroll
+            for (int j = 0; j < RN; ++j)
+                in.resid[j][r] = live && tile0 + j < n_tiles ? g.resid[(size_t)(row0 + r) * g.ldr + (tile0 + j) * 16 + c] : 0.f;
+        }
+    }
+}
+
 // One finished 16 x 16 accumulator tile (row tile rt, feature tile `tile`): lane holds rows rt*16 + (lane/16)*4 + r,
-// feature tile*16 + lane%16. Every lane runs the same shuffles; only stores are predicated.
+// feature tile*16 + lane%16. Every lane runs the same shuffles; only stores are predicated. rstd / resid: the lane's
+// entries of PrefillEpilogueInputs for this tile.
 template <int EPI>
-__device__ __forceinline__ void prefill_epilogue(const PrefillGemmArgs& p, int rt, int tile, int lane, const f32x4& acc) {
+__device__ __forceinline__ void prefill_epilogue(const PrefillGemmArgs& p, int rt, int tile, int lane, const f32x4& acc,
+                                                 const float (&rstd)[4], const float (&resid)[4]) {
     const GemmArgs& g = p.g;
     const int c = lane & 15, col = tile * 16 + c, row0 = rt * 16 + (lane >> 4) * 4;
     if constexpr (EPI == kEpiQkv) {
@@ -94,7 +123,7 @@ __device__ __forceinline__ void prefill_epilogue(const PrefillGemmArgs& p, int r
         for (int r = 0; r < 4; ++r) {
             const int row = row0 + r;
             const bool live = row < g.n_rows;
-            const float own = acc[r] * (live ? p.rstd[row] : 0.f);
+            const float own = acc[r] * rstd[r];
             const float partner = __shfl_xor(own, 8);
             if (!live) continue;
             const int pos = o.pos0 + row;
@@ -127,10 +156,10 @@ __device__ __forceinline__ void prefill_epilogue(const PrefillGemmArgs& p, int r
             const bool live = row < g.n_rows;
             float v = 0.f;
             if (live) {
-                v = g.resid[(size_t)row * g.ldr + col] + acc[r];
+                v = resid[r] + acc[r];
                 g.out[(size_t)row * g.ldo + col] = v;
             }
-            if (g.next_op) store_operand<kDtBf16>(g.next_op, g.R, 0, row, col, v * gain);  // dead rows of the tile: zeros
+            if (g.next_op) store_operand_fmt(g.next_op, g.R, row, col, v * gain, p.op_f16);  // dead rows of the tile: zeros
             const float sq = sum16(v * v);
             if (g.next_ss && c == 0 && live) g.next_ss[(size_t)tile * p.ld_ss + row] = sq;
         }
@@ -139,10 +168,10 @@ __device__ __forceinline__ void prefill_epilogue(const PrefillGemmArgs& p, int r
         for (int r = 0; r < 4; ++r) {
             const int row = row0 + r;
             const bool live = row < g.n_rows;
-            const float own = acc[r] * (live ? p.rstd[row] : 0.f);
+            const float own = acc[r] * rstd[r];
             const float up = __shfl_xor(own, 8);
             const float v = live ? own / (1.0f + expf(-own)) * up : 0.f;
-            if (c < 8) store_operand<kDtBf16>(g.next_op, g.R, 0, row, tile * 8 + c, v);
+            if (c < 8) store_operand_fmt(g.next_op, g.R, row, tile * 8 + c, v, p.op_f16);
         }
     }
 }
@@ -151,9 +180,16 @@ constexpr int kPrefillRM = 4;                      // 16-row tiles per wavefront
 constexpr int kPrefillRows = 2 * kPrefillRM * 16;  // rows of the 128-row workgroup tile; chunk sizes are multiples of it
 
 // D = k-steps a stage is requested ahead of its use (register sets in flight); D + 1 LDS stages
-template <int RM, int RN, int D>
+template <int RM, int RN, int D, bool F16 = false>
 constexpr size_t prefill_gemm_lds_bytes() {
-    return (size_t)(D + 1) * (2 * 2 * RM + 2 * RN) * 1024;
+    return (size_t)(D + 1) * (2 * (F16 ? 1 : 2) * RM + 2 * RN) * 1024;
+}
+
+// acc += A fragment x B fragment on the matrix cores, operands bf16 or fp16 as the pass runs
+template <bool F16>
+__device__ __forceinline__ f32x4 prefill_mma(const u32x4& a, const u32x4& b, const f32x4& acc) {
+    if constexpr (F16) return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), acc, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(b), acc, 0, 0, 0);
 }
 
 // Workgroup = 2 x 2 wavefronts; wavefront (wm, wn) accumulates row tiles wm*RM .. +RM-1 times feature tiles wn*RN ..
@@ -166,10 +202,11 @@ constexpr size_t prefill_gemm_lds_bytes() {
 // LDS and 152 registers, three workgroups per CU).
 // Workgroups are numbered so that the ones resident on an XCD at the same time share weight columns: the XCD's L2
 // then sees each weight fragment from HBM once and serves the sibling row blocks.
-template <int EPI, int RM, int RN, int D, int WPS>
+template <int EPI, int RM, int RN, int D, int WPS, bool F16 = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WPS, WPS))) void prefill_gemm_kernel(PrefillGemmArgs p) {
     constexpr int NSTAGE = D + 1, ROWS = 2 * RM * 16;
-    constexpr int A_FR = 2 * 2 * RM, B_FR = 2 * RN, FR = A_FR + B_FR, NL = FR / 4;
+    constexpr int NP = F16 ? 1 : 2;  // planes of an activation fragment: fp16, or bf16 hi + lo
+    constexpr int A_FR = 2 * NP * RM, B_FR = 2 * RN, FR = A_FR + B_FR, NL = FR / 4;
     static_assert(FR % 4 == 0 && (D == 1 || D == 2), "fragments are dealt to four wavefronts");
     extern __shared__ u32x4 prefill_lds[];  // [NSTAGE][FR][64]
     const GemmArgs& g = p.g;
@@ -190,10 +227,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WPS, WPS)))
 #pragma unroll
     for (int j = 0; j < NL; ++j) {
         const int f = w + 4 * j;
-        if (f < A_FR) {  // activation fragment: row tile f/2, plane f%2; fetched in the order the MFMA lanes want it
-            const int rg = min(rb * (2 * RM) + (f >> 1), g.R - 1);
-            src[j] = reinterpret_cast<const u32x4*>(g.A) + ((size_t)rg * 2 + (f & 1)) * 64 + (lane & 15) * 4 + (lane >> 4);
-            step[j] = (size_t)g.R * 2 * 64;
+        if (f < A_FR) {  // activation fragment: row tile f/NP, plane f%NP; fetched in the order the MFMA lanes want it
+            const int rg = min(rb * (2 * RM) + f / NP, g.R - 1);
+            // bf16 planes are row-major (lane q*16 + r takes row r, 16-byte piece q); the fp16 plane is in lane order
+            src[j] = reinterpret_cast<const u32x4*>(g.A) + ((size_t)rg * NP + f % NP) * 64 +
+                     (F16 ? lane : (lane & 15) * 4 + (lane >> 4));
+            step[j] = (size_t)g.R * NP * 64;
         } else {
             const int tile = min(cb * B_FR + (f - A_FR), n_tiles - 1);
             int mi = 0, tl = tile;
@@ -226,23 +265,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WPS, WPS)))
         u32x4 bf[RN];
 #pragma unroll
         for (int j = 0; j < RN; ++j) bf[j] = L[(A_FR + wn * RN + j) * 64];
-        // the hi / lo pair of the next row tile is requested before this tile's MFMAs are issued (the scheduling
-        // fences keep the compiler from sinking the reads below them): LDS latency hides behind 16 MFMAs
-        u32x4 a_hi = L[(wm * RM * 2) * 64], a_lo = L[(wm * RM * 2 + 1) * 64];
+        // the next row tile's fragment(s) are requested before this tile's MFMAs are issued (the scheduling fences
+        // keep the compiler from sinking the reads below them): LDS latency hides behind the MFMAs
+        u32x4 a[NP];
+#pragma unroll
+        for (int h = 0; h < NP; ++h) a[h] = L[(wm * RM * NP + h) * 64];
 #pragma unroll
         for (int i = 0; i < RM; ++i) {
-            const u32x4 c_hi = a_hi, c_lo = a_lo;
+            u32x4 c[NP];
+#pragma unroll
+            for (int h = 0; h < NP; ++h) c[h] = a[h];
             if (i + 1 < RM) {
-                a_hi = L[((wm * RM + i + 1) * 2) * 64];
-                a_lo = L[((wm * RM + i + 1) * 2 + 1) * 64];
+#pragma unroll
+                for (int h = 0; h < NP; ++h) a[h] = L[((wm * RM + i + 1) * NP + h) * 64];
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int j = 0; j < RN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(c_hi), as_bf16x8(bf[j]), acc[i][j], 0, 0, 0);
+            for (int h = 0; h < NP; ++h)
 #pragma unroll
-            for (int j = 0; j < RN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(c_lo), as_bf16x8(bf[j]), acc[i][j], 0, 0, 0);
+                for (int j = 0; j < RN; ++j) acc[i][j] = prefill_mma<F16>(c[h], bf[j], acc[i][j]);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -281,10 +322,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WPS, WPS)))
     for (int i = 0; i < RM; ++i) {
         const int rt = rb * (2 * RM) + wm * RM + i;
         if (rt >= g.R) continue;
+        PrefillEpilogueInputs<EPI, RN> in;
+        prefill_epilogue_fetch<EPI, RN>(p, rt, cb * B_FR + wn * RN, n_tiles, lane, in);
 #pragma unroll
         for (int j = 0; j < RN; ++j) {
             const int tile = cb * B_FR + wn * RN + j;
-            if (tile < n_tiles) prefill_epilogue<EPI>(p, rt, tile, lane, acc[i][j]);
+            if (tile < n_tiles) prefill_epilogue<EPI>(p, rt, tile, lane, acc[i][j], in.rstd, in.resid[j]);
         }
     }
 }
@@ -298,7 +341,7 @@ __global__ __launch_bounds__(256) void prefill_reduce_kernel(PrefillGemmArgs p, 
     float v = g.resid[(size_t)row * g.ldr + c];
     for (int s = 0; s < p.k_split; ++s) v += parts[(size_t)s * p.slab + (size_t)row * g.ldo + c];
     g.out[(size_t)row * g.ldo + c] = v;
-    if (g.next_op) store_operand<kDtBf16>(g.next_op, g.R, 0, row, c, v * (g.next_gain ? g.next_gain[c] : 1.0f));
+    if (g.next_op) store_operand_fmt(g.next_op, g.R, row, c, v * (g.next_gain ? g.next_gain[c] : 1.0f), p.op_f16);
     const float sq = sum16(v * v);
     if (g.next_ss && (c & 15) == 0) g.next_ss[(size_t)(c >> 4) * p.ld_ss + row] = sq;
 }
@@ -314,9 +357,38 @@ __global__ __launch_bounds__(256) void prefill_reduce_kernel(PrefillGemmArgs p, 
 // stay in flight); nothing else in the loop touches global memory, and the counter is drained before the epilogue.
 // (The same loop on 32 x 32 x 16 MFMAs, whose operands a lane can gather from two neighbouring fragments, measured 12 %
 // slower.)
-constexpr int kPrefillBigRows = 256, kPrefillBigStages = 3;
-constexpr int kPrefillBigFrags = 4 * kPrefillRM * 2 + 2 * 8;  // 32 activation + 16 weight fragments per k-step
-constexpr size_t kPrefillBigLds = (size_t)kPrefillBigStages * kPrefillBigFrags * 1024;
+// With fp16 operands a k-step is 16 + 16 fragments (32 KiB) and the ring has four stages, three of them in flight.
+constexpr int kPrefillBigRows = 256;
+#ifndef CLASP_PREFILL_GROUP_ROWS
+#define CLASP_PREFILL_GROUP_ROWS 4
+#endif
+#ifndef CLASP_PREFILL_REGPIPE
+#define CLASP_PREFILL_REGPIPE 1
+#endif
+#ifndef CLASP_PREFILL_F16_STAGES
+#define CLASP_PREFILL_F16_STAGES 4
+#endif
+template <bool F16>
+constexpr int prefill_big_stages() { return F16 ? CLASP_PREFILL_F16_STAGES : 3; }
+template <bool F16>
+constexpr int prefill_big_frags() { return 4 * kPrefillRM * (F16 ? 1 : 2) + 2 * 8; }  // activation + weight fragments per k-step
+template <bool F16>
+constexpr size_t prefill_big_lds() { return (size_t)prefill_big_stages<F16>() * prefill_big_frags<F16>() * 1024; }
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {  // all but the newest N vector-memory operations of this wavefront are done
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// ... all but the newest `stages` (0..4, wave-uniform) groups of NL operations
+template <int NL>
+__device__ __forceinline__ void wait_all_but_stages(int stages) {
+    static_assert(4 * NL < 64, "the counter has six bits");
+    if (stages >= 4) wait_vmcnt<4 * NL>();
+    else if (stages == 3) wait_vmcnt<3 * NL>();
+    else if (stages == 2) wait_vmcnt<2 * NL>();
+    else if (stages == 1) wait_vmcnt<NL>();
+    else wait_vmcnt<0>();
+}
 
 // lds_byte_addr must be the same in every lane (the hardware takes it from M0, a reserved register that the compiler
 // sets itself before each of its own uses); lane l's 16 bytes land at + l * 16.
@@ -325,11 +397,24 @@ __device__ __forceinline__ void load_to_lds_16(const u32x4* g, unsigned lds_byte
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(g) : "memory");
 }
 
-template <int EPI>
+// The same with the global address split into a wave-uniform base (a scalar register pair, advanced with scalar
+// arithmetic) and a 32-bit byte offset per lane.
+__device__ __forceinline__ void load_to_lds_16(const void* uniform_base, unsigned lane_offset, unsigned lds_byte_addr) {
+    const uintptr_t b = reinterpret_cast<uintptr_t>(uniform_base);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)b), hi = __builtin_amdgcn_readfirstlane((unsigned)(b >> 32));
+    const unsigned long long sb = ((unsigned long long)hi << 32) | lo;
+    const unsigned base = __builtin_amdgcn_readfirstlane(lds_byte_addr);
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(base), "v"(lane_offset), "s"(sb) : "memory");
+}
+
+template <int EPI, bool F16 = false>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_gemm256_kernel(PrefillGemmArgs p) {
-    constexpr int RM = kPrefillRM, RN = 8, A_FR = 4 * RM * 2, B_FR = 2 * RN, FR = A_FR + B_FR, NL = FR / 8;
-    constexpr int NSTAGE = kPrefillBigStages;
-    static_assert(FR == kPrefillBigFrags && FR % 8 == 0, "fragments are dealt to eight wavefronts");
+    constexpr int NP = F16 ? 1 : 2;  // planes of an activation fragment: fp16, or bf16 hi + lo
+    constexpr int RM = kPrefillRM, RN = 8, A_FR = 4 * RM * NP, B_FR = 2 * RN, FR = A_FR + B_FR, NL = FR / 8;
+    constexpr int NSTAGE = prefill_big_stages<F16>(), AHEAD = NSTAGE - 1;
+    static_assert(FR == prefill_big_frags<F16>() && FR % 8 == 0, "fragments are dealt to eight wavefronts");
+    static_assert((F16 && CLASP_PREFILL_REGPIPE) || AHEAD == 2 || AHEAD == 3,
+                  "the waits of the plain loop are written out for two or three stages in flight");
     extern __shared__ u32x4 prefill_lds[];  // [NSTAGE][FR][64]
     const GemmArgs& g = p.g;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -339,31 +424,41 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int total = nrb * ncb, per_xcd = (total + 7) >> 3;
     const int pid = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
     if (pid >= total) return;
-    const int rb = pid % nrb, cb = pid / nrb;
+    // consecutive ids walk the row blocks of a group of GR first, then the column blocks: the workgroups an XCD runs at
+    // the same time then cover GR x (32 / GR) tiles and share GR + 32 / GR operand panels in its L2
+    constexpr int GR = CLASP_PREFILL_GROUP_ROWS;
+    const int grp = pid / (GR * ncb), in_grp = pid - grp * (GR * ncb), rows_grp = min(GR, nrb - grp * GR);
+    const int rb = grp * GR + in_grp % rows_grp, cb = in_grp / rows_grp;
 
-    const u32x4* src[NL];
+    // this wavefront's fragments w, w + 8, .. of a stage: a wave-uniform address each (kept in scalar registers) plus
+    // one of two per-lane offsets (activation fragments are fetched in the order the MFMA lanes want them)
+    static_assert(A_FR % 8 == 0, "a wavefront's j-th fragment is an activation fragment in all wavefronts or in none");
+    const char* src[NL];
     size_t step[NL];
+    // bf16 planes are row-major (lane q*16 + r takes row r, 16-byte piece q); the fp16 plane is in lane order
+    const unsigned lane_off_b = (unsigned)lane * 16;
+    const unsigned lane_off_a = F16 ? lane_off_b : (unsigned)((lane & 15) * 4 + (lane >> 4)) * 16;
 #pragma unroll
     for (int j = 0; j < NL; ++j) {
         const int f = w + 8 * j;
         if (f < A_FR) {
-            const int rg = min(rb * (A_FR / 2) + (f >> 1), g.R - 1);
-            src[j] = reinterpret_cast<const u32x4*>(g.A) + ((size_t)rg * 2 + (f & 1)) * 64 + (lane & 15) * 4 + (lane >> 4);
-            step[j] = (size_t)g.R * 2 * 64;
+            const int rg = min(rb * (A_FR / NP) + f / NP, g.R - 1);
+            src[j] = reinterpret_cast<const char*>(g.A) + ((size_t)rg * NP + f % NP) * 1024;
+            step[j] = (size_t)g.R * NP * 1024;
         } else {
             const int tile = min(cb * B_FR + (f - A_FR), n_tiles - 1);
             int mi = 0, tl = tile;
             if (tile >= g.tile_end[0]) { mi = 1; tl = tile - g.tile_end[0]; }
             if (tile >= g.tile_end[1]) { mi = 2; tl = tile - g.tile_end[1]; }
-            src[j] = reinterpret_cast<const u32x4*>(g.W[mi]) + (size_t)tl * KS * 64 + lane;
-            step[j] = 64;
+            src[j] = reinterpret_cast<const char*>(g.W[mi]) + (size_t)tl * KS * 1024;
+            step[j] = 1024;
         }
     }
     const unsigned lds_base = (unsigned)(uintptr_t)((__attribute__((address_space(3))) char*)prefill_lds);
-    auto issue = [&](int buf) {  // this wavefront's six fragments of the next stage in line
+    auto issue = [&](int buf) {  // this wavefront's NL fragments of the next stage in line
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
-            load_to_lds_16(src[j], lds_base + (unsigned)((buf * FR + w + 8 * j) * 1024));
+            load_to_lds_16(src[j], 8 * j < A_FR ? lane_off_a : lane_off_b, lds_base + (unsigned)((buf * FR + w + 8 * j) * 1024));
             src[j] += step[j];
         }
     };
@@ -378,51 +473,154 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         u32x4 bf[RN];
 #pragma unroll
         for (int j = 0; j < RN; ++j) bf[j] = L[(A_FR + wn * RN + j) * 64];
-        u32x4 a_hi = L[(wm * RM * 2) * 64], a_lo = L[(wm * RM * 2 + 1) * 64];
+        u32x4 a[NP];
+#pragma unroll
+        for (int h = 0; h < NP; ++h) a[h] = L[(wm * RM * NP + h) * 64];
 #pragma unroll
         for (int i = 0; i < RM; ++i) {
-            const u32x4 c_hi = a_hi, c_lo = a_lo;
+            u32x4 c[NP];
+#pragma unroll
+            for (int h = 0; h < NP; ++h) c[h] = a[h];
             if (i + 1 < RM) {
-                a_hi = L[((wm * RM + i + 1) * 2) * 64];
-                a_lo = L[((wm * RM + i + 1) * 2 + 1) * 64];
+#pragma unroll
+                for (int h = 0; h < NP; ++h) a[h] = L[((wm * RM + i + 1) * NP + h) * 64];
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int j = 0; j < RN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(c_hi), as_bf16x8(bf[j]), acc[i][j], 0, 0, 0);
+            for (int h = 0; h < NP; ++h)
 #pragma unroll
-            for (int j = 0; j < RN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(c_lo), as_bf16x8(bf[j]), acc[i][j], 0, 0, 0);
+                for (int j = 0; j < RN; ++j) acc[i][j] = prefill_mma<F16>(c[h], bf[j], acc[i][j]);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    // stage s lives in LDS stage s % 3; it is requested two k-steps before its use, right after the barrier that
+    if constexpr (F16 && CLASP_PREFILL_REGPIPE) {
+        // fp16 operands leave room for a second set of fragment registers: the fragments of stage s + 1 are read from
+        // LDS while the MFMAs of stage s run from registers, so LDS reads and matrix cores overlap inside a wavefront
+        // instead of alternating in lockstep across the workgroup behind the barrier. A stage's LDS slot is free once
+        // every wavefront holds it in registers (the barrier of the k-step that multiplies it), so all NSTAGE slots
+        // are in use: one being read, the others in flight.
+        static_assert(NSTAGE >= 3 && NSTAGE <= 5, "wait_all_but_stages handles up to four stages in flight");
+        u32x4 a0[RM], b0[RN], a1[RM], b1[RN];
+        auto fetch = [&](int buf, u32x4 (&a)[RM], u32x4 (&b)[RN]) {
+            const u32x4* L = prefill_lds + (size_t)buf * FR * 64 + lane;
+#pragma unroll
+            for (int j = 0; j < RN; ++j) b[j] = L[(A_FR + wn * RN + j) * 64];
+#pragma unroll
+            for (int i = 0; i < RM; ++i) a[i] = L[(wm * RM + i) * 64];
+        };
+#pragma unroll
+        for (int t = 0; t < NSTAGE; ++t)
+            if (t < KS) issue(t);
+        wait_all_but_stages<NL>(min(KS, NSTAGE) - 1);  // own loads of stage 0 have landed
+        __syncthreads();
+        fetch(0, a0, b0);
+        int buf = 0;  // LDS slot of stage s
+        auto mma = [&](const u32x4 (&a)[RM], const u32x4 (&b)[RN]) {
+#pragma unroll
+            for (int i = 0; i < RM; ++i)
+#pragma unroll
+                for (int j = 0; j < RN; ++j) acc[i][j] = prefill_mma<true>(a[i], b[j], acc[i][j]);
+        };
+        // k-step s < KS - 1: stage s + 1 goes to the other register set while stage s is multiplied. Every path through
+        // it reads before it multiplies: a k-step that could skip the reads would make the compiler wait for them in
+        // front of the MFMAs on the common path as well (the wait counters are merged where paths meet).
+        auto kstep = [&](int s, const u32x4 (&ca)[RM], const u32x4 (&cb_)[RN], u32x4 (&na)[RM], u32x4 (&nb)[RN]) {
+            const int later = KS - 1 - s;
+            // own loads of stage s + 1 have landed; stages s + 2 .. s + NSTAGE - 1 (where they exist) may stay in flight
+            wait_all_but_stages<NL>(min(later - 1, NSTAGE - 2));
+            __syncthreads();  // everybody's have, and every wavefront has stage s in registers
+            if (s + NSTAGE < KS) issue(buf);
+            buf = buf == NSTAGE - 1 ? 0 : buf + 1;
+            // the RM + RN reads of stage s + 1 are spread between the RM * RN MFMAs of stage s (two or three MFMAs after
+            // each read, pinned by scheduling fences): issued in one burst by all eight wavefronts after the barrier they
+            // would fill the LDS queue, and a wavefront whose read is not accepted cannot issue the MFMAs behind it
+            const u32x4* L = prefill_lds + (size_t)buf * FR * 64 + lane;
+            constexpr int NR = RM + RN, NM = RM * RN;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int t = 0; t < NR; ++t) {
+                if (t < RN) nb[t] = L[(A_FR + wn * RN + t) * 64];
+                else na[t - RN] = L[(wm * RM + t - RN) * 64];
+#pragma unroll
+                for (int m = t * NM / NR; m < (t + 1) * NM / NR; ++m)
+                    acc[m / RN][m % RN] = prefill_mma<true>(ca[m / RN], cb_[m % RN], acc[m / RN][m % RN]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        // KS is even (the launcher sends other contractions to the smaller tiles): pairs of k-steps alternate the two
+        // register sets, and the last pair ends without a read
+        for (int s = 0; s + 2 < KS; s += 2) {
+            kstep(s, a0, b0, a1, b1);
+            kstep(s + 1, a1, b1, a0, b0);
+        }
+        kstep(KS - 2, a0, b0, a1, b1);
+        mma(a1, b1);
+    } else {
+    // stage s lives in LDS stage s % NSTAGE; it is requested AHEAD k-steps before its use, right after the barrier that
     // tells that every wavefront has finished reading the stage it replaces
-    issue(0);
-    if (KS > 1) issue(1);
+#pragma unroll
+    for (int t = 0; t < AHEAD; ++t)
+        if (t < KS) issue(t);
     int buf = 0;
     for (int s = 0; s < KS; ++s) {
-        if (s + 1 < KS) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");  // own loads of stage s have landed
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        // own loads of stage s have landed: the stages requested after it (at most AHEAD - 1, fewer at the end) may
+        // stay in flight
+        const int later = KS - 1 - s;
+        if (later >= AHEAD - 1) wait_vmcnt<(AHEAD - 1) * NL>();
+        else if (AHEAD == 3 && later == 1) wait_vmcnt<NL>();
+        else wait_vmcnt<0>();
         __syncthreads();  // everybody's have, and stage s - 1 is no longer read
-        if (s + 2 < KS) issue(buf == 0 ? 2 : buf - 1);  // (s + 2) % 3
+        if (s + AHEAD < KS) issue(buf == 0 ? NSTAGE - 1 : buf - 1);  // (s + AHEAD) % NSTAGE
         compute(buf);
         buf = buf == NSTAGE - 1 ? 0 : buf + 1;
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    wait_vmcnt<0>();
 
 #pragma unroll
     for (int i = 0; i < RM; ++i) {
-        const int rt = rb * (A_FR / 2) + wm * RM + i;
+        const int rt = rb * (A_FR / NP) + wm * RM + i;
         if (rt >= g.R) continue;
+        PrefillEpilogueInputs<EPI, RN> in;
+        prefill_epilogue_fetch<EPI, RN>(p, rt, cb * B_FR + wn * RN, n_tiles, lane, in);
 #pragma unroll
         for (int j = 0; j < RN; ++j) {
             const int tile = cb * B_FR + wn * RN + j;
-            if (tile < n_tiles) prefill_epilogue<EPI>(p, rt, tile, lane, acc[i][j]);
+            if (tile < n_tiles) prefill_epilogue<EPI>(p, rt, tile, lane, acc[i][j], in.rstd, in.resid[j]);
         }
     }
 }
+// ---- weights of one layer as fp16 ------------------------------------------------------------------------------------
+// Element-wise bf16 -> fp16 of up to six packed matrices (fragment order is kept: the copy is read exactly like the
+// original). Exact for every weight of magnitude >= 2^-17; smaller ones round to the fp16 subnormal grid (2^-24).
+struct ConvertArgs {
+    const u32x4* src[6];
+    u32x4* dst[6];
+    size_t end[6];  // running total of 16-byte units after each matrix
+};
+
+__global__ __launch_bounds__(256) void prefill_convert_f16_kernel(ConvertArgs c) {
+    const size_t total = c.end[5];
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const u32x4* sp = c.src[0];
+        u32x4* dp = c.dst[0];
+        size_t first = 0;
+#pragma unroll
+        for (int k = 1; k < 6; ++k)
+            if (i >= c.end[k - 1]) { sp = c.src[k]; dp = c.dst[k]; first = c.end[k - 1]; }
+        const size_t j = i - first;
+        const u32x4 v = __builtin_nontemporal_load(sp + j);
+        u32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const f16 a = (f16)__uint_as_float(v[e] << 16), b = (f16)__uint_as_float(v[e] & 0xffff0000u);
+            o[e] = (unsigned)__builtin_bit_cast(unsigned short, a) | ((unsigned)__builtin_bit_cast(unsigned short, b) << 16);
+        }
+        dp[j] = o;
+    }
+}
+
 // ---- causal attention over the cache for a chunk of rows ----------------------------------------------------------
 struct PrefillAttnArgs {
     const void* q_frag;  // [n_kv_heads][R*G tiles][head_dim/32][64][8], rotated and scaled by the q/k/v epilogue
@@ -430,6 +628,7 @@ struct PrefillAttnArgs {
     const void* Vt;
     void* out_op;        // operand of the output projection, R row groups
     int n_rows, R, n_heads, n_kv_heads, pos0, t_max;
+    int op_f16;          // format of out_op, as PrefillGemmArgs::op_f16
 };
 
 constexpr int kPrefillAttnNT = 2, kPrefillAttnWaves = 4;
@@ -503,7 +702,7 @@ __global__ __launch_bounds__(kPrefillAttnWaves * 64) void prefill_attn_kernel(Pr
         const int row = qi / G, h = kvh * G + qi % G;
 #pragma unroll
         for (int c = 0; c < CT; ++c)
-            store_operand4<kDtBf16>(a.out_op, a.R, 0, row, h * HD + c * 16 + q4 * 4, st.o[t][c] * inv);
+            store_operand4_fmt(a.out_op, a.R, row, h * HD + c * 16 + q4 * 4, st.o[t][c] * inv, a.op_f16);
     }
 }
 
@@ -621,7 +820,7 @@ __global__ __launch_bounds__(NW * 64) void prefill_attn_lds_kernel(PrefillAttnAr
         const int row = qi / G, h = kvh * G + qi % G;
 #pragma unroll
         for (int c = 0; c < CT; ++c)
-            store_operand4<kDtBf16>(a.out_op, a.R, 0, row, h * HD + c * 16 + q4 * 4, st.o[t][c] * inv);
+            store_operand4_fmt(a.out_op, a.R, row, h * HD + c * 16 + q4 * 4, st.o[t][c] * inv, a.op_f16);
     }
 }
 

@@ -2,7 +2,10 @@
 the cache it leaves (read back with clasp_kv_read), and the states / logits of the prompt's last token, which
 clasp_verify_forward computes on top of that cache. Tolerance as for the other bf16 calls: 2e-2 of the largest
 magnitude of the oracle tensor. Prompt lengths are chosen ragged (not multiples of 16, 128 or the chunk), several
-chunks long; from 1024 tokens on the attention shares key / value blocks through LDS (head_dim 64 and 128); the wide-FFN shape (1024 column tiles in gate|up) takes the 256 x 256 tile of that projection at 800 tokens.
+chunks long; from 1024 tokens on the attention shares key / value blocks through LDS (head_dim 64 and 128); the
+wide-FFN shape (1024 column tiles in gate|up) takes the 256 x 256 tile of that projection at 800 tokens. Passes of 1024
+rows or more run on fp16 operands (one fp16 plane per activation, weights converted per layer): the 1100-, 1300- and
+1700-token cases, the 24-layer shape among them, with the 256 x 256 tile in its fp16 form at 1300 tokens.
 """
 import numpy as np
 import pytest
@@ -40,7 +43,8 @@ def check_cache(eng, cache, lo, hi, what=""):
 
 @pytest.mark.parametrize("name,T,chunk", [("small-bf16", 203, 128), ("small-bf16-hd128", 333, 256),
                                            ("small-bf16-deep", 150, 128), ("small-bf16", 130, 128), ("small-bf16", 1100, 1152),
-                                           ("small-bf16-hd128", 1700, 2048), ("small-bf16-wide-ffn", 800, 1024)])
+                                           ("small-bf16-hd128", 1700, 2048), ("small-bf16-wide-ffn", 800, 1024),
+                                           ("small-bf16-wide-ffn", 1300, 1408), ("small-bf16-deep", 1100, 1152)])
 def test_prefill_cache_and_last_token_match_oracle(name, T, chunk):
     shape = si.SHAPES[name]
     max_seq = (T + 31) // 32 * 32
