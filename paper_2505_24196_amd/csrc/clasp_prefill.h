@@ -4,18 +4,21 @@
 // part (~310) from a few hundred rows on, so unlike the decode-time kernels these are organised around the matrix
 // cores and around getting operands to them:
 //   * prefill_gemm256_kernel: 256 x 256 workgroup tiles, 4 x 2 wavefronts with 64 x 128 accumulators; both operands
-//     are stored in MFMA fragment order already (weights as packed for the decode kernels, activations as the hi / lo
-//     operand planes every producer writes), so staging is a copy of whole KiB fragments, done by direct global -> LDS
-//     loads into a ring of three stages.
+//     are stored in MFMA fragment order already (weights as packed for the decode kernels, activations as the operand
+//     planes every producer writes), so staging is a copy of whole KiB fragments, done by direct global -> LDS loads
+//     into a ring of three or four stages.
 //   * prefill_gemm_kernel: 128 x 128 or 64 x 128 tiles staged through registers, for the q/k/v projection and for
 //     passes too short for the big tile; prefill_reduce_kernel finishes a K-split of very short passes.
 //   * prefill_attn_lds_kernel / prefill_attn_kernel: causal flash attention over the fragment-order cache; a wavefront
 //     owns two tiles of 16 queries (row x head of one KV group); long prefixes share each 32-key block among the eight
 //     wavefronts of a workgroup through a ring of LDS stages, short ones are read by every wavefront itself.
-// The activations keep the decode path's hi + lo split (two MFMAs per fragment pair), so that the cache a prompt leaves
-// behind does not depend on how many rows went through at once beyond rounding order. Epilogues write exactly what the
-// decode kernels' epilogues write (rotated, scaled query fragments; keys and values into the cache; residual stream,
-// next operand, sum-of-squares partials; SwiGLU operand).
+// Passes of fewer than 1024 rows keep the decode path's hi + lo bf16 activation split (two MFMAs per fragment pair), so
+// that the cache a short prompt leaves behind equals the row-limited path's up to rounding order. Longer passes are
+// bound by the matrix cores, where the split doubles the work: they run on fp16 operands instead (one fp16 plane per
+// activation, 11 significant bits; the layer's bf16 weights converted to fp16, which represents them exactly down to
+// 2^-17, by prefill_convert_f16_kernel at the start of each layer; fp32 accumulation). Epilogues write exactly what
+// the decode kernels' epilogues write (rotated, scaled query fragments; keys and values into the cache; residual
+// stream, next operand in the pass's format, sum-of-squares partials; SwiGLU operand).
 #pragma once
 #include "clasp_attn.h"
 #include "clasp_common.h"
@@ -82,6 +85,7 @@ template <int EPI, int RN>
 struct PrefillEpilogueInputs {
     float rstd[4];       // 1/rms of the lane's four rows (projections that follow a norm), 0 for rows that do not exist
     float resid[RN][4];  // kEpiResid: the residual values of the lane's four rows in each feature tile
+    float2 rope[RN][4];  // kEpiQkv: (cos, sin) of the lane's rotary pair at the four rows' positions (q and k tiles)
 };
 
 template <int EPI, int RN>
@@ -98,6 +102,17 @@ __device__ __forceinline__ void prefill_epilogue_fetch(const PrefillGemmArgs& p,
             for (int j = 0; j < RN; ++j)
                 in.resid[j][r] = live && tile0 + j < n_tiles ? g.resid[(size_t)(row0 + r) * g.ldr + (tile0 + j) * 16 + c] : 0.f;
         }
+        if constexpr (EPI == kEpiQkv) {
+            const QkvOut& o = g.qkv;
+            const int HALF = o.head_dim >> 1, tph = o.head_dim >> 4;
+#pragma unroll
+            for (int j = 0; j < RN; ++j) {
+                const int tile = tile0 + j;  // a q or k tile starts a whole number of heads after its matrix's first tile
+                const int tl = tile - (tile < g.tile_end[0] ? 0 : g.tile_end[0]);
+                const int e = (tl % tph) * 8 + (c & 7);
+                in.rope[j][r] = live && tile < g.tile_end[1] ? o.rope[(size_t)(o.pos0 + row0 + r) * HALF + e] : float2{1.f, 0.f};
+            }
+        }
     }
 }
 
@@ -106,7 +121,7 @@ __device__ __forceinline__ void prefill_epilogue_fetch(const PrefillGemmArgs& p,
 // entries of PrefillEpilogueInputs for this tile.
 template <int EPI>
 __device__ __forceinline__ void prefill_epilogue(const PrefillGemmArgs& p, int rt, int tile, int lane, const f32x4& acc,
-                                                 const float (&rstd)[4], const float (&resid)[4]) {
+                                                 const float (&rstd)[4], const float (&resid)[4], const float2 (&rope)[4]) {
     const GemmArgs& g = p.g;
     const int c = lane & 15, col = tile * 16 + c, row0 = rt * 16 + (lane >> 4) * 4;
     if constexpr (EPI == kEpiQkv) {
@@ -131,7 +146,7 @@ __device__ __forceinline__ void prefill_epilogue(const PrefillGemmArgs& p, int r
                 vc[vfrag_offset(HD, pos, u * 16 + c)] = to_bf16(own);
                 continue;
             }
-            const float2 cs = o.rope[(size_t)pos * HALF + e];
+            const float2 cs = rope[r];
             const float rot = own * cs.x + ((c & 8) ? partner : -partner) * cs.y;
             if (which == 0) {
                 // query index inside its KV head: row * G + head % G; g.R * G tiles of 16 queries per KV head
@@ -327,7 +342,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WPS, WPS)))
 #pragma unroll
         for (int j = 0; j < RN; ++j) {
             const int tile = cb * B_FR + wn * RN + j;
-            if (tile < n_tiles) prefill_epilogue<EPI>(p, rt, tile, lane, acc[i][j], in.rstd, in.resid[j]);
+            if (tile < n_tiles) prefill_epilogue<EPI>(p, rt, tile, lane, acc[i][j], in.rstd, in.resid[j], in.rope[j]);
         }
     }
 }
@@ -587,7 +602,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int j = 0; j < RN; ++j) {
             const int tile = cb * B_FR + wn * RN + j;
-            if (tile < n_tiles) prefill_epilogue<EPI>(p, rt, tile, lane, acc[i][j], in.rstd, in.resid[j]);
+            if (tile < n_tiles) prefill_epilogue<EPI>(p, rt, tile, lane, acc[i][j], in.rstd, in.resid[j], in.rope[j]);
         }
     }
 }
