@@ -53,6 +53,28 @@ def test_sizes_and_validation_without_a_gpu():
     assert lib.clasp_destroy(None) == -1
 
 
+def test_prefill_workspace_sizes_without_a_gpu():
+    """The prompt pass's workspace: refused chunk sizes give 0; it grows with the chunk; from 1024 rows on it also holds
+    the fp16 copy of one layer's matrices."""
+    from paper_2505_24196_amd import binding
+    import synth_inputs as si
+    lib = binding.lib()
+    s = si.LLAMA3_8B
+    cfg = binding.Config(s.n_layers, s.d_model, s.n_heads, s.n_kv_heads, s.head_dim, s.d_ffn, s.vocab, 8192, 16, 1,
+                         s.rms_eps, s.rope_base)
+    size = lambda rows: lib.clasp_prefill_workspace_bytes(C.byref(cfg), rows)
+    for bad in (0, 100, 64, 8192 + 128, -128):
+        assert size(bad) == 0
+    assert 0 < size(128) < size(256) < size(896)
+    per_128_rows = size(1280) - size(1152)  # beyond 1024 rows every buffer that grows grows with the rows
+    assert size(1152) - size(1024) == per_128_rows
+    assert size(1024) - size(896) >= per_128_rows + s.layer_weight_elems() * 2
+    f32 = si.TINY_F32
+    cfg32 = binding.Config(f32.n_layers, f32.d_model, f32.n_heads, f32.n_kv_heads, f32.head_dim, f32.d_ffn, f32.vocab,
+                           64, 16, 0, f32.rms_eps, f32.rope_base)
+    assert lib.clasp_prefill_workspace_bytes(C.byref(cfg32), 128) == 0  # fp32 models take the row-limited path
+
+
 def test_engine_refuses_to_run_without_a_gpu():
     import torch
     if torch.cuda.is_available():
