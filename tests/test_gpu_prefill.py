@@ -92,6 +92,21 @@ def test_prefill_continues_a_long_prefix():
     check_cache(eng, cache, 0, T)
 
 
+@pytest.mark.parametrize("T,chunk", [(300, 128), (1100, 1152)])
+def test_prefill_twice_is_bit_identical(T, chunk):
+    """No atomics, fixed-order sums: the same prompt pass leaves the same bits (bf16 passes and fp16 passes alike)."""
+    name = "small-bf16"
+    shape = si.SHAPES[name]
+    eng = engine(name, max_seq=(T + 31) // 32 * 32)
+    tt = dev(prompt(shape, T), torch.int32)
+    eng.clasp_prefill(tt, 0, chunk)
+    first = [tuple(t.clone() for t in eng.clasp_kv_read(l, 0, T)) for l in range(shape.n_layers)]
+    eng.clasp_prefill(tt, 0, chunk)
+    for l in range(shape.n_layers):
+        K, V = eng.clasp_kv_read(l, 0, T)
+        assert torch.equal(K, first[l][0]) and torch.equal(V, first[l][1]), f"layer {l}"
+
+
 def test_prefill_agrees_with_the_row_limited_path():
     """Same prompt through clasp_verify_forward in chunks of max_rows: the two caches agree to rounding."""
     name, T = "small-bf16-hd128", 300
