@@ -78,52 +78,59 @@ __global__ __launch_bounds__(256) void prefill_embed_kernel(const int32_t* token
     if ((c & 15) == 0) ss[(size_t)(c >> 4) * ld_ss + row] = sq;
 }
 
-// What the epilogue of a row tile reads from memory, fetched for all of a wavefront's feature tiles before any of them
-// is stored: the compiler cannot move a load across the epilogue's stores (they might alias), so loads issued tile by
-// tile would each wait out a memory latency in turn (o_proj and down: 128 of them per wavefront).
-template <int EPI, int RN>
-struct PrefillEpilogueInputs {
-    float rstd[4];       // 1/rms of the lane's four rows (projections that follow a norm), 0 for rows that do not exist
-    float resid[RN][4];  // kEpiResid: the residual values of the lane's four rows in each feature tile
-    float2 rope[RN][4];  // kEpiQkv: (cos, sin) of the lane's rotary pair at the four rows' positions (q and k tiles)
+// The GEMMs below multiply with the weight fragment as the MFMA's first operand and the activation fragment as its
+// second, so a finished 16 x 16 accumulator tile is D[feature][row]: lane holds row rt*16 + lane%16 and the four
+// consecutive features tile*16 + (lane/16)*4 + r. Four consecutive features of one row are contiguous in everything an
+// epilogue touches (residual stream, operand planes, query fragments, key cache), so each of its loads and stores
+// moves 8 or 16 bytes per lane (with the other orientation, four rows of one feature per lane, they were 2 or 4 bytes
+// wide and four times as many).
+//
+// What the epilogues of one feature tile read from memory, for all RM row tiles of a wavefront. The compiler cannot move
+// a load across the epilogue's stores (they might alias), so loads issued tile by tile would each wait out a memory
+// latency in turn; instead the batch of the next feature tile is requested before the current one is stored.
+template <int EPI, int RM>
+struct PrefillEpilogueBatch {
+    f32x4 gain;           // kEpiResid: the next norm's gains of the lane's four features
+    f32x4 resid[RM];      // kEpiResid: the residual values of those features in the lane's row of each row tile
+    f32x4 rope[RM][2];    // kEpiQkv: (cos, sin) x 4 of the lane's four rotary pairs at its rows' positions (q and k tiles)
 };
 
-template <int EPI, int RN>
-__device__ __forceinline__ void prefill_epilogue_fetch(const PrefillGemmArgs& p, int rt, int tile0, int n_tiles, int lane,
-                                                       PrefillEpilogueInputs<EPI, RN>& in) {
+template <int EPI, int RM>
+__device__ __forceinline__ void prefill_epilogue_fetch(const PrefillGemmArgs& p, int rt0, int tile, int n_tiles, int lane,
+                                                       PrefillEpilogueBatch<EPI, RM>& b) {
     const GemmArgs& g = p.g;
-    const int c = lane & 15, row0 = rt * 16 + (lane >> 4) * 4;
+    const int f0 = (lane >> 4) * 4, col0 = tile * 16 + f0;
+    const bool there = tile < n_tiles;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f}, one = {1.f, 1.f, 1.f, 1.f};
+    if constexpr (EPI == kEpiResid) b.gain = g.next_gain && there ? *reinterpret_cast<const f32x4*>(g.next_gain + col0) : one;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const bool live = row0 + r < g.n_rows;
-        in.rstd[r] = (EPI == kEpiQkv || EPI == kEpiSwiglu) && live ? p.rstd[row0 + r] : 0.f;
-        if constexpr (EPI == kEpiResid) {
-#pragma unroll
-            for (int j = 0; j < RN; ++j)
-                in.resid[j][r] = live && tile0 + j < n_tiles ? g.resid[(size_t)(row0 + r) * g.ldr + (tile0 + j) * 16 + c] : 0.f;
-        }
+    for (int i = 0; i < RM; ++i) {
+        const int row = (rt0 + i) * 16 + (lane & 15);
+        const bool live = row < g.n_rows;
+        if constexpr (EPI == kEpiResid)
+            b.resid[i] = live && there ? *reinterpret_cast<const f32x4*>(g.resid + (size_t)row * g.ldr + col0) : zero;
         if constexpr (EPI == kEpiQkv) {
             const QkvOut& o = g.qkv;
             const int HALF = o.head_dim >> 1, tph = o.head_dim >> 4;
-#pragma unroll
-            for (int j = 0; j < RN; ++j) {
-                const int tile = tile0 + j;  // a q or k tile starts a whole number of heads after its matrix's first tile
-                const int tl = tile - (tile < g.tile_end[0] ? 0 : g.tile_end[0]);
-                const int e = (tl % tph) * 8 + (c & 7);
-                in.rope[j][r] = live && tile < g.tile_end[1] ? o.rope[(size_t)(o.pos0 + row0 + r) * HALF + e] : float2{1.f, 0.f};
-            }
+            // a q or k tile starts a whole number of heads after its matrix's first tile; pairs e0 .. e0 + 3
+            const int tl = tile - (tile < g.tile_end[0] ? 0 : g.tile_end[0]);
+            const int e0 = (tl % tph) * 8 + (f0 & 7);
+            const f32x4* cs = reinterpret_cast<const f32x4*>(o.rope + (size_t)(o.pos0 + row) * HALF + e0);
+            const bool rotated = live && tile < g.tile_end[1];
+            b.rope[i][0] = rotated ? cs[0] : zero;
+            b.rope[i][1] = rotated ? cs[1] : zero;
         }
     }
 }
 
-// One finished 16 x 16 accumulator tile (row tile rt, feature tile `tile`): lane holds rows rt*16 + (lane/16)*4 + r,
-// feature tile*16 + lane%16. Every lane runs the same shuffles; only stores are predicated. rstd / resid: the lane's
-// entries of PrefillEpilogueInputs for this tile.
+// One finished accumulator tile (row tile rt, feature tile `tile`), lane layout as described above. Every lane runs the
+// same shuffles; only stores are predicated. resid / gain / rope: the lane's entries of PrefillEpilogueBatch for this tile.
 template <int EPI>
 __device__ __forceinline__ void prefill_epilogue(const PrefillGemmArgs& p, int rt, int tile, int lane, const f32x4& acc,
-                                                 const float (&rstd)[4], const float (&resid)[4], const float2 (&rope)[4]) {
+                                                 float rstd, const f32x4& resid, const f32x4& gain, const f32x4 (&rope)[2]) {
     const GemmArgs& g = p.g;
-    const int c = lane & 15, col = tile * 16 + c, row0 = rt * 16 + (lane >> 4) * 4;
+    const int row = rt * 16 + (lane & 15), f0 = (lane >> 4) * 4, col0 = tile * 16 + f0;
+    const bool live = row < g.n_rows;
     if constexpr (EPI == kEpiQkv) {
         const QkvOut& o = g.qkv;
         const int HD = o.head_dim, HALF = HD >> 1, tph = HD >> 4, KK = HD >> 5;
@@ -131,63 +138,92 @@ __device__ __forceinline__ void prefill_epilogue(const PrefillGemmArgs& p, int r
         const int which = tile < g.tile_end[0] ? 0 : (tile < g.tile_end[1] ? 1 : 2);
         const int tl = tile - (which == 0 ? 0 : (which == 1 ? g.tile_end[0] : g.tile_end[1]));
         const int head = tl / tph, u = tl % tph;
-        bf16* kc = reinterpret_cast<bf16*>(o.k_cache) + (size_t)head * o.t_max * HD;
-        bf16* vc = reinterpret_cast<bf16*>(o.v_cache) + (size_t)head * o.t_max * HD;
-        const int e = u * 8 + (c & 7), x = e + ((c & 8) ? HALF : 0);  // q / k: rotary pair (e, e + HALF) in one tile
+        // q / k tiles hold the rotary pairs (e, e + HALF), e = u*8 .. u*8 + 7: features 0..7 of the tile are the first
+        // halves, features 8..15 their partners, i.e. the lane 32 further on holds this lane's partners
+        const bool second = f0 >= 8;
+        f32x4 own, partner;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int row = row0 + r;
-            const bool live = row < g.n_rows;
-            const float own = acc[r] * rstd[r];
-            const float partner = __shfl_xor(own, 8);
-            if (!live) continue;
-            const int pos = o.pos0 + row;
-            if (which == 2) {
-                vc[vfrag_offset(HD, pos, u * 16 + c)] = to_bf16(own);
-                continue;
-            }
-            const float2 cs = rope[r];
-            const float rot = own * cs.x + ((c & 8) ? partner : -partner) * cs.y;
-            if (which == 0) {
-                // query index inside its KV head: row * G + head % G; g.R * G tiles of 16 queries per KV head
-                const int kvh = head / G, qi = row * G + head % G;
-                const size_t off = (((((size_t)kvh * (g.R * G) + (qi >> 4)) * KK + (x >> 5)) * 64) +
-                                    ((x >> 3) & 3) * 16 + (qi & 15)) * 8 + (x & 7);
-                reinterpret_cast<bf16*>(o.q_frag)[off] = to_bf16(rot * o.q_scale);
-            } else {
-                kc[kfrag_offset(HD, pos, x)] = to_bf16(rot);
-            }
+            own[r] = acc[r] * rstd;
+            partner[r] = __shfl_xor(own[r], 32);
+        }
+        if (!live) return;
+        const int pos = o.pos0 + row;
+        if (which == 2) {
+            bf16* vc = reinterpret_cast<bf16*>(o.v_cache) + (size_t)head * o.t_max * HD;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) vc[vfrag_offset(HD, pos, u * 16 + f0 + r)] = to_bf16(own[r]);
+            return;
+        }
+        typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+        const int x0 = u * 8 + (f0 & 7) + (second ? HALF : 0);  // four consecutive elements x0 .. x0 + 3 of the head
+        const float scale = which == 0 ? o.q_scale : 1.0f;
+        bf16x4 out;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float cs = rope[r >> 1][(r & 1) * 2], sn = rope[r >> 1][(r & 1) * 2 + 1];
+            out[r] = to_bf16((own[r] * cs + (second ? partner[r] : -partner[r]) * sn) * scale);
+        }
+        if (which == 0) {
+            // query index inside its KV head: row * G + head % G; g.R * G tiles of 16 queries per KV head
+            const int kvh = head / G, qi = row * G + head % G;
+            const size_t off = (((((size_t)kvh * (g.R * G) + (qi >> 4)) * KK + (x0 >> 5)) * 64) +
+                                ((x0 >> 3) & 3) * 16 + (qi & 15)) * 8 + (x0 & 7);
+            *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(o.q_frag) + off) = out;
+        } else {
+            bf16* kc = reinterpret_cast<bf16*>(o.k_cache) + (size_t)head * o.t_max * HD;
+            *reinterpret_cast<bf16x4*>(kc + kfrag_offset(HD, pos, x0)) = out;
         }
     } else if constexpr (EPI == kEpiPartial) {
         float* slab = g.out + (size_t)blockIdx.y * p.slab;
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-            if (row0 + r < g.n_rows) slab[(size_t)(row0 + r) * g.ldo + col] = acc[r];
+        if (live) *reinterpret_cast<f32x4*>(slab + (size_t)row * g.ldo + col0) = acc;
     } else if constexpr (EPI == kEpiResid) {
-        const float gain = g.next_gain ? g.next_gain[col] : 1.0f;
+        const f32x4 v = live ? resid + acc : f32x4{0.f, 0.f, 0.f, 0.f};
+        if (live) *reinterpret_cast<f32x4*>(g.out + (size_t)row * g.ldo + col0) = v;
+        if (g.next_op) store_operand4_fmt(g.next_op, g.R, row, col0, v * gain, p.op_f16);  // rows that do not exist: zeros
+        // sum of squares over the tile's 16 features: the lane's four, then the four lanes of the row
+        float sq = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+        sq += __shfl_xor(sq, 16);
+        sq += __shfl_xor(sq, 32);
+        if (g.next_ss && f0 == 0 && live) g.next_ss[(size_t)tile * p.ld_ss + row] = sq;
+    } else {  // kEpiSwiglu: features 0..7 of a tile are gate features 8*tile .., features 8..15 the matching up features
+        f32x4 v;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int row = row0 + r;
-            const bool live = row < g.n_rows;
-            float v = 0.f;
-            if (live) {
-                v = resid[r] + acc[r];
-                g.out[(size_t)row * g.ldo + col] = v;
-            }
-            if (g.next_op) store_operand_fmt(g.next_op, g.R, row, col, v * gain, p.op_f16);  // dead rows of the tile: zeros
-            const float sq = sum16(v * v);
-            if (g.next_ss && c == 0 && live) g.next_ss[(size_t)tile * p.ld_ss + row] = sq;
+            const float own = acc[r] * rstd;  // 0 for a row that does not exist
+            const float up = __shfl_xor(own, 32);
+            v[r] = live ? own / (1.0f + expf(-own)) * up : 0.f;
         }
-    } else {  // kEpiSwiglu: lanes 0..7 hold gate features 8*tile .., lanes 8..15 the matching up features
+        if (f0 < 8) store_operand4_fmt(g.next_op, g.R, row, tile * 8 + f0, v, p.op_f16);
+    }
+}
+
+// All accumulator tiles of a wavefront: row tiles rt0 .. rt0 + RM - 1 (those below g.R) x feature tiles tile0 ..
+// tile0 + RN - 1 (those below n_tiles), feature tile by feature tile, the next one's inputs in flight meanwhile.
+template <int EPI, int RM, int RN>
+__device__ __forceinline__ void prefill_epilogue_all(const PrefillGemmArgs& p, int rt0, int tile0, int n_tiles, int lane,
+                                                     const f32x4 (&acc)[RM][RN]) {
+    const GemmArgs& g = p.g;
+    float rstd[RM];  // 1/rms of the lane's row in each row tile (projections that follow a norm), 0 for rows that do not exist
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int row = row0 + r;
-            const bool live = row < g.n_rows;
-            const float own = acc[r] * rstd[r];
-            const float up = __shfl_xor(own, 8);
-            const float v = live ? own / (1.0f + expf(-own)) * up : 0.f;
-            if (c < 8) store_operand_fmt(g.next_op, g.R, row, tile * 8 + c, v, p.op_f16);
-        }
+    for (int i = 0; i < RM; ++i) {
+        const int row = (rt0 + i) * 16 + (lane & 15);
+        rstd[i] = (EPI == kEpiQkv || EPI == kEpiSwiglu) && row < g.n_rows ? p.rstd[row] : 0.f;
+    }
+    // (the residual epilogue of the 256 x 256 tile, whose 32 accumulator tiles leave no room for a second batch of
+    // 20 registers, fetches each feature tile's batch right before it is used)
+    constexpr bool AHEAD = !(EPI == kEpiResid && RM * RN >= 32);
+    PrefillEpilogueBatch<EPI, RM> batch[2];
+    prefill_epilogue_fetch<EPI, RM>(p, rt0, tile0, n_tiles, lane, batch[0]);
+#pragma unroll
+    for (int j = 0; j < RN; ++j) {
+        if (AHEAD && j + 1 < RN) prefill_epilogue_fetch<EPI, RM>(p, rt0, tile0 + j + 1, n_tiles, lane, batch[(j + 1) & 1]);
+        if (!AHEAD && j > 0) prefill_epilogue_fetch<EPI, RM>(p, rt0, tile0 + j, n_tiles, lane, batch[j & 1]);
+        const PrefillEpilogueBatch<EPI, RM>& b = batch[j & 1];
+        if (tile0 + j >= n_tiles) continue;
+#pragma unroll
+        for (int i = 0; i < RM; ++i)
+            if (rt0 + i < g.R) prefill_epilogue<EPI>(p, rt0 + i, tile0 + j, lane, acc[i][j], rstd[i], b.resid[i], b.gain, b.rope[i]);
     }
 }
 
@@ -200,11 +236,12 @@ constexpr size_t prefill_gemm_lds_bytes() {
     return (size_t)(D + 1) * (2 * (F16 ? 1 : 2) * RM + 2 * RN) * 1024;
 }
 
-// acc += A fragment x B fragment on the matrix cores, operands bf16 or fp16 as the pass runs
+// acc += (activation fragment a) x (weight fragment b) on the matrix cores, operands bf16 or fp16 as the pass runs
 template <bool F16>
 __device__ __forceinline__ f32x4 prefill_mma(const u32x4& a, const u32x4& b, const f32x4& acc) {
-    if constexpr (F16) return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), acc, 0, 0, 0);
-    else return __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(b), acc, 0, 0, 0);
+    // weights first: the tile comes out as D[feature][row] (see the epilogue)
+    if constexpr (F16) return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, b), __builtin_bit_cast(f16x8, a), acc, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(b), as_bf16x8(a), acc, 0, 0, 0);
 }
 
 // Workgroup = 2 x 2 wavefronts; wavefront (wm, wn) accumulates row tiles wm*RM .. +RM-1 times feature tiles wn*RN ..
@@ -333,18 +370,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WPS, WPS)))
         }
     }
 
-#pragma unroll
-    for (int i = 0; i < RM; ++i) {
-        const int rt = rb * (2 * RM) + wm * RM + i;
-        if (rt >= g.R) continue;
-        PrefillEpilogueInputs<EPI, RN> in;
-        prefill_epilogue_fetch<EPI, RN>(p, rt, cb * B_FR + wn * RN, n_tiles, lane, in);
-#pragma unroll
-        for (int j = 0; j < RN; ++j) {
-            const int tile = cb * B_FR + wn * RN + j;
-            if (tile < n_tiles) prefill_epilogue<EPI>(p, rt, tile, lane, acc[i][j], in.rstd, in.resid[j], in.rope[j]);
-        }
-    }
+    prefill_epilogue_all<EPI, RM, RN>(p, rb * (2 * RM) + wm * RM, cb * B_FR + wn * RN, n_tiles, lane, acc);
 }
 
 // Sum of the k_split slices a split contraction left behind, in slice order, plus the residual epilogue (output, next
@@ -592,19 +618,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
     }
     wait_vmcnt<0>();
-
-#pragma unroll
-    for (int i = 0; i < RM; ++i) {
-        const int rt = rb * (A_FR / NP) + wm * RM + i;
-        if (rt >= g.R) continue;
-        PrefillEpilogueInputs<EPI, RN> in;
-        prefill_epilogue_fetch<EPI, RN>(p, rt, cb * B_FR + wn * RN, n_tiles, lane, in);
-#pragma unroll
-        for (int j = 0; j < RN; ++j) {
-            const int tile = cb * B_FR + wn * RN + j;
-            if (tile < n_tiles) prefill_epilogue<EPI>(p, rt, tile, lane, acc[i][j], in.rstd, in.resid[j], in.rope[j]);
-        }
-    }
+    // nothing of the epilogue is scheduled into the last k-steps, where both fragment sets and all accumulators are live
+    __builtin_amdgcn_sched_barrier(0);
+    prefill_epilogue_all<EPI, RM, RN>(p, rb * (A_FR / NP) + wm * RM, cb * B_FR + wn * RN, n_tiles, lane, acc);
 }
 // ---- weights of one layer as fp16 ------------------------------------------------------------------------------------
 // Element-wise bf16 -> fp16 of up to six packed matrices (fragment order is kept: the copy is read exactly like the
