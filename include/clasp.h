@@ -9,7 +9,8 @@
  *     weights, workspace and KV caches are borrowed for the lifetime of the context.
  *   - After clasp_create the library allocates no device memory: everything lives in the caller's workspace.
  *   - Every call is asynchronous on the given HIP stream (a hipStream_t passed as void*, NULL = default
- *     stream); the caller synchronises. Calls on one context must not overlap.
+ *     stream); the caller synchronises. Calls on one context must not overlap, and calls into the library from
+ *     several host threads must be serialised by the caller (launch set-up keeps process-wide state).
  *   - Every function returns CLASP_OK (0) or a negative CLASP_E_* code; nothing aborts or throws.
  *   - One GPU, the current HIP device at clasp_create time.
  *
@@ -23,7 +24,8 @@
  *     is fp32; the KV cache is bf16.
  *   - dtype CLASP_F32: matrices are fp32 row-major [out_features][in_features] (clasp_pack_matrix is a copy);
  *     everything is fp32.
- *   - embed is always row-major [vocab][d_model] in the model dtype. RMSNorm gains are fp32 [d_model].
+ *   - embed is always row-major [vocab][d_model] in the model dtype. RMSNorm gains are fp32 [d_model], 16-byte
+ *     aligned like every other device pointer handed to the library.
  *   - KV cache, per K and per V: clasp_kv_cache_bytes() bytes in the model dtype, [layer][kv_head] major; inside a
  *     head the order is the library's own (fp32: K [max_seq][head_dim], V [head_dim][max_seq]; bf16: blocks of 32
  *     positions in MFMA operand order), so contents from elsewhere go in through clasp_kv_load. Keys are stored

@@ -1015,10 +1015,13 @@ int clasp_create(const clasp_config* cfg, const clasp_weights* w, void* workspac
     if (!w->embed || !w->lm_head || !w->final_norm || !w->attn_norm || !w->mlp_norm || !w->wq || !w->wk || !w->wv ||
         !w->wo || !w->w_gate_up || !w->w_down)
         return CLASP_E_INVALID_ARG;
-    for (int l = 0; l < cfg->n_layers; ++l)
-        if (!w->attn_norm[l] || !w->mlp_norm[l] || !w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] ||
-            !w->w_gate_up[l] || !w->w_down[l])
-            return CLASP_E_INVALID_ARG;
+    auto misaligned = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; };  // 16-byte vector loads
+    if (misaligned(w->embed) || misaligned(w->lm_head) || misaligned(w->final_norm)) return CLASP_E_INVALID_ARG;
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        const void* ptrs[8] = {w->attn_norm[l], w->mlp_norm[l], w->wq[l], w->wk[l], w->wv[l], w->wo[l], w->w_gate_up[l], w->w_down[l]};
+        for (const void* ptr : ptrs)
+            if (!ptr || misaligned(ptr)) return CLASP_E_INVALID_ARG;
+    }
     clasp_ctx* ctx = new (std::nothrow) clasp_ctx();
     if (!ctx) return CLASP_E_INVALID_ARG;
     ctx->cfg = *cfg;

@@ -53,6 +53,39 @@ def test_sizes_and_validation_without_a_gpu():
     assert lib.clasp_destroy(None) == -1
 
 
+def test_create_rejects_null_and_misaligned_weight_pointers_before_touching_the_gpu():
+    """clasp_create validates every pointer on the host first: a missing or not 16-byte aligned matrix / gain pointer is
+    CLASP_E_INVALID_ARG (the addresses below are made up and never dereferenced)."""
+    from paper_2505_24196_amd import binding
+    import synth_inputs as si
+    lib = binding.lib()
+    s = si.SMALL_BF16
+    cfg = binding.Config(s.n_layers, s.d_model, s.n_heads, s.n_kv_heads, s.head_dim, s.d_ffn, s.vocab, 64, 16, 1,
+                         s.rms_eps, s.rope_base)
+    L = s.n_layers
+    arr = lambda bad_layer=None, bad=0: (C.c_void_p * L)(*[(bad if l == bad_layer else 0x10000000 + 0x1000 * l) for l in range(L)])
+    big = C.c_size_t(1 << 40)
+    out = C.c_void_p()
+
+    def create(**over):
+        w = binding.Weights()
+        w.embed, w.lm_head, w.final_norm = 0x20000000, 0x30000000, 0x40000000
+        fields = dict(attn_norm=arr(), mlp_norm=arr(), wq=arr(), wk=arr(), wv=arr(), wo=arr(), w_gate_up=arr(), w_down=arr())
+        fields.update(over)
+        for k, v in fields.items():
+            if k in ("embed", "lm_head", "final_norm"):
+                setattr(w, k, v)
+            else:
+                setattr(w, k, C.cast(v, C.POINTER(C.c_void_p)))
+        return lib.clasp_create(C.byref(cfg), C.byref(w), C.c_void_p(0x50000000), big, C.c_void_p(0x60000000),
+                                C.c_void_p(0x70000000), C.byref(out))
+
+    assert create(mlp_norm=arr(3, 0x10000004)) == -1   # gains not 16-byte aligned
+    assert create(w_down=arr(L - 1, None)) == -1       # a missing matrix
+    assert create(wq=arr(0, 0x10000008)) == -1
+    assert create(final_norm=0x40000002) == -1
+
+
 def test_prefill_workspace_sizes_without_a_gpu():
     """The prompt pass's workspace: refused chunk sizes give 0; it grows with the chunk; from 1024 rows on it also holds
     the fp16 copy of one layer's matrices."""
