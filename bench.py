@@ -34,6 +34,10 @@ WORKLOADS = {
     "llama3-8b-shape/T4096/M12/K6": dict(shape="llama3-8b-shape", T=4096, M=12, K=6),
     "llama3-8b-shape/T2048/M12/K4": dict(shape="llama3-8b-shape", T=2048, M=12, K=4),
     "llama3-8b-shape/T8192/M12/K4": dict(shape="llama3-8b-shape", T=8192, M=12, K=4),
+    "llama3-8b-shape/T2048/M8/K4": dict(shape="llama3-8b-shape", T=2048, M=8, K=4),
+    "llama3-8b-shape/T2048/M16/K4": dict(shape="llama3-8b-shape", T=2048, M=16, K=4),
+    "llama3-8b-shape/T8192/M8/K4": dict(shape="llama3-8b-shape", T=8192, M=8, K=4),
+    "llama3-8b-shape/T8192/M16/K4": dict(shape="llama3-8b-shape", T=8192, M=16, K=4),
     "llama3-8b-shape/T32768/M12/K4": dict(shape="llama3-8b-shape", T=32768, M=12, K=4),
     "llama3-8b-shape/T32768/M8/K4": dict(shape="llama3-8b-shape", T=32768, M=8, K=4),
     "llama3-8b-shape/T32768/M16/K4": dict(shape="llama3-8b-shape", T=32768, M=16, K=4),
