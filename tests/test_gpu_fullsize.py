@@ -87,6 +87,16 @@ def test_8b_long_prefix_verify_dp_and_draft(setup_8b):
     verify_dp_draft(shape, T, eng, om, cache, M=8)
 
 
+def test_8b_mid_prefix_largest_budget(setup_8b):
+    """2048-token prefix with the context sweep's largest skip budget, M = 16: a full 16-row group of candidates from
+    level 17 on (the DP, its lean form, and a draft step with 16 of the 32 layers skipped)."""
+    shape, _, eng, om, _ = setup_8b
+    T = 2048
+    cache = oc.KVCache(shape, T + 8)
+    load_prefix(shape, eng, cache, T, shape.n_layers)
+    verify_dp_draft(shape, T, eng, om, cache, M=16)
+
+
 def test_8b_longest_prefix_first_layers(setup_8b):
     """32768-token prefix (two query tiles per workgroup, 64-way split, merge kernel). The oracle's plain attention
     loop takes ~0.7 s per row and layer here, so the comparison covers the first 8 layers: two verify rows' states
