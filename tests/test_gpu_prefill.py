@@ -78,17 +78,20 @@ def test_prefill_continues_an_existing_prefix():
     check_cache(eng, cache, 0, T)
 
 
-def test_prefill_continues_a_long_prefix():
-    """1003 tokens in place, 300 more on top: the chunk's attention walks 41 blocks through the LDS ring, starting from a
-    position that is not a multiple of 32."""
-    name, T0, T = "small-bf16", 1003, 1303
+@pytest.mark.parametrize("T0,T,chunk0,chunk1", [(1003, 1303, 1024, 384), (1100, 2301, 1152, 1280)])
+def test_prefill_continues_a_long_prefix(T0, T, chunk0, chunk1):
+    """T0 tokens in place, the rest on top: the second call's attention walks the whole prefix through the LDS ring,
+    starting from a position that is not a multiple of 32. First case: both calls are bf16 passes; second case: both are
+    fp16 passes (1100 and 1201 rows)."""
+    name = "small-bf16"
     shape = si.SHAPES[name]
-    om, eng = oracle_model(name), engine(name, max_seq=1312)
+    max_seq = (T + 31) // 32 * 32
+    om, eng = oracle_model(name), engine(name, max_seq=max_seq)
     toks = prompt(shape, T)
-    cache, _, _ = oracle_cache(om, toks, 1312, want_last=False)
+    cache, _, _ = oracle_cache(om, toks, max_seq, want_last=False)
     tt = dev(toks, torch.int32)
-    eng.clasp_prefill(tt[:T0], 0, 1024)
-    eng.clasp_prefill(tt[T0:], T0, 384)
+    eng.clasp_prefill(tt[:T0], 0, chunk0)
+    eng.clasp_prefill(tt[T0:], T0, chunk1)
     check_cache(eng, cache, 0, T)
 
 
