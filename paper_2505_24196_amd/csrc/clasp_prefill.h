@@ -394,11 +394,12 @@ __global__ __launch_bounds__(256) void prefill_reduce_kernel(PrefillGemmArgs p, 
 // fragments go straight from global memory into a ring of three LDS stages with global_load_lds_dwordx4 (per lane a
 // global address, destination = wave-uniform LDS base + lane * 16, which is exactly a fragment): no staging registers,
 // two k-steps (96 KiB per CU) in flight while the third is consumed. The loads are written as inline assembly
-// because their completion has to be awaited stage by stage (s_waitcnt vmcnt(6): the six loads of the next stage may
+// because their completion has to be awaited stage by stage (s_waitcnt vmcnt(N): the N loads of the later stages may
 // stay in flight); nothing else in the loop touches global memory, and the counter is drained before the epilogue.
 // (The same loop on 32 x 32 x 16 MFMAs, whose operands a lane can gather from two neighbouring fragments, measured 12 %
 // slower.)
-// With fp16 operands a k-step is 16 + 16 fragments (32 KiB) and the ring has four stages, three of them in flight.
+// With fp16 operands a k-step is 16 + 16 fragments (32 KiB) and the ring has four stages: one being read into registers
+// a k-step ahead of its MFMAs, three in flight (see the loop).
 constexpr int kPrefillBigRows = 256;
 #ifndef CLASP_PREFILL_GROUP_ROWS
 #define CLASP_PREFILL_GROUP_ROWS 4
