@@ -86,11 +86,16 @@ __device__ __forceinline__ void attn_load(AttnFrags<HD>& f, KF kf, VF vf) {
 //              exponentiated scores as the B fragments pf[t] of the second product.
 //   valid(u, r, t) -> whether key (lane/16)*8 + u*4 + r of the block is visible to query t*16 + lane%16
 // attn_pv:     O^T += V^T P^T.
-template <int HD, int NT, class VALID>
-__device__ __forceinline__ void attn_scores(AttnState<HD, NT>& st, const bf16x8 (&qf)[NT][HD / 32],
-                                            const bf16x8 (&kfr)[2][HD / 32], VALID valid, bf16x8 (&pf)[NT]) {
-    constexpr int KK = HD / 32, CT = HD / 16;
-    f32x4 s[2][NT];
+//   masked (wave-uniform) = false promises that valid() holds for every key of the block and every query of the
+//   wavefront (a block below the diagonal of a causal pass), and the comparisons are left out.
+// The exponentials are the hardware's 2^x (v_exp_f32: arguments are <= 0, results in [0, 1], tiny ones may flush to 0).
+// O^T and the running sum are only rescaled in blocks where some query's running maximum grows (for the others the
+// factor is exactly 1): after the first few blocks of a long prefix that is rare, and the rescaling is a third of the
+// vector work of a block.
+// attn_qk: the raw scores S^T = K Q^T of one block (MFMAs only); attn_softmax: everything between the two products.
+template <int HD, int NT>
+__device__ __forceinline__ void attn_qk(f32x4 (&s)[2][NT], const bf16x8 (&qf)[NT][HD / 32], const bf16x8 (&kfr)[2][HD / 32]) {
+    constexpr int KK = HD / 32;
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
 #pragma unroll
@@ -102,35 +107,66 @@ __device__ __forceinline__ void attn_scores(AttnState<HD, NT>& st, const bf16x8 
                 s[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr[u][kk], qf[t][kk], s[u][t], 0, 0, 0);
         }
     }
+}
+
+template <int HD, int NT, class VALID>
+__device__ __forceinline__ void attn_softmax(AttnState<HD, NT>& st, f32x4 (&s)[2][NT], VALID valid, bf16x8 (&pf)[NT], bool masked) {
+    constexpr int CT = HD / 16;
+    if (masked) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (!valid(u, r, t)) s[u][t][r] = -INFINITY;
+    }
+    float m_safe[NT], m_new[NT];
+    bool grew = false;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         float mx = -INFINITY;
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                if (!valid(u, r, t)) s[u][t][r] = -INFINITY;
-                mx = fmaxf(mx, s[u][t][r]);
-            }
+            for (int r = 0; r < 4; ++r) mx = fmaxf(mx, s[u][t][r]);
         mx = fmaxf(mx, __shfl_xor(mx, 16));
         mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(st.m[t], mx);
-        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = exp2f(st.m[t] - m_safe);
+        m_new[t] = fmaxf(st.m[t], mx);
+        m_safe[t] = (m_new[t] == -INFINITY) ? 0.f : m_new[t];
+        grew = grew || m_new[t] > st.m[t];
+    }
+    if (__builtin_amdgcn_ballot_w64(grew) != 0) {  // wave-uniform: some query's maximum grew
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const float alpha = __builtin_amdgcn_exp2f(st.m[t] - m_safe[t]);
+            st.l[t] *= alpha;
+            st.m[t] = m_new[t];
+#pragma unroll
+            for (int c = 0; c < CT; ++c) st.o[t][c] *= alpha;
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
         float psum = 0.f;
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float p = exp2f(s[u][t][r] - m_safe);
+                const float p = __builtin_amdgcn_exp2f(s[u][t][r] - m_safe[t]);
                 psum += p;
                 pf[t][u * 4 + r] = to_bf16(p);
             }
-        st.l[t] = st.l[t] * alpha + psum;
-        st.m[t] = m_new;
-#pragma unroll
-        for (int c = 0; c < CT; ++c) st.o[t][c] *= alpha;
+        st.l[t] += psum;
     }
+}
+
+template <int HD, int NT, class VALID>
+__device__ __forceinline__ void attn_scores(AttnState<HD, NT>& st, const bf16x8 (&qf)[NT][HD / 32],
+                                            const bf16x8 (&kfr)[2][HD / 32], VALID valid, bf16x8 (&pf)[NT], bool masked = true) {
+    f32x4 s[2][NT];
+    attn_qk<HD, NT>(s, qf, kfr);
+    attn_softmax<HD, NT>(st, s, valid, pf, masked);
 }
 
 template <int HD, int NT>
@@ -145,9 +181,9 @@ __device__ __forceinline__ void attn_pv(AttnState<HD, NT>& st, const bf16x8 (&vf
 
 template <int HD, int NT, class VALID>
 __device__ __forceinline__ void attn_compute(AttnState<HD, NT>& st, const bf16x8 (&qf)[NT][HD / 32],
-                                             const AttnFrags<HD>& f, VALID valid) {
+                                             const AttnFrags<HD>& f, VALID valid, bool masked = true) {
     bf16x8 pf[NT];
-    attn_scores<HD, NT>(st, qf, f.k, valid, pf);
+    attn_scores<HD, NT>(st, qf, f.k, valid, pf, masked);
     attn_pv<HD, NT>(st, f.v, pf);
 }
 

@@ -665,6 +665,18 @@ struct PrefillAttnArgs {
 
 constexpr int kPrefillAttnNT = 2, kPrefillAttnWaves = 4;
 
+// Smallest cache position limit among a wavefront's queries (-1 if one of them does not exist): blocks that end at or
+// below it are visible to all of them and need no masking.
+template <int NT>
+__device__ __forceinline__ int prefill_attn_min_limit(const int (&limit)[NT]) {
+    int v = limit[0];
+#pragma unroll
+    for (int t = 1; t < NT; ++t) v = min(v, limit[t]);
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) v = min(v, __shfl_xor(v, off));
+    return __builtin_amdgcn_readfirstlane(v);
+}
+
 // Grid (n_kv_heads, ceil(query tiles / 8)). Query qi = row * G + head % G of KV head kvh sees cache positions
 // 0 .. pos0 + row.
 template <int HD>
@@ -672,7 +684,9 @@ __global__ __launch_bounds__(kPrefillAttnWaves * 64) void prefill_attn_kernel(Pr
     constexpr int NT = kPrefillAttnNT, KK = HD / 32, CT = HD / 16;
     const int kvh = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int G = a.n_heads / a.n_kv_heads, nQ = a.n_rows * G, n_qt = a.R * G;
-    const int t0 = ((int)blockIdx.y * kPrefillAttnWaves + wave) * NT;  // first query tile of this wavefront
+    // workgroups are handed out in blockIdx order: the last queries (most keys) go first, so that the CUs that finish
+    // early pick up the short ones
+    const int t0 = ((int)(gridDim.y - 1 - blockIdx.y) * kPrefillAttnWaves + wave) * NT;  // first query tile of this wavefront
     if (t0 * 16 >= nQ) return;
     const int m16 = lane & 15, q4 = lane >> 4;
 
@@ -708,9 +722,11 @@ __global__ __launch_bounds__(kPrefillAttnWaves * 64) void prefill_attn_kernel(Pr
         attn_load<HD>(f, [&](int u, int kk) { return as_bf16x8(kp[(u * KK + kk) * 64]); },
                       [&](int c) { return as_bf16x8(vp[c * 64]); });
     };
+    const int min_limit = prefill_attn_min_limit<NT>(limit);
     auto compute_blk = [&](const AttnFrags<HD>& f, int blk) {
         const int kb = blk << 5;
-        attn_compute<HD, NT>(st, qf, f, [&](int u, int r, int t) { return kb + q4 * 8 + u * 4 + r <= limit[t]; });
+        attn_compute<HD, NT>(st, qf, f, [&](int u, int r, int t) { return kb + q4 * 8 + u * 4 + r <= limit[t]; },
+                             kb + 31 > min_limit);
     };
     AttnFrags<HD> f0, f1;
     load_blk(f0, 0);
@@ -757,7 +773,9 @@ __global__ __launch_bounds__(NW * 64) void prefill_attn_lds_kernel(PrefillAttnAr
     const int kvh = blockIdx.x, lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int G = a.n_heads / a.n_kv_heads, nQ = a.n_rows * G, n_qt = a.R * G;
-    const int t_wg = (int)blockIdx.y * NW * NT;  // first query tile of the workgroup
+    // workgroups are handed out in blockIdx order: the last queries (most keys) go first, so that the CUs that finish
+    // early pick up the short ones
+    const int t_wg = (int)(gridDim.y - 1 - blockIdx.y) * NW * NT;  // first query tile of the workgroup
     if (t_wg * 16 >= nQ) return;
     const int t0 = t_wg + wave * NT;
     const int m16 = lane & 15, q4 = lane >> 4;
@@ -798,46 +816,60 @@ __global__ __launch_bounds__(NW * 64) void prefill_attn_lds_kernel(PrefillAttnAr
             load_to_lds_16(src, lds_base + (unsigned)((stage * FRB + f) * 1024));
         }
     };
-    // Steady state of step blk: the fragments of block blk are in registers (read from LDS during step blk - 1), block
-    // blk + 1 is awaited and read into the other register set while block blk is multiplied, blocks blk + 2 ..
-    // blk + NSTAGE - 1 are in flight (the newest requested right after the barrier, into the stage of block blk - 1).
-    auto wait_oldest = [&](int ahead) {  // until at most `ahead` blocks' worth of this wavefront's loads are pending
-        if (ahead == NSTAGE - 2) {
-            if constexpr ((NSTAGE - 2) * PER == 24) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
-            else if constexpr ((NSTAGE - 2) * PER == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-        } else {
-            if constexpr ((NSTAGE - 3) * PER == 20) asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
-            else if constexpr ((NSTAGE - 3) * PER == 10) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
-        }
-    };
-    static_assert(NSTAGE == 8 && (PER == 1 || PER == 2 || PER == 4), "the wait counts above are spelled out for these");
-    auto read_frags = [&](AttnFrags<HD>& f, int stage) {
+    // Software pipeline of a wavefront over the blocks (step b, after the barrier that tells that blocks <= b + 2 are
+    // complete in LDS and that nobody reads the slot of block b - 1 any more):
+    //   scores of block b + 1 (MFMAs; its keys were read from LDS during step b - 1)
+    //   values of block b: LDS -> registers (needed at the end of this step)
+    //   softmax of block b's scores, computed in step b - 1 (vector work, while the MFMAs above execute)
+    //   keys of block b + 2: LDS -> the key registers the MFMAs above have consumed
+    //   O^T += V^T P^T of block b (MFMAs)
+    // so that the matrix cores work on one block's scores while the vector units exponentiate the previous block's,
+    // instead of the two taking turns. Blocks b + 3 .. b + NSTAGE - 1 are in flight (the newest requested right after
+    // the barrier, into the slot of block b - 1). Blocks beyond the last are clamped copies of it: their loads keep the
+    // counts constant, their scores are never used.
+    static_assert(NSTAGE == 8, "five blocks in flight at the barrier");
+    auto read_keys = [&](bf16x8 (&k)[2][KK], int stage) {
         const u32x4* L = attn_lds + (size_t)stage * FRB * 64 + lane;
-        attn_load<HD>(f, [&](int u, int kk) { return as_bf16x8(L[(u * KK + kk) * 64]); },
-                      [&](int c) { return as_bf16x8(L[(2 * KK + c) * 64]); });
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) k[u][kk] = as_bf16x8(L[(u * KK + kk) * 64]);
     };
+    auto read_values = [&](bf16x8 (&v)[CT], int stage) {
+        const u32x4* L = attn_lds + (size_t)stage * FRB * 64 + lane;
+#pragma unroll
+        for (int c = 0; c < CT; ++c) v[c] = as_bf16x8(L[(2 * KK + c) * 64]);
+    };
+    auto next_stage = [&](int stage) { return stage == NSTAGE - 1 ? 0 : stage + 1; };
 #pragma unroll 1
     for (int b = 0; b < NSTAGE - 1; ++b) issue(b, b);
-    AttnFrags<HD> f0, f1;
-    wait_oldest(NSTAGE - 2);
+    const int min_limit = prefill_attn_min_limit<NT>(limit);
+    bf16x8 kreg[2][KK], vreg[CT];
+    f32x4 s0[2][NT], s1[2][NT];
+    wait_vmcnt<(NSTAGE - 3) * PER>();  // blocks 0 and 1 have landed (own loads; the barrier covers the others')
     __syncthreads();
-    read_frags(f0, 0);
+    read_keys(kreg, 0);
+    attn_qk<HD, NT>(s0, qf, kreg);
+    read_keys(kreg, 1);
     int stage = 0;  // of block blk
-    auto step = [&](int blk, const AttnFrags<HD>& cur, AttnFrags<HD>& nxt) {
-        wait_oldest(NSTAGE - 3);
-        __syncthreads();  // block blk + 1 is complete in LDS, and every wavefront is done with block blk - 1
+    auto step = [&](int blk, f32x4 (&s_cur)[2][NT], f32x4 (&s_nxt)[2][NT]) {
+        wait_vmcnt<(NSTAGE - 4) * PER>();
+        __syncthreads();
         issue(blk + NSTAGE - 1, stage == 0 ? NSTAGE - 1 : stage - 1);
-        stage = stage == NSTAGE - 1 ? 0 : stage + 1;
-        read_frags(nxt, stage);
+        attn_qk<HD, NT>(s_nxt, qf, kreg);  // block blk + 1
+        read_values(vreg, stage);
         const int kb = blk << 5;
-        attn_compute<HD, NT>(st, qf, cur, [&](int u, int r, int t) { return kb + q4 * 8 + u * 4 + r <= limit[t]; });
+        bf16x8 pf[NT];
+        attn_softmax<HD, NT>(st, s_cur, [&](int u, int r, int t) { return kb + q4 * 8 + u * 4 + r <= limit[t]; }, pf,
+                             kb + 31 > min_limit);
+        read_keys(kreg, next_stage(next_stage(stage)));  // block blk + 2
+        attn_pv<HD, NT>(st, vreg, pf);
+        stage = next_stage(stage);
     };
 #pragma unroll 1
     for (int blk = 0; blk < nblk; blk += 2) {
-        step(blk, f0, f1);
-        if (blk + 1 < nblk) step(blk + 1, f1, f0);
+        step(blk, s0, s1);
+        if (blk + 1 < nblk) step(blk + 1, s1, s0);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
