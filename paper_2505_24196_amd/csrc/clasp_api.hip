@@ -384,12 +384,13 @@ int launch_attn_one(const AttnArgs& a, dim3 grid, hipStream_t st) {
 template <int HD>
 int launch_attn_bf16(const AttnArgs& a, bool short_prefix, int nt, dim3 grid, hipStream_t st) {
     if (short_prefix) return launch_attn_one<HD, 1, CLASP_ATTN_SHORT_WAVES, false>(a, grid, st);
-    switch (nt) {
-        case 1: return launch_attn_one<HD, 1, 8, true>(a, grid, st);
-        case 2: return launch_attn_one<HD, 2, 8, true>(a, grid, st);
-        case 3: return launch_attn_one<HD, 3, 8, true>(a, grid, st);
-        default: return launch_attn_one<HD, 4, 8, true>(a, grid, st);
+    if (nt == 1) return launch_attn_one<HD, 1, 8, true>(a, grid, st);
+    if (nt == 2) return launch_attn_one<HD, 2, 8, true>(a, grid, st);
+    if constexpr (HD <= 64) {  // head_dim 128 never takes more than two query tiles (registers)
+        if (nt == 3) return launch_attn_one<HD, 3, 8, true>(a, grid, st);
+        return launch_attn_one<HD, 4, 8, true>(a, grid, st);
     }
+    return CLASP_E_UNSUPPORTED;
 }
 
 // Prefix splits of a one-row launch whose merge the output projection takes over (0 = merge here as usual): the
