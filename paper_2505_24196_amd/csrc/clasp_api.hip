@@ -733,13 +733,15 @@ size_t carve_prefill(const clasp_config& c, int chunk, char* base, PrefillWs* ws
 template <int EPI, bool F16>
 int launch_prefill_gemm(const clasp_ctx* ctx, const PrefillGemmArgs& p, hipStream_t st, float* parts = nullptr) {
     const int tiles = p.g.N / 16;
-    if constexpr (EPI != kEpiQkv) {
-        const int nrb = (p.g.R * 16 + kPrefillBigRows - 1) / kPrefillBigRows, total = nrb * ((tiles + 15) / 16);
+    if constexpr (EPI != kEpiQkv || F16) {
+        // q/k/v (fp16 passes only: with the bf16 planes its epilogue does not fit the registers): 192 columns per workgroup
+        constexpr int RN = EPI == kEpiQkv ? 6 : 8;
+        const int nrb = (p.g.R * 16 + kPrefillBigRows - 1) / kPrefillBigRows, total = nrb * ((tiles + 2 * RN - 1) / (2 * RN));
         // (the fp16 variant of the big tile walks the contraction in pairs of k-steps)
         if (CLASP_PREFILL_BIG && total >= ctx->n_cu && (!F16 || (p.g.K / 32) % 2 == 0)) {
             static bool opted_in = false;  // more than 64 KiB of LDS per workgroup has to be requested once per kernel
-            auto kernel = prefill_gemm256_kernel<EPI, F16>;
-            constexpr size_t big_lds = prefill_big_lds<F16>();
+            auto kernel = prefill_gemm256_kernel<EPI, F16, RN>;
+            constexpr size_t big_lds = prefill_big_lds<F16, RN>();
             if (!opted_in) {
                 if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)big_lds) !=
                     hipSuccess)

@@ -412,10 +412,14 @@ constexpr int kPrefillBigRows = 256;
 #endif
 template <bool F16>
 constexpr int prefill_big_stages() { return F16 ? CLASP_PREFILL_F16_STAGES : 3; }
-template <bool F16>
-constexpr int prefill_big_frags() { return 4 * kPrefillRM * (F16 ? 1 : 2) + 2 * 8; }  // activation + weight fragments per k-step
-template <bool F16>
-constexpr size_t prefill_big_lds() { return (size_t)prefill_big_stages<F16>() * prefill_big_frags<F16>() * 1024; }
+// RN = feature tiles per wavefront: 8 (256 columns per workgroup) or 6 (192 columns: the q/k/v projection, whose 384
+// feature tiles make 512 workgroups = two full rounds of CUs that way, and whose epilogue needs the registers)
+template <bool F16, int RN = 8>
+constexpr int prefill_big_frags() {  // activation + weight fragments per k-step, padded to eight wavefronts' equal shares
+    return (4 * kPrefillRM * (F16 ? 1 : 2) + 2 * RN + 7) / 8 * 8;
+}
+template <bool F16, int RN = 8>
+constexpr size_t prefill_big_lds() { return (size_t)prefill_big_stages<F16>() * prefill_big_frags<F16, RN>() * 1024; }
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {  // all but the newest N vector-memory operations of this wavefront are done
@@ -449,12 +453,14 @@ __device__ __forceinline__ void load_to_lds_16(const void* uniform_base, unsigne
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(base), "v"(lane_offset), "s"(sb) : "memory");
 }
 
-template <int EPI, bool F16 = false>
+template <int EPI, bool F16 = false, int RN = 8>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_gemm256_kernel(PrefillGemmArgs p) {
     constexpr int NP = F16 ? 1 : 2;  // planes of an activation fragment: fp16, or bf16 hi + lo
-    constexpr int RM = kPrefillRM, RN = 8, A_FR = 4 * RM * NP, B_FR = 2 * RN, FR = A_FR + B_FR, NL = FR / 8;
+    // FR: slots of a stage (1 KiB each); the last FR - A_FR - B_FR of them are padding that receives copies of the last
+    // weight fragment, so that every wavefront issues the same number of loads per stage
+    constexpr int RM = kPrefillRM, A_FR = 4 * RM * NP, B_FR = 2 * RN, FR = prefill_big_frags<F16, RN>(), NL = FR / 8;
     constexpr int NSTAGE = prefill_big_stages<F16>(), AHEAD = NSTAGE - 1;
-    static_assert(FR == prefill_big_frags<F16>() && FR % 8 == 0, "fragments are dealt to eight wavefronts");
+    static_assert(FR >= A_FR + B_FR && FR % 8 == 0, "fragments are dealt to eight wavefronts");
     static_assert((F16 && CLASP_PREFILL_REGPIPE) || AHEAD == 2 || AHEAD == 3,
                   "the waits of the plain loop are written out for two or three stages in flight");
     extern __shared__ u32x4 prefill_lds[];  // [NSTAGE][FR][64]
@@ -488,7 +494,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             src[j] = reinterpret_cast<const char*>(g.A) + ((size_t)rg * NP + f % NP) * 1024;
             step[j] = (size_t)g.R * NP * 1024;
         } else {
-            const int tile = min(cb * B_FR + (f - A_FR), n_tiles - 1);
+            const int tile = min(cb * B_FR + min(f - A_FR, B_FR - 1), n_tiles - 1);
             int mi = 0, tl = tile;
             if (tile >= g.tile_end[0]) { mi = 1; tl = tile - g.tile_end[0]; }
             if (tile >= g.tile_end[1]) { mi = 2; tl = tile - g.tile_end[1]; }

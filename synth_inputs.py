@@ -53,11 +53,12 @@ SMALL_BF16 = ModelShape("small-bf16", 6, 512, 8, 2, 64, 1408, 2064, "bf16", 1e-5
 SMALL_BF16_HD128 = ModelShape("small-bf16-hd128", 4, 1024, 8, 2, 128, 2816, 4112, "bf16", 1e-5, 500000.0)
 SMALL_BF16_DEEP = ModelShape("small-bf16-deep", 24, 256, 4, 2, 64, 512, 1024, "bf16", 1e-5, 500000.0)
 SMALL_BF16_WIDE_FFN = ModelShape("small-bf16-wide-ffn", 2, 512, 8, 2, 64, 8192, 2064, "bf16", 1e-5, 500000.0)
+SMALL_BF16_MANY_HEADS = ModelShape("small-bf16-many-heads", 2, 512, 32, 32, 64, 1408, 2064, "bf16", 1e-5, 500000.0)
 LLAMA3_8B = ModelShape("llama3-8b-shape", 32, 4096, 32, 8, 128, 14336, 128256, "bf16", 1e-5, 500000.0)
 LLAMA3_70B = ModelShape("llama3-70b-shape", 80, 8192, 64, 8, 128, 28672, 128256, "bf16", 1e-5, 500000.0)
 
-SHAPES = {s.name: s for s in (TINY_F32, SMALL_BF16, SMALL_BF16_HD128, SMALL_BF16_DEEP, SMALL_BF16_WIDE_FFN, LLAMA3_8B,
-                              LLAMA3_70B)}
+SHAPES = {s.name: s for s in (TINY_F32, SMALL_BF16, SMALL_BF16_HD128, SMALL_BF16_DEEP, SMALL_BF16_WIDE_FFN,
+                              SMALL_BF16_MANY_HEADS, LLAMA3_8B, LLAMA3_70B)}
 
 _MASK64 = (1 << 64) - 1
 

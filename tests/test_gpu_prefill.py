@@ -5,7 +5,9 @@ magnitude of the oracle tensor. Prompt lengths are chosen ragged (not multiples 
 chunks long; from 1024 tokens on the attention shares key / value blocks through LDS (head_dim 64 and 128); the
 wide-FFN shape (1024 column tiles in gate|up) takes the 256 x 256 tile of that projection at 800 tokens. Passes of 1024
 rows or more run on fp16 operands (one fp16 plane per activation, weights converted per layer): the 1100-, 1300- and
-1700-token cases, the 24-layer shape among them, with the 256 x 256 tile in its fp16 form at 1300 tokens.
+1700-token cases, the 24-layer shape among them, with the 256 x 256 tile in its fp16 form at 1300 tokens; the
+many-heads shape (32 query and 32 KV heads of 64: 384 feature tiles in q/k/v, as many as the 8B shape has) sends the
+q/k/v projection of its 2000 tokens through the 256 x 192 tile.
 """
 import numpy as np
 import pytest
@@ -44,7 +46,8 @@ def check_cache(eng, cache, lo, hi, what=""):
 @pytest.mark.parametrize("name,T,chunk", [("small-bf16", 203, 128), ("small-bf16-hd128", 333, 256),
                                            ("small-bf16-deep", 150, 128), ("small-bf16", 130, 128), ("small-bf16", 1100, 1152),
                                            ("small-bf16-hd128", 1700, 2048), ("small-bf16-wide-ffn", 800, 1024),
-                                           ("small-bf16-wide-ffn", 1300, 1408), ("small-bf16-deep", 1100, 1152)])
+                                           ("small-bf16-wide-ffn", 1300, 1408), ("small-bf16-deep", 1100, 1152),
+                                           ("small-bf16-many-heads", 2000, 2048)])
 def test_prefill_cache_and_last_token_match_oracle(name, T, chunk):
     shape = si.SHAPES[name]
     max_seq = (T + 31) // 32 * 32
