@@ -138,8 +138,9 @@ int clasp_verify_forward(clasp_ctx *ctx, const int32_t *tokens, int n_tokens, in
  * magnitude per layer, inside the 2e-2 every bf16 result of this library is held to.
  *   tokens       dev int32 [n_tokens]; ids outside [0, vocab) are clamped
  *   n_tokens     >= 1;  pos0 >= 0, pos0 + n_tokens <= max_seq
- *   chunk_rows   rows per pass: a multiple of 128 in 128..8192 (larger = fewer passes over the weights; 4096 is what the
- *                measurements use: from there on every projection of an 8B-shaped model fills the chip with 256 x 256 tiles)
+ *   chunk_rows   rows per pass: a multiple of 128 in 128..8192 (larger = fewer passes over the weights: from 4096 on
+ *                every projection of an 8B-shaped model fills the chip with 256 x 256 tiles, and 8192 is a few per cent
+ *                faster still on prompts that long)
  *   workspace    dev, 256-byte aligned, >= clasp_prefill_workspace_bytes(cfg, chunk_rows) bytes, caller-owned, only
  *                used during the call (on `stream`); for chunk_rows >= 1024 it includes room for one layer's weights
  * clasp_prefill_workspace_bytes returns 0 for an unsupported configuration or chunk_rows.

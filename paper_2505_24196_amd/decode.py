@@ -18,7 +18,7 @@ PREFILL_MIN_ROWS = 64  # prompts at least this long go through the many-row kern
 def prefill(engine: Engine, prompt: Sequence[int], pos0: int = 0, chunk_rows: Optional[int] = None):
     """Full model over the prompt. Returns (states [L+1][d] of the last token, its argmax, its margin). All tokens
     but the last go through clasp_prefill (compute-bound kernels, `chunk_rows` rows per pass; default: the prompt
-    length rounded up to 128, at most 4096) when the model is bf16 and the prompt is long enough, else through
+    length rounded up to 128, at most 8192) when the model is bf16 and the prompt is long enough, else through
     clasp_verify_forward in chunks of max_rows; the last token always takes clasp_verify_forward, which yields its
     per-layer states. chunk_rows = 0 forces the clasp_verify_forward path."""
     toks = torch.as_tensor(list(prompt), dtype=torch.int32, device=engine.device)
@@ -27,7 +27,7 @@ def prefill(engine: Engine, prompt: Sequence[int], pos0: int = 0, chunk_rows: Op
     start = 0
     if engine.shape.dtype == "bf16" and chunk_rows != 0 and n - 1 >= PREFILL_MIN_ROWS:
         if chunk_rows is None:
-            chunk_rows = min(4096, (n - 1 + 127) // 128 * 128)
+            chunk_rows = min(8192, (n - 1 + 127) // 128 * 128)
         engine.clasp_prefill(toks[:n - 1], pos0, chunk_rows)
         start = n - 1
     for s in range(start, n, step):
