@@ -214,10 +214,11 @@ def test_8b_closed_loop_emits_plain_greedy_tokens(setup_8b):
         assert margins[first] < 1e-3, f"token {first} differs where plain decoding's margin is {margins[first]}"
 
 
-@pytest.mark.parametrize("n,chunk", [(700, 1024), (4100, 4096)])
+@pytest.mark.parametrize("n,chunk", [(700, 1024), (4100, 4096), (8200, 8192)])
 def test_8b_prefill_in_the_timed_configuration(setup_8b, n, chunk):
-    """Ragged prompts in passes of 1024 rows (256 x 256 tiles for gate|up, 128 x 128 elsewhere) and of 4096 rows (the
-    timed configuration: 256 x 256 tiles for o_proj, gate|up and down). Against the oracle: layer 0's keys / values at
+    """Ragged prompts in passes of 1024 rows (256 x 256 tiles for gate|up, 128 x 128 elsewhere), of 4096 rows (the
+    timed configuration: 256 x 256 tiles for o_proj, gate|up and down, 256 x 192 for q/k/v, fp16 operands) and of 8192
+    rows (the largest pass, what decode.prefill uses for prompts that long). Against the oracle: layer 0's keys / values at
     sampled positions (they need no prefix) and layer 1's at the first 16 positions (they go through all of layer 0:
     attention over a short prefix, o_proj, gate|up, down). Every layer's cache against the one clasp_verify_forward
     leaves for the same prompt in chunks of max_rows, which test_8b_verify_dp_and_draft ties to the oracle."""
