@@ -683,6 +683,14 @@ int dp_select_window(clasp_ctx* ctx, const float* states, size_t layer_stride, i
 #ifndef CLASP_PREFILL_BIG
 #define CLASP_PREFILL_BIG 1  // 256 x 256 tiles fed by direct global -> LDS loads where the grid is large enough
 #endif
+// The big tiles are taken when they give at least this fraction of the CUs a workgroup: half (measured at the 8B
+// shape: 512 tokens 18.9 -> 15.9 ms, 3072 tokens 63.3 -> 50.3 ms against "every CU"; a third costs short passes).
+#ifndef CLASP_PREFILL_BIG_FILL_NUM
+#define CLASP_PREFILL_BIG_FILL_NUM 1
+#endif
+#ifndef CLASP_PREFILL_BIG_FILL_DEN
+#define CLASP_PREFILL_BIG_FILL_DEN 2
+#endif
 constexpr int kPrefillMaxChunk = 8192;
 // Passes of at least this many rows run their GEMMs on fp16 MFMAs: one fp16 plane per activation instead of the bf16
 // hi / lo pair (half the matrix-core work) against an fp16 copy of the layer's weights made at the start of the layer
@@ -723,11 +731,12 @@ size_t carve_prefill(const clasp_config& c, int chunk, char* base, PrefillWs* ws
 }
 
 // Which GEMM kernel a projection of the prompt pass takes (measured at the 8B shape):
-//  * o_proj, gate|up, down: 256 x 256 tiles fed by direct global -> LDS loads when they give every CU a workgroup
-//    (gate|up from 513 rows on, the projections onto d_model from 3841 rows on: 4096 rows, gate|up 1.51 ms against
-//    1.63 with 128 x 256 tiles, o_proj + down 1.03 ms against 1.32), else 128 x 128 tiles, two workgroups per CU;
-//  * q/k/v: 128 x 128 tiles with three lighter workgroups per CU (its epilogue does not fit the larger tiles' register
-//    budget, and 24 column blocks of 256 would leave half of a second round of CUs idle);
+//  * o_proj, gate|up, down: 256 x 256 tiles fed by direct global -> LDS loads when they give at least half of the CUs a
+//    workgroup (gate|up from 257 rows on, the projections onto d_model from 1793 rows on), else 128 x 128 tiles, two
+//    workgroups per CU;
+//  * q/k/v: in fp16 passes 256 x 192 tiles of the same kernel (two full rounds of CUs at 4096 rows) under the same
+//    condition; in bf16 passes (hi + lo planes: its epilogue does not fit the big tile's register budget) 128 x 128
+//    tiles with three lighter workgroups per CU;
 //  * any of them: 64 x 128 tiles when even the 128 x 128 grid has fewer workgroups than CUs.
 //  F16: the pass runs on fp16 operands (p.g.A is an fp16 plane, p.g.W an fp16 copy of the weights).
 template <int EPI, bool F16>
@@ -738,7 +747,7 @@ int launch_prefill_gemm(const clasp_ctx* ctx, const PrefillGemmArgs& p, hipStrea
         constexpr int RN = EPI == kEpiQkv ? 6 : 8;
         const int nrb = (p.g.R * 16 + kPrefillBigRows - 1) / kPrefillBigRows, total = nrb * ((tiles + 2 * RN - 1) / (2 * RN));
         // (the fp16 variant of the big tile walks the contraction in pairs of k-steps)
-        if (CLASP_PREFILL_BIG && total >= ctx->n_cu && (!F16 || (p.g.K / 32) % 2 == 0)) {
+        if (CLASP_PREFILL_BIG && total * CLASP_PREFILL_BIG_FILL_DEN >= ctx->n_cu * CLASP_PREFILL_BIG_FILL_NUM && (!F16 || (p.g.K / 32) % 2 == 0)) {
             static bool opted_in = false;  // more than 64 KiB of LDS per workgroup has to be requested once per kernel
             auto kernel = prefill_gemm256_kernel<EPI, F16, RN>;
             constexpr size_t big_lds = prefill_big_lds<F16, RN>();
