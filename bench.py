@@ -210,8 +210,8 @@ def main():
         p_layer = p_qkv + qd * d + 3 * d * F
         flops = 2.0 * n * ((L - 1) * p_layer + p_qkv) + (L - 1) * 4.0 * qd * n * (n + 1) / 2
         tf = flops / ms / 1e9
-        # passes of 1024 rows or more run on fp16 MFMAs (one fp16 operand per activation, weights converted per layer)
-        f16_pass = min(n, args.prefill_chunk) >= 1024
+        # passes of 640 rows or more run on fp16 MFMAs (one fp16 operand per activation, weights converted per layer)
+        f16_pass = min(n, args.prefill_chunk) >= 640
         note = ("algorithmic flops; projections on fp16 MFMAs (fp32 accumulation), attention on bf16" if f16_pass else
                 "algorithmic flops; activations enter as bf16 hi + lo, so the matrix cores execute twice the GEMM flops "
                 "counted here")

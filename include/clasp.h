@@ -128,9 +128,9 @@ int clasp_verify_forward(clasp_ctx *ctx, const int32_t *tokens, int n_tokens, in
  * in passes of chunk_rows rows through compute-bound MFMA GEMMs and causal flash attention. Writes the rows'
  * keys/values into every layer's cache and nothing else; the states and the next token of the prompt's last token
  * come from clasp_verify_forward on that token (or on the last few) afterwards. bf16 models only
- * (CLASP_E_UNSUPPORTED otherwise). Passes of fewer than 1024 rows compute as clasp_verify_forward does (bf16 weights,
- * hi + lo bf16 activation operands, fp32 accumulation) and leave the same cache up to rounding order. Passes of 1024
- * rows or more (chunk_rows >= 1024 and that many rows left) run their projections on fp16 matrix instructions: each
+ * (CLASP_E_UNSUPPORTED otherwise). Passes of fewer than 640 rows compute as clasp_verify_forward does (bf16 weights,
+ * hi + lo bf16 activation operands, fp32 accumulation) and leave the same cache up to rounding order. Passes of 640
+ * rows or more (chunk_rows >= 640 and that many rows left) run their projections on fp16 matrix instructions: each
  * activation is rounded to one fp16 number (11 significant bits instead of the pair's 16), the layer's weights are
  * converted to fp16 into the workspace at the start of the layer (exact for every bf16 weight of magnitude >= 2^-17,
  * rounding to multiples of 2^-24 below), accumulation stays fp32, keys / values / attention stay bf16 as elsewhere. That
@@ -142,7 +142,7 @@ int clasp_verify_forward(clasp_ctx *ctx, const int32_t *tokens, int n_tokens, in
  *                every projection of an 8B-shaped model fills the chip with 256 x 256 tiles, and 8192 is a few per cent
  *                faster still on prompts that long)
  *   workspace    dev, 256-byte aligned, >= clasp_prefill_workspace_bytes(cfg, chunk_rows) bytes, caller-owned, only
- *                used during the call (on `stream`); for chunk_rows >= 1024 it includes room for one layer's weights
+ *                used during the call (on `stream`); for chunk_rows >= 640 it includes room for one layer's weights
  * clasp_prefill_workspace_bytes returns 0 for an unsupported configuration or chunk_rows.
  */
 size_t clasp_prefill_workspace_bytes(const clasp_config *cfg, int chunk_rows);

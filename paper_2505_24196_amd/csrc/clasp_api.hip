@@ -692,11 +692,11 @@ int dp_select_window(clasp_ctx* ctx, const float* states, size_t layer_stride, i
 #define CLASP_PREFILL_BIG_FILL_DEN 2
 #endif
 constexpr int kPrefillMaxChunk = 8192;
-// Passes of at least this many rows run their GEMMs on fp16 MFMAs: one fp16 plane per activation instead of the bf16
+// Passes of at least this many rows (640: measured break-even at the 8B shape is between 512 and 640) run their GEMMs on fp16 MFMAs: one fp16 plane per activation instead of the bf16
 // hi / lo pair (half the matrix-core work) against an fp16 copy of the layer's weights made at the start of the layer
 // (one more read and write of the layer per pass, which shorter passes would not earn back). 0 = never.
 #ifndef CLASP_PREFILL_F16_ROWS
-#define CLASP_PREFILL_F16_ROWS 1024
+#define CLASP_PREFILL_F16_ROWS 640
 #endif
 
 struct PrefillWs {

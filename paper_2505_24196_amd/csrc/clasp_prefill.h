@@ -12,7 +12,7 @@
 //   * prefill_attn_lds_kernel / prefill_attn_kernel: causal flash attention over the fragment-order cache; a wavefront
 //     owns two tiles of 16 queries (row x head of one KV group); long prefixes share each 32-key block among the eight
 //     wavefronts of a workgroup through a ring of LDS stages, short ones are read by every wavefront itself.
-// Passes of fewer than 1024 rows keep the decode path's hi + lo bf16 activation split (two MFMAs per fragment pair), so
+// Passes of fewer than 640 rows keep the decode path's hi + lo bf16 activation split (two MFMAs per fragment pair), so
 // that the cache a short prompt leaves behind equals the row-limited path's up to rounding order. Longer passes are
 // bound by the matrix cores, where the split doubles the work: they run on fp16 operands instead (one fp16 plane per
 // activation, 11 significant bits; the layer's bf16 weights converted to fp16, which represents them exactly down to

@@ -87,7 +87,7 @@ def test_create_rejects_null_and_misaligned_weight_pointers_before_touching_the_
 
 
 def test_prefill_workspace_sizes_without_a_gpu():
-    """The prompt pass's workspace: refused chunk sizes give 0; it grows with the chunk; from 1024 rows on it also holds
+    """The prompt pass's workspace: refused chunk sizes give 0; it grows with the chunk; from 640 rows on it also holds
     the fp16 copy of one layer's matrices."""
     from paper_2505_24196_amd import binding
     import synth_inputs as si
@@ -98,10 +98,11 @@ def test_prefill_workspace_sizes_without_a_gpu():
     size = lambda rows: lib.clasp_prefill_workspace_bytes(C.byref(cfg), rows)
     for bad in (0, 100, 64, 8192 + 128, -128):
         assert size(bad) == 0
-    assert 0 < size(128) < size(256) < size(896)
-    per_128_rows = size(1280) - size(1152)  # beyond 1024 rows every buffer that grows grows with the rows
-    assert size(1152) - size(1024) == per_128_rows
-    assert size(1024) - size(896) >= per_128_rows + s.layer_weight_elems() * 2
+    assert 0 < size(128) < size(256) < size(512)
+    per_128_rows = size(512) - size(384)
+    assert size(384) - size(256) == per_128_rows
+    assert size(640) - size(512) >= per_128_rows + s.layer_weight_elems() * 2  # the fp16 copy of a layer's matrices
+    assert size(768) - size(640) == per_128_rows
     f32 = si.TINY_F32
     cfg32 = binding.Config(f32.n_layers, f32.d_model, f32.n_heads, f32.n_kv_heads, f32.head_dim, f32.d_ffn, f32.vocab,
                            64, 16, 0, f32.rms_eps, f32.rope_base)
