@@ -134,8 +134,9 @@ int clasp_verify_forward(clasp_ctx *ctx, const int32_t *tokens, int n_tokens, in
  * activation is rounded to one fp16 number (11 significant bits instead of the pair's 16), the layer's weights are
  * converted to fp16 into the workspace at the start of the layer (exact for every bf16 weight of magnitude >= 2^-17,
  * rounding to multiples of 2^-24 below), accumulation stays fp32, keys / values / attention stay bf16 as elsewhere. That
- * halves the matrix-core work of a pass; the cache then agrees with clasp_verify_forward's to ~1e-3 of its largest
- * magnitude per layer, inside the 2e-2 every bf16 result of this library is held to.
+ * halves the matrix-core work of a pass; the cache then agrees with clasp_verify_forward's as closely as that of the
+ * shorter passes does (measured at the 8B shape: entries differ by one bf16 unit in the last place at most, 5e-3 to 9e-3
+ * of a layer's largest magnitude, for both), inside the 2e-2 every bf16 result of this library is held to.
  *   tokens       dev int32 [n_tokens]; ids outside [0, vocab) are clamped
  *   n_tokens     >= 1;  pos0 >= 0, pos0 + n_tokens <= max_seq
  *   chunk_rows   rows per pass: a multiple of 128 in 128..8192 (larger = fewer passes over the weights: from 4096 on
