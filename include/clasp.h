@@ -151,6 +151,22 @@ int clasp_prefill(clasp_ctx *ctx, const int32_t *tokens, int n_tokens, int pos0,
                   size_t workspace_bytes, void *stream);
 
 /*
+ * clasp_prefill for callers that cannot allocate device memory and hold no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc. Same passes, same kernels and the same cache contents
+ * as clasp_prefill with this chunk_rows, but the pass's working buffers live in a static device array inside the
+ * library (clasp_static_scratch_bytes() = 32 MiB per GPU that loads the library, held until the process ends) whose
+ * address on the context's GPU clasp_create looked up. The call allocates and frees nothing.
+ *   CLASP_E_WORKSPACE   clasp_prefill_workspace_bytes(cfg, chunk_rows) exceeds the array (8B-shaped models fit with
+ *                       chunk_rows = 128; wider models or longer passes need clasp_prefill with a caller workspace)
+ *   CLASP_E_INVALID_ARG also when the current HIP device is not the one the context was created on
+ * Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, two contexts, two threads)
+ * race, and must be serialised by the caller. Nothing in the array has to start at zero, and nothing is carried from
+ * one call to the next.
+ */
+int clasp_prefill_static(clasp_ctx *ctx, const int32_t *tokens, int n_tokens, int pos0, int chunk_rows, void *stream);
+size_t clasp_static_scratch_bytes(void);
+
+/*
  * Layer optimisation (Sec. 3.4, Eq. 2, Algorithm 1; batching of the candidates of one layer: Sec. 3.6).
  * For the token at position `pos` with stored verify states x_0..x_L, runs the dynamic program
  *   D(i,j) = max{ cos(x_i, g(i-1,j-1)), cos(x_i, f_{i-1}(g(i-1,j))) },  i = 1..L, j = 1..min(i, M)

@@ -19,7 +19,7 @@ EXPORTS = ("clasp_strerror", "clasp_packed_bytes", "clasp_pack_matrix", "clasp_p
            "clasp_kv_cache_bytes", "clasp_create", "clasp_destroy", "clasp_verify_forward", "clasp_dp_select",
            "clasp_draft_step", "clasp_sample_token", "clasp_draft_sample", "clasp_spec_accept", "clasp_kv_load",
            "clasp_kv_read", "clasp_prefill_workspace_bytes", "clasp_prefill", "clasp_dp_select_window", "clasp_skip_cosine",
-           "clasp_kernel_timer_begin", "clasp_kernel_timer_end")
+           "clasp_kernel_timer_begin", "clasp_kernel_timer_end", "clasp_prefill_static", "clasp_static_scratch_bytes")
 
 KERNEL_KINDS = {"qkv": 0, "attention": 1, "o_proj": 2, "gate_up": 3, "down": 4, "lm_head": 5}
 
@@ -77,6 +77,9 @@ def lib():
         l.clasp_prefill_workspace_bytes.restype = sz
         l.clasp_prefill_workspace_bytes.argtypes = [C.POINTER(Config), i32]
         l.clasp_prefill.argtypes = [vp, vp, i32, i32, i32, vp, sz, vp]
+        l.clasp_prefill_static.argtypes = [vp, vp, i32, i32, i32, vp]
+        l.clasp_static_scratch_bytes.restype = sz
+        l.clasp_static_scratch_bytes.argtypes = []
         l.clasp_kernel_timer_begin.argtypes = [vp, i32, i32, i32]
         l.clasp_kernel_timer_end.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int)]
         _lib = l
@@ -241,6 +244,11 @@ class Engine:
             ws = self._prefill_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
         _check(lib().clasp_prefill(self._ctx, _ptr(tokens, torch.int32), tokens.numel(), pos0, chunk_rows, ws.data_ptr(),
                                    ws.numel(), _stream()), "clasp_prefill")
+
+    def clasp_prefill_static(self, tokens: torch.Tensor, pos0: int, chunk_rows: int = 128):
+        """clasp_prefill on the library's static scratch array: no workspace, no allocation."""
+        _check(lib().clasp_prefill_static(self._ctx, _ptr(tokens, torch.int32), tokens.numel(), pos0, chunk_rows,
+                                          _stream()), "clasp_prefill_static")
 
     def clasp_verify_forward(self, tokens: torch.Tensor, pos0: int, want_hidden: bool = False, want_logits: bool = False,
                              want_margin: bool = False):

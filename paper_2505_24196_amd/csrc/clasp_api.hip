@@ -22,7 +22,28 @@
 
 using namespace clasp;
 
+// Working memory of clasp_prefill_static (the prompt pass for callers that cannot allocate and hold no workspace):
+// one copy per GPU that loads the library, kept until the process ends. Host code never uses this name as an address:
+// static_scratch_ptr() asks the runtime for the device address once per device and every launch takes that pointer.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (null on failure).
+void* static_scratch_ptr() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
 
 // Tuning constants (each can be overridden on the compiler command line for sweeps; the values are the measured best
 // on MI355X at the LLaMA-3-8B and -70B shapes).
@@ -178,6 +199,8 @@ struct clasp_ctx {
     int32_t* tok_tmp;
     // optional per-kernel timing (host-side event objects only; no device memory)
     int n_cu = 256;  // compute units of the device (grid size of the persistent kernels)
+    int device = 0;  // the HIP device the context was created on
+    void* static_scratch = nullptr;  // that device's copy of the library's static scratch array
     int timer_kind = -1, timer_every = 1;
     size_t timer_used = 0, timer_seen = 0;
     std::vector<hipEvent_t> timer_start, timer_stop;
@@ -1058,6 +1081,12 @@ int clasp_create(const clasp_config* cfg, const clasp_weights* w, void* workspac
         if (hipGetDevice(&dev) == hipSuccess &&
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
             ctx->n_cu = cus;
+        ctx->device = dev;
+        ctx->static_scratch = static_scratch_ptr();
+        if (!ctx->static_scratch) {
+            delete ctx;
+            return CLASP_E_HIP;
+        }
     }
 
     const size_t kvb = clasp_kv_cache_bytes(cfg);
@@ -1204,6 +1233,24 @@ int clasp_prefill(clasp_ctx* ctx, const int32_t* tokens, int n_tokens, int pos0,
     }
     return CLASP_OK;
 }
+
+int clasp_prefill_static(clasp_ctx* ctx, const int32_t* tokens, int n_tokens, int pos0, int chunk_rows, void* stream) {
+    if (!ctx || !tokens) return CLASP_E_INVALID_ARG;
+    const clasp_config& c = ctx->cfg;
+    if (c.dtype != CLASP_BF16) return CLASP_E_UNSUPPORTED;
+    if (n_tokens < 1 || pos0 < 0 || (long long)pos0 + n_tokens > c.max_seq) return CLASP_E_INVALID_ARG;
+    const size_t need = clasp_prefill_workspace_bytes(&c, chunk_rows);
+    if (!need) return CLASP_E_INVALID_ARG;
+    if (need > kStaticScratchBytes) return CLASP_E_WORKSPACE;  // model x chunk_rows beyond the static array
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return CLASP_E_HIP;
+    if (dev != ctx->device || !ctx->static_scratch) return CLASP_E_INVALID_ARG;  // the array of another GPU
+    // Every buffer of a pass is written before it is read (rows beyond n_tokens in a 16-row group only feed results
+    // that are never stored), so what the previous call left in the array needs no clearing.
+    return clasp_prefill(ctx, tokens, n_tokens, pos0, chunk_rows, ctx->static_scratch, kStaticScratchBytes, stream);
+}
+
+size_t clasp_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 int clasp_draft_step(clasp_ctx* ctx, const uint8_t* mask, const int32_t* token, int pos, int32_t* next_token_out,
                      float* top1_prob_out, void* stream) {
