@@ -20,15 +20,19 @@
  *
  * Data layouts
  *   - dtype CLASP_BF16: matrices are bf16 in the packed tile order written by clasp_pack_matrix; activations,
- *     residual stream, hidden states, scores and logits are fp32; MFMA inputs are rounded to bf16, accumulation
- *     is fp32; the KV cache is bf16.
+ *     residual stream, hidden states, scores and logits are fp32. The projections multiply bf16 weights by activations
+ *     split into two bf16 numbers (hi + lo, 16 significant bits), accumulating in fp32. Attention runs on fp16
+ *     matrix instructions: queries, cached keys / values and softmax weights are fp16 (2 bytes per element like bf16,
+ *     11 significant bits instead of 8; the paper's own runs are FP16, Experiments), accumulation is fp32. Conversions
+ *     to fp16 saturate: a key, value or scaled query beyond +-65504 is stored as +-65504, never as an infinity.
  *   - dtype CLASP_F32: matrices are fp32 row-major [out_features][in_features] (clasp_pack_matrix is a copy);
  *     everything is fp32.
  *   - embed is always row-major [vocab][d_model] in the model dtype. RMSNorm gains are fp32 [d_model], 16-byte
  *     aligned like every other device pointer handed to the library.
- *   - KV cache, per K and per V: clasp_kv_cache_bytes() bytes in the model dtype, [layer][kv_head] major; inside a
- *     head the order is the library's own (fp32: K [max_seq][head_dim], V [head_dim][max_seq]; bf16: blocks of 32
- *     positions in MFMA operand order), so contents from elsewhere go in through clasp_kv_load. Keys are stored
+ *   - KV cache, per K and per V: clasp_kv_cache_bytes() bytes, [layer][kv_head] major, 4 bytes per element for fp32
+ *     models and 2 (fp16) for bf16 models; inside a head the order is the library's own (fp32: K [max_seq][head_dim],
+ *     V [head_dim][max_seq]; bf16 models: blocks of 32 positions in MFMA operand order), so contents from elsewhere go
+ *     in through clasp_kv_load. Keys are stored
  *     after rotation. Validity is the caller's length counter: the library reads positions below the `pos` it is
  *     given and never beyond. clasp_create zero-fills both caches.
  */
@@ -131,12 +135,12 @@ int clasp_verify_forward(clasp_ctx *ctx, const int32_t *tokens, int n_tokens, in
  * (CLASP_E_UNSUPPORTED otherwise). Passes of fewer than 640 rows compute as clasp_verify_forward does (bf16 weights,
  * hi + lo bf16 activation operands, fp32 accumulation) and leave the same cache up to rounding order. Passes of 640
  * rows or more (chunk_rows >= 640 and that many rows left) run their projections on fp16 matrix instructions: each
- * activation is rounded to one fp16 number (11 significant bits instead of the pair's 16), the layer's weights are
- * converted to fp16 into the workspace at the start of the layer (exact for every bf16 weight of magnitude >= 2^-17,
- * rounding to multiples of 2^-24 below), accumulation stays fp32, keys / values / attention stay bf16 as elsewhere. That
- * halves the matrix-core work of a pass; the cache then agrees with clasp_verify_forward's as closely as that of the
- * shorter passes does (measured at the 8B shape: entries differ by one bf16 unit in the last place at most, 5e-3 to 9e-3
- * of a layer's largest magnitude, for both), inside the 2e-2 every bf16 result of this library is held to.
+ * activation is rounded to one fp16 number (11 significant bits instead of the pair's 16; values beyond +-65504, which
+ * an un-normalised hidden state times its gain or a SwiGLU product of a trained model may in principle reach, saturate
+ * there instead of becoming infinities), the layer's weights are converted to fp16 into the workspace at the start of
+ * the layer (exact for every bf16 weight of magnitude >= 2^-17, rounding to multiples of 2^-24 below), accumulation
+ * stays fp32, attention is the same fp16 kernel family as elsewhere. That halves the matrix-core work of a pass; the
+ * cache stays inside the 2e-2 of the fp64 reference that every result of a bf16 model is held to.
  *   tokens       dev int32 [n_tokens]; ids outside [0, vocab) are clamped
  *   n_tokens     >= 1;  pos0 >= 0, pos0 + n_tokens <= max_seq
  *   chunk_rows   rows per pass: a multiple of 128 in 128..8192 (larger = fewer passes over the weights: from 4096 on
@@ -246,7 +250,7 @@ int clasp_spec_accept(clasp_ctx *ctx, const float *p_logits, const float *q_logi
                       int32_t *n_accepted_out, int32_t *next_token_out, void *stream);
 
 /* Installs cache contents for one layer: K, V dev fp32 [n_tokens][n_kv_heads][head_dim] (keys already rotated) are
- * converted to the cache dtype and layout at positions 0..n_tokens-1. For callers that hold a cache from elsewhere
+ * converted to the cache's element type (fp32, or saturating fp16 for bf16 models) and layout at positions 0..n_tokens-1. For callers that hold a cache from elsewhere
  * (and for tests that feed synthetic cache contents). */
 int clasp_kv_load(clasp_ctx *ctx, int layer, const float *K, const float *V, int n_tokens, void *stream);
 

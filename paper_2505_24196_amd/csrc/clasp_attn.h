@@ -65,7 +65,7 @@ struct AttnState {
 // rows c*16..c*16+15.
 template <int HD>
 struct AttnFrags {
-    bf16x8 k[2][HD / 32], v[HD / 16];
+    kvx8 k[2][HD / 32], v[HD / 16];
 };
 
 // All of a block's key and value fragments are requested together (and, in the pipelined loop, one block ahead), so
@@ -94,7 +94,7 @@ __device__ __forceinline__ void attn_load(AttnFrags<HD>& f, KF kf, VF vf) {
 // vector work of a block.
 // attn_qk: the raw scores S^T = K Q^T of one block (MFMAs only); attn_softmax: everything between the two products.
 template <int HD, int NT>
-__device__ __forceinline__ void attn_qk(f32x4 (&s)[2][NT], const bf16x8 (&qf)[NT][HD / 32], const bf16x8 (&kfr)[2][HD / 32]) {
+__device__ __forceinline__ void attn_qk(f32x4 (&s)[2][NT], const kvx8 (&qf)[NT][HD / 32], const kvx8 (&kfr)[2][HD / 32]) {
     constexpr int KK = HD / 32;
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
@@ -104,13 +104,13 @@ __device__ __forceinline__ void attn_qk(f32x4 (&s)[2][NT], const bf16x8 (&qf)[NT
         for (int kk = 0; kk < KK; ++kk) {
 #pragma unroll
             for (int t = 0; t < NT; ++t)
-                s[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr[u][kk], qf[t][kk], s[u][t], 0, 0, 0);
+                s[u][t] = mfma_kv(kfr[u][kk], qf[t][kk], s[u][t]);
         }
     }
 }
 
 template <int HD, int NT, class VALID>
-__device__ __forceinline__ void attn_softmax(AttnState<HD, NT>& st, f32x4 (&s)[2][NT], VALID valid, bf16x8 (&pf)[NT], bool masked) {
+__device__ __forceinline__ void attn_softmax(AttnState<HD, NT>& st, f32x4 (&s)[2][NT], VALID valid, kvx8 (&pf)[NT], bool masked) {
     constexpr int CT = HD / 16;
     if (masked) {
 #pragma unroll
@@ -155,34 +155,34 @@ __device__ __forceinline__ void attn_softmax(AttnState<HD, NT>& st, f32x4 (&s)[2
             for (int r = 0; r < 4; ++r) {
                 const float p = __builtin_amdgcn_exp2f(s[u][t][r] - m_safe[t]);
                 psum += p;
-                pf[t][u * 4 + r] = to_bf16(p);
+                pf[t][u * 4 + r] = (kv_t)p;  // p in [0, 1]
             }
         st.l[t] += psum;
     }
 }
 
 template <int HD, int NT, class VALID>
-__device__ __forceinline__ void attn_scores(AttnState<HD, NT>& st, const bf16x8 (&qf)[NT][HD / 32],
-                                            const bf16x8 (&kfr)[2][HD / 32], VALID valid, bf16x8 (&pf)[NT], bool masked = true) {
+__device__ __forceinline__ void attn_scores(AttnState<HD, NT>& st, const kvx8 (&qf)[NT][HD / 32],
+                                            const kvx8 (&kfr)[2][HD / 32], VALID valid, kvx8 (&pf)[NT], bool masked = true) {
     f32x4 s[2][NT];
     attn_qk<HD, NT>(s, qf, kfr);
     attn_softmax<HD, NT>(st, s, valid, pf, masked);
 }
 
 template <int HD, int NT>
-__device__ __forceinline__ void attn_pv(AttnState<HD, NT>& st, const bf16x8 (&vfr)[HD / 16], const bf16x8 (&pf)[NT]) {
+__device__ __forceinline__ void attn_pv(AttnState<HD, NT>& st, const kvx8 (&vfr)[HD / 16], const kvx8 (&pf)[NT]) {
 #pragma unroll
     for (int c = 0; c < HD / 16; ++c) {
 #pragma unroll
         for (int t = 0; t < NT; ++t)
-            st.o[t][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vfr[c], pf[t], st.o[t][c], 0, 0, 0);
+            st.o[t][c] = mfma_kv(vfr[c], pf[t], st.o[t][c]);
     }
 }
 
 template <int HD, int NT, class VALID>
-__device__ __forceinline__ void attn_compute(AttnState<HD, NT>& st, const bf16x8 (&qf)[NT][HD / 32],
+__device__ __forceinline__ void attn_compute(AttnState<HD, NT>& st, const kvx8 (&qf)[NT][HD / 32],
                                              const AttnFrags<HD>& f, VALID valid, bool masked = true) {
-    bf16x8 pf[NT];
+    kvx8 pf[NT];
     attn_scores<HD, NT>(st, qf, f.k, valid, pf, masked);
     attn_pv<HD, NT>(st, f.v, pf);
 }
@@ -201,17 +201,17 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(AttnArgs a) {
     const int G = a.n_heads / a.n_kv_heads, nQ = a.n_rows * G;
     const int q_base = qg * NT * 16;
     const int m16 = lane & 15, q4 = lane >> 4;
-    const bf16* Kc = reinterpret_cast<const bf16*>(a.Kc);
-    const bf16* Vt = reinterpret_cast<const bf16*>(a.Vt);
+    const kv_t* Kc = reinterpret_cast<const kv_t*>(a.Kc);
+    const kv_t* Vt = reinterpret_cast<const kv_t*>(a.Vt);
 
     // query fragments straight from HBM/L2 (already rotated, scaled and in B-operand order)
-    bf16x8 qf[NT][KK];
+    kvx8 qf[NT][KK];
     {
         const u32x4* qp = reinterpret_cast<const u32x4*>(a.q_frag) + ((size_t)kvh * (2 * G) + qg * NT) * KK * 64 + lane;
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk) qf[t][kk] = as_bf16x8(qp[(t * KK + kk) * 64]);
+            for (int kk = 0; kk < KK; ++kk) qf[t][kk] = as_kvx8(qp[(t * KK + kk) * 64]);
     }
     // visibility: query qi of row r sees cache keys <= limit (verify/draft: pos0 + r, its own position, whose
     // key/value the projection kernel has just written; DP candidates: pos0 - 1) and, for DP candidates, its own
@@ -241,8 +241,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(AttnArgs a) {
     auto load_blk = [&](AttnFrags<HD>& f, int blk) {
         const u32x4* kp = Kh + (size_t)blk * (2 * KK * 64);
         const u32x4* vp = Vh + (size_t)blk * (CT * 64);
-        attn_load<HD>(f, [&](int u, int kk) { return as_bf16x8(load_kv<STREAM>(kp + (u * KK + kk) * 64)); },
-                      [&](int c) { return as_bf16x8(load_kv<STREAM>(vp + c * 64)); });
+        attn_load<HD>(f, [&](int u, int kk) { return as_kvx8(load_kv<STREAM>(kp + (u * KK + kk) * 64)); },
+                      [&](int c) { return as_kvx8(load_kv<STREAM>(vp + c * 64)); });
     };
     auto compute_blk = [&](const AttnFrags<HD>& f, int blk) {
         const int kb = blk << 5;
@@ -270,12 +270,12 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
             for (int u = 0; u < 2; ++u)
 #pragma unroll
-                for (int kk = 0; kk < KK; ++kk) f.k[u][kk] = as_bf16x8(load_kv<STREAM>(kp + (u * KK + kk) * 64));
+                for (int kk = 0; kk < KK; ++kk) f.k[u][kk] = as_kvx8(load_kv<STREAM>(kp + (u * KK + kk) * 64));
         };
         auto load_v = [&](int b) {
             const u32x4* vp = Vh + (size_t)b * (CT * 64);
 #pragma unroll
-            for (int c = 0; c < CT; ++c) f.v[c] = as_bf16x8(load_kv<STREAM>(vp + c * 64));
+            for (int c = 0; c < CT; ++c) f.v[c] = as_kvx8(load_kv<STREAM>(vp + c * 64));
         };
         if (blk < b1) {
             load_k(blk);
@@ -283,7 +283,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(AttnArgs a) {
         }
         for (; blk < b1; blk += NW) {
             const int kb = blk << 5;
-            bf16x8 pf[NT];
+            kvx8 pf[NT];
             attn_scores<HD, NT>(st, qf, f.k, [&](int u, int r, int t) { return kb + q4 * 8 + u * 4 + r <= limit[t]; }, pf);
             if (blk + NW < b1) load_k(blk + NW);
             attn_pv<HD, NT>(st, f.v, pf);
@@ -294,8 +294,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(AttnArgs a) {
         const u32x4* kp = reinterpret_cast<const u32x4*>(a.k_self) + (size_t)kvh * (2 * KK * 64) + lane;
         const u32x4* vp = reinterpret_cast<const u32x4*>(a.v_self) + (size_t)kvh * (CT * 64) + lane;
         AttnFrags<HD> f;
-        attn_load<HD>(f, [&](int u, int kk) { return as_bf16x8(kp[(u * KK + kk) * 64]); },
-                      [&](int c) { return as_bf16x8(vp[c * 64]); });
+        attn_load<HD>(f, [&](int u, int kk) { return as_kvx8(kp[(u * KK + kk) * 64]); },
+                      [&](int c) { return as_kvx8(vp[c * 64]); });
         attn_compute<HD, NT>(st, qf, f, [&](int u, int r, int t) { return q4 * 8 + u * 4 + r == qrow[t]; });
     }
 

@@ -28,7 +28,24 @@ __device__ __forceinline__ size_t frag_elem_offset(int R, int row, int k) {
 }
 constexpr int kLoPlane = 512;
 
-// ---- bf16 KV cache layout -------------------------------------------------------------------------------------
+// ---- attention operand type (bf16 models) ---------------------------------------------------------------------
+// Keys, values, queries and the softmax weights enter the attention MFMAs as fp16 (v_mfma_f32_16x16x32_f16, the rate
+// of the bf16 instruction): 11 significant bits instead of bf16's 8 at the same 2 bytes per element, which is what keeps
+// a 32-layer random-init model inside 2e-2 of an fp64 reference when the cache is the model's own (the paper's runs
+// are FP16 throughout, Experiments). Conversions saturate at the largest finite fp16 number, so an outlier becomes
+// +-65504 instead of an infinity that would turn a whole softmax row into NaN.
+typedef _Float16 f16;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef f16 kv_t;
+typedef f16x8 kvx8;
+__device__ __forceinline__ kv_t to_kv(float x) { return (kv_t)fminf(fmaxf(x, -65504.f), 65504.f); }
+__device__ __forceinline__ float from_kv(kv_t x) { return (float)x; }
+__device__ __forceinline__ kvx8 as_kvx8(u32x4 v) { return __builtin_bit_cast(kvx8, v); }
+__device__ __forceinline__ f32x4 mfma_kv(kvx8 a, kvx8 b, f32x4 acc) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc, 0, 0, 0);
+}
+
+// ---- KV cache layout (bf16 models; elements are kv_t) ------------------------------------------------------------
 // Per KV head the cache is a sequence of 32-position blocks, each stored as the MFMA operand fragments the
 // attention kernel consumes, so that every wavefront-wide load is one contiguous KiB (gathers of 64-byte row pieces
 // cost this part several times more issue time than they move data):
@@ -127,8 +144,6 @@ __device__ __forceinline__ void store_operand4(void* buf, int R, int ld, int row
 // magnitude >= 2^-17 is an fp16 number). Inside the KiB the order is the MFMA operand's own: lane q*16 + r owns the 16
 // bytes X[rg*16 + r][s*32 + q*8 .. +8] at byte offset lane * 16, so a wavefront fetches a fragment with consecutive
 // lanes on consecutive addresses, exactly like a weight fragment.
-typedef _Float16 f16;
-typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 __device__ __forceinline__ size_t frag16_elem_offset(int R, int row, int k) {
     const int s = k >> 5, rg = row >> 4, r = row & 15, q = (k >> 3) & 3;
     return ((((size_t)s * R + rg) * 4 + q) * 16 + r) * 8 + (k & 7);
@@ -136,7 +151,7 @@ __device__ __forceinline__ size_t frag16_elem_offset(int R, int row, int k) {
 
 // Operand element in the format a prompt pass runs in: fp16 plane (f16 != 0) or the bf16 hi / lo planes.
 __device__ __forceinline__ void store_operand_fmt(void* buf, int R, int row, int k, float v, int f16_plane) {
-    if (f16_plane) reinterpret_cast<f16*>(buf)[frag16_elem_offset(R, row, k)] = (f16)v;
+    if (f16_plane) reinterpret_cast<f16*>(buf)[frag16_elem_offset(R, row, k)] = to_kv(v);
     else store_operand<kDtBf16>(buf, R, 0, row, k, v);
 }
 
@@ -145,7 +160,7 @@ __device__ __forceinline__ void store_operand4_fmt(void* buf, int R, int row, in
         typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
         f16x4 h;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) h[i] = (f16)v[i];
+        for (int i = 0; i < 4; ++i) h[i] = to_kv(v[i]);
         *reinterpret_cast<f16x4*>(reinterpret_cast<f16*>(buf) + frag16_elem_offset(R, row, k)) = h;
     } else {
         store_operand4<kDtBf16>(buf, R, 0, row, k, v);

@@ -39,7 +39,7 @@ struct QkvOut {
     int n_heads, n_kv_heads, head_dim, pos0, mode, t_max;
     const float2* rope;  // [max_seq][head_dim/2] (cos, sin)
     float q_scale;       // softmax scale * log2(e), folded into q
-    void* q_frag;        // [n_kv_heads][2*group][head_dim/32][64][8] bf16 (see attention kernel)
+    void* q_frag;        // [n_kv_heads][2*group][head_dim/32][64][8] kv_t (see attention kernel)
     void* k_cache;       // this layer, per KV head t_max/32 blocks in fragment order (kfrag_offset)
     void* v_cache;       // this layer, same (vfrag_offset)
     void* k_self;        // [n_kv_heads] one block each: the DP candidates' own keys
@@ -230,8 +230,8 @@ __device__ __forceinline__ void qkv_epilogue(const GemmArgs& g, int tile, int la
     const int which = tile < g.tile_end[0] ? 0 : (tile < g.tile_end[1] ? 1 : 2);
     const int tl = tile - (which == 0 ? 0 : g.tile_end[which - 1]);
     const int head = tl / tph, u = tl % tph;
-    bf16* kc = reinterpret_cast<bf16*>(o.k_cache);
-    bf16* vc = reinterpret_cast<bf16*>(o.v_cache);
+    kv_t* kc = reinterpret_cast<kv_t*>(o.k_cache);
+    kv_t* vc = reinterpret_cast<kv_t*>(o.v_cache);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int row = row0 + r;
@@ -240,9 +240,9 @@ __device__ __forceinline__ void qkv_epilogue(const GemmArgs& g, int tile, int la
         if (which == 2) {  // v: plain feature order
             const int x = u * 16 + c;
             if (row < g.n_rows) {
-                const bf16 v = to_bf16(own);
+                const kv_t v = to_kv(own);
                 if (o.mode) vc[(size_t)head * o.t_max * HD + vfrag_offset(HD, o.pos0 + row, x)] = v;
-                else reinterpret_cast<bf16*>(o.v_self)[(size_t)head * 32 * HD + vfrag_offset(HD, row, x)] = v;
+                else reinterpret_cast<kv_t*>(o.v_self)[(size_t)head * 32 * HD + vfrag_offset(HD, row, x)] = v;
             }
             continue;
         }
@@ -256,11 +256,11 @@ __device__ __forceinline__ void qkv_epilogue(const GemmArgs& g, int tile, int la
                 const int kvh = head / G, qi = row * G + head % G;
                 const size_t off = (((((size_t)kvh * (2 * G) + (qi >> 4)) * (HD >> 5) + (x >> 5)) * 64) +
                                     ((x >> 3) & 3) * 16 + (qi & 15)) * 8 + (x & 7);
-                reinterpret_cast<bf16*>(o.q_frag)[off] = to_bf16(rot * o.q_scale);
+                reinterpret_cast<kv_t*>(o.q_frag)[off] = to_kv(rot * o.q_scale);
             } else if (o.mode) {
-                kc[(size_t)head * o.t_max * HD + kfrag_offset(HD, pos, x)] = to_bf16(rot);
+                kc[(size_t)head * o.t_max * HD + kfrag_offset(HD, pos, x)] = to_kv(rot);
             } else {
-                reinterpret_cast<bf16*>(o.k_self)[(size_t)head * 32 * HD + kfrag_offset(HD, row, x)] = to_bf16(rot);
+                reinterpret_cast<kv_t*>(o.k_self)[(size_t)head * 32 * HD + kfrag_offset(HD, row, x)] = to_kv(rot);
             }
         }
     }

@@ -95,8 +95,8 @@ __global__ void kv_load_kernel(const float* K, const float* V, void* Kc, void* V
         const size_t ko = ((size_t)kvh * t_max + t) * hd + e, vo = ((size_t)kvh * hd + e) * t_max + t;
         if constexpr (DT == kDtBf16) {
             const size_t head = (size_t)kvh * t_max * hd;
-            reinterpret_cast<bf16*>(Kc)[head + kfrag_offset(hd, (int)t, e)] = to_bf16(K[i]);
-            reinterpret_cast<bf16*>(Vt)[head + vfrag_offset(hd, (int)t, e)] = to_bf16(V[i]);
+            reinterpret_cast<kv_t*>(Kc)[head + kfrag_offset(hd, (int)t, e)] = to_kv(K[i]);
+            reinterpret_cast<kv_t*>(Vt)[head + vfrag_offset(hd, (int)t, e)] = to_kv(V[i]);
         } else {
             reinterpret_cast<float*>(Kc)[ko] = K[i];
             reinterpret_cast<float*>(Vt)[vo] = V[i];
@@ -115,8 +115,8 @@ __global__ void kv_read_kernel(const void* Kc, const void* Vt, float* K, float* 
         const size_t t = pos0 + i / ((size_t)hd * nkv);
         if constexpr (DT == kDtBf16) {
             const size_t head = (size_t)kvh * t_max * hd;
-            K[i] = from_bf16(reinterpret_cast<const bf16*>(Kc)[head + kfrag_offset(hd, (int)t, e)]);
-            V[i] = from_bf16(reinterpret_cast<const bf16*>(Vt)[head + vfrag_offset(hd, (int)t, e)]);
+            K[i] = from_kv(reinterpret_cast<const kv_t*>(Kc)[head + kfrag_offset(hd, (int)t, e)]);
+            V[i] = from_kv(reinterpret_cast<const kv_t*>(Vt)[head + vfrag_offset(hd, (int)t, e)]);
         } else {
             K[i] = reinterpret_cast<const float*>(Kc)[((size_t)kvh * t_max + t) * hd + e];
             V[i] = reinterpret_cast<const float*>(Vt)[((size_t)kvh * hd + e) * t_max + t];

@@ -150,29 +150,29 @@ __device__ __forceinline__ void prefill_epilogue(const PrefillGemmArgs& p, int r
         if (!live) return;
         const int pos = o.pos0 + row;
         if (which == 2) {
-            bf16* vc = reinterpret_cast<bf16*>(o.v_cache) + (size_t)head * o.t_max * HD;
+            kv_t* vc = reinterpret_cast<kv_t*>(o.v_cache) + (size_t)head * o.t_max * HD;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) vc[vfrag_offset(HD, pos, u * 16 + f0 + r)] = to_bf16(own[r]);
+            for (int r = 0; r < 4; ++r) vc[vfrag_offset(HD, pos, u * 16 + f0 + r)] = to_kv(own[r]);
             return;
         }
-        typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+        typedef __attribute__((ext_vector_type(4))) _Float16 kvx4;
         const int x0 = u * 8 + (f0 & 7) + (second ? HALF : 0);  // four consecutive elements x0 .. x0 + 3 of the head
         const float scale = which == 0 ? o.q_scale : 1.0f;
-        bf16x4 out;
+        kvx4 out;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const float cs = rope[r >> 1][(r & 1) * 2], sn = rope[r >> 1][(r & 1) * 2 + 1];
-            out[r] = to_bf16((own[r] * cs + (second ? partner[r] : -partner[r]) * sn) * scale);
+            out[r] = to_kv((own[r] * cs + (second ? partner[r] : -partner[r]) * sn) * scale);
         }
         if (which == 0) {
             // query index inside its KV head: row * G + head % G; g.R * G tiles of 16 queries per KV head
             const int kvh = head / G, qi = row * G + head % G;
             const size_t off = (((((size_t)kvh * (g.R * G) + (qi >> 4)) * KK + (x0 >> 5)) * 64) +
                                 ((x0 >> 3) & 3) * 16 + (qi & 15)) * 8 + (x0 & 7);
-            *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(o.q_frag) + off) = out;
+            *reinterpret_cast<kvx4*>(reinterpret_cast<kv_t*>(o.q_frag) + off) = out;
         } else {
-            bf16* kc = reinterpret_cast<bf16*>(o.k_cache) + (size_t)head * o.t_max * HD;
-            *reinterpret_cast<bf16x4*>(kc + kfrag_offset(HD, pos, x0)) = out;
+            kv_t* kc = reinterpret_cast<kv_t*>(o.k_cache) + (size_t)head * o.t_max * HD;
+            *reinterpret_cast<kvx4*>(kc + kfrag_offset(HD, pos, x0)) = out;
         }
     } else if constexpr (EPI == kEpiPartial) {
         float* slab = g.out + (size_t)blockIdx.y * p.slab;
@@ -696,7 +696,7 @@ __global__ __launch_bounds__(kPrefillAttnWaves * 64) void prefill_attn_kernel(Pr
     if (t0 * 16 >= nQ) return;
     const int m16 = lane & 15, q4 = lane >> 4;
 
-    bf16x8 qf[NT][KK];
+    kvx8 qf[NT][KK];
     int limit[NT];
     {
         const u32x4* qp = reinterpret_cast<const u32x4*>(a.q_frag) + (size_t)kvh * n_qt * KK * 64 + lane;
@@ -704,7 +704,7 @@ __global__ __launch_bounds__(kPrefillAttnWaves * 64) void prefill_attn_kernel(Pr
         for (int t = 0; t < NT; ++t) {
             const int qt = min(t0 + t, n_qt - 1), qi = (t0 + t) * 16 + m16;
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk) qf[t][kk] = as_bf16x8(qp[((size_t)qt * KK + kk) * 64]);
+            for (int kk = 0; kk < KK; ++kk) qf[t][kk] = as_kvx8(qp[((size_t)qt * KK + kk) * 64]);
             limit[t] = qi < nQ ? a.pos0 + qi / G : -1;
         }
     }
@@ -720,13 +720,13 @@ __global__ __launch_bounds__(kPrefillAttnWaves * 64) void prefill_attn_kernel(Pr
 #pragma unroll
         for (int c = 0; c < CT; ++c) st.o[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    const u32x4* Kh = reinterpret_cast<const u32x4*>(reinterpret_cast<const bf16*>(a.Kc) + (size_t)kvh * a.t_max * HD) + lane;
-    const u32x4* Vh = reinterpret_cast<const u32x4*>(reinterpret_cast<const bf16*>(a.Vt) + (size_t)kvh * a.t_max * HD) + lane;
+    const u32x4* Kh = reinterpret_cast<const u32x4*>(reinterpret_cast<const kv_t*>(a.Kc) + (size_t)kvh * a.t_max * HD) + lane;
+    const u32x4* Vh = reinterpret_cast<const u32x4*>(reinterpret_cast<const kv_t*>(a.Vt) + (size_t)kvh * a.t_max * HD) + lane;
     auto load_blk = [&](AttnFrags<HD>& f, int blk) {
         const u32x4* kp = Kh + (size_t)blk * (2 * KK * 64);
         const u32x4* vp = Vh + (size_t)blk * (CT * 64);
-        attn_load<HD>(f, [&](int u, int kk) { return as_bf16x8(kp[(u * KK + kk) * 64]); },
-                      [&](int c) { return as_bf16x8(vp[c * 64]); });
+        attn_load<HD>(f, [&](int u, int kk) { return as_kvx8(kp[(u * KK + kk) * 64]); },
+                      [&](int c) { return as_kvx8(vp[c * 64]); });
     };
     const int min_limit = prefill_attn_min_limit<NT>(limit);
     auto compute_blk = [&](const AttnFrags<HD>& f, int blk) {
@@ -786,7 +786,7 @@ __global__ __launch_bounds__(NW * 64) void prefill_attn_lds_kernel(PrefillAttnAr
     const int t0 = t_wg + wave * NT;
     const int m16 = lane & 15, q4 = lane >> 4;
 
-    bf16x8 qf[NT][KK];
+    kvx8 qf[NT][KK];
     int limit[NT];
     {
         const u32x4* qp = reinterpret_cast<const u32x4*>(a.q_frag) + (size_t)kvh * n_qt * KK * 64 + lane;
@@ -794,7 +794,7 @@ __global__ __launch_bounds__(NW * 64) void prefill_attn_lds_kernel(PrefillAttnAr
         for (int t = 0; t < NT; ++t) {
             const int qt = min(t0 + t, n_qt - 1), qi = (t0 + t) * 16 + m16;
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk) qf[t][kk] = as_bf16x8(qp[((size_t)qt * KK + kk) * 64]);
+            for (int kk = 0; kk < KK; ++kk) qf[t][kk] = as_kvx8(qp[((size_t)qt * KK + kk) * 64]);
             limit[t] = qi < nQ ? a.pos0 + qi / G : -1;
         }
     }
@@ -810,8 +810,8 @@ __global__ __launch_bounds__(NW * 64) void prefill_attn_lds_kernel(PrefillAttnAr
 #pragma unroll
         for (int c = 0; c < CT; ++c) st.o[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    const u32x4* Kh = reinterpret_cast<const u32x4*>(reinterpret_cast<const bf16*>(a.Kc) + (size_t)kvh * a.t_max * HD) + lane;
-    const u32x4* Vh = reinterpret_cast<const u32x4*>(reinterpret_cast<const bf16*>(a.Vt) + (size_t)kvh * a.t_max * HD) + lane;
+    const u32x4* Kh = reinterpret_cast<const u32x4*>(reinterpret_cast<const kv_t*>(a.Kc) + (size_t)kvh * a.t_max * HD) + lane;
+    const u32x4* Vh = reinterpret_cast<const u32x4*>(reinterpret_cast<const kv_t*>(a.Vt) + (size_t)kvh * a.t_max * HD) + lane;
     const unsigned lds_base = (unsigned)(uintptr_t)((__attribute__((address_space(3))) char*)attn_lds);
     auto issue = [&](int blk, int stage) {  // this wavefront's PER fragments of block min(blk, nblk - 1)
         const int b = min(blk, nblk - 1);
@@ -834,23 +834,23 @@ __global__ __launch_bounds__(NW * 64) void prefill_attn_lds_kernel(PrefillAttnAr
     // the barrier, into the slot of block b - 1). Blocks beyond the last are clamped copies of it: their loads keep the
     // counts constant, their scores are never used.
     static_assert(NSTAGE == 8, "five blocks in flight at the barrier");
-    auto read_keys = [&](bf16x8 (&k)[2][KK], int stage) {
+    auto read_keys = [&](kvx8 (&k)[2][KK], int stage) {
         const u32x4* L = attn_lds + (size_t)stage * FRB * 64 + lane;
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk) k[u][kk] = as_bf16x8(L[(u * KK + kk) * 64]);
+            for (int kk = 0; kk < KK; ++kk) k[u][kk] = as_kvx8(L[(u * KK + kk) * 64]);
     };
-    auto read_values = [&](bf16x8 (&v)[CT], int stage) {
+    auto read_values = [&](kvx8 (&v)[CT], int stage) {
         const u32x4* L = attn_lds + (size_t)stage * FRB * 64 + lane;
 #pragma unroll
-        for (int c = 0; c < CT; ++c) v[c] = as_bf16x8(L[(2 * KK + c) * 64]);
+        for (int c = 0; c < CT; ++c) v[c] = as_kvx8(L[(2 * KK + c) * 64]);
     };
     auto next_stage = [&](int stage) { return stage == NSTAGE - 1 ? 0 : stage + 1; };
 #pragma unroll 1
     for (int b = 0; b < NSTAGE - 1; ++b) issue(b, b);
     const int min_limit = prefill_attn_min_limit<NT>(limit);
-    bf16x8 kreg[2][KK], vreg[CT];
+    kvx8 kreg[2][KK], vreg[CT];
     f32x4 s0[2][NT], s1[2][NT];
     wait_vmcnt<(NSTAGE - 3) * PER>();  // blocks 0 and 1 have landed (own loads; the barrier covers the others')
     __syncthreads();
@@ -865,7 +865,7 @@ __global__ __launch_bounds__(NW * 64) void prefill_attn_lds_kernel(PrefillAttnAr
         attn_qk<HD, NT>(s_nxt, qf, kreg);  // block blk + 1
         read_values(vreg, stage);
         const int kb = blk << 5;
-        bf16x8 pf[NT];
+        kvx8 pf[NT];
         attn_softmax<HD, NT>(st, s_cur, [&](int u, int r, int t) { return kb + q4 * 8 + u * 4 + r <= limit[t]; }, pf,
                              kb + 31 > min_limit);
         read_keys(kreg, next_stage(next_stage(stage)));  // block blk + 2

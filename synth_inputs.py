@@ -179,7 +179,8 @@ def gen_kv(shape: ModelShape, seed: int, n_layers: int, n_tokens: int, device="c
     """Synthetic cache contents standing in for a prefill the oracle cannot afford at large shapes.
 
     Returns (K, V), each float32 [n_layers][n_tokens][n_kv_heads][head_dim] ~ N(0,1), already rounded to the
-    model dtype's grid (so a bf16 cache and the fp64 oracle read identical values).
+    model dtype's grid. For bf16 models the device caches fp16: a bf16-grid value of magnitude >= 2^-14 is an fp16
+    number too, so the device cache and the fp64 oracle read identical values there (smaller ones move by <= 2^-25).
     """
     n = n_layers * n_tokens * shape.kv_dim
     outs = []

@@ -1,13 +1,16 @@
-"""Parity at the benchmark's full size (LLaMA-3-8B shape, bf16, M = 12; T = 512 and the long prefixes of the context
-sweep), in the launch configuration bench.py times. The oracle cannot afford a 512-token prefill at this size, so a seeded synthetic KV prefix (shared input)
-stands in for it on both sides; the verify rows, the DP and a draft step are then compared call by call."""
+"""Parity at the benchmark's full size (LLaMA-3-8B shape, bf16, M = 12), in the launch configuration bench.py times.
+test_8b_model_made_prefix_* is the setting of Sec. 3.1 / 3.4 as it stands: each side (fp64 oracle, device) runs the
+full model over the same prompt itself, and the verify states, the DP on the device's own states and a draft step are
+compared on top of each side's own cache, so the rounding of the device's cached keys / values is part of what is
+measured. For the long prefixes of the context sweep (T >= 2048; the oracle's prefill would take hours) a seeded
+synthetic KV prefix, a shared input, stands in on both sides."""
 import numpy as np
 import pytest
 import torch
 
 import synth_inputs as si
 from oracle import clasp_oracle as oc
-from tests.test_gpu_parity import HID_TOL, check_dp, dev, relerr
+from tests.test_gpu_parity import COS_TOL, HID_TOL, assert_close, check_dp, dev, relerr, relerr_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -43,22 +46,36 @@ def verify_dp_draft(shape, T, eng, om, cache, M=12):
     ost, olg = np.stack(st, 1), np.stack(lg)
     out = eng.clasp_verify_forward(dev(toks, torch.int32), T, want_hidden=True, want_logits=True)
     for l in range(shape.n_layers + 1):
-        assert relerr(out["hidden"][l].cpu().numpy(), ost[l]) <= HID_TOL["bf16"], f"layer {l}"
-    assert relerr(out["logits"].cpu().numpy(), olg) <= HID_TOL["bf16"]
-    # DP on row 1 (position T+1): cache rows 0..T of the oracle are the synthetic prefix plus row 0's own k/v
+        assert_close(out["hidden"][l].cpu().numpy(), ost[l], HID_TOL["bf16"], f"layer {l}")
+    assert_close(out["logits"].cpu().numpy(), olg, HID_TOL["bf16"], "logits")
+    # DP on row 1 (position T+1), the device on the states its own verify pass captured, the oracle on its own;
+    # cache rows 0..T are the prefix plus row 0's own k/v on either side
     print("oracle dp", flush=True)
-    gpu, ref = check_dp(om, eng, ost[:, 1], T + 1, cache, M)
+    stats = {}
+    X_dev = out["hidden"][:, 1, :].contiguous()
+    gpu, ref = check_dp(om, eng, ost[:, 1], T + 1, cache, M, X_dev=X_dev, stats=stats)
+    L = shape.n_layers
+    assert stats["cells"] == sum(min(i, M) for i in range(1, L + 1)) and stats["forced"] <= stats["cells"] // 25, stats
     # the call as bench.py issues it (no tables: cells that cannot reach (L, M) are left out) selects the same set
-    lean = eng.clasp_dp_select(dev(ost[:, 1]), T + 1, M)
+    lean = eng.clasp_dp_select(X_dev, T + 1, M)
     assert torch.equal(lean["mask"], gpu["mask"])
-    # one draft step with the selected skip set, from row 2's token at position T+2
+    # one draft step with the selected skip set, from row 2's token at position T+2: the draft model's logits (every
+    # one of them, whatever the margin), its greedy token where the margin allows, and the top-1 probability
     print("oracle draft", flush=True)
-    nxt = torch.zeros(1, dtype=torch.int32, device="cuda")
-    eng.clasp_draft_step(ref["mask"].tolist(), dev(toks[2:3], torch.int32), T + 2, nxt)
+    mask = ref["mask"].tolist()
+    nxt = torch.zeros(2, dtype=torch.int32, device="cuda")
+    prob = torch.zeros(1, dtype=torch.float32, device="cuda")
+    lg_dev = torch.empty(shape.vocab, dtype=torch.float32, device="cuda")
+    eng.clasp_draft_sample(mask, dev(toks[2:3], torch.int32), T + 2, 1.0, dev([0.5]), lg_dev, nxt[1:2])
+    eng.clasp_draft_step(mask, dev(toks[2:3], torch.int32), T + 2, nxt[0:1], prob)
     _, dl = om.token(toks[2], T + 2, cache, skip=ref["mask"])
+    assert_close(lg_dev.cpu().numpy()[None], dl[None], HID_TOL["bf16"], "draft logits")
+    assert int(nxt[0]) == int(torch.argmax(lg_dev))
     ref_tok, ref_margin = oc.argmax_margin(dl)
     if ref_margin > HID_TOL["bf16"] * np.abs(dl).max() * 2:
-        assert int(nxt) == ref_tok
+        assert int(nxt[0]) == ref_tok
+    assert abs(float(prob) - oc.top1_prob(dl)) <= 0.05 * oc.top1_prob(dl)
+    return stats
 
 
 def test_8b_verify_dp_and_draft(setup_8b):
@@ -159,25 +176,47 @@ def test_8b_vocab_sampling_and_acceptance(setup_8b):
     assert compared >= 3
 
 
-def deep_tol(l):
-    """Tolerance against the oracle in a context the model generated itself, 32 layers deep: the device keeps keys,
-    values and attention operands in bf16, the oracle in fp64, and with random-init weights (no slow drift of the
-    hidden state) that difference grows layer by layer; both device paths measure 0.025-0.027 of the largest
-    magnitude beyond layer 20 (0.02 is reached at layer ~16). The stated bf16 tolerance up to layer 16, 1.5 x beyond."""
-    return HID_TOL["bf16"] * (1.0 if l < 16 else 1.5)
+def test_8b_model_made_prefix_verify_dp_and_draft(setup_8b):
+    """Benchmark configuration 2 as the paper defines it (Sec. 3.1, 3.4): the DP runs on states and a cache that the
+    verify model itself produced. Oracle and device each run the full model over the same 160 random prompt tokens
+    (the device through clasp_prefill in passes of 128 rows, then again through clasp_verify_forward in chunks of
+    max_rows: both caches are held to the oracle's, layer by layer, at the stated bf16 bound), then two verify rows
+    (all 33 states), the DP with M = 12 on the device's own states, and a draft step, each on the side's own cache."""
+    shape, _, eng, om, _ = setup_8b
+    T = 160
+    toks = [int(t) for t in si.gen_tokens(2, T, shape.vocab, stream=13)]
+    cache = oc.KVCache(shape, T + 8)
+    for t, tk in enumerate(toks):
+        if t % 16 == 0:
+            print(f"oracle prompt token {t}", flush=True)
+        om.token(tk, t, cache, want_logits=False)
+    tt = dev(toks, torch.int32)
+    for s in range(0, T, eng.max_rows):
+        eng.clasp_verify_forward(tt[s:s + eng.max_rows], s)
+    rows = [tuple(x.cpu().numpy() for x in eng.clasp_kv_read(l, 0, T)) for l in range(shape.n_layers)]
+    eng.clasp_prefill(tt, 0, 128)
+    worst = 0.0
+    for l in range(shape.n_layers):
+        K, V = (x.cpu().numpy() for x in eng.clasp_kv_read(l, 0, T))
+        for name, got, slow, ref in (("K", K, rows[l][0], cache.K[l, :T]), ("V", V, rows[l][1], cache.V[l, :T])):
+            assert_close(got.reshape(T, -1), ref.reshape(T, -1), HID_TOL["bf16"], f"{name} layer {l}")
+            assert_close(slow.reshape(T, -1), ref.reshape(T, -1), HID_TOL["bf16"], f"{name} layer {l}, row-limited path")
+            worst = max(worst, relerr(got, ref), relerr(slow, ref))
+    print(f"largest cache error over 32 layers: {worst:.3e}", flush=True)
+    stats = verify_dp_draft(shape, T, eng, om, cache)
+    print(f"dp cells compared: {stats}", flush=True)
 
 
 def test_8b_prefill_short_prompt_against_oracle(setup_8b):
     """clasp_prefill at the full layer shapes against the oracle's token-by-token forward: 23 prompt tokens leave the
-    cache, the 24th goes through clasp_verify_forward on top of it (the oracle affords ~0.6 s per token here). The
-    row-limited path on the same prompt is held to the same bounds, and the two device caches to each other."""
+    cache, the 24th goes through clasp_verify_forward on top of it. The row-limited path on the same prompt is held to
+    the same bound (the stated bf16 one, on every layer), and the two device caches to each other."""
     shape, T, eng, om, _ = setup_8b
     n = 24
     toks = [int(t) for t in si.gen_tokens(2, n, shape.vocab, stream=11)]
     cache = oc.KVCache(shape, 32)
     ost = None
     for t, tk in enumerate(toks):
-        print(f"oracle prompt token {t}", flush=True)
         ost, _ = om.token(tk, t, cache, want_states=(t == n - 1), want_logits=False)
     tt = dev(toks, torch.int32)
     eng.clasp_verify_forward(tt[:16], 0)
@@ -187,13 +226,13 @@ def test_8b_prefill_short_prompt_against_oracle(setup_8b):
     for l in range(shape.n_layers):
         K, V = (x.cpu().numpy() for x in eng.clasp_kv_read(l, 0, n - 1))
         for name, got, slow, ref in (("K", K, rows[l][0], cache.K[l, :n - 1]), ("V", V, rows[l][1], cache.V[l, :n - 1])):
-            assert relerr(got, ref) <= deep_tol(l), f"{name} layer {l}"
-            assert relerr(slow, ref) <= deep_tol(l), f"{name} layer {l}, row-limited path"
+            assert relerr(got, ref) <= HID_TOL["bf16"], f"{name} layer {l}"
+            assert relerr(slow, ref) <= HID_TOL["bf16"], f"{name} layer {l}, row-limited path"
             assert relerr(got, slow) <= HID_TOL["bf16"], f"{name} layer {l}, between the device paths"
     out = eng.clasp_verify_forward(tt[n - 1:], n - 1, want_hidden=True)
     hid = out["hidden"][:, 0].cpu().numpy()
     for l in range(shape.n_layers + 1):
-        assert relerr(hid[l], ost[l]) <= deep_tol(l), f"layer {l}"
+        assert relerr(hid[l], ost[l]) <= HID_TOL["bf16"], f"layer {l}"
 
 
 def test_8b_closed_loop_emits_plain_greedy_tokens(setup_8b):

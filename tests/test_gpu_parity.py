@@ -20,9 +20,25 @@ COS_MARGIN = 2e-3
 
 
 def relerr(a, b):
+    """Largest absolute error over the largest magnitude of the oracle tensor."""
     a = np.asarray(a, dtype=np.float64)
     b = np.asarray(b, dtype=np.float64)
     return float(np.abs(a - b).max() / (np.abs(b).max() + 1e-30))
+
+
+def relerr_rows(a, b):
+    """The same figure taken row by row (last axis = one hidden state / one row of logits), largest over the rows:
+    no row borrows the scale of a larger one."""
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    a, b = a.reshape(-1, a.shape[-1]), b.reshape(-1, b.shape[-1])
+    return float((np.abs(a - b).max(axis=1) / (np.abs(b).max(axis=1) + 1e-30)).max())
+
+
+def assert_close(a, b, tol, what=""):
+    """Tensor-wide and per-row relative error both within tol."""
+    e, er = relerr(a, b), relerr_rows(a, b)
+    assert e <= tol and er <= tol, f"{what}: tensor-wide {e:.3e}, per-row {er:.3e} > {tol}"
 
 
 _ENGINES = {}
@@ -51,20 +67,11 @@ def oracle_prefill(om, toks, t_max):
     return cache, np.stack(st, 1), np.stack(lg)
 
 
-def check_dp(om, eng, X, pos, cache, M, lo=0, hi=None):
-    """Margin-aware comparison of one DP call (restricted to the layers lo..hi-1 when given; X then still holds all
-    L+1 states, of which lo..hi are read). Returns (device result, oracle result)."""
-    L_all = om.shape.n_layers
-    hi = L_all if hi is None else hi
-    L = hi - lo
-    windowed = (lo, hi) != (0, L_all)
-    if windowed:
-        gpu = eng.clasp_dp_select_window(dev(X), pos, M, lo, hi, want_tables=True)
-        om, cache, Xw = om.window(lo, hi), cache.window(lo, hi), X[lo:hi + 1]
-    else:
-        gpu = eng.clasp_dp_select(dev(X), pos, M, want_tables=True)
-        Xw = X
-    g_choice = gpu["choice"].cpu().numpy()
+def oracle_dp_following(om, Xw, pos, cache, M, g_choice, stats=None):
+    """The oracle's DP, with every cell where it and the device decide differently forced to the device's choice -
+    allowed only where the oracle's own margin |sigma_c - sigma_s| is within COS_MARGIN - so that everything
+    downstream of a near-tie is still compared. stats (dict) counts the decided cells and the forced ones."""
+    L = om.shape.n_layers
     ov = np.full((L + 1, M + 1), -1, dtype=np.int8)
     for _ in range(16):
         ref = om.dp(Xw, pos, cache, M, override=ov)
@@ -78,6 +85,29 @@ def check_dp(om, eng, X, pos, cache, M, lo=0, hi=None):
             ov[i, j] = g_choice[i, j]
     else:
         raise AssertionError("device and oracle choices do not converge")
+    if stats is not None:
+        stats["cells"] = stats.get("cells", 0) + int((ref["choice"] != 255).sum())
+        stats["forced"] = stats.get("forced", 0) + int((ov >= 0).sum())
+    return ref
+
+
+def check_dp(om, eng, X, pos, cache, M, lo=0, hi=None, X_dev=None, stats=None):
+    """Margin-aware comparison of one DP call (restricted to the layers lo..hi-1 when given; X then still holds all
+    L+1 states, of which lo..hi are read). X: the oracle's stored states; X_dev: the states the device's own verify pass
+    produced for the same row (a device tensor; default: the oracle's, uploaded). Returns (device result, oracle result)."""
+    L_all = om.shape.n_layers
+    hi = L_all if hi is None else hi
+    L = hi - lo
+    windowed = (lo, hi) != (0, L_all)
+    Xd = dev(X) if X_dev is None else X_dev
+    if windowed:
+        gpu = eng.clasp_dp_select_window(Xd, pos, M, lo, hi, want_tables=True)
+        om, cache, Xw = om.window(lo, hi), cache.window(lo, hi), X[lo:hi + 1]
+    else:
+        gpu = eng.clasp_dp_select(Xd, pos, M, want_tables=True)
+        Xw = X
+    g_choice = gpu["choice"].cpu().numpy()
+    ref = oracle_dp_following(om, Xw, pos, cache, M, g_choice, stats)
     sc = gpu["scores"].cpu().numpy().astype(np.float64)
     for k, key in enumerate(("sigma_c", "sigma_s")):
         assert np.array_equal(np.isnan(sc[..., k]), np.isnan(ref[key])), key
@@ -88,6 +118,66 @@ def check_dp(om, eng, X, pos, cache, M, lo=0, hi=None):
     assert int(mask.sum()) == M and not mask[:lo].any() and not mask[hi:].any()
     assert relerr(gpu["g_final"].cpu().numpy(), ref["g_final"]) <= HID_TOL[om.shape.dtype]
     return gpu, ref
+
+
+def replay_against_oracle(om, prompt_toks, spec, M, K, logit_tol, thr=None, dp_interval=1):  # noqa: C901
+    """The oracle driven call by call along a traced device run of the Draft -> Verify -> Layer-Optimisation loop
+    (decode.clasp_generate(trace=True)): every DP table, every skip set, every draft and verify token of every round is
+    compared. Where the two sides decide differently the oracle's own margin must be within tolerance (COS_MARGIN for a
+    DP cell, logit_tol for an argmax), and the oracle then follows the device's decision, so the comparison goes on to
+    the end of the run instead of stopping at the first near-tie. Returns the counts of what was compared."""
+    shape = om.shape
+    n_rounds = len(spec["rounds"])
+    cache = oc.KVCache(shape, len(prompt_toks) + sum(r["accepted"] + 1 for r in spec["rounds"]) + K + 2)
+    states, logits = om.prefill(prompt_toks, cache)
+    st = {"rounds": 0, "cells": 0, "forced": 0, "tokens": 0, "tokens_forced": 0}
+
+    def same_token(dev_tok, lg, what):
+        ref_tok, margin = oc.argmax_margin(lg)
+        st["tokens"] += 1
+        if dev_tok != ref_tok:
+            assert margin <= logit_tol, f"{what}: device {dev_tok}, oracle {ref_tok} with margin {margin}"
+            st["tokens_forced"] += 1
+
+    pending = spec["tokens"][0]
+    same_token(pending, logits, "first token")
+    pos = len(prompt_toks)
+    dp_states, dp_pos = states, pos - 1
+    ref = None
+    for r, rg in enumerate(spec["rounds"]):
+        assert rg["pos"] == pos
+        if r % dp_interval == 0:
+            ref = oracle_dp_following(om, dp_states, dp_pos, cache, M, rg["dp"]["choice"].numpy(), st)
+            sc = rg["dp"]["scores"].numpy().astype(np.float64)
+            for k, key in enumerate(("sigma_c", "sigma_s")):
+                assert np.array_equal(np.isnan(sc[..., k]), np.isnan(ref[key])), key
+                if not np.isnan(ref[key]).all():
+                    assert np.nanmax(np.abs(sc[..., k] - ref[key])) <= COS_TOL, f"round {r} {key}"
+        assert rg["mask"] == ref["mask"].tolist(), f"round {r}: skip sets differ"
+        tok = pending
+        for k, d in enumerate(rg["drafts"]):
+            _, lg = om.token(tok, pos + k, cache, skip=ref["mask"])
+            same_token(d, lg, f"round {r} draft {k}")
+            if thr is not None:  # the confidence that decides whether the round goes on (the device's own rule is
+                conf = oc.top1_prob(lg)  # checked by the caller on the device's figures)
+                assert abs(rg["draft_conf"][k] - conf) <= 5e-3 * conf + 1e-6, f"round {r} draft {k} confidence"
+            tok = d
+        rows = [pending] + rg["drafts"]
+        v_states = []
+        for i, tk in enumerate(rows):
+            s_i, lg = om.token(tk, pos + i, cache, want_states=True)
+            v_states.append(s_i)
+            same_token(rg["verify"][i], lg, f"round {r} verify row {i}")
+        a = rg["accepted"]
+        assert a == next((i for i in range(len(rg["drafts"])) if rg["drafts"][i] != rg["verify"][i]), len(rg["drafts"]))
+        if "states" in rg:
+            assert relerr(rg["states"].numpy(), v_states[a]) <= HID_TOL[shape.dtype], f"round {r}: states of row {a}"
+        dp_states, dp_pos = v_states[a], pos + a
+        pending = rg["verify"][a]
+        pos += a + 1
+        st["rounds"] += 1
+    assert st["rounds"] == n_rounds
+    return st
 
 
 @pytest.mark.parametrize("name", ["tiny-f32", "small-bf16", "small-bf16-hd128"])
@@ -147,12 +237,9 @@ def test_dp_select_on_device_states_end_to_end():
         c = oc.KVCache(shape, 32)
         c.K[:, :row] = cache.K[:, :row]
         c.V[:, :row] = cache.V[:, :row]
-        ref = om.dp(ost[:, row], row, c, 3)
-        res = eng.clasp_dp_select(out["hidden"][:, row, :], row, 3, want_tables=True)
-        margins = np.abs(ref["sigma_c"] - ref["sigma_s"])
-        if np.nanmin(margins) > COS_MARGIN:
-            assert res["mask"].cpu().numpy().tolist() == ref["mask"].tolist()
-            assert relerr(res["g_final"].cpu().numpy(), ref["g_final"]) <= 1e-4
+        stats = {}
+        check_dp(om, eng, ost[:, row], row, c, 3, X_dev=out["hidden"][:, row, :], stats=stats)
+        assert stats["cells"] >= 3 * shape.n_layers - 3 and stats["forced"] <= 2, stats
 
 
 @pytest.mark.parametrize("name", ["tiny-f32", "small-bf16"])
@@ -235,7 +322,7 @@ def test_single_row_forward_over_long_prefix(name, T):
     assert relerr(one["hidden"][:, 0].cpu().numpy(), st) <= HID_TOL["bf16"]
     assert relerr(one["logits"][0].cpu().numpy(), lg) <= HID_TOL["bf16"]
     two = eng.clasp_verify_forward(dev(toks, torch.int32), T, want_hidden=True)
-    # (the softmax weights enter the MFMA as bf16 and the two launches scale them against different running maxima)
+    # (the softmax weights enter the MFMA as fp16 and the two launches scale them against different running maxima)
     assert relerr(one["hidden"][:, 0].cpu().numpy(), two["hidden"][:, 0].cpu().numpy()) <= 5e-3
     # a draft step with a skip set at the next position
     mask = np.zeros(shape.n_layers, dtype=np.uint8)
@@ -263,6 +350,28 @@ def test_two_row_groups_32_rows_and_budget_above_16():
         assert relerr(hid[l], ost[l]) <= HID_TOL["bf16"], f"layer {l}"
     check_dp(om, eng, ost[:, -1], 36, cache, 20)
     check_dp(om, eng, ost[:, -1], 36, cache, 16)
+
+
+def test_cache_conversion_saturates_instead_of_overflowing():
+    """Keys / values of a bf16 model are cached as fp16: magnitudes beyond 65504 are stored as +-65504, not as
+    infinities, and a forward pass over such a cache stays finite."""
+    name = "small-bf16"
+    shape = si.SHAPES[name]
+    eng = engine(name, max_seq=64)
+    K, V = si.gen_kv(shape, 5, 1, 40)
+    K, V = K[0].clone(), V[0].clone()
+    K[3, 0, 5], K[7, 1, 0], V[2, 0, 9], V[11, 1, 63] = 1.0e6, -7.0e4, -3.0e38, 65520.0
+    eng.clasp_kv_load(0, K, V)
+    Kr, Vr = eng.clasp_kv_read(0, 0, 40)
+    assert float(Kr[3, 0, 5]) == 65504.0 and float(Kr[7, 1, 0]) == -65504.0
+    assert float(Vr[2, 0, 9]) == -65504.0 and float(Vr[11, 1, 63]) == 65504.0
+    assert torch.isfinite(Kr).all() and torch.isfinite(Vr).all()
+    ok = K.abs() < 6.0e4
+    assert torch.equal(Kr.cpu()[ok], K[ok].to(torch.float16).float())  # bf16-rounded inputs below the limit: exact or fp16-rounded
+    out = eng.clasp_verify_forward(dev(prompt(shape, 3), torch.int32), 40, want_hidden=True, want_logits=True)
+    assert torch.isfinite(out["hidden"]).all() and torch.isfinite(out["logits"]).all()
+    eng.k_cache.zero_()
+    eng.v_cache.zero_()
 
 
 def test_empty_prefix_and_single_row():
@@ -334,15 +443,12 @@ def test_closed_loop_tiny_matches_oracle_and_is_lossless(resid_scale, M):
             break
     spec_ref = om.spec_decode(pr, 32, M, 4)
     assert spec_ref["tokens"] == plain_ref
-    if plain_gpu == plain_ref:
-        for rg, ro in zip(spec_gpu["rounds"], spec_ref["rounds"]):
-            near_tie = np.nanmin(np.abs(ro["dp"]["sigma_c"] - ro["dp"]["sigma_s"])) <= COS_MARGIN if M else False
-            if near_tie:
-                break  # the two trajectories may legitimately part here; the per-call tests cover such cells
-            assert rg["mask"] == ro["mask"].tolist()
-            if min(ro["verify_margin"]) < 1e-3:
-                break
-            assert rg["accepted"] == ro["accepted"] and rg["drafts"][:rg["accepted"]] == ro["drafts"][:ro["accepted"]]
+    # every round of the device run against the oracle driven along it (near-ties follow the device, and are counted)
+    st = replay_against_oracle(om, pr, spec_gpu, M, 4, 1e-3)
+    assert st["rounds"] == len(spec_gpu["rounds"]) >= 32 // 5
+    assert st["tokens"] >= 1 + 6 * st["rounds"] - 5 and st["tokens_forced"] <= max(2, st["tokens"] // 20), st
+    if M:
+        assert st["cells"] >= st["rounds"] * (M * shape.n_layers - M * M) and st["forced"] <= st["cells"] // 50 + 2, st
     if M == 0:
         assert all(r["accepted"] == 4 for r in spec_gpu["rounds"])
     if resid_scale == 0.05 and M:
@@ -371,14 +477,16 @@ def test_closed_loop_with_draft_exiting_threshold(thr):
     plain_ref, plain_margin = om.greedy_decode(pr, n_gen)
     spec_ref = om.spec_decode(pr, n_gen, M, K, det_threshold=thr)
     assert spec_ref["tokens"] == plain_ref
-    if plain_gpu == plain_ref:
+    # the oracle along the device's rounds: tables, skip sets, tokens and the confidences that end the rounds
+    st = replay_against_oracle(om, pr, spec_gpu, M, K, 1e-3, thr=thr)
+    assert st["rounds"] == len(spec_gpu["rounds"]) and st["tokens"] >= 2 * st["rounds"]
+    assert st["tokens_forced"] <= max(2, st["tokens"] // 20) and st["forced"] <= st["cells"] // 50 + 2, st
+    # where no confidence sits within 5 % of the threshold the oracle's own run has rounds of the same lengths
+    if plain_gpu == plain_ref and not st["tokens_forced"] and not st["forced"]:
         for rg, ro in zip(spec_gpu["rounds"], spec_ref["rounds"]):
-            if np.nanmin(np.abs(ro["dp"]["sigma_c"] - ro["dp"]["sigma_s"])) <= COS_MARGIN:
+            if any(abs(c - thr) <= 0.05 * thr for c in ro["draft_conf"]):
                 break
-            if any(abs(c - thr) <= 0.05 * thr for c in ro["draft_conf"]) or min(ro["verify_margin"]) < 1e-3:
-                break
-            assert rg["mask"] == ro["mask"].tolist() and len(rg["drafts"]) == len(ro["drafts"])
-            np.testing.assert_allclose(rg["draft_conf"], ro["draft_conf"], rtol=5e-3)
+            assert len(rg["drafts"]) == len(ro["drafts"])
 
 
 def test_two_row_groups_head_dim_128():
