@@ -80,6 +80,95 @@ def algorithmic_bytes(shape, T, M):
             "kv_share_per_layer": kv / (wl + kv)}
 
 
+def timed_calls(eng, shape, T, M, K, n=10):
+    """Mean times of clasp_verify_forward (K+1 rows), clasp_dp_select and clasp_draft_step on a synthetic prefix of T
+    tokens (drawn per layer on the device and installed with clasp_kv_load), each with its algorithmic bytes and the
+    fraction of the 8 TB/s peak. Reuses a loaded engine: only the cache contents change."""
+    import torch
+    import synth_inputs as si
+    for l in range(shape.n_layers):
+        Kp, Vp = si.gen_kv(shape, 1000 + l, 1, T, "cuda")
+        eng.clasp_kv_load(l, Kp[0], Vp[0])
+    del Kp, Vp
+    tok = si.gen_tokens(2, K + 1, shape.vocab, stream=9).cuda()
+    ver = eng.clasp_verify_forward(tok, T, want_hidden=True)
+    states = ver["hidden"][:, 1, :].contiguous()
+    dp = eng.clasp_dp_select(states, T + 1, M)
+    mask = dp["mask"].cpu().tolist()
+    nxt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    eng.clasp_draft_step(mask, tok[:1], T + K + 1, nxt)
+    torch.cuda.synchronize()
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    e[0].record()
+    for _ in range(n):
+        eng.clasp_verify_forward(tok, T, want_hidden=True)
+    e[1].record()
+    for _ in range(n):
+        eng.clasp_dp_select(states, T + 1, M, out=dp)
+    e[2].record()
+    for _ in range(n):
+        eng.clasp_draft_step(mask, tok[:1], T + K + 1, nxt)
+    e[3].record()
+    torch.cuda.synchronize()
+    ms = {"verify_forward": e[0].elapsed_time(e[1]) / n, "dp_select": e[1].elapsed_time(e[2]) / n,
+          "draft_step": e[2].elapsed_time(e[3]) / n}
+    ab = algorithmic_bytes(shape, T, M)
+    return {"context_tokens": T, "skip_budget_M": M, "calls_timed": n,
+            "dp_select_ms": round(ms["dp_select"], 4), "draft_step_ms": round(ms["draft_step"], 4),
+            "draft_tokens_per_s": round(1e3 / ms["draft_step"], 1), "verify_forward_ms": round(ms["verify_forward"], 4),
+            "algorithmic_GB": {k: round(ab[k] / 1e9, 3) for k in ms},
+            "hbm_frac_of_8TBs": {k: round(ab[k] / (v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for k, v in ms.items()},
+            "kv_share_of_layer_bytes": round(ab["kv_share_per_layer"], 4)}
+
+
+def closed_loop_run(eng, shape, T, M, K, n_gen):
+    """Benchmark configuration 5 on a loaded engine: plain greedy decoding and the Draft -> Verify -> Layer-Optimisation
+    loop over the same T-token prompt, n_gen tokens each (prompt pass included in both times), compared token for
+    token. Between the two, the row-count check: plain decoding's own sequence is fed back K+1 rows at a time through
+    clasp_verify_forward (the launch shape of a verify pass) and every row's greedy token is compared with what the
+    one-row launches of plain decoding produced at that position - the lossless claim holds on the device exactly as
+    far as a row's result does not depend on how many rows share its launch."""
+    import torch
+    import synth_inputs as si
+    from paper_2505_24196_amd import decode
+    prompt = [int(t) for t in si.gen_tokens(2, T, shape.vocab)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    plain, margins = decode.greedy_generate(eng, prompt, n_gen)
+    torch.cuda.synchronize()
+    t_plain = time.perf_counter() - t0
+    # plain[i] sits at position T + i; a verify pass over rows plain[s .. s+K] at positions T+s.. predicts plain[s+1 ..]
+    seq = torch.as_tensor(plain, dtype=torch.int32, device=eng.device)
+    differs = []
+    compared = 0
+    for s0 in range(0, n_gen - 1, K + 1):
+        rows = seq[s0:min(s0 + K + 1, n_gen - 1)]
+        out = eng.clasp_verify_forward(rows, T + s0, want_margin=True)
+        got = out["argmax"].cpu().tolist()
+        for r, g in enumerate(got):
+            compared += 1
+            if g != plain[s0 + r + 1]:
+                differs.append({"position": T + s0 + r, "plain_margin": round(margins[s0 + r + 1], 6),
+                                "verify_margin": round(float(out["margin"][r]), 6)})
+    t0 = time.perf_counter()
+    spec = decode.clasp_generate(eng, prompt, n_gen, M, K)
+    torch.cuda.synchronize()
+    t_spec = time.perf_counter() - t0
+    first_diff = next((i for i, (a, b) in enumerate(zip(plain, spec["tokens"])) if a != b), None)
+    acc = [r["accepted"] for r in spec["rounds"]]
+    return {"workload": f"{shape.name}/T{T}/M{M}/K{K}", "generated": n_gen, "includes_prompt_pass": True,
+            "plain_greedy_tokens_per_s": round(n_gen / t_plain, 2), "clasp_tokens_per_s": round(n_gen / t_spec, 2),
+            "speedup": round(t_plain / t_spec, 3), "rounds": len(acc),
+            "mean_tokens_per_round": round(n_gen / max(1, len(acc)), 3),
+            "tokens_equal": first_diff is None, "first_difference_at": first_diff,
+            "plain_margin_at_difference": None if first_diff is None else margins[first_diff],
+            "smallest_plain_margin": round(min(margins), 6),
+            "row_count_check": {"rows_per_launch": K + 1, "positions_compared": compared,
+                                "greedy_token_differs": len(differs), "where": differs[:8]},
+            "note": "random-init weights: draft and full model rarely agree, so the loop is slower than plain decoding; "
+                    "the figure that carries over to trained weights is the per-call cost"}
+
+
 def cpu_baseline(shape, host_model, T, M, budget_s=30.0):
     """Times the oracle (as it stands) on the host cores: one DP layer selection and one draft step on the same model,
     with a seeded synthetic KV prefix of T tokens standing in for the prefill the oracle cannot afford."""
@@ -126,6 +215,9 @@ def main():
     ap.add_argument("--workload", default="llama3-8b-shape/T512/M12/K4", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timer", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="default workload only: leave out the context sweep (T = 2048 / 8192 / 32768) and the 512-token "
+                         "closed loop of benchmark configuration 5 that otherwise follow the timed steps on the same engine")
     ap.add_argument("--closed-loop", type=int, default=0, metavar="N_TOKENS",
                     help="instead of the step benchmark: generate N_TOKENS with the full draft/verify/optimise loop and "
                          "with plain greedy decoding on the chosen workload, compare the tokens, report tokens/s of both")
@@ -265,6 +357,9 @@ def main():
         return
     total_steps = args.steps + args.warmup
     max_seq = ((T + (K + 1) * (total_steps + 2) + 31) // 32) * 32
+    extras = (not args.no_extras) and args.workload == "llama3-8b-shape/T512/M12/K4"
+    if extras:
+        max_seq = max(max_seq, 32768 + 64)
     want_cpu = not args.no_cpu_baseline
     eng, host = build_engine(shape, 1, max_seq, 32 if M > 16 else 16, keep_host=want_cpu)
     dev = eng.device
@@ -369,8 +464,13 @@ def main():
                            else "gemm_f32_kernel<SwiGLU> (gate/up projection)",
                            "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                            "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get(shape.name),
+                           "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under profiles/, "
+                                             "not measured in this run",
                            "launches": kt_n,
                            "avg_us": round(avg_ms * 1e3, 2), "bytes_per_launch": ab["gate_up_kernel"]}
+    if extras:  # benchmark configurations 3 (context sweep) and 5 (closed loop) on the same engine
+        out["context_sweep"] = [timed_calls(eng, shape, Ts, M, K) for Ts in (2048, 8192, 32768)]
+        out["closed_loop"] = closed_loop_run(eng, shape, 4096, 12, 6, 512)
     eng.close()
     del eng
     torch.cuda.empty_cache()

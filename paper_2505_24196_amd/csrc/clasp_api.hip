@@ -102,16 +102,6 @@ void* static_scratch_ptr() {
 #ifndef CLASP_DOWNP_NACC
 #define CLASP_DOWNP_NACC 2
 #endif
-// the folded DP's down projection (full K per workgroup, one column tile): wavefronts that split K, k-steps per stage
-#ifndef CLASP_DPDOWN_KW
-#define CLASP_DPDOWN_KW 16
-#endif
-#ifndef CLASP_DPDOWN_DEPTH
-#define CLASP_DPDOWN_DEPTH 4
-#endif
-#ifndef CLASP_DPDOWN_SPLIT
-#define CLASP_DPDOWN_SPLIT CLASP_ACT_SPLIT  // timing experiments only: 1 = hi plane alone
-#endif
 // launches with two 16-row groups (17..32 rows): four activation loads per k-step, shared by this many column tiles
 #ifndef CLASP_R2_NACC
 #define CLASP_R2_NACC 4
@@ -202,8 +192,6 @@ struct clasp_ctx {
     float *a_buf, *h[2], *g[2], *G;
     float* logits;
     float* attn_partial;
-    float *dp_partC, *dp_partS[2];  // the folded DP's per-tile pieces (see DpFold)
-    void* dp_opS[2];                // operands of the skip candidates, by level parity
     float* down_parts;  // [CLASP_DOWNP_KS][32][d] K-slices of the DP's down projection
     void* head_parts;   // [32][vocab/16] x 16 bytes: per-tile pieces of the greedy head
     void *q_frag, *k_self, *v_self;
@@ -243,11 +231,6 @@ size_t carve(const clasp_config& c, char* base, clasp_ctx* ctx) {
     auto* part = w.take<float>((size_t)c.n_kv_heads * (2 * grp + 4) * 16 * kMaxSplit * (c.head_dim + 2) * 4);
     auto* head_parts = w.take<void>((size_t)(c.vocab / 16) * rows * 16);
     auto* down_parts = w.take<float>((size_t)CLASP_DOWNP_KS * rows * d * 4);
-    auto* dp_partC = w.take<float>((size_t)2 * kMaxRows * (d / 16) * 4);
-    auto* dp_partS0 = w.take<float>((size_t)2 * kDpSlots * (d / 16) * 4);
-    auto* dp_partS1 = w.take<float>((size_t)2 * kDpSlots * (d / 16) * 4);
-    auto* dp_opS0 = w.take<void>(rows * d * 4);
-    auto* dp_opS1 = w.take<void>(rows * d * 4);
     auto* q_frag = w.take<void>(qd * 64 + 4 * (size_t)c.head_dim * 32);  // + 4 query tiles of slack for padded groups
     auto* k_self = w.take<void>(kvd * 64);
     auto* v_self = w.take<void>(kvd * 64);
@@ -258,8 +241,6 @@ size_t carve(const clasp_config& c, char* base, clasp_ctx* ctx) {
         ctx->op_act = op_act; ctx->ss_h = ss_h; ctx->ss_a = ss_a; ctx->a_buf = a_buf; ctx->h[0] = h0; ctx->h[1] = h1;
         ctx->g[0] = g0; ctx->g[1] = g1; ctx->G = G; ctx->logits = logits; ctx->attn_partial = part;
         ctx->choice = choice; ctx->tok_tmp = tok; 
-        ctx->dp_partC = dp_partC; ctx->dp_partS[0] = dp_partS0; ctx->dp_partS[1] = dp_partS1;
-        ctx->dp_opS[0] = dp_opS0; ctx->dp_opS[1] = dp_opS1;
         ctx->down_parts = down_parts; ctx->head_parts = head_parts; ctx->q_frag = q_frag; ctx->k_self = k_self; ctx->v_self = v_self;
     }
     return w.off;
@@ -509,16 +490,9 @@ int launch_attention(const clasp_ctx* ctx, int layer, int n, int R, int mode, in
 // the operand / sums of squares of h_out for whatever consumes it next, and a copy for hidden-state capture.
 // down_split > 1: the down projection only leaves its K-slices in ctx->down_parts (rows of a_buf are the residual);
 // the caller's next kernel adds them up (the DP's select kernel does).
-// dp (the folded DP): the q/k/v projection takes the previous level's decisions and picks its operands itself (h_in
-// must be where it writes that level out), and the down projection leaves the per-tile pieces of the cosines.
-struct DpLayer {
-    DpFold fold;
-    float* partC;
-    const float* x_i;
-};
 int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, const float* h_in, float* h_out,
               void* next_op, const float* next_gain, float* next_ss, float* capture, hipStream_t st,
-              int down_split = 1, const DpLayer* dp = nullptr) {
+              int down_split = 1) {
     const clasp_config& c = ctx->cfg;
     const int d = c.d_model, F = c.d_ffn;
     int rc;
@@ -538,18 +512,7 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
             o.k_cache = ctx->k_cache + (size_t)l * ctx->kv_layer_bytes;
             o.v_cache = ctx->v_cache + (size_t)l * ctx->kv_layer_bytes;
             o.k_self = ctx->k_self; o.v_self = ctx->v_self;
-            if (dp) {
-                g.dp = dp->fold;
-                TimerScope timer(ctx, CLASP_KERNEL_QKV, st, false);
-                const int tiles = g.N / 16;
-                if (R == 1)
-                    launch_timed(timer, gemm_bf16_kernel<1, 1, CLASP_QKV_KW, kEpiQkv, CLASP_STREAM_DEPTH, CLASP_ACT_SPLIT, 1, true>,
-                                 dim3(tiles), dim3(CLASP_QKV_KW * 64), 0, st, g);
-                else
-                    launch_timed(timer, gemm_bf16_kernel<2, 1, CLASP_QKV_KW, kEpiQkv, CLASP_R2_DEPTH, CLASP_ACT_SPLIT, CLASP_R2_NACC, true>,
-                                 dim3((tiles + CLASP_R2_NACC - 1) / CLASP_R2_NACC), dim3(CLASP_QKV_KW * 64), 0, st, g);
-                CLASP_LAUNCH_CHECK();
-            } else if ((rc = launch_gemm<kEpiQkv, CLASP_QKV_CW, CLASP_QKV_KW, CLASP_QKV_NACC>(ctx, g, st, CLASP_KERNEL_QKV))) return rc;
+            if ((rc = launch_gemm<kEpiQkv, CLASP_QKV_CW, CLASP_QKV_KW, CLASP_QKV_NACC>(ctx, g, st, CLASP_KERNEL_QKV))) return rc;
         } else {
             if ((rc = launch_gemm<kEpiScale, 1, 1>(ctx, g, st, CLASP_KERNEL_QKV))) return rc;
         }
@@ -605,15 +568,6 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
         g.out = h_out; g.ldo = d; g.resid = ctx->a_buf; g.ldr = d;
         g.next_op = next_op; g.next_gain = next_gain; g.next_ss = next_ss;
         g.capture = capture; g.ldc = d;
-        if (dp && R == 1 && c.dtype == CLASP_BF16) {
-            g.dp_parts = dp->partC; g.dp_x = dp->x_i;
-            TimerScope timer(ctx, CLASP_KERNEL_DOWN, st, false);
-            launch_timed(timer, gemm_bf16_kernel<1, 1, CLASP_DPDOWN_KW, kEpiResid, CLASP_DPDOWN_DEPTH, CLASP_DPDOWN_SPLIT, 1>,
-                         dim3(d / 16), dim3(CLASP_DPDOWN_KW * 64), 0, st, g);
-            CLASP_LAUNCH_CHECK();
-            return CLASP_OK;
-        }
-        if (dp) { g.dp_parts = dp->partC; g.dp_x = dp->x_i; }
         if ((rc = launch_gemm<kEpiResid, CLASP_DOWN_CW, CLASP_DOWN_KW, CLASP_DOWN_NACC>(ctx, g, st, CLASP_KERNEL_DOWN))) return rc;
     }
     return CLASP_OK;
@@ -693,62 +647,6 @@ int draft_forward(clasp_ctx* ctx, const uint8_t* mask, const int32_t* token, int
     return run_head(ctx, 1, 1, logits_out, argmax_out, nullptr, top1_prob_out, st);
 }
 
-#ifndef CLASP_DP_FOLD
-#define CLASP_DP_FOLD 1  // 0: every level ends in the select kernel (the form fp32 models and degenerate budgets keep)
-#endif
-
-// Algorithm 1 with the score / select step folded into the kernels around it (see DpFold): per level the five kernels
-// of the layer and nothing else. bf16 models with d_model % 64 == 0, 1 <= M, and at least one candidate to push through
-// a layer at every level from the second on.
-int dp_select_fold(clasp_ctx* ctx, const float* states, size_t layer_stride, int pos, int M, int lo, int hi,
-                   uint8_t* mask_out, float* score_out, uint8_t* choice, float* g_final_out, bool full_table,
-                   hipStream_t st) {
-    const clasp_config& c = ctx->cfg;
-    const int L = hi - lo, d = c.d_model, R = M > 16 ? 2 : 1, n_tiles = d / 16;
-    const float* x0 = states + (size_t)lo * layer_stride;
-    auto X = [&](int i) { return x0 + (size_t)i * layer_stride; };
-    auto first_cell = [&](int i) { return full_table ? 0 : std::max(0, M - (L - i)); };
-    auto level = [&](int i) {  // cells and tables of level i; partS of parity i & 1 holds its skip side
-        DpLevel lv{};
-        lv.i = i; lv.M = M; lv.j0 = first_cell(i); lv.jc0 = std::max(1, lv.j0);
-        lv.ell = std::min(i - 1, M); lv.jmax = std::min(i, M); lv.n_tiles = n_tiles;
-        lv.partC = ctx->dp_partC; lv.partS = ctx->dp_partS[i & 1];
-        lv.choice = choice; lv.scores = score_out;
-        return lv;
-    };
-    // level 0 written out; its row is level 1's only skip candidate and, kept, the first row pushed through a layer
-    hipLaunchKernelGGL(dp_fold_init_kernel, dim3((d + 255) / 256), dim3(256), 0, st, x0, X(1), d, R, ctx->g[0],
-                       L >= 2 ? ctx->dp_opS[1] : nullptr, L >= 2 ? ctx->attn_norm[lo + 1] : nullptr, ctx->dp_partS[1]);
-    CLASP_LAUNCH_CHECK();
-    int rc;
-    for (int i = 2; i <= L; ++i) {  // layer lo+i-1 on g(i-1, jc0..ell); its q/k/v projection decides level i-1
-        const DpLevel cur = level(i);
-        DpLayer dp{};
-        DpFold& f = dp.fold;
-        f.lv = level(i - 1);
-        f.jc0_next = cur.jc0;
-        f.opC = ctx->op_h; f.opS = ctx->dp_opS[(i - 1) & 1];
-        f.Cb = ctx->G; f.g_prev = ctx->g[i & 1]; f.g_cur = ctx->g[(i - 1) & 1];
-        f.x_i = X(i - 1); f.x_next = X(i);
-        f.opS_next = (i < L) ? ctx->dp_opS[i & 1] : nullptr;
-        f.gain_next = (i < L) ? ctx->attn_norm[lo + i] : nullptr;
-        f.partS_next = ctx->dp_partS[i & 1];
-        f.d = d;
-        dp.partC = ctx->dp_partC; dp.x_i = X(i);
-        const int n_comp = cur.ell - cur.jc0 + 1;
-        if ((rc = run_layer(ctx, lo + i - 1, n_comp, R, 0, pos, ctx->g[(i - 1) & 1] + (size_t)cur.jc0 * d, ctx->G,
-                            (i < L) ? ctx->op_h : nullptr, (i < L) ? ctx->attn_norm[lo + i] : nullptr, nullptr, nullptr, st,
-                            1, &dp)))
-            return rc;
-    }
-    DpFold f{};
-    f.lv = level(L);
-    f.Cb = ctx->G; f.g_prev = ctx->g[(L - 1) & 1]; f.x_i = X(L); f.d = d;
-    hipLaunchKernelGGL(dp_fold_finish_kernel, dim3(1), dim3(1024), 0, st, f, L, mask_out, lo, c.n_layers, g_final_out);
-    CLASP_LAUNCH_CHECK();
-    return CLASP_OK;
-}
-
 // Algorithm 1 over the layers lo .. hi-1 (tables indexed from the window's first layer), everything outside kept.
 int dp_select_window(clasp_ctx* ctx, const float* states, size_t layer_stride, int pos, int M, int lo, int hi,
                      uint8_t* mask_out, float* score_out, uint8_t* choice_out, float* g_final_out, hipStream_t st) {
@@ -765,14 +663,6 @@ int dp_select_window(clasp_ctx* ctx, const float* states, size_t layer_stride, i
     // they are computed only when the caller asked for the tables. first_cell(i) = first cell of level i that is needed.
     const bool full_table = score_out || choice_out;
     auto first_cell = [&](int i) { return full_table ? 0 : std::max(0, M - (L - i)); };
-    if (CLASP_DP_FOLD && c.dtype == CLASP_BF16 && d % 64 == 0 && M >= 1 && L >= 2) {
-        bool every_level_runs_a_layer = true;  // false only when M = L without tables (nothing is ever computed)
-        for (int i = 2; i <= L; ++i)
-            if (std::min(i - 1, M) - std::max(1, first_cell(i)) + 1 < 1) every_level_runs_a_layer = false;
-        if (every_level_runs_a_layer)
-            return dp_select_fold(ctx, states, layer_stride, pos, M, lo, hi, mask_out, score_out, choice, g_final_out,
-                                  full_table, st);
-    }
     int rc;
     for (int i = 1; i <= L; ++i) {
         const int ell = (i - 1 < M) ? i - 1 : M;

@@ -46,150 +46,6 @@ struct QkvOut {
     void* v_self;        // [n_kv_heads] one block each
 };
 
-// ---- the DP's score / select step folded into the kernels around it (Algorithm 1, Eq. 2) ----------------------------
-// Level i of the DP decides, for every cell j >= 1, between the computed candidate c(i,j) = f_{i-1}(g(i-1,j)) and the skip
-// candidate g(i-1,j-1) by their cosines with x_i. Nothing of that needs a kernel of its own:
-//   * the down projection that finishes c(i,.) leaves <c, x_i> and <c, c> per 16-feature tile (GemmArgs::dp_parts);
-//   * the q/k/v projection of level i+1, the first kernel that needs g(i,.), adds the tiles up in its prologue (every
-//     workgroup the same sums in the same order, so all of them take the same decisions), picks each row's operand
-//     from the two candidates' ready-made operands, and, once its own contraction is done, its idle wavefronts write
-//     g(i,.) out for the kernels behind it, together with what level i+1 needs from these rows as ITS skip candidates:
-//     their operand under the next layer's gains, <g, x_{i+1}> and <g, g> per tile, and <x_{i+1}, x_{i+1}>.
-// Cells are addressed by j; a level covers cells j0..jmax, its computed candidates cells jc0..ell (row j - jc0 of the
-// layer's launches). Slot s of the skip-side arrays belongs to g(i-1, s), the skip candidate of cell s + 1.
-constexpr int kDpSlots = kMaxRows + 2;  // skip-side slots 0..kMaxRows, last slot (array 0): <x, x>
-struct DpLevel {
-    int i, M, j0, jc0, ell, jmax;
-    int n_tiles;          // d_model / 16, a multiple of 4
-    const float* partC;   // [2][kMaxRows][n_tiles]: <c, x_i>, <c, c>
-    const float* partS;   // [2][kDpSlots][n_tiles]: <s, x_i>, <s, s>; partS[0][kDpSlots - 1] = <x_i, x_i>
-    uint8_t* choice;      // [(L+1)][(M+1)] or null (only workgroup 0 writes)
-    float* scores;        // [(L+1)][(M+1)][2] or null
-};
-struct DpFold {
-    DpLevel lv;           // the level decided here (the previous one)
-    int jc0_next;         // launch row r is cell jc0_next + r of that level
-    const void* opC;      // operands of the computed candidates (row j - jc0), written by the down projection
-    const void* opS;      // operands of the skip candidates (slot j - 1)
-    const float* Cb;      // computed candidates, fp32 [kMaxRows][d]
-    const float* g_prev;  // g(i-1, .), fp32 [kMaxRows + 1][d]
-    float* g_cur;         // g(i, .), written here
-    const float* x_i;     // [d]
-    const float* x_next;  // x_{i+1}, [d]
-    void* opS_next;       // operands of g(i, .) under gain_next (slot = cell), null after the last layer
-    const float* gain_next;
-    float* partS_next;    // [2][kDpSlots][n_tiles] for level i+1
-    int d;
-};
-
-// Decisions of one level from the per-tile pieces. Pairs (array, row) are dealt to the NW wavefronts; a wavefront adds
-// a pair's tiles four at a time per lane and then across lanes, always in the same order. Leaves per cell j:
-// keep_s[j] = 1 when the computed candidate is kept, ssq_s[j] = <g(i,j), g(i,j)>. All threads of the workgroup call it.
-struct DpShared {
-    float tot[4][kDpSlots];
-    float ssq[kDpSlots];
-    int keep[kDpSlots];
-};
-__device__ __forceinline__ void dp_decide(const DpLevel& lv, DpShared& sh, bool write_tables) {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, NW = blockDim.x >> 6;
-    const int n_comp = lv.ell - lv.jc0 + 1, s_lo = max(1, lv.j0) - 1, n_s = lv.jmax - 1 - s_lo + 1;
-    const int n_pairs = 2 * max(n_comp, 0) + 2 * max(n_s, 0) + 1, n4 = lv.n_tiles >> 2;
-    auto pair_ptr = [&](int p, int& arr, int& slot) -> const f32x4* {
-        if (p < 2 * n_comp) {
-            arr = p & 1; slot = p >> 1;
-            return reinterpret_cast<const f32x4*>(lv.partC + ((size_t)arr * kMaxRows + slot) * lv.n_tiles);
-        }
-        p -= 2 * max(n_comp, 0);
-        if (p < 2 * n_s) {
-            arr = 2 + (p & 1); slot = s_lo + (p >> 1);
-            return reinterpret_cast<const f32x4*>(lv.partS + ((size_t)(p & 1) * kDpSlots + slot) * lv.n_tiles);
-        }
-        arr = 2; slot = kDpSlots - 1;
-        return reinterpret_cast<const f32x4*>(lv.partS + (size_t)(kDpSlots - 1) * lv.n_tiles);
-    };
-    constexpr int B = 16;  // pairs whose pieces are requested together: one memory round trip per batch and 256 tiles
-    for (int p0 = wave; p0 < n_pairs; p0 += NW * B) {
-        const f32x4* q[B];
-        int arr[B], slot[B];
-        float acc[B];
-#pragma unroll
-        for (int b = 0; b < B; ++b) {
-            acc[b] = 0.f;
-            q[b] = pair_ptr(min(p0 + b * NW, n_pairs - 1), arr[b], slot[b]);
-        }
-        for (int c0 = 0; c0 < n4; c0 += 64) {
-            const int c = min(c0 + lane, n4 - 1);
-            f32x4 v[B];
-#pragma unroll
-            for (int b = 0; b < B; ++b) v[b] = q[b][c];  // all requests first, then the sums
-            if (c0 + lane < n4) {
-#pragma unroll
-                for (int b = 0; b < B; ++b) acc[b] += (v[b][0] + v[b][1]) + (v[b][2] + v[b][3]);
-            }
-        }
-#pragma unroll
-        for (int b = 0; b < B; ++b) {
-            const float t = wave_sum(acc[b]);
-            if (lane == 0 && p0 + b * NW < n_pairs) sh.tot[arr[b]][slot[b]] = t;
-        }
-    }
-    __syncthreads();
-    const int j = threadIdx.x;
-    if (j >= max(1, lv.j0) && j <= lv.jmax) {
-        const float nx = fmaxf(sqrtf(sh.tot[2][kDpSlots - 1]), 1e-12f);
-        const float ds = sh.tot[2][j - 1], ns = sh.tot[3][j - 1];
-        const float sig_s = ds / (fmaxf(sqrtf(ns), 1e-12f) * nx);
-        const bool has_comp = j >= lv.jc0 && j <= lv.ell;
-        float sig_c = __builtin_nanf(""), nc = 0.f;
-        if (has_comp) {
-            nc = sh.tot[1][j - lv.jc0];
-            sig_c = sh.tot[0][j - lv.jc0] / (fmaxf(sqrtf(nc), 1e-12f) * nx);
-        }
-        const bool keep = has_comp && (sig_c > sig_s);
-        sh.keep[j] = keep ? 1 : 0;
-        sh.ssq[j] = keep ? nc : ns;
-        if (write_tables) {
-            const size_t cell = (size_t)lv.i * (lv.M + 1) + j;
-            if (lv.choice) lv.choice[cell] = keep ? 0 : 1;
-            if (lv.scores) {
-                lv.scores[cell * 2] = sig_c;
-                lv.scores[cell * 2 + 1] = sig_s;
-            }
-        }
-    }
-    __syncthreads();
-}
-
-// g(i, j)[col] for a decided level: x_i for j = 0, else the kept candidate.
-__device__ __forceinline__ float dp_resolve(const DpFold& f, const DpShared& sh, int j, int col) {
-    if (j == 0) return f.x_i[col];
-    return sh.keep[j] ? f.Cb[(size_t)(j - f.lv.jc0) * f.d + col] : f.g_prev[(size_t)(j - 1) * f.d + col];
-}
-
-// Writes g(i, .) of tile `tile` (16 features) and what the next level needs from it; run by `n_thr` threads (a multiple
-// of 16, thread index sid) after dp_decide.
-__device__ __forceinline__ void dp_materialize_tile(const DpFold& f, const DpShared& sh, int tile, int sid, int n_thr,
-                                                    int R) {
-    const int n_cells = f.lv.jmax - f.lv.j0 + 1, c16 = sid & 15, col = tile * 16 + c16;
-    const float xn = f.x_next ? f.x_next[col] : 0.f;
-    const float gn = f.gain_next ? f.gain_next[col] : 1.0f;
-    for (int item = sid; item < n_cells * 16; item += n_thr) {
-        const int j = f.lv.j0 + (item >> 4);
-        const float v = dp_resolve(f, sh, j, col);
-        f.g_cur[(size_t)j * f.d + col] = v;
-        if (f.opS_next && j < f.lv.M) store_operand<kDtBf16>(f.opS_next, R, 0, j, col, v * gn);  // slot M is no cell's skip candidate
-        const float sx = sum16(v * xn), sq = sum16(v * v);
-        if (f.partS_next && c16 == 0) {
-            f.partS_next[((size_t)j) * f.lv.n_tiles + tile] = sx;
-            f.partS_next[((size_t)kDpSlots + j) * f.lv.n_tiles + tile] = sq;
-        }
-    }
-    if (f.partS_next && sid < 16) {
-        const float xx = sum16(xn * xn);
-        if (c16 == 0) f.partS_next[(size_t)(kDpSlots - 1) * f.lv.n_tiles + tile] = xx;
-    }
-}
-
 struct GemmArgs {
     const void* W[3];   // up to three matrices stacked along N (q|k|v); fp32 kEpiSwiglu: W[0] = gate, W[1] = up
     int tile_end[3];    // exclusive end tile (16 features) of each stacked matrix
@@ -214,12 +70,6 @@ struct GemmArgs {
     // (O^T[attn_hd], max, sum) at attn_partial + ((v * attn_split + s) * 16 + j) * (attn_hd + 2)
     const float* attn_partial;
     int attn_split, attn_group, attn_hd;
-    // kEpiResid inside the DP (Algorithm 1): besides the finished rows c = resid + acc, the epilogue leaves what the
-    // cosine of Eq. 2 needs from them, per row and 16-feature tile: <c, x_i> and <c, c>, as dp_parts[0][row][tile] and
-    // dp_parts[1][row][tile] (kMaxRows rows, N/16 tiles). The next level's first kernel adds the tiles up.
-    float* dp_parts;
-    const float* dp_x;  // x_i, the stored verify state the level's candidates are scored against, [N]
-    DpFold dp;          // kEpiQkv inside the DP only
 };
 
 // (largest, index, second largest) of two disjoint sets; equal maxima keep the lower index.
@@ -324,31 +174,8 @@ __device__ __forceinline__ void gemm_issue(GemmStage<R, NACC, P, SPLIT>& st, con
 }
 
 template <int R, int NACC, int P, int SPLIT>
-__device__ __forceinline__ void gemm_issue_weights(GemmStage<R, NACC, P, SPLIT>& st, const u32x4* const (&w)[NACC], int s,
-                                                   int ks1) {
-#pragma unroll
-    for (int u = 0; u < P; ++u) {
-        const int ss = min(s + u, ks1 - 1);
-#pragma unroll
-        for (int a = 0; a < NACC; ++a) st.b[a][u] = load_stream(w[a] + (size_t)ss * 64);
-    }
-}
-template <int R, int NACC, int P, int SPLIT>
-__device__ __forceinline__ void gemm_issue_acts(GemmStage<R, NACC, P, SPLIT>& st, const u32x4* const (&af)[R], int s,
-                                                int ks1) {
-#pragma unroll
-    for (int u = 0; u < P; ++u) {
-        const int ss = min(s + u, ks1 - 1);
-#pragma unroll
-        for (int rg = 0; rg < R; ++rg)
-#pragma unroll
-            for (int h = 0; h < SPLIT; ++h) st.a[u][rg][h] = af[rg][((size_t)ss * R * 2 + h) * 64];
-    }
-}
-
-template <int R, int NACC, int P, int SPLIT>
-__device__ __forceinline__ void gemm_compute_ab(const u32x4 (&sa)[P][R][SPLIT], const u32x4 (&sb)[NACC][P],
-                                                f32x4 (&acc)[NACC][R], int s, int ks1) {
+__device__ __forceinline__ void gemm_compute(const GemmStage<R, NACC, P, SPLIT>& st, f32x4 (&acc)[NACC][R], int s,
+                                             int ks1) {
 #pragma unroll
     for (int u = 0; u < P; ++u) {
         if (s + u < ks1) {
@@ -358,15 +185,10 @@ __device__ __forceinline__ void gemm_compute_ab(const u32x4 (&sa)[P][R][SPLIT], 
                 for (int h = 0; h < SPLIT; ++h)
 #pragma unroll
                     for (int a = 0; a < NACC; ++a)
-                        acc[a][rg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(sa[u][rg][h]), as_bf16x8(sb[a][u]),
-                                                                             acc[a][rg], 0, 0, 0);
+                        acc[a][rg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(st.a[u][rg][h]),
+                                                                             as_bf16x8(st.b[a][u]), acc[a][rg], 0, 0, 0);
         }
     }
-}
-template <int R, int NACC, int P, int SPLIT>
-__device__ __forceinline__ void gemm_compute(const GemmStage<R, NACC, P, SPLIT>& st, f32x4 (&acc)[NACC][R], int s,
-                                             int ks1) {
-    gemm_compute_ab<R, NACC, P, SPLIT>(st.a, st.b, acc, s, ks1);
 }
 
 // Inputs of the epilogue that do not depend on the contraction (residual values, gain, rotary factors). The
@@ -375,7 +197,6 @@ struct EpiPre {
     float resid[4];
     float2 cs[4];
     float gain;
-    float xv;  // x_i[col] when the DP's pieces are asked for
 };
 
 template <int EPI>
@@ -383,7 +204,6 @@ __device__ __forceinline__ void epi_prefetch(const GemmArgs& g, int tile, int la
     const int c = lane & 15, col = tile * 16 + c, row0 = rg * 16 + (lane >> 4) * 4;
     if constexpr (EPI == kEpiResid) {
         pre.gain = g.next_gain ? g.next_gain[col] : 1.0f;
-        pre.xv = g.dp_parts ? g.dp_x[col] : 0.f;
 #pragma unroll
         for (int r = 0; r < 4; ++r) pre.resid[r] = (row0 + r < g.n_rows) ? g.resid[(size_t)(row0 + r) * g.ldr + col] : 0.f;
     } else if constexpr (EPI == kEpiQkv) {
@@ -497,16 +317,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, int tile, int l
                 if (g.capture) g.capture[(size_t)row * g.ldc + col] = v;
             }
             if (g.next_op) store_operand<kDtBf16>(g.next_op, g.R, 0, row, col, v * gain);
-            if (g.next_ss || g.dp_parts) {
+            if (g.next_ss) {
                 const float sq = sum16(v * v);
-                if (g.next_ss && (lane & 15) == 0) g.next_ss[(size_t)tile * kMaxRows + row] = sq;
-                if (g.dp_parts) {
-                    const float cx = sum16(v * pre.xv);
-                    if ((lane & 15) == 0) {
-                        g.dp_parts[(size_t)row * (g.N >> 4) + tile] = cx;
-                        g.dp_parts[((size_t)kMaxRows + row) * (g.N >> 4) + tile] = sq;
-                    }
-                }
+                if ((lane & 15) == 0) g.next_ss[(size_t)tile * kMaxRows + row] = sq;
             }
         }
     } else {
@@ -531,17 +344,12 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, int tile, int l
 // tile are summed through LDS in slice order.
 // (Cross-workgroup split-K inside one kernel is not used: agent-scope release fences cost far more than they save
 // on this part, every one of them writes the whole L2 back.)
-// FOLD (q/k/v projection inside the DP, CW = 1, KW > 1): the prologue takes the previous level's decisions (dp_decide)
-// instead of reading ready-made sums of squares, every lane picks its row's operand between the two candidates, and the
-// wavefronts that have nothing left to do after the reduction write the level out (dp_materialize_tile).
-template <int R, int CW, int KW, int EPI, int P, int SPLIT, int NACC = 1, bool FOLD = false>
+template <int R, int CW, int KW, int EPI, int P, int SPLIT, int NACC = 1>
 __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
     constexpr int NW = CW * KW;
-    static_assert(!FOLD || (EPI == kEpiQkv && CW == 1 && KW > 1), "the fold lives in the DP's q/k/v projection");
     __shared__ f32x4 red[KW][CW][NACC][R][64];
     __shared__ float rstd_s[kMaxRows];
     __shared__ float tmp_s[NW * 64];
-    __shared__ DpShared dp_s;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int cw = wave % CW, kw = wave / CW;
     const int n_tiles = g.N >> 4;
@@ -563,6 +371,12 @@ __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
         w[a] = reinterpret_cast<const u32x4*>(g.W[mi]) + (size_t)tl * KS * 64 + lane;
     }
     const u32x4* af[R];
+#pragma unroll
+    for (int rg = 0; rg < R; ++rg) {  // row of this lane, clamped to the last live row; may sit in an earlier group
+        const int row = min(rg * 16 + (lane & 15), g.n_rows - 1);
+        af[rg] = reinterpret_cast<const u32x4*>(g.A) + (size_t)(row >> 4) * 128 + (row & 15) * 4 + (lane >> 4);
+    }
+
     f32x4 acc[NACC][R];
 #pragma unroll
     for (int a = 0; a < NACC; ++a)
@@ -571,86 +385,16 @@ __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
 
     GemmStage<R, NACC, P, SPLIT> st0, st1;
     int s = ks0;
+    if (s < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w, af, s, ks1);  // weights first: independent of rstd
+
     EpiPre pre[NACC][R];
-    if constexpr (FOLD) {
-        // Two weight stages go out before anything else (they depend on nothing), and with them the first stage's
-        // operands of BOTH candidates of this lane's row, so that the level's pieces (dp_decide) and the operands travel
-        // in the same memory round trip: a load that depends on another one queues behind everything the weight
-        // stream has in flight. The first stage is multiplied for both candidates and the kept one's sums survive.
-        const u32x4 *af_c[R], *af_s[R];
+    if (kw == 0) {
 #pragma unroll
-        for (int rg = 0; rg < R; ++rg) {  // this lane's row, clamped to the last live one
-            const int j = g.dp.jc0_next + min(rg * 16 + (lane & 15), g.n_rows - 1);
-            const int rc = max(j - g.dp.lv.jc0, 0), rs = j - 1;  // (a cell without a computed candidate always keeps the other)
-            af_c[rg] = reinterpret_cast<const u32x4*>(g.dp.opC) + (size_t)(rc >> 4) * 128 + (rc & 15) * 4 + (lane >> 4);
-            af_s[rg] = reinterpret_cast<const u32x4*>(g.dp.opS) + (size_t)(rs >> 4) * 128 + (rs & 15) * 4 + (lane >> 4);
-        }
-        if (s < ks1) {
-            gemm_issue_weights<R, NACC, P, SPLIT>(st0, w, s, ks1);
-            gemm_issue_acts<R, NACC, P, SPLIT>(st0, af_c, s, ks1);
-            gemm_issue_acts<R, NACC, P, SPLIT>(st1, af_s, s, ks1);  // st1's operand registers are free until stage two
-        }
-        if (s + P < ks1) gemm_issue_weights<R, NACC, P, SPLIT>(st1, w, s + P, ks1);
-        if (kw == 0) {
+        for (int a = 0; a < NACC; ++a)
 #pragma unroll
-            for (int a = 0; a < NACC; ++a)
-#pragma unroll
-                for (int rg = 0; rg < R; ++rg) epi_prefetch<EPI>(g, tile[a], lane, rg, pre[a][rg]);
-        }
-        dp_decide(g.dp.lv, dp_s, blockIdx.x == 0);
-        if (threadIdx.x < kMaxRows) {  // read by the epilogue, after the barrier that follows the contraction
-            const int j = g.dp.jc0_next + min((int)threadIdx.x, g.n_rows - 1);
-            rstd_s[threadIdx.x] = 1.0f / sqrtf(dp_s.ssq[j] * g.inv_dim + g.eps);
-        }
-#pragma unroll
-        for (int rg = 0; rg < R; ++rg) {
-            const int j = g.dp.jc0_next + min(rg * 16 + (lane & 15), g.n_rows - 1);
-            af[rg] = dp_s.keep[j] ? af_c[rg] : af_s[rg];
-        }
-        if (s < ks1) {
-            f32x4 acc_s[NACC][R];
-#pragma unroll
-            for (int a = 0; a < NACC; ++a)
-#pragma unroll
-                for (int rg = 0; rg < R; ++rg) acc_s[a][rg] = f32x4{0.f, 0.f, 0.f, 0.f};
-            gemm_compute<R, NACC, P, SPLIT>(st0, acc, s, ks1);
-            gemm_compute_ab<R, NACC, P, SPLIT>(st1.a, st0.b, acc_s, s, ks1);
-#pragma unroll
-            for (int rg = 0; rg < R; ++rg)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {  // an accumulator lane holds rows (lane / 16) * 4 + r of one feature
-                    const int j = g.dp.jc0_next + min(rg * 16 + (lane >> 4) * 4 + r, g.n_rows - 1);
-                    const bool keep = dp_s.keep[j] != 0;
-#pragma unroll
-                    for (int a = 0; a < NACC; ++a) acc[a][rg][r] = keep ? acc[a][rg][r] : acc_s[a][rg][r];
-                }
-            s += P;
-            if (s < ks1) gemm_issue_acts<R, NACC, P, SPLIT>(st1, af, s, ks1);  // its weights are in flight already
-        }
-        while (s < ks1) {  // the usual two-stage loop, st1 first
-            if (s + P < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w, af, s + P, ks1);
-            gemm_compute<R, NACC, P, SPLIT>(st1, acc, s, ks1);
-            s += P;
-            if (s >= ks1) break;
-            if (s + P < ks1) gemm_issue<R, NACC, P, SPLIT>(st1, w, af, s + P, ks1);
-            gemm_compute<R, NACC, P, SPLIT>(st0, acc, s, ks1);
-            s += P;
-        }
-    } else {
-#pragma unroll
-        for (int rg = 0; rg < R; ++rg) {  // row of this lane, clamped to the last live row; may sit in an earlier group
-            const int row = min(rg * 16 + (lane & 15), g.n_rows - 1);
-            af[rg] = reinterpret_cast<const u32x4*>(g.A) + (size_t)(row >> 4) * 128 + (row & 15) * 4 + (lane >> 4);
-        }
-        if (s < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w, af, s, ks1);  // weights first: independent of rstd
-        if (kw == 0) {
-#pragma unroll
-            for (int a = 0; a < NACC; ++a)
-#pragma unroll
-                for (int rg = 0; rg < R; ++rg) epi_prefetch<EPI>(g, tile[a], lane, rg, pre[a][rg]);
-        }
-        if constexpr (EPI != kEpiResid && EPI != kEpiPartial) compute_rstd(g, rstd_s, tmp_s);
+            for (int rg = 0; rg < R; ++rg) epi_prefetch<EPI>(g, tile[a], lane, rg, pre[a][rg]);
     }
+    if constexpr (EPI != kEpiResid && EPI != kEpiPartial) compute_rstd(g, rstd_s, tmp_s);
 
     while (s < ks1) {
         if (s + P < ks1) gemm_issue<R, NACC, P, SPLIT>(st1, w, af, s + P, ks1);
@@ -685,14 +429,7 @@ __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
             for (int rg = 0; rg < R; ++rg) sum[a][rg] = acc[a][rg];
     }
 
-    if (kw != 0) {
-        if constexpr (FOLD) {  // the level just decided, written out tile by tile by the wavefronts that are done
-            const int sid = (kw - 1) * 64 + lane;
-            for (int t = blockIdx.x; t < g.dp.lv.n_tiles; t += gridDim.x)
-                dp_materialize_tile(g.dp, dp_s, t, sid, (KW - 1) * 64, g.R);
-        }
-        return;
-    }
+    if (kw != 0) return;
 
 #pragma unroll
     for (int a = 0; a < NACC; ++a) {

@@ -2,7 +2,6 @@
 // the DP's cosine/select step (Algorithm 1), backtracking, and greedy argmax over the logits.
 #pragma once
 #include "clasp_common.h"
-#include "clasp_gemm.h"
 
 namespace clasp {
 
@@ -261,50 +260,6 @@ __global__ void dp_backtrack_kernel(const uint8_t* choice, int L, int M, uint8_t
         }
     } else if (g_final) {
         for (int c = threadIdx.x; c < d; c += blockDim.x) g_final[c] = g_last[(size_t)M * d + c];
-    }
-}
-
-// ---- the folded DP (see DpFold): what stands before its first and after its last layer --------------------------------
-// Level 0 written out: g(0,0) = x_0, and what level 1 needs from it as its only skip candidate (its operand under the
-// gains of the first layer that is run, <x_0, x_1>, <x_0, x_0>, <x_1, x_1> per tile). One thread per feature.
-__global__ __launch_bounds__(256) void dp_fold_init_kernel(const float* x0, const float* x1, int d, int R, float* g0,
-                                                           void* opS_next, const float* gain_next, float* partS_next) {
-    const int col = blockIdx.x * 256 + threadIdx.x;
-    if (col >= d) return;  // d % 16 == 0: a 16-feature tile is all in or all out
-    const int tile = col >> 4, n_tiles = d >> 4;
-    const float v = x0[col], xn = x1[col];
-    g0[col] = v;
-    if (opS_next) store_operand<kDtBf16>(opS_next, R, 0, 0, col, v * (gain_next ? gain_next[col] : 1.0f));
-    const float sx = sum16(v * xn), sq = sum16(v * v), xx = sum16(xn * xn);
-    if ((col & 15) == 0) {
-        partS_next[tile] = sx;
-        partS_next[(size_t)kDpSlots * n_tiles + tile] = sq;
-        partS_next[(size_t)(kDpSlots - 1) * n_tiles + tile] = xx;
-    }
-}
-
-// The last level's decisions, g(L, M), and the backtrack from (L, M): a kept skip candidate at (i, j) means layer i-1 of
-// the window is skipped. One workgroup.
-__global__ __launch_bounds__(1024) void dp_fold_finish_kernel(DpFold f, int L, uint8_t* mask, int lo, int L_all,
-                                                              float* g_final) {
-    __shared__ DpShared sh;
-    dp_decide(f.lv, sh, true);
-    const int M = f.lv.M;
-    if (g_final)
-        for (int c = threadIdx.x; c < f.d; c += blockDim.x) g_final[c] = dp_resolve(f, sh, M, c);
-    for (int l = threadIdx.x; l < L_all; l += blockDim.x) mask[l] = 0;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int i = L, j = M;
-        while (i > 0 && j > 0) {
-            // level L was decided by this workgroup a moment ago: its choices are taken from LDS
-            const bool skip = (i == L) ? !sh.keep[j] : f.lv.choice[(size_t)i * (M + 1) + j] == 1;
-            if (skip) {
-                mask[lo + i - 1] = 1;
-                --j;
-            }
-            --i;
-        }
     }
 }
 
