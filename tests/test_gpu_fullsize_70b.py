@@ -5,6 +5,10 @@ The fp64 oracle needs ~0.5 s per row and layer at this width, so the comparison 
     layer shapes: d_model 8192, 64 / 8 heads, d_ffn 28672, vocab 128256) over a 1024-token synthetic prefix: verify
     rows, the search with and without tables (M = 3), a draft step, and a verify pass of 18 rows (two 16-row groups, the
     second ragged: the launch shape the search takes at M = 32);
+  * against the oracle, element by element: the FIRST 24 layers of the same model with a prefix of 40 tokens that each
+    side produces itself (the device in verify passes of 32 and 8 rows), then two verify rows, the search with M = 20
+    on the device's own states (two 16-row groups from level 18 on: four column tiles per wavefront in the projections,
+    the two-group K-split down projection and select step), the search without tables, and a draft step;
   * on the whole 80-layer model with M = 32, where the oracle cannot follow: what holds for any correct search
     (Algorithm 1's structure; the skip set replayed layer by layer reproduces the score the table ends on).
 """
@@ -44,6 +48,35 @@ def test_70b_layer_shapes_against_the_oracle():
         out = eng.clasp_verify_forward(dev(toks, torch.int32), T, want_hidden=True)
         for l in range(shape.n_layers + 1):
             assert relerr(out["hidden"][l].cpu().numpy(), ost[l]) <= HID_TOL["bf16"], f"layer {l}"
+    finally:
+        eng.close()
+
+
+def test_70b_24_layers_two_row_groups_against_the_oracle():
+    import bench
+    shape = dataclasses.replace(si.LLAMA3_70B, name="llama3-70b-shape-first-24-layers", n_layers=24)
+    n_prompt, M = 40, 20
+    eng, host = bench.build_engine(shape, 1, 128, 32, keep_host=True)
+    try:
+        om = oc.OracleModel(shape, host)
+        toks = [int(t) for t in si.gen_tokens(2, n_prompt, shape.vocab, stream=31)]
+        cache = oc.KVCache(shape, n_prompt + 8)
+        for t, tk in enumerate(toks):
+            if t % 8 == 0:
+                print(f"oracle prompt token {t} of {n_prompt}", flush=True)
+            om.token(tk, t, cache, want_logits=False)
+        tt = dev(toks, torch.int32)
+        eng.clasp_verify_forward(tt[:32], 0)
+        eng.clasp_verify_forward(tt[32:], 32)
+        worst = 0.0
+        for l in range(shape.n_layers):
+            K, V = (x.cpu().numpy() for x in eng.clasp_kv_read(l, 0, n_prompt))
+            ek, ev = relerr(K, cache.K[l, :n_prompt]), relerr(V, cache.V[l, :n_prompt])
+            assert ek <= HID_TOL["bf16"] and ev <= HID_TOL["bf16"], f"cache layer {l}: K {ek:.3e} V {ev:.3e}"
+            worst = max(worst, ek, ev)
+        print(f"largest cache error over 24 layers: {worst:.3e}", flush=True)
+        stats = verify_dp_draft(shape, n_prompt, eng, om, cache, M=M)
+        print(f"dp cells compared: {stats}", flush=True)
     finally:
         eng.close()
 
