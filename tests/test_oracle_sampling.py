@@ -131,3 +131,66 @@ def test_sampling_loop_structure():
         assert 0 <= r["accepted"] <= K and r["mask"].sum() == 3 and r["pos"] == len(pr) + emitted - 1
         emitted += r["accepted"] + 1
     assert emitted >= n_gen
+
+
+def test_argmax_margin_closed_forms():
+    """argmax_margin: lowest index of the maximum, and the gap to the runner-up (0 on a tie, inf for one entry)."""
+    assert oc.argmax_margin(np.array([1.0, 5.0, 3.0])) == (1, 2.0)
+    assert oc.argmax_margin(np.array([2.0, 7.0, 7.0, 1.0])) == (1, 0.0)
+    assert oc.argmax_margin(np.array([-4.0, -9.5, -4.25])) == (0, 0.25)
+    i, m = oc.argmax_margin(np.array([3.0]))
+    assert i == 0 and m == float("inf")
+    lg = np.array([0.5, -1.0, 0.25, 0.5 - 1e-9])
+    i, m = oc.argmax_margin(lg)
+    assert i == 0 and abs(m - 1e-9) < 1e-15
+    # shifting every logit moves neither the index nor the margin; scaling scales the margin
+    assert oc.argmax_margin(lg + 11.0)[0] == 0 and abs(oc.argmax_margin(3.0 * lg)[1] - 3e-9) < 1e-14
+
+
+def test_sampling_loop_with_no_skipped_layer_is_plain_ancestral_sampling():
+    """M = 0: draft model = full model, so p = q, every draft is kept, and the loop must emit exactly what sampling the
+    full model token by token emits when it is handed the same uniform numbers in the order the loop consumes them:
+    first, then per round K draft numbers and the round's final number. This pins the loop's bookkeeping (positions,
+    cache rows, which uniform number feeds which draw) to the textbook procedure, written here without any rounds."""
+    om = oracle_model("tiny-f32", 1, 0.05)
+    pr = prompt(om.shape, 12)
+    K, n_gen, temp = 3, 13, 0.8
+    un = _uniforms(9, n_gen, K)
+    spec = om.spec_sample_decode(pr, n_gen, 0, K, un, temperature=temp)
+    order = [un["first"][0]]
+    for r in range(n_gen):
+        order += list(un["draft"][r * K:(r + 1) * K]) + [un["final"][r]]
+    cache = oc.KVCache(om.shape, len(pr) + n_gen + 2)
+    _, lg = om.prefill(pr, cache)
+    plain = []
+    for t in range(n_gen):
+        tok, _ = oc.sample_cdf(oc.softmax_t(lg, temp), order[t])
+        plain.append(tok)
+        _, lg = om.token(tok, len(pr) + t, cache)
+    assert spec["tokens"] == plain
+    assert all(r["accepted"] == K for r in spec["rounds"])
+
+
+def test_sampling_loop_keeps_every_draft_when_the_acceptance_numbers_are_zero():
+    """u * q(x) < p(x) holds for u = 0 wherever p(x) > 0: with all acceptance numbers zero every round keeps its K
+    drafts whatever the skip set, emits K + 1 tokens, and the next round starts K + 1 positions further on."""
+    om = oracle_model("tiny-f32", 1, 1.0)
+    pr = prompt(om.shape, 10)
+    K, n_gen = 2, 10
+    un = _uniforms(5, n_gen, K)
+    un["accept"] = np.zeros_like(un["accept"])
+    spec = om.spec_sample_decode(pr, n_gen, 3, K, un)
+    assert all(r["accepted"] == K for r in spec["rounds"])
+    assert [r["pos"] for r in spec["rounds"]] == [len(pr) + (K + 1) * i for i in range(len(spec["rounds"]))]
+    flat = [spec["tokens"][0]]
+    for r in spec["rounds"]:
+        flat += r["drafts"] + [r["next"]]
+    assert flat[:n_gen] == spec["tokens"]
+    # and with acceptance numbers just below one, a model whose draft differs from the full model rejects early
+    # (a draft x drawn from q is rejected exactly when q(x) > p(x) then: about every other one on this model)
+    n_gen = 30
+    un = _uniforms(5, n_gen, K)
+    un["accept"] = np.full_like(un["accept"], 1.0 - 2.0 ** -24)
+    spec = om.spec_sample_decode(pr, n_gen, 3, K, un)
+    kept = sum(r["accepted"] for r in spec["rounds"])
+    assert 0 < kept < K * len(spec["rounds"]) and len(spec["rounds"]) >= n_gen // (K + 1)
