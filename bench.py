@@ -22,8 +22,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel from rocprofv3 PMC runs (FETCH_SIZE + WRITE_SIZE, each scaled by what the
 # counter reads for a 1 GiB copy); see profiles/gate_up_gemm_llama3-8b-shape_hbm_traffic.md. The projection runs as two
-# kernels (up to 8 rows: 235.8 + 1.84 MB, above: 237.3 + 1.84 MB); a step of the default workload launches them 120 : 23.
-MEASURED_TRAFFIC = {"llama3-8b-shape": (120 * (235.8e6 + 1.84e6) + 23 * (237.3e6 + 1.84e6)) / 143}
+# kernels (up to 8 rows: 236.0 + 1.84 MB, above: 236.8 + 1.84 MB); a step of the default workload launches them 128 : 15.
+MEASURED_TRAFFIC = {"llama3-8b-shape": (128 * (236.0e6 + 1.84e6) + 15 * (236.8e6 + 1.84e6)) / 143}
 
 WORKLOADS = {
     # benchmark configuration 2: the one the metric is quoted on
@@ -239,6 +239,10 @@ def main():
                     help="only time the prompt pass (clasp_prefill) over N_TOKENS synthetic tokens of the workload's "
                          "model; prints its own JSON line (tokens/s, algorithmic TFLOP/s against the bf16 MFMA peak)")
     ap.add_argument("--prefill-chunk", type=int, default=4096, help="rows per pass of --prefill (multiple of 128)")
+    ap.add_argument("--call", choices=["dp_select", "draft_step", "verify_forward"], default=None,
+                    help="only issue this one call --steps times on the workload's model over a synthetic prefix of the "
+                         "workload's length (after one warm-up round of all three calls): what a rocprofv3 run of a single "
+                         "call's kernels is taken from; prints the call's mean time")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="only run plain device copies of a known size (1 GiB read + 1 GiB written per copy), to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -263,6 +267,39 @@ def main():
     wl = WORKLOADS[args.workload]
     shape = si.SHAPES[wl["shape"]]
     T, M, K = wl["T"], wl["M"], wl["K"]
+    if args.call:
+        eng, _ = build_engine(shape, 1, ((T + 64 + 31) // 32) * 32, 32 if M > 16 else 16)
+        print("model loaded", file=sys.stderr, flush=True)
+        for l in range(shape.n_layers):
+            Kp, Vp = si.gen_kv(shape, 1000 + l, 1, T, "cuda")
+            eng.clasp_kv_load(l, Kp[0], Vp[0])
+        tok = si.gen_tokens(2, K + 1, shape.vocab, stream=9).cuda()
+        ver = eng.clasp_verify_forward(tok, T, want_hidden=True)
+        states = ver["hidden"][:, 1, :].contiguous()
+        dp = eng.clasp_dp_select(states, T + 1, M)
+        mask = dp["mask"].cpu().tolist()
+        nxt = torch.zeros(1, dtype=torch.int32, device="cuda")
+        eng.clasp_draft_step(mask, tok[:1], T + K + 1, nxt)
+        torch.cuda.synchronize()
+        print("prefix loaded, warm-up round done", file=sys.stderr, flush=True)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n = max(1, args.steps)
+        e0.record()
+        for _ in range(n):
+            if args.call == "dp_select":
+                eng.clasp_dp_select(states, T + 1, M, out=dp)
+            elif args.call == "draft_step":
+                eng.clasp_draft_step(mask, tok[:1], T + K + 1, nxt)
+            else:
+                eng.clasp_verify_forward(tok, T, want_hidden=True)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / n
+        ab = algorithmic_bytes(shape, T, M)[args.call]
+        print(json.dumps({"call": args.call, "workload": args.workload, "calls": n, "warmup_calls_of_each_kind": 1,
+                          "ms_per_call": round(ms, 4), "algorithmic_GB": round(ab / 1e9, 3),
+                          "hbm_frac_of_8TBs": round(ab / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}))
+        return
     if args.markov_study:
         eng, _ = build_engine(shape, 1, ((T + 64 + 31) // 32) * 32, 16, resid_scale=args.resid_scale)
         Kp, Vp = si.gen_kv(shape, 3, 1, T, "cuda")
