@@ -409,11 +409,15 @@ int launch_attn_bf16(const AttnArgs& a, bool short_prefix, int nt, dim3 grid, hi
     if (short_prefix) return launch_attn_one<HD, 1, CLASP_ATTN_SHORT_WAVES, false>(a, grid, st);
     if (nt == 1) return launch_attn_one<HD, 1, 8, true>(a, grid, st);
     if (nt == 2) return launch_attn_one<HD, 2, 8, true>(a, grid, st);
-    if constexpr (HD <= 64) {  // head_dim 128 never takes more than two query tiles (registers)
+    if constexpr (HD <= 64) {
         if (nt == 3) return launch_attn_one<HD, 3, 8, true>(a, grid, st);
         return launch_attn_one<HD, 4, 8, true>(a, grid, st);
+    } else {
+        // head_dim 128: three or four query tiles (33..64 queries of a KV group: 9..16 DP rows at 4 heads per group) need
+        // more registers than two wavefronts per SIMD leave: four wavefronts, one per SIMD, each with the whole file
+        if (nt == 3) return launch_attn_one<HD, 3, 4, true>(a, grid, st);
+        return launch_attn_one<HD, 4, 4, true>(a, grid, st);
     }
-    return CLASP_E_UNSUPPORTED;
 }
 
 // Prefix splits of a one-row launch whose merge the output projection takes over (0 = merge here as usual): the
@@ -460,7 +464,10 @@ int launch_attention(const clasp_ctx* ctx, int layer, int n, int R, int mode, in
     const bool short_prefix = nblk <= CLASP_ATTN_SHORT_BLOCKS;
     // query tiles per workgroup: what the register file holds without spilling (O^T alone is head_dim/4 registers
     // per tile); further tiles go to sibling workgroups, launched next to each other so that their key reads meet in L2
-    const int max_nt = c.head_dim > 64 ? (nblk >= CLASP_ATTN_NT2_BLOCKS ? 2 : 1) : 4;
+    // (head_dim 128: one tile below CLASP_ATTN_NT2_BLOCKS blocks; from there on as many as the queries fill, up to 4: one
+    // pass over the prefix serves all of them, where sibling workgroups re-read 12 % of it from HBM and take 33 us
+    // instead of 24 per layer at 32768 tokens)
+    const int max_nt = c.head_dim > 64 ? (nblk >= CLASP_ATTN_NT2_BLOCKS ? 4 : 1) : 4;
     const int nt = short_prefix ? 1 : (ntq < max_nt ? ntq : max_nt), qgroups = (ntq + nt - 1) / nt;
     int split = short_prefix ? 1 : (nblk + CLASP_ATTN_BLOCKS_PER_SPLIT - 1) / CLASP_ATTN_BLOCKS_PER_SPLIT;
     {   // a CU holds one of these workgroups: a launch a little above a whole number of rounds would leave most CUs
@@ -479,7 +486,7 @@ int launch_attention(const clasp_ctx* ctx, int layer, int n, int R, int mode, in
                                     : launch_attn_bf16<128>(a, short_prefix, nt, grid, st);
     if (rc) return rc;
     if (split > 1 && !deferred_splits) {
-        hipLaunchKernelGGL(attn_combine_kernel, dim3(c.n_kv_heads, nQ), dim3(c.head_dim), 0, st, a, nt, qgroups);
+        hipLaunchKernelGGL(attn_combine_kernel, dim3(c.n_kv_heads, nQ), dim3(kCombineWaves * 64), 0, st, a, nt, qgroups);
         CLASP_LAUNCH_CHECK();
     }
     return CLASP_OK;

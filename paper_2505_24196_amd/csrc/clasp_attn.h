@@ -249,7 +249,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(AttnArgs a) {
         attn_compute<HD, NT>(st, qf, f, [&](int u, int r, int t) { return kb + q4 * 8 + u * 4 + r <= limit[t]; });
     };
     int blk = b0 + wave;
-    if constexpr (NT <= CLASP_ATTN_DOUBLE_NT) {  // registers allow a second fragment set: the next block is in flight during the MFMAs
+    if constexpr (NT <= CLASP_ATTN_DOUBLE_NT || (NW <= 4 && NT <= 3)) {  // registers allow a second fragment set (four wavefronts: one per SIMD, the whole register file each): the next block is in flight during the MFMAs
         AttnFrags<HD> f0, f1;
         if (blk < b1) load_blk(f0, blk);
         while (blk < b1) {
@@ -351,27 +351,49 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(AttnArgs a) {
     }
 }
 
-// Merges the n_split partial results of one query in split order and writes the output-projection operand.
-// Grid (kv heads, queries), one thread per head-dim element.
-__global__ void attn_combine_kernel(AttnArgs a, int nt, int qgroups) {
+// Merges the n_split partial results of one query and writes the output-projection operand. Grid (kv heads, queries),
+// kCombineWaves wavefronts: every thread first takes the largest of the splits' maxima (the same few words for the whole
+// workgroup), then wavefront w adds the rescaled sums of splits w, w + kCombineWaves, .. for two head-dim elements per
+// lane (all of a wavefront's loads in flight together), and the wavefronts' sums are added in order through LDS.
+constexpr int kCombineWaves = 4;
+__global__ __launch_bounds__(kCombineWaves * 64) void attn_combine_kernel(AttnArgs a, int nt, int qgroups) {
+    __shared__ float sL[kCombineWaves];
+    __shared__ float2 sO[kCombineWaves][64];
     const int kvh = blockIdx.x, qi = blockIdx.y, HD = a.head_dim;
     const int G = a.n_heads / a.n_kv_heads;
     const int qg = qi / (nt * 16), ql = qi % (nt * 16);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const size_t sstride = (size_t)nt * 16 * (HD + 2);
     const float* pq = a.partial + (((size_t)kvh * qgroups + qg) * a.n_split) * sstride + (size_t)ql * (HD + 2);
     float mstar = -INFINITY;
+#pragma unroll 8
     for (int s = 0; s < a.n_split; ++s) mstar = fmaxf(mstar, pq[s * sstride + HD]);
-    for (int e = threadIdx.x; e < HD; e += blockDim.x) {
-        float L = 0.f, O = 0.f;
+    float L = 0.f;
+    float2 O = make_float2(0.f, 0.f);
+    const bool live = 2 * lane < HD;  // head_dim 64: half of the lanes carry elements
 #pragma unroll 4
-        for (int s = 0; s < a.n_split; ++s) {
-            const float ms = pq[s * sstride + HD];
-            const float f = (ms == -INFINITY) ? 0.f : exp2f(ms - mstar);
-            L += f * pq[s * sstride + HD + 1];
-            O += f * pq[s * sstride + e];
+    for (int s = wave; s < a.n_split; s += kCombineWaves) {
+        const float2 ml = *reinterpret_cast<const float2*>(pq + s * sstride + HD);
+        const float2 ov = live ? *reinterpret_cast<const float2*>(pq + s * sstride + 2 * lane) : make_float2(0.f, 0.f);
+        const float f = (ml.x == -INFINITY) ? 0.f : exp2f(ml.x - mstar);
+        L += f * ml.y;
+        O.x += f * ov.x;
+        O.y += f * ov.y;
+    }
+    if (lane == 0) sL[wave] = L;
+    sO[wave][lane] = O;
+    __syncthreads();
+    if (wave == 0 && live) {
+        float Lt = sL[0];
+        float2 Ot = sO[0][lane];
+        for (int w = 1; w < kCombineWaves; ++w) {
+            Lt += sL[w];
+            Ot.x += sO[w][lane].x;
+            Ot.y += sO[w][lane].y;
         }
         const int row = qi / G, h = kvh * G + qi % G;
-        store_operand<kDtBf16>(a.out_op, a.R, 0, row, h * HD + e, O / L);
+        store_operand<kDtBf16>(a.out_op, a.R, 0, row, h * HD + 2 * lane, Ot.x / Lt);
+        store_operand<kDtBf16>(a.out_op, a.R, 0, row, h * HD + 2 * lane + 1, Ot.y / Lt);
     }
 }
 

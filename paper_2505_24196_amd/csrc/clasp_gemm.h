@@ -451,7 +451,7 @@ __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
 // workgroup, KW wavefronts split K; the register stages hold weights only. `nks_max` = LDS k-steps reserved per
 // wavefront (>= ceil(K/32/KW), <= 16*kGemvLoads/SPLIT); dynamic LDS = KW * nks_max * SPLIT * 64 bytes.
 // ASRC = 1 (output projection of a draft step): the row is not read from an operand but merged here from the pieces
-// that split attention left per (KV head, prefix split, query): same arithmetic and order as attn_combine_kernel, so
+// that split attention left per (KV head, prefix split, query): the arithmetic of attn_combine_kernel with the splits taken in order, so
 // the attention kernel needs neither a second launch nor a single workgroup per KV head.
 constexpr int kGemvLoads = 8;
 constexpr int kGemvMaxSplit = 8;
@@ -517,7 +517,7 @@ __global__ __launch_bounds__(KW * 64) void gemv_bf16_kernel(GemmArgs g, int nks_
                 }
             }
         };
-        auto merge_store = [&](const Piece& pc, int pp) {  // attn_combine_kernel's arithmetic, then hi/lo into LDS
+        auto merge_store = [&](const Piece& pc, int pp) {  // the merge of attn_combine_kernel, splits in order, then hi/lo into LDS
             float mstar = -INFINITY;
 #pragma unroll
             for (int sp = 0; sp < kGemvMaxSplit; ++sp)

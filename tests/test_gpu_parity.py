@@ -303,6 +303,34 @@ def test_long_prefix_split_and_ragged_blocks(T):
     check_dp(om, eng, ost[:, 2], T + 2, c, 3)
 
 
+@pytest.mark.parametrize("n_rows", [10, 13])
+def test_very_long_prefix_three_and_four_query_tiles_per_workgroup(n_rows):
+    """head_dim 128 over a 16500-token prefix (516 key blocks): from 512 blocks on, one workgroup of four wavefronts
+    carries all query tiles of a KV group (10 rows x 4 heads = 40 queries = 3 tiles, 13 rows = 52 queries = 4 tiles)
+    through one pass over the prefix, split 32 ways, merged by the combine kernel. Verify rows (causal among
+    themselves) and the DP's candidate rows (own key / value from the self block) against the oracle."""
+    name, T = "small-bf16-hd128", 16500
+    shape = si.SHAPES[name]
+    om, eng = oracle_model(name), engine(name, max_seq=16640)
+    K, V = si.gen_kv(shape, 7, shape.n_layers, T)
+    cache = oc.KVCache(shape, T + 16)
+    cache.load(K.numpy().astype(np.float64), V.numpy().astype(np.float64))
+    for l in range(shape.n_layers):
+        eng.clasp_kv_load(l, K[l], V[l])
+    toks = prompt(shape, n_rows, seed=8)
+    st = []
+    for r, tk in enumerate(toks):
+        s, _ = om.token(tk, T + r, cache, want_states=True, want_logits=False)
+        st.append(s)
+    ost = np.stack(st, 1)
+    out = eng.clasp_verify_forward(dev(toks, torch.int32), T, want_hidden=True)
+    for l in range(shape.n_layers + 1):
+        assert_close(out["hidden"][l].cpu().numpy(), ost[l], HID_TOL["bf16"], f"layer {l}")
+    if n_rows == 10:  # the search with M = L - 1... the model has 4 layers: M = 3 pushes up to 3 rows; its attention
+        # launches take one query tile, the verify rows above are what takes three and four
+        check_dp(om, eng, ost[:, 1], T + 1, cache, 3, X_dev=out["hidden"][:, 1, :].contiguous())
+
+
 @pytest.mark.parametrize("name,T", [("small-bf16", 300), ("small-bf16", 700), ("small-bf16", 1500),
                                     ("small-bf16-hd128", 2601)])
 def test_single_row_forward_over_long_prefix(name, T):
