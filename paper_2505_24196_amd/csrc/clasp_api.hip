@@ -198,7 +198,8 @@ struct clasp_ctx {
     uint8_t* choice;
     int32_t* tok_tmp;
     // optional per-kernel timing (host-side event objects only; no device memory)
-    int n_cu = 256;  // compute units of the device (grid size of the persistent kernels)
+    std::vector<int> kept;  // host scratch of masked_layers (sized once at create: no allocation per call)
+    int n_cu = 256;  // compute units of the device, queried at create (this value only if the query fails)
     int device = 0;  // the HIP device the context was created on
     void* static_scratch = nullptr;  // that device's copy of the library's static scratch array
     int timer_kind = -1, timer_every = 1;
@@ -629,7 +630,8 @@ int run_head(const clasp_ctx* ctx, int n, int R, float* logits_out, int32_t* arg
 // result (the state before the final norm); op_h / ss_h hold its operand for the head.
 int masked_layers(clasp_ctx* ctx, const uint8_t* mask, const int32_t* token, int pos, hipStream_t st, int* h_index) {
     const int L = ctx->cfg.n_layers;
-    std::vector<int> kept;
+    std::vector<int>& kept = ctx->kept;
+    kept.clear();  // capacity n_layers since clasp_create
     for (int l = 0; l < L; ++l)
         if (!mask || !mask[l]) kept.push_back(l);
     int rc;
@@ -1079,6 +1081,7 @@ int clasp_create(const clasp_config* cfg, const clasp_weights* w, void* workspac
     ctx->wq.assign(w->wq, w->wq + L); ctx->wk.assign(w->wk, w->wk + L); ctx->wv.assign(w->wv, w->wv + L);
     ctx->wo.assign(w->wo, w->wo + L); ctx->w_gate_up.assign(w->w_gate_up, w->w_gate_up + L);
     ctx->w_down.assign(w->w_down, w->w_down + L);
+    ctx->kept.reserve(L);
     ctx->k_cache = static_cast<char*>(k_cache);
     ctx->v_cache = static_cast<char*>(v_cache);
     ctx->kv_layer_bytes = (size_t)cfg->n_kv_heads * cfg->max_seq * cfg->head_dim * ctx->esz;
