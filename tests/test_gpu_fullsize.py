@@ -10,7 +10,8 @@ import torch
 
 import synth_inputs as si
 from oracle import clasp_oracle as oc
-from tests.test_gpu_parity import COS_TOL, HID_TOL, assert_close, check_dp, dev, relerr, relerr_rows
+from tests.test_gpu_parity import (COS_TOL, HID_TOL, assert_close, check_dp, dev, relerr, relerr_rows,
+                                   replay_against_oracle)
 
 pytestmark = pytest.mark.gpu
 
@@ -204,7 +205,7 @@ def test_8b_model_made_prefix_verify_dp_and_draft(setup_8b):
     shape, _, eng, om, _ = setup_8b
     T = 160
     toks = [int(t) for t in si.gen_tokens(2, T, shape.vocab, stream=13)]
-    cache = oc.KVCache(shape, T + 8)
+    cache = oc.KVCache(shape, T + 40)
     for t, tk in enumerate(toks):
         if t % 16 == 0:
             print(f"oracle prompt token {t}", flush=True)
@@ -224,6 +225,19 @@ def test_8b_model_made_prefix_verify_dp_and_draft(setup_8b):
     print(f"largest cache error over 32 layers: {worst:.3e}", flush=True)
     stats = verify_dp_draft(shape, T, eng, om, cache)
     print(f"dp cells compared: {stats}", flush=True)
+    # benchmark configuration 2's loop (M = 12, K = 4) from this prompt for a few rounds, the oracle driven along the
+    # device's trace on the cache it built above (rows beyond the prompt are rewritten by the rounds themselves)
+    from paper_2505_24196_amd import decode
+    n_gen = 6
+    spec = decode.clasp_generate(eng, toks, n_gen, 12, 4, trace=True)
+    assert len(spec["tokens"]) == n_gen
+    print(f"closed loop: {len(spec['rounds'])} rounds", flush=True)
+    st_last, lg_last = om.token(toks[-1], T - 1, cache, want_states=True)
+    logit_tol = HID_TOL["bf16"] * float(np.abs(lg_last).max()) * 2
+    rs = replay_against_oracle(om, toks, spec, 12, 4, logit_tol, prefilled=(cache, st_last, lg_last))
+    print(f"closed loop replay: {rs}", flush=True)
+    assert rs["rounds"] == len(spec["rounds"]) >= 1 and rs["cells"] >= 318 * rs["rounds"]
+    assert rs["forced"] <= rs["cells"] // 25 and rs["tokens"] >= 1 + 9 * rs["rounds"] - 8
 
 
 def test_8b_prefill_short_prompt_against_oracle(setup_8b):

@@ -120,16 +120,21 @@ def check_dp(om, eng, X, pos, cache, M, lo=0, hi=None, X_dev=None, stats=None):
     return gpu, ref
 
 
-def replay_against_oracle(om, prompt_toks, spec, M, K, logit_tol, thr=None, dp_interval=1):  # noqa: C901
+def replay_against_oracle(om, prompt_toks, spec, M, K, logit_tol, thr=None, dp_interval=1, prefilled=None):  # noqa: C901
     """The oracle driven call by call along a traced device run of the Draft -> Verify -> Layer-Optimisation loop
     (decode.clasp_generate(trace=True)): every DP table, every skip set, every draft and verify token of every round is
     compared. Where the two sides decide differently the oracle's own margin must be within tolerance (COS_MARGIN for a
     DP cell, logit_tol for an argmax), and the oracle then follows the device's decision, so the comparison goes on to
-    the end of the run instead of stopping at the first near-tie. Returns the counts of what was compared."""
+    the end of the run instead of stopping at the first near-tie. prefilled = (cache, states, logits): the oracle's own
+    prompt pass when the caller has it already. Returns the counts of what was compared."""
     shape = om.shape
     n_rounds = len(spec["rounds"])
-    cache = oc.KVCache(shape, len(prompt_toks) + sum(r["accepted"] + 1 for r in spec["rounds"]) + K + 2)
-    states, logits = om.prefill(prompt_toks, cache)
+    if prefilled is None:
+        cache = oc.KVCache(shape, len(prompt_toks) + sum(r["accepted"] + 1 for r in spec["rounds"]) + K + 2)
+        states, logits = om.prefill(prompt_toks, cache)
+    else:
+        cache, states, logits = prefilled
+        assert cache.t_max >= len(prompt_toks) + sum(r["accepted"] + 1 for r in spec["rounds"]) + K + 1
     st = {"rounds": 0, "cells": 0, "forced": 0, "tokens": 0, "tokens_forced": 0}
 
     def same_token(dev_tok, lg, what):
