@@ -431,7 +431,9 @@ int attn_deferred_splits(const clasp_ctx* ctx, int n, int R, int mode, int pos0)
     if (!gemv_lds_bytes<CLASP_GEMV_KW_RESID>(ctx->q_dim)) return 0;
     const int nblk = (pos0 + (mode ? n : 0) + 31) / 32;
     const int per = nblk <= CLASP_ATTN_SHORT_BLOCKS ? CLASP_ATTN_SHORT_WAVES : CLASP_ATTN_BLOCKS_PER_SPLIT;
-    const int split = (nblk + per - 1) / per;
+    int split = (nblk + per - 1) / per;
+    // a few thousand tokens: as many pieces as the merge takes, so that 64 rather than 16 workgroups pull the prefix
+    if (nblk > CLASP_ATTN_SHORT_BLOCKS && split < kGemvMaxSplit) split = std::min(kGemvMaxSplit, (nblk + 7) / 8);
     return (split >= 2 && split <= kGemvMaxSplit) ? split : 0;
 }
 
@@ -478,6 +480,12 @@ int launch_attention(const clasp_ctx* ctx, int layer, int n, int R, int mode, in
             const int rounds = (wgs + ctx->n_cu / 2) / ctx->n_cu, trimmed = rounds * ctx->n_cu / per_split;
             if (trimmed >= 1 && trimmed < split) split = trimmed;
         }
+    }
+    if (!short_prefix) {
+        // a few thousand tokens leave the launch well below one workgroup per CU at 32 blocks per split: split further, down
+        // to 4 blocks per workgroup, until the CUs are covered (a workgroup pulls ~50 GB/s, the chip a hundred times that)
+        const int per_split = c.n_kv_heads * qgroups, fill = ctx->n_cu / per_split, most = nblk / 4;
+        if (split < fill) split = std::max(split, std::min(fill, most));
     }
     split = split < 1 ? 1 : (split > kMaxSplit ? kMaxSplit : split);
     if (deferred_splits) split = deferred_splits;
