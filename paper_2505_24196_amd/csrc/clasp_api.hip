@@ -73,6 +73,9 @@ void* static_scratch_ptr() {
 #ifndef CLASP_GATEUP_KW
 #define CLASP_GATEUP_KW 2
 #endif
+#ifndef CLASP_GATEUP_NACC
+#define CLASP_GATEUP_NACC 4  // column tiles per wavefront when gate|up streams (K too long for the resident kernels: 70B shape)
+#endif
 #ifndef CLASP_DOWN_CW
 #define CLASP_DOWN_CW 1
 #endif
@@ -557,7 +560,7 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
         g.A = ctx->op_a; g.n_rows = n; g.K = d; g.R = R;
         g.ss_parts = ctx->ss_a; g.n_parts = d / 16; g.inv_dim = 1.0f / d; g.eps = c.rms_eps;
         g.next_op = ctx->op_act;
-        if ((rc = launch_gemm<kEpiSwiglu, CLASP_GATEUP_CW, CLASP_GATEUP_KW>(ctx, g, st, CLASP_KERNEL_GATE_UP))) return rc;
+        if ((rc = launch_gemm<kEpiSwiglu, CLASP_GATEUP_CW, CLASP_GATEUP_KW, CLASP_GATEUP_NACC>(ctx, g, st, CLASP_KERNEL_GATE_UP))) return rc;
     }
     if (down_split > 1 && c.dtype == CLASP_BF16) {
         GemmArgs g{};
@@ -669,7 +672,6 @@ int dp_select_window(clasp_ctx* ctx, const float* states, size_t layer_stride, i
                      uint8_t* mask_out, float* score_out, uint8_t* choice_out, float* g_final_out, hipStream_t st) {
     const clasp_config& c = ctx->cfg;
     const int L = hi - lo, d = c.d_model;
-    const int R = M > 16 ? 2 : 1;
     const int down_split = (c.dtype == CLASP_BF16 && c.d_ffn / 32 >= CLASP_DOWNP_KS * CLASP_DOWNP_KW * 4) ? CLASP_DOWNP_KS : 1;
     uint8_t* choice = choice_out ? choice_out : ctx->choice;
     const int cells = (L + 1) * (M + 1);
@@ -680,6 +682,11 @@ int dp_select_window(clasp_ctx* ctx, const float* states, size_t layer_stride, i
     // they are computed only when the caller asked for the tables. first_cell(i) = first cell of level i that is needed.
     const bool full_table = score_out || choice_out;
     auto first_cell = [&](int i) { return full_table ? 0 : std::max(0, M - (L - i)); };
+    // candidates level i pushes through its layer: cells max(1, first_cell(i)) .. min(i-1, M) of level i-1
+    auto rows_of = [&](int i) { return i > L ? 0 : std::min(i - 1, M) - std::max(1, first_cell(i)) + 1; };
+    // 16-row groups of a level's launches: levels with at most 16 candidates (the first 17 always; without tables also
+    // the last ones) take the one-group kernels, which are the faster ones
+    auto groups_of = [&](int i) { return rows_of(i) > 16 ? 2 : 1; };
     int rc;
     for (int i = 1; i <= L; ++i) {
         const int ell = (i - 1 < M) ? i - 1 : M;
@@ -688,12 +695,12 @@ int dp_select_window(clasp_ctx* ctx, const float* states, size_t layer_stride, i
         const float* g_prev = (i == 1) ? x0 : ctx->g[(i - 1) & 1];
         float* g_cur = ctx->g[i & 1];
         if (n_comp > 0) {  // candidates g(i-1, jc0..ell) through the window's layer i-1, all at position `pos`
-            if ((rc = run_layer(ctx, lo + i - 1, n_comp, R, 0, pos, g_prev + (size_t)jc0 * d, ctx->G, nullptr, nullptr,
+            if ((rc = run_layer(ctx, lo + i - 1, n_comp, groups_of(i), 0, pos, g_prev + (size_t)jc0 * d, ctx->G, nullptr, nullptr,
                                 nullptr, nullptr, st, down_split)))
                 return rc;
         }
         SelectArgs s{};
-        s.i = i; s.M = M; s.d = d; s.R = R;
+        s.i = i; s.M = M; s.d = d; s.R = groups_of(i + 1);  // the operand it writes is the next level's
         s.j0 = j0; s.jc0 = jc0; s.jn0 = jn0;
         s.x_i = x0 + (size_t)i * layer_stride;
         s.g_prev = g_prev; s.g_cur = g_cur;
