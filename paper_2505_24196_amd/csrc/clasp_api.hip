@@ -112,6 +112,13 @@ void* static_scratch_ptr() {
 #ifndef CLASP_R2_DEPTH
 #define CLASP_R2_DEPTH 2  // k-steps per register stage of those launches
 #endif
+// ... per projection (tiles per wavefront, column-tile wavefronts, K-slice wavefronts of a two-group launch)
+#ifndef CLASP_R2_OPROJ
+#define CLASP_R2_OPROJ 2, 1, 8
+#endif
+#ifndef CLASP_R2_QKV
+#define CLASP_R2_QKV 4, 1, 4
+#endif
 // k-steps per register stage (two stages in flight)
 #ifndef CLASP_STREAM_DEPTH
 #define CLASP_STREAM_DEPTH 8  // several-row streaming kernel, one row group
@@ -340,7 +347,7 @@ int launch_gemv(const TimerScope& timer, const GemmArgs& g, size_t lds, hipStrea
     return CLASP_OK;
 }
 
-template <int EPI, int CW, int KW, int NACC = 1>
+template <int EPI, int CW, int KW, int NACC = 1, int R2NACC = CLASP_R2_NACC, int R2CW = CW, int R2KW = KW>
 int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kind) {
     const int tiles = g.N / 16;
     TimerScope timer(ctx, kind, st, false);
@@ -379,9 +386,11 @@ int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kin
                 launch_timed(timer, gemm_bf16_kernel<1, CW, KW, EPI, CLASP_STREAM_DEPTH / NACC, CLASP_ACT_SPLIT, NACC>, grid,
                              dim3(CW * KW * 64), 0, st, g);
             } else {
-                const dim3 grid((tiles + CW * CLASP_R2_NACC - 1) / (CW * CLASP_R2_NACC));
-                launch_timed(timer, gemm_bf16_kernel<2, CW, KW, EPI, CLASP_R2_DEPTH, CLASP_ACT_SPLIT, CLASP_R2_NACC>, grid,
-                             dim3(CW * KW * 64), 0, st, g);
+                // two row groups: R2NACC column tiles per wavefront share the four activation loads of a k-step (weight
+                // fragments per stage stay the same, so fewer tiles per wavefront mean more k-steps per stage)
+                const dim3 grid((tiles + R2CW * R2NACC - 1) / (R2CW * R2NACC));
+                launch_timed(timer, gemm_bf16_kernel<2, R2CW, R2KW, EPI, CLASP_R2_DEPTH * CLASP_R2_NACC / R2NACC, CLASP_ACT_SPLIT, R2NACC>,
+                             grid, dim3(R2CW * R2KW * 64), 0, st, g);
             }
         }
     } else {
@@ -531,7 +540,7 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
             o.k_cache = ctx->k_cache + (size_t)l * ctx->kv_layer_bytes;
             o.v_cache = ctx->v_cache + (size_t)l * ctx->kv_layer_bytes;
             o.k_self = ctx->k_self; o.v_self = ctx->v_self;
-            if ((rc = launch_gemm<kEpiQkv, CLASP_QKV_CW, CLASP_QKV_KW, CLASP_QKV_NACC>(ctx, g, st, CLASP_KERNEL_QKV))) return rc;
+            if ((rc = launch_gemm<kEpiQkv, CLASP_QKV_CW, CLASP_QKV_KW, CLASP_QKV_NACC, CLASP_R2_QKV>(ctx, g, st, CLASP_KERNEL_QKV))) return rc;
         } else {
             if ((rc = launch_gemm<kEpiScale, 1, 1>(ctx, g, st, CLASP_KERNEL_QKV))) return rc;
         }
@@ -547,7 +556,7 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
         }
         g.out = ctx->a_buf; g.ldo = d; g.resid = h_in; g.ldr = d;
         g.next_op = ctx->op_a; g.next_gain = ctx->mlp_norm[l]; g.next_ss = ctx->ss_a;
-        if ((rc = launch_gemm<kEpiResid, CLASP_OPROJ_CW, CLASP_OPROJ_KW, CLASP_OPROJ_NACC>(ctx, g, st, CLASP_KERNEL_O_PROJ))) return rc;
+        if ((rc = launch_gemm<kEpiResid, CLASP_OPROJ_CW, CLASP_OPROJ_KW, CLASP_OPROJ_NACC, CLASP_R2_OPROJ>(ctx, g, st, CLASP_KERNEL_O_PROJ))) return rc;
     }
     {
         GemmArgs g{};
