@@ -128,3 +128,24 @@ def test_skip_set_jaccard_curve_by_hand():
     assert curve == pytest.approx([(1 / 3 + 1 + 0) / 3, (1 / 3 + 0) / 2, 0.0])
     assert skip_set_jaccard([[0, 0], [0, 0]]) == [1.0]  # two empty sets are identical
     assert skip_set_jaccard([[1, 0]]) == []
+
+
+def test_algorithmic_bytes_of_the_benchmark_configurations():
+    """bench.py prices every call against the bytes the method itself has to move: the weights of each evaluated layer
+    once plus the shared KV prefix once per layer (the DP never evaluates layer 0; a draft step runs L - M layers and
+    the head). The figures for the LLaMA-3-8B and -70B shapes, worked out by hand from the shapes."""
+    import bench
+    import synth_inputs as si
+    s = si.LLAMA3_8B
+    w_layer = (4096 * (4096 + 2 * 1024) + 4096 * 4096 + 3 * 4096 * 14336) * 2
+    assert s.layer_weight_elems() * s.elem_bytes() == w_layer == 436_207_616
+    ab = bench.algorithmic_bytes(s, 512, 12)
+    kv = 2 * 1024 * 2 * 512
+    assert ab["dp_select"] == 31 * (w_layer + kv) and abs(ab["dp_select"] / 1e9 - 13.59) < 0.01
+    assert ab["draft_step"] == 20 * (w_layer + kv) + 128256 * 4096 * 2 and abs(ab["draft_step"] / 1e9 - 9.82) < 0.01
+    assert ab["verify_forward"] == 32 * (w_layer + kv) + 128256 * 4096 * 2
+    assert ab["gate_up_kernel"] == 234_881_024
+    assert abs(bench.algorithmic_bytes(s, 32768, 12)["dp_select"] / 1e9 - 17.68) < 0.01
+    assert abs(bench.algorithmic_bytes(s, 32768, 12)["kv_share_per_layer"] - 0.2353) < 1e-3
+    b70 = bench.algorithmic_bytes(si.LLAMA3_70B, 1024, 32)
+    assert abs(b70["dp_select"] / 1e9 - 135.5) < 0.1 and abs(b70["draft_step"] / 1e9 - 84.4) < 0.1
