@@ -152,35 +152,42 @@ struct SelectArgs {
     int j0, jc0, jn0;
 };
 
-// One workgroup of 1024 threads per cell; every thread owns 4 consecutive columns per pass, all loads of a pass are
-// issued together and the five dot products share one block reduction.
-template <int DT>
-__global__ __launch_bounds__(1024) void dp_select_kernel(SelectArgs a) {
-    __shared__ float red[16][5];
-    const int j = a.j0 + blockIdx.x, d = a.d;
-    const int ell = min(a.i - 1, a.M);
+// One workgroup of 1024 threads per cell; a thread owns the 4-column chunks threadIdx.x, threadIdx.x + 1024, ...
+// Everything a thread reads - x_i, the skip candidate, the computed candidate with its K-slices, the next layer's
+// gains - is requested before the first value is used (NP, the number of K-slices, is a compile-time constant for that
+// reason: a loop over a run-time count waits for every slice before it asks for the next), so a cell costs one trip to
+// memory, the block reduction of the five dot products, and the stores. The first kSelectKeep chunks of a thread stay
+// in registers (d <= 8192); chunks beyond them are read again after the decision.
+constexpr int kSelectKeep = 2;
+
+template <int DT, bool HAS_COMP, int NP>
+__device__ __forceinline__ void select_cell(const SelectArgs& a, int j, float (*red)[5]) {
+    const int d = a.d, nc = d / 4, tid = threadIdx.x;
     float* dst = a.g_cur + (size_t)j * d;
     const f32x4* x4 = reinterpret_cast<const f32x4*>(a.x_i);
-    if (j == 0) {
-        for (int c = threadIdx.x; c < d / 4; c += blockDim.x) reinterpret_cast<f32x4*>(dst)[c] = x4[c];
-        return;
-    }
     const f32x4* skip4 = reinterpret_cast<const f32x4*>(a.g_prev + (size_t)(j - 1) * d);
-    const bool has_comp = j <= ell;  // cells of a launch never lie below jc0
-    const f32x4* comp4 = reinterpret_cast<const f32x4*>(a.G + (size_t)(j - a.jc0) * d);
     // the computed candidate: a finished row, or residual + K-slices of the down projection added in slice order
+    const f32x4* comp4 = reinterpret_cast<const f32x4*>(a.G + (size_t)(j - a.jc0) * d);
     const f32x4* part4 = reinterpret_cast<const f32x4*>(a.parts + (size_t)(j - a.jc0) * d);
+    const size_t ps4 = a.part_stride / 4;
+    const bool feeds = a.op && j >= a.jn0;  // this cell is row j - jn0 of the next layer's input
+    const f32x4* gain4 = feeds ? reinterpret_cast<const f32x4*>(a.gain) : nullptr;
+    const f32x4 zero = f32x4{0.f, 0.f, 0.f, 0.f}, ones = f32x4{1.f, 1.f, 1.f, 1.f};
     auto load_comp = [&](int c) -> f32x4 {
         f32x4 v = comp4[c];
-        for (int p = 0; p < a.n_parts; ++p) v += part4[p * (a.part_stride / 4) + c];
+        if constexpr (NP >= 0) {
+            f32x4 p[NP > 0 ? NP : 1];
+#pragma unroll
+            for (int k = 0; k < NP; ++k) p[k] = part4[k * ps4 + c];
+#pragma unroll
+            for (int k = 0; k < NP; ++k) v += p[k];
+        } else {
+            for (int k = 0; k < a.n_parts; ++k) v += part4[k * ps4 + c];
+        }
         return v;
     };
     float acc[5] = {0.f, 0.f, 0.f, 0.f, 0.f};  // x.x, s.x, s.s, c.x, c.c
-    f32x4 s_first = f32x4{0.f, 0.f, 0.f, 0.f}, g_first = s_first;  // the thread's first chunk stays in registers
-    for (int c = threadIdx.x; c < d / 4; c += blockDim.x) {
-        const f32x4 x = x4[c], s = skip4[c];
-        const f32x4 g = has_comp ? load_comp(c) : f32x4{0.f, 0.f, 0.f, 0.f};
-        if (c == (int)threadIdx.x) { s_first = s; g_first = g; }
+    auto dots = [&](const f32x4& x, const f32x4& s, const f32x4& g) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             acc[0] = fmaf(x[e], x[e], acc[0]);
@@ -189,12 +196,31 @@ __global__ __launch_bounds__(1024) void dp_select_kernel(SelectArgs a) {
             acc[3] = fmaf(g[e], x[e], acc[3]);
             acc[4] = fmaf(g[e], g[e], acc[4]);
         }
+    };
+    f32x4 s_keep[kSelectKeep], g_keep[kSelectKeep], gn_keep[kSelectKeep];
+#pragma unroll
+    for (int u = 0; u < kSelectKeep; ++u) {
+        const int c = tid + u * 1024;
+        const bool live = c < nc;
+        const int cc = live ? c : 0;  // a thread without a chunk reads chunk 0 and adds zeros
+        f32x4 x = x4[cc], s = skip4[cc], g = zero;
+        if constexpr (HAS_COMP) g = load_comp(cc);
+        gn_keep[u] = gain4 ? gain4[cc] : ones;
+        if (!live) x = s = g = zero;
+        s_keep[u] = s;
+        g_keep[u] = g;
+        dots(x, s, g);
     }
-    const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    for (int c = tid + kSelectKeep * 1024; c < nc; c += 1024) {
+        f32x4 g = zero;
+        if constexpr (HAS_COMP) g = load_comp(c);
+        dots(x4[c], skip4[c], g);
+    }
+    const int wave = tid >> 6, nw = blockDim.x >> 6;
 #pragma unroll
     for (int k = 0; k < 5; ++k) {
         acc[k] = wave_sum(acc[k]);
-        if ((threadIdx.x & 63) == 0) red[wave][k] = acc[k];
+        if ((tid & 63) == 0) red[wave][k] = acc[k];
     }
     __syncthreads();
 #pragma unroll
@@ -205,9 +231,9 @@ __global__ __launch_bounds__(1024) void dp_select_kernel(SelectArgs a) {
     }
     const float nx = fmaxf(sqrtf(acc[0]), 1e-12f);
     const float sig_s = acc[1] / (fmaxf(sqrtf(acc[2]), 1e-12f) * nx);
-    const float sig_c = has_comp ? acc[3] / (fmaxf(sqrtf(acc[4]), 1e-12f) * nx) : __builtin_nanf("");
-    const bool keep_comp = has_comp && (sig_c > sig_s);
-    if (threadIdx.x == 0) {
+    const float sig_c = HAS_COMP ? acc[3] / (fmaxf(sqrtf(acc[4]), 1e-12f) * nx) : __builtin_nanf("");
+    const bool keep_comp = HAS_COMP && (sig_c > sig_s);
+    if (tid == 0) {
         const size_t cell = (size_t)a.i * (a.M + 1) + j;
         a.choice[cell] = keep_comp ? 0 : 1;
         if (a.scores) {
@@ -215,19 +241,45 @@ __global__ __launch_bounds__(1024) void dp_select_kernel(SelectArgs a) {
             a.scores[cell * 2 + 1] = sig_s;
         }
     }
-    const f32x4* gain4 = reinterpret_cast<const f32x4*>(a.gain);
-    for (int c = threadIdx.x; c < d / 4; c += blockDim.x) {
-        const f32x4 v = c == (int)threadIdx.x ? (keep_comp ? g_first : s_first) : (keep_comp ? load_comp(c) : skip4[c]);
+    auto emit = [&](int c, const f32x4& v, const f32x4& gn) {
         reinterpret_cast<f32x4*>(dst)[c] = v;
-        if (a.op && j >= a.jn0) {
-            const f32x4 gn = gain4 ? gain4[c] : f32x4{1.f, 1.f, 1.f, 1.f};
+        if (feeds) {
             store_operand4<DT>(a.op, a.R, d, j - a.jn0, c * 4, v * gn);
             float sq = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];  // 4 lanes cover one 16-column tile
             sq += __shfl_xor(sq, 1);
             sq += __shfl_xor(sq, 2);
             if ((c & 3) == 0) a.ss[(size_t)(c >> 2) * kMaxRows + (j - a.jn0)] = sq;
         }
+    };
+#pragma unroll
+    for (int u = 0; u < kSelectKeep; ++u) {
+        const int c = tid + u * 1024;
+        if (c < nc) emit(c, keep_comp ? g_keep[u] : s_keep[u], gn_keep[u]);
     }
+    for (int c = tid + kSelectKeep * 1024; c < nc; c += 1024) {
+        f32x4 v = skip4[c];
+        if constexpr (HAS_COMP) {
+            if (keep_comp) v = load_comp(c);
+        }
+        emit(c, v, gain4 ? gain4[c] : ones);
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(1024) void dp_select_kernel(SelectArgs a) {
+    __shared__ float red[16][5];
+    const int j = a.j0 + blockIdx.x, d = a.d;
+    if (j == 0) {
+        float* dst = a.g_cur;
+        const f32x4* x4 = reinterpret_cast<const f32x4*>(a.x_i);
+        for (int c = threadIdx.x; c < d / 4; c += blockDim.x) reinterpret_cast<f32x4*>(dst)[c] = x4[c];
+        return;
+    }
+    const bool has_comp = j <= min(a.i - 1, a.M);  // cells of a launch never lie below jc0
+    if (!has_comp) select_cell<DT, false, 0>(a, j, red);
+    else if (a.n_parts == 0) select_cell<DT, true, 0>(a, j, red);
+    else if (a.n_parts == 4) select_cell<DT, true, 4>(a, j, red);
+    else select_cell<DT, true, -1>(a, j, red);
 }
 
 __global__ void dp_table_init_kernel(float* scores, uint8_t* choice, int cells) {
