@@ -29,6 +29,8 @@
 //               q as ready-made MFMA fragments, k and v into the KV cache (verify/draft rows) or into the small
 //               per-launch self block (DP candidates, which must not touch the cache)
 #pragma once
+#include <type_traits>
+
 #include "clasp_common.h"
 
 namespace clasp {
@@ -173,7 +175,10 @@ __device__ __forceinline__ void gemm_issue(GemmStage<R, NACC, P, SPLIT>& st, con
     }
 }
 
-template <int R, int NACC, int P, int SPLIT>
+// WT = false: accumulator tile D[row][feature], a lane holds rows 4*(lane/16) .. +3 of feature lane%16.
+// WT = true (weights as the first operand): D[feature][row], a lane holds features 4*(lane/16) .. +3 of row lane%16,
+// i.e. four consecutive columns of one output row: what the epilogues that write rows (residual, K-slices) want.
+template <int R, int NACC, int P, int SPLIT, bool WT = false>
 __device__ __forceinline__ void gemm_compute(const GemmStage<R, NACC, P, SPLIT>& st, f32x4 (&acc)[NACC][R], int s,
                                              int ks1) {
 #pragma unroll
@@ -184,9 +189,14 @@ __device__ __forceinline__ void gemm_compute(const GemmStage<R, NACC, P, SPLIT>&
 #pragma unroll
                 for (int h = 0; h < SPLIT; ++h)
 #pragma unroll
-                    for (int a = 0; a < NACC; ++a)
-                        acc[a][rg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(st.a[u][rg][h]),
-                                                                             as_bf16x8(st.b[a][u]), acc[a][rg], 0, 0, 0);
+                    for (int a = 0; a < NACC; ++a) {
+                        if constexpr (WT)
+                            acc[a][rg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(st.b[a][u]),
+                                                                                 as_bf16x8(st.a[u][rg][h]), acc[a][rg], 0, 0, 0);
+                        else
+                            acc[a][rg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(st.a[u][rg][h]),
+                                                                                 as_bf16x8(st.b[a][u]), acc[a][rg], 0, 0, 0);
+                    }
         }
     }
 }
@@ -337,6 +347,58 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, int tile, int l
     }
 }
 
+// The residual and K-slice epilogues on a transposed accumulator tile (gemm_compute<.., WT = true>): a lane owns columns
+// tile*16 + 4*(lane/16) .. +3 of row rg*16 + lane%16, so the residual, the output row, the captured state and the
+// next GEMM's operand move as 16-byte (operand planes: 8-byte) pieces, and a row's sum of squares over the tile needs
+// two shuffles. With one feature per lane the same epilogue took 12-16 stores of 2 or 4 bytes and 16 shuffles per lane
+// at the very end of the kernel, where nothing overlaps them.
+struct EpiPreT {
+    f32x4 resid, gain;
+};
+
+template <int EPI>
+__device__ __forceinline__ void epi_prefetch_t(const GemmArgs& g, int tile, int lane, int rg, EpiPreT& pre) {
+    if constexpr (EPI == kEpiResid) {
+        const int row = rg * 16 + (lane & 15), col0 = tile * 16 + (lane >> 4) * 4;
+        pre.gain = g.next_gain ? *reinterpret_cast<const f32x4*>(g.next_gain + col0) : f32x4{1.f, 1.f, 1.f, 1.f};
+        pre.resid = row < g.n_rows ? *reinterpret_cast<const f32x4*>(g.resid + (size_t)row * g.ldr + col0)
+                                   : f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+}
+
+template <int EPI>
+__device__ __forceinline__ void gemm_epilogue_t(const GemmArgs& g, int tile, int lane, int rg, const f32x4& sum,
+                                                const EpiPreT& pre) {
+    static_assert(EPI == kEpiResid || EPI == kEpiPartial, "row-writing epilogues only");
+    const int row = rg * 16 + (lane & 15), col0 = tile * 16 + (lane >> 4) * 4;
+    if constexpr (EPI == kEpiPartial) {
+        float* slab = g.out + (size_t)blockIdx.y * g.ldr;  // ldr = elements per slab
+        if (row < g.n_rows) *reinterpret_cast<f32x4*>(slab + (size_t)row * g.ldo + col0) = sum;
+    } else {
+        f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (row < g.n_rows) {
+            v = pre.resid + sum;
+            *reinterpret_cast<f32x4*>(g.out + (size_t)row * g.ldo + col0) = v;
+            if (g.capture) {  // the caller's buffer: 16-byte stores only if it is aligned for them
+                float* cp = g.capture + (size_t)row * g.ldc + col0;
+                if ((reinterpret_cast<uintptr_t>(g.capture) & 15) == 0 && (g.ldc & 3) == 0) {
+                    *reinterpret_cast<f32x4*>(cp) = v;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) cp[e] = v[e];
+                }
+            }
+        }
+        if (g.next_op) store_operand4<kDtBf16>(g.next_op, g.R, 0, row, col0, v * pre.gain);
+        if (g.next_ss) {
+            float sq = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+            sq += __shfl_xor(sq, 16);
+            sq += __shfl_xor(sq, 32);
+            if (lane < 16) g.next_ss[(size_t)tile * kMaxRows + row] = sq;
+        }
+    }
+}
+
 // Workgroup = CW x KW wavefronts: wavefront (cw, kw) streams NACC neighbouring column tiles, starting at tile
 // (blockIdx.x*CW + cw)*NACC, over k-slice kw of KW equal slices; with NACC = 2 one activation fragment feeds two weight
 // fragments, which halves the activation loads per weight byte. The CW wavefronts that share a k-slice read the same
@@ -387,22 +449,26 @@ __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
     int s = ks0;
     if (s < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w, af, s, ks1);  // weights first: independent of rstd
 
-    EpiPre pre[NACC][R];
+    constexpr bool kWT = (EPI == kEpiResid || EPI == kEpiPartial);  // row-writing epilogues take transposed tiles
+    typename std::conditional<kWT, EpiPreT, EpiPre>::type pre[NACC][R];
     if (kw == 0) {
 #pragma unroll
         for (int a = 0; a < NACC; ++a)
 #pragma unroll
-            for (int rg = 0; rg < R; ++rg) epi_prefetch<EPI>(g, tile[a], lane, rg, pre[a][rg]);
+            for (int rg = 0; rg < R; ++rg) {
+                if constexpr (kWT) epi_prefetch_t<EPI>(g, tile[a], lane, rg, pre[a][rg]);
+                else epi_prefetch<EPI>(g, tile[a], lane, rg, pre[a][rg]);
+            }
     }
     if constexpr (EPI != kEpiResid && EPI != kEpiPartial) compute_rstd(g, rstd_s, tmp_s);
 
     while (s < ks1) {
         if (s + P < ks1) gemm_issue<R, NACC, P, SPLIT>(st1, w, af, s + P, ks1);
-        gemm_compute<R, NACC, P, SPLIT>(st0, acc, s, ks1);
+        gemm_compute<R, NACC, P, SPLIT, kWT>(st0, acc, s, ks1);
         s += P;
         if (s >= ks1) break;
         if (s + P < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w, af, s + P, ks1);
-        gemm_compute<R, NACC, P, SPLIT>(st1, acc, s, ks1);
+        gemm_compute<R, NACC, P, SPLIT, kWT>(st1, acc, s, ks1);
         s += P;
     }
 
@@ -436,9 +502,13 @@ __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
         if (tile0 + a >= n_tiles) continue;
 #pragma unroll
         for (int rg = 0; rg < R; ++rg) {
-            f32x4 fin[1];
-            fin[0] = sum[a][rg];
-            gemm_epilogue<EPI, 1>(g, tile[a], lane, rg, fin, rstd_s, pre[a][rg]);
+            if constexpr (kWT) {
+                gemm_epilogue_t<EPI>(g, tile[a], lane, rg, sum[a][rg], pre[a][rg]);
+            } else {
+                f32x4 fin[1];
+                fin[0] = sum[a][rg];
+                gemm_epilogue<EPI, 1>(g, tile[a], lane, rg, fin, rstd_s, pre[a][rg]);
+            }
         }
     }
 }
