@@ -354,6 +354,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, int tile, int l
 // at the very end of the kernel, where nothing overlaps them.
 struct EpiPreT {
     f32x4 resid, gain;
+    f32x4 cs[2];  // rotary (cos, sin) of the lane's four features
 };
 
 template <int EPI>
@@ -363,15 +364,82 @@ __device__ __forceinline__ void epi_prefetch_t(const GemmArgs& g, int tile, int 
         pre.gain = g.next_gain ? *reinterpret_cast<const f32x4*>(g.next_gain + col0) : f32x4{1.f, 1.f, 1.f, 1.f};
         pre.resid = row < g.n_rows ? *reinterpret_cast<const f32x4*>(g.resid + (size_t)row * g.ldr + col0)
                                    : f32x4{0.f, 0.f, 0.f, 0.f};
+    } else if constexpr (EPI == kEpiQkv) {
+        const QkvOut& o = g.qkv;
+        const int HALF = o.head_dim >> 1, tph = o.head_dim >> 4;
+        const int tl = tile - (tile < g.tile_end[0] ? 0 : g.tile_end[0]);  // q or k tile inside its matrix
+        const int q4 = lane >> 4, row = rg * 16 + (lane & 15);
+        const int e0 = (tl % tph) * 8 + (q4 & 1) * 4;
+        pre.cs[0] = pre.cs[1] = f32x4{1.f, 0.f, 1.f, 0.f};
+        if (tile < g.tile_end[1] && row < g.n_rows) {
+            const f32x4* rp = reinterpret_cast<const f32x4*>(o.rope + (size_t)(o.pos0 + (o.mode ? row : 0)) * HALF + e0);
+            pre.cs[0] = rp[0];
+            pre.cs[1] = rp[1];
+        }
+    }
+}
+
+// q/k/v epilogue of one lane on a transposed tile: 4 features x 1 row. Tile features 0..7 are rotary features
+// e = 8u .. 8u+7 of a head, 8..15 their partners e + head_dim/2 (the packing of wq / wk), so the partner of a lane's
+// values sits 32 lanes away; q and k leave as 8-byte pieces of their fragments, v (stored transposed) element by element.
+__device__ __forceinline__ void qkv_epilogue_t(const GemmArgs& g, int tile, int lane, int rg, const f32x4& sum,
+                                               const float* rstd_s, const EpiPreT& pre) {
+    typedef __attribute__((ext_vector_type(4))) _Float16 kvx4;
+    static_assert(sizeof(kv_t) == 2, "8-byte pieces of four cache elements");
+    const QkvOut& o = g.qkv;
+    const int HD = o.head_dim, HALF = HD >> 1, tph = HD >> 4;  // tiles per head
+    const int q4 = lane >> 4, row = rg * 16 + (lane & 15);
+    const int G = o.n_heads / o.n_kv_heads;
+    const int which = tile < g.tile_end[0] ? 0 : (tile < g.tile_end[1] ? 1 : 2);
+    const int tl = tile - (which == 0 ? 0 : g.tile_end[which - 1]);
+    const int head = tl / tph, u = tl % tph;
+    const float rs = rstd_s[row & 31];
+    f32x4 own, partner;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        own[i] = sum[i] * rs;
+        partner[i] = __shfl_xor(own[i], 32);
+    }
+    if (row >= g.n_rows) return;
+    if (which == 2) {  // v: plain feature order
+        kv_t* base = o.mode ? reinterpret_cast<kv_t*>(o.v_cache) + (size_t)head * o.t_max * HD
+                            : reinterpret_cast<kv_t*>(o.v_self) + (size_t)head * 32 * HD;
+        const int t = o.mode ? o.pos0 + row : row;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) base[vfrag_offset(HD, t, u * 16 + q4 * 4 + i)] = to_kv(own[i]);
+        return;
+    }
+    const bool upper = q4 >= 2;
+    const int x0 = u * 8 + (q4 & 1) * 4 + (upper ? HALF : 0);
+    const float qs = which == 0 ? o.q_scale : 1.0f;
+    kvx4 out;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float cs_x = pre.cs[i >> 1][(i & 1) * 2], cs_y = pre.cs[i >> 1][(i & 1) * 2 + 1];
+        const float rot = own[i] * cs_x + (upper ? partner[i] : -partner[i]) * cs_y;
+        out[i] = which == 0 ? to_kv(rot * qs) : to_kv(rot);
+    }
+    if (which == 0) {
+        const int kvh = head / G, qi = row * G + head % G;
+        const size_t off = (((((size_t)kvh * (2 * G) + (qi >> 4)) * (HD >> 5) + (x0 >> 5)) * 64) +
+                            ((x0 >> 3) & 3) * 16 + (qi & 15)) * 8 + (x0 & 7);
+        *reinterpret_cast<kvx4*>(reinterpret_cast<kv_t*>(o.q_frag) + off) = out;
+    } else if (o.mode) {
+        *reinterpret_cast<kvx4*>(reinterpret_cast<kv_t*>(o.k_cache) + (size_t)head * o.t_max * HD +
+                                 kfrag_offset(HD, o.pos0 + row, x0)) = out;
+    } else {
+        *reinterpret_cast<kvx4*>(reinterpret_cast<kv_t*>(o.k_self) + (size_t)head * 32 * HD + kfrag_offset(HD, row, x0)) = out;
     }
 }
 
 template <int EPI>
 __device__ __forceinline__ void gemm_epilogue_t(const GemmArgs& g, int tile, int lane, int rg, const f32x4& sum,
-                                                const EpiPreT& pre) {
-    static_assert(EPI == kEpiResid || EPI == kEpiPartial, "row-writing epilogues only");
+                                                const float* rstd_s, const EpiPreT& pre) {
+    static_assert(EPI == kEpiResid || EPI == kEpiPartial || EPI == kEpiQkv, "row-writing epilogues only");
     const int row = rg * 16 + (lane & 15), col0 = tile * 16 + (lane >> 4) * 4;
-    if constexpr (EPI == kEpiPartial) {
+    if constexpr (EPI == kEpiQkv) {
+        qkv_epilogue_t(g, tile, lane, rg, sum, rstd_s, pre);
+    } else if constexpr (EPI == kEpiPartial) {
         float* slab = g.out + (size_t)blockIdx.y * g.ldr;  // ldr = elements per slab
         if (row < g.n_rows) *reinterpret_cast<f32x4*>(slab + (size_t)row * g.ldo + col0) = sum;
     } else {
@@ -449,7 +517,7 @@ __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
     int s = ks0;
     if (s < ks1) gemm_issue<R, NACC, P, SPLIT>(st0, w, af, s, ks1);  // weights first: independent of rstd
 
-    constexpr bool kWT = (EPI == kEpiResid || EPI == kEpiPartial);  // row-writing epilogues take transposed tiles
+    constexpr bool kWT = (EPI == kEpiResid || EPI == kEpiPartial || EPI == kEpiQkv);  // row-writing epilogues take transposed tiles
     typename std::conditional<kWT, EpiPreT, EpiPre>::type pre[NACC][R];
     if (kw == 0) {
 #pragma unroll
@@ -503,7 +571,7 @@ __global__ __launch_bounds__(CW * KW * 64) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
         for (int rg = 0; rg < R; ++rg) {
             if constexpr (kWT) {
-                gemm_epilogue_t<EPI>(g, tile[a], lane, rg, sum[a][rg], pre[a][rg]);
+                gemm_epilogue_t<EPI>(g, tile[a], lane, rg, sum[a][rg], rstd_s, pre[a][rg]);
             } else {
                 f32x4 fin[1];
                 fin[0] = sum[a][rg];
