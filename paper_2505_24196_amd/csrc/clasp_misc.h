@@ -158,7 +158,10 @@ struct SelectArgs {
 // reason: a loop over a run-time count waits for every slice before it asks for the next), so a cell costs one trip to
 // memory, the block reduction of the five dot products, and the stores. The first kSelectKeep chunks of a thread stay
 // in registers (d <= 8192); chunks beyond them are read again after the decision.
-constexpr int kSelectKeep = 2;
+#ifndef CLASP_SELECT_KEEP
+#define CLASP_SELECT_KEEP 2
+#endif
+constexpr int kSelectKeep = CLASP_SELECT_KEEP;
 
 template <int DT, bool HAS_COMP, int NP>
 __device__ __forceinline__ void select_cell(const SelectArgs& a, int j, float (*red)[5]) {
