@@ -58,6 +58,9 @@ void* static_scratch_ptr() {
 #ifndef CLASP_QKV_NACC
 #define CLASP_QKV_NACC 1
 #endif
+#ifndef CLASP_QKV_WIDE_NACC
+#define CLASP_QKV_WIDE_NACC 4  // column tiles per wavefront when the projection has 2 x CUs tiles or more
+#endif
 #ifndef CLASP_OPROJ_CW
 #define CLASP_OPROJ_CW 1
 #endif
@@ -381,6 +384,17 @@ int launch_gemm(const clasp_ctx* ctx, const GemmArgs& g, hipStream_t st, int kin
             }
             return launch_gemv<EPI, KWV>(timer, g, gemv_lds, st);
         } else {
+            if constexpr (EPI == kEpiQkv && NACC == 1 && CLASP_QKV_WIDE_NACC > 1) {
+                // a projection with at least two column tiles per CU and wavefront-to-be (the 70B shape's q|k|v: 640
+                // tiles) lets a wavefront carry several tiles, which share its activation loads, and still fills the chip
+                if (g.R == 1 && tiles >= 2 * ctx->n_cu) {
+                    constexpr int WN = CLASP_QKV_WIDE_NACC;
+                    launch_timed(timer, gemm_bf16_kernel<1, CW, KW, EPI, CLASP_STREAM_DEPTH / WN, CLASP_ACT_SPLIT, WN>,
+                                 dim3((tiles + CW * WN - 1) / (CW * WN)), dim3(CW * KW * 64), 0, st, g);
+                    CLASP_LAUNCH_CHECK();
+                    return CLASP_OK;
+                }
+            }
             if (g.R == 1) {  // NACC tiles per wavefront share the activation fragments; the stage depth shrinks to match
                 const dim3 grid((tiles + CW * NACC - 1) / (CW * NACC));
                 launch_timed(timer, gemm_bf16_kernel<1, CW, KW, EPI, CLASP_STREAM_DEPTH / NACC, CLASP_ACT_SPLIT, NACC>, grid,
