@@ -119,6 +119,9 @@ void* static_scratch_ptr() {
 #ifndef CLASP_R2_OPROJ
 #define CLASP_R2_OPROJ 2, 1, 8
 #endif
+#ifndef CLASP_R2_GATEUP
+#define CLASP_R2_GATEUP CLASP_R2_NACC, CLASP_GATEUP_CW, CLASP_GATEUP_KW
+#endif
 #ifndef CLASP_R2_QKV
 #define CLASP_R2_QKV 4, 1, 4
 #endif
@@ -583,7 +586,7 @@ int run_layer(const clasp_ctx* ctx, int l, int n, int R, int mode, int pos0, con
         g.A = ctx->op_a; g.n_rows = n; g.K = d; g.R = R;
         g.ss_parts = ctx->ss_a; g.n_parts = d / 16; g.inv_dim = 1.0f / d; g.eps = c.rms_eps;
         g.next_op = ctx->op_act;
-        if ((rc = launch_gemm<kEpiSwiglu, CLASP_GATEUP_CW, CLASP_GATEUP_KW, CLASP_GATEUP_NACC>(ctx, g, st, CLASP_KERNEL_GATE_UP))) return rc;
+        if ((rc = launch_gemm<kEpiSwiglu, CLASP_GATEUP_CW, CLASP_GATEUP_KW, CLASP_GATEUP_NACC, CLASP_R2_GATEUP>(ctx, g, st, CLASP_KERNEL_GATE_UP))) return rc;
     }
     if (down_split > 1 && c.dtype == CLASP_BF16) {
         GemmArgs g{};
