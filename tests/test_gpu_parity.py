@@ -213,6 +213,29 @@ def test_verify_forward_hidden_states_and_logits(name):
     assert relerr(one["hidden"][:, 0].cpu().numpy(), ost[:, 20]) <= tol
 
 
+@pytest.mark.parametrize("name", ["small-bf16", "small-bf16-hd128"])
+def test_verify_forward_every_row_count_of_a_launch(name):
+    """A prompt of 1 + 2 + .. + 17 + 32 tokens goes through verify passes of 1, 2, .., 17 and 32 rows (every row count
+    of one row group, a ragged and a full second group), each on top of the cache the passes before it left: the states
+    of every row at every layer against the oracle, tensor-wide and row by row."""
+    shape = si.SHAPES[name]
+    sizes = list(range(1, 18)) + [32]
+    n = sum(sizes)
+    om, eng = oracle_model(name), engine(name, max_seq=256, max_rows=32)
+    toks = prompt(shape, n)
+    _, ost, _ = oracle_prefill(om, toks, 256)
+    tt = dev(toks, torch.int32)
+    tol, p0 = HID_TOL[shape.dtype], 0
+    for k in sizes:
+        out = eng.clasp_verify_forward(tt[p0:p0 + k], p0, True)
+        hid = out["hidden"].cpu().numpy()
+        assert hid.shape[1] == k
+        for l in range(shape.n_layers + 1):
+            assert_close(hid[l], ost[l, p0:p0 + k], tol, f"{k} rows at position {p0}, layer {l}")
+        p0 += k
+    assert p0 == n
+
+
 @pytest.mark.parametrize("name,M", [("tiny-f32", 0), ("tiny-f32", 1), ("tiny-f32", 3), ("tiny-f32", 8),
                                     ("small-bf16", 2), ("small-bf16", 6), ("small-bf16-hd128", 3)])
 @pytest.mark.parametrize("resid_scale", [1.0, 0.05])
